@@ -1,0 +1,273 @@
+"""CPU oracle for the LIME inference hot path (arXiv 2510.18239).
+
+THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  Only the tests, the smoke check
+and the benchmark's ``cpu_baseline`` leg may import it.  It shares no code with
+the HIP library and never imports it.
+
+Everything is evaluated in float64 with numpy, un-fused and un-blocked, in the
+order and notation of the paper, so that it can be checked against the paper by
+eye.  Inputs are whatever values the caller hands over (bf16-rounded or fp32
+values are simply up-cast; no rounding happens in here).
+
+Notation (Appendix A): E history [N, d]; T candidates [C, d]; L raw links
+[m, d]; L^C contextualised links; L^P personalised links; theta = {W_Q, W_K,
+W_V}, each [d, d] and applied on the right (X~ = X W, Section 3.1, Eq. 1).
+
+Readings of points the paper leaves open (each is repeated where it is used):
+  * heads: the d projected columns are cut into h contiguous blocks of d/h; the
+    heads are independent and their outputs are concatenated; there is no
+    output projection because theta holds only W_Q, W_K, W_V (Eq. 1).
+  * "scaled softmax": the logit scale is an explicit argument.
+  * ragged histories: a user's result is the result on that user's first
+    len_b history rows only; equivalently the mask is applied inside the
+    softmax (masked positions take part in neither the maximum nor the sum).
+    For phi = SiLU this coincides with Eq. 1's Hadamard mask.
+  * an empty history (len_b = 0) gives all-zero link states.
+  * XORA: phi(s) = SiLU(s) / (size of the opposite partition) (Appendix I,
+    Algorithm 1 and the masking line of Algorithm 2); the mask is the
+    exclusive-or of "query is source" and "key is source" (Algorithm 1), which
+    is also what Eq. 7 and Appendix H.1 state.
+
+Pinned by tests/test_oracle_*.py (closed forms, brute force, a library routine,
+invariants, hand-derived fixtures).  The only unpinned statement is the
+paper's claim that LIME approximates full target attention (Appendix D): that
+needs trained links and is not tested ("parity unpinned").
+"""
+
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = [
+    "project",
+    "silu",
+    "phi_softmax",
+    "phi_silu",
+    "mha",
+    "xor_mask_and_denominator",
+    "lime_link_history",
+    "lime_xor_history",
+    "xora_quadratic",
+    "lime_score_candidates",
+    "mha_target_attention",
+]
+
+
+def _f64(x):
+    return None if x is None else np.asarray(x, dtype=np.float64)
+
+
+def project(X, W):
+    """X~ = X W (Eq. 1).  ``W is None`` stands for the identity."""
+    X = _f64(X)
+    if W is None:
+        return X
+    return X @ _f64(W)
+
+
+def silu(x):
+    """SiLU(x) = x * sigmoid(x) = x / (1 + exp(-x))."""
+    x = _f64(x)
+    return x / (1.0 + np.exp(-x))
+
+
+def phi_softmax(S, M):
+    """Row-wise softmax of S over the positions where M is true.
+
+    Masked positions get weight 0 and take part in neither the maximum nor the
+    sum, so every row with at least one valid position sums to 1.  A row with
+    no valid position gets all-zero weights (reading for an empty history).
+    """
+    S = _f64(S)
+    M = np.asarray(M, dtype=bool)
+    with np.errstate(invalid="ignore", over="ignore"):
+        row_max = np.where(M, S, -np.inf).max(axis=1, keepdims=True, initial=-np.inf)
+        row_max = np.where(np.isfinite(row_max), row_max, 0.0)
+        e = np.where(M, np.exp(S - row_max), 0.0)
+    row_sum = e.sum(axis=1, keepdims=True)
+    return e / np.where(row_sum > 0.0, row_sum, 1.0)
+
+
+def phi_silu(S, M, denom):
+    """S[i,j] <- M[i,j] ? SiLU(S[i,j]) / denom[i] : 0 (Algorithm 2's masking step).
+
+    ``denom`` holds one normaliser per query row (Algorithm 1's d).
+    """
+    S = _f64(S)
+    M = np.asarray(M, dtype=bool)
+    denom = _f64(denom).reshape(-1, 1)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        A = silu(S) / denom
+    return np.where(M, A, 0.0)
+
+
+def mha(Q, K, V, M, Wq, Wk, Wv, h, scale, phi="softmax", denom=None, return_weights=False):
+    """MHA(Q, K, V; M; theta) of Eq. 1, with h heads.
+
+    Q [q, d]; K, V [n, d]; M boolean [q, n] (None = the all-ones mask J).
+    phi = "softmax": weights = softmax over the unmasked keys of scale * Q~ K~^T.
+    phi = "silu":    weights = M ? SiLU(scale * Q~ K~^T) / denom[row] : 0.
+    Returns [q, d] (and the per-head weights [h, q, n] on request).
+    """
+    Qt, Kt, Vt = project(Q, Wq), project(K, Wk), project(V, Wv)
+    q, d = Qt.shape
+    n = Kt.shape[0]
+    assert d % h == 0
+    dh = d // h
+    if M is None:
+        M = np.ones((q, n), dtype=bool)
+    out = np.zeros((q, d))
+    weights = np.zeros((h, q, n)) if return_weights else None
+    for a in range(h):
+        cols = slice(a * dh, (a + 1) * dh)
+        S = scale * (Qt[:, cols] @ Kt[:, cols].T)
+        if phi == "softmax":
+            A = phi_softmax(S, M)
+        elif phi == "silu":
+            A = phi_silu(S, M, denom)
+        else:
+            raise ValueError(phi)
+        if return_weights:
+            weights[a] = A
+        out[:, cols] = A @ Vt[:, cols]
+    return (out, weights) if return_weights else out
+
+
+def xor_mask_and_denominator(i, j, n_s, n_t):
+    """Algorithm 1: the XOR mask bit and the normaliser for query i, key j.
+
+    Positions [0, n_s) are source (history), [n_s, n_s + n_t) target (links).
+    A pair attends iff exactly one of the two is a source; the normaliser is
+    the size of the partition the query does NOT belong to.
+    """
+    q_is_source = i < n_s
+    k_is_source = j < n_s
+    attend = q_is_source != k_is_source
+    normaliser = n_t if q_is_source else n_s
+    return bool(attend), int(normaliser)
+
+
+def _lens(lens, B, N):
+    if lens is None:
+        return np.full(B, N, dtype=np.int64)
+    lens = np.asarray(lens, dtype=np.int64)
+    assert lens.shape == (B,) and (lens >= 0).all() and (lens <= N).all()
+    return lens
+
+
+def _links_of_user(LC, b):
+    LC = _f64(LC)
+    return LC if LC.ndim == 2 else LC[b]
+
+
+def lime_link_history(E, lens, LC, Wq, Wk, Wv, h, scale, return_weights=False):
+    """L^P = MHA(L^C, E, E; J; theta) per user (Eq. 3), phi = scaled softmax.
+
+    E [B, N, d]; lens [B] or None; LC [m, d] (shared) or [B, m, d].
+    User b sees only E[b, :lens[b]].  Returns [B, m, d].
+    """
+    E = _f64(E)
+    B, N, d = E.shape
+    lens = _lens(lens, B, N)
+    m = _links_of_user(LC, 0).shape[0]
+    LP = np.zeros((B, m, d))
+    W = []
+    for b in range(B):
+        Eb = E[b, : lens[b]]
+        if lens[b] == 0:
+            W.append(np.zeros((h, m, 0)))
+            continue
+        r = mha(_links_of_user(LC, b), Eb, Eb, None, Wq, Wk, Wv, h, scale, "softmax", return_weights=return_weights)
+        if return_weights:
+            LP[b], w = r
+            W.append(w)
+        else:
+            LP[b] = r
+    return (LP, W) if return_weights else LP
+
+
+def lime_xor_history(E, lens, LC, Wq, Wk, Wv, h, scale=1.0, want_os=True):
+    """One XORA layer in its block form (Eq. 7, Appendix H.1).
+
+    With source = history (n_s = lens[b] rows) and target = links (n_t = m):
+      O[T] = phi(Q[T] K[S]^T) V[S],  phi = SiLU / n_s   -> the link states [B, m, d]
+      O[S] = phi(Q[S] K[T]^T) V[T],  phi = SiLU / n_t   -> [B, N, d], rows >= lens[b] zero
+    All six projections use the one theta of Eq. 6.  ``scale`` multiplies the
+    logits before SiLU (Algorithm 2 uses none, i.e. 1.0).
+    """
+    E = _f64(E)
+    B, N, d = E.shape
+    lens = _lens(lens, B, N)
+    m = _links_of_user(LC, 0).shape[0]
+    OT = np.zeros((B, m, d))
+    OS = np.zeros((B, N, d)) if want_os else None
+    for b in range(B):
+        n_s, n_t = int(lens[b]), m
+        if n_s == 0:
+            continue
+        Eb, Lb = E[b, :n_s], _links_of_user(LC, b)
+        OT[b] = mha(Lb, Eb, Eb, None, Wq, Wk, Wv, h, scale, "silu", denom=np.full(n_t, n_s))
+        if want_os:
+            OS[b, :n_s] = mha(Eb, Lb, Lb, None, Wq, Wk, Wv, h, scale, "silu", denom=np.full(n_s, n_t))
+    return OT, OS
+
+
+def xora_quadratic(Eb, Lb, Wq, Wk, Wv, h, scale=1.0):
+    """XORA(X, X, X; theta) = MHA(X, X, X; M_xor; theta), X = E (+) L^C (Eq. 6).
+
+    The full (n_s + n_t)^2 score matrix is formed and Algorithm 1 is evaluated
+    for every (i, j).  One user; Eb holds that user's n_s valid rows.
+    Returns (O[S] [n_s, d], O[T] [n_t, d]).
+    """
+    Eb, Lb = _f64(Eb), _f64(Lb)
+    n_s, n_t = Eb.shape[0], Lb.shape[0]
+    n = n_s + n_t
+    X = np.concatenate([Eb, Lb], axis=0)
+    M = np.zeros((n, n), dtype=bool)
+    denom = np.zeros(n)
+    for i in range(n):
+        for j in range(n):
+            M[i, j], denom[i] = xor_mask_and_denominator(i, j, n_s, n_t)
+    O = mha(X, X, X, M, Wq, Wk, Wv, h, scale, "silu", denom=denom)
+    return O[:n_s], O[n_s:]
+
+
+def lime_score_candidates(T, L, LP, Wq, Wk, Wv, h, scale, return_weights=False):
+    """O = MHA(T, L, L^P; J; theta) per user (Eq. 4): keys are the raw links L,
+    values the personalised links L^P, phi = scaled softmax over the m links.
+
+    T [B, C, d]; L [m, d]; LP [B, m, d].  Any of Wq, Wk, Wv may be None
+    (identity), which gives the literal phi(T L^t) L^P.  Returns [B, C, d].
+    """
+    T, LP = _f64(T), _f64(LP)
+    B, C, d = T.shape
+    O = np.zeros((B, C, d))
+    W = []
+    for b in range(B):
+        r = mha(T[b], L, LP[b], None, Wq, Wk, Wv, h, scale, "softmax", return_weights=return_weights)
+        if return_weights:
+            O[b], w = r
+            W.append(w)
+        else:
+            O[b] = r
+    return (O, W) if return_weights else O
+
+
+def mha_target_attention(T, E, lens, Wq, Wk, Wv, h, scale):
+    """Full target attention MHA(T, E, E; M; theta) per user (Eq. 1 with the
+    candidates as queries and the history as keys and values; the "MHA
+    skyline" of Section 4.1).  M masks history rows >= lens[b].
+
+    T [B, C, d]; E [B, N, d].  Returns [B, C, d]; a user with an empty history
+    gets zeros.
+    """
+    T, E = _f64(T), _f64(E)
+    B, C, d = T.shape
+    lens = _lens(lens, B, E.shape[1])
+    O = np.zeros((B, C, d))
+    for b in range(B):
+        if lens[b] == 0:
+            continue
+        Eb = E[b, : lens[b]]
+        O[b] = mha(T[b], Eb, Eb, None, Wq, Wk, Wv, h, scale, "softmax")
+    return O

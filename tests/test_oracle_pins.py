@@ -1,0 +1,510 @@
+"""Pins for the CPU oracle: things the paper and the mathematics fix, none of
+which is the oracle's own formula re-typed with the same library calls.
+
+  * hand-worked closed-form cases (tests/golden/*.json),
+  * scalar brute force written from Eq. 1 with math.exp and Python loops,
+  * a library routine (torch's scaled_dot_product_attention, CPU fp64),
+  * closed forms (uniform attention, identity links, constant logits),
+  * invariants (rows sum to one, permutations, zero cross-dependence, masks),
+  * planted mistakes: each mutation of the oracle must break at least one pin.
+"""
+
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import lime_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------- helpers
+
+def _val(x):
+    if isinstance(x, str):
+        return float(eval(x, {"__builtins__": {}}, {"ln": math.log}))
+    return float(x)
+
+
+def _arr(x):
+    if x is None:
+        return None
+    if isinstance(x, list):
+        return np.array([_arr(v) for v in x], dtype=np.float64)
+    return _val(x)
+
+
+def _load(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return json.load(f)
+
+
+def _rand(seed, *shape):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+def _problem(seed, B=2, N=7, C=5, d=8, m=3):
+    r = np.random.default_rng(seed)
+    return dict(E=r.standard_normal((B, N, d)), T=r.standard_normal((B, C, d)), L=r.standard_normal((m, d)),
+                Wq=r.standard_normal((d, d)) / 2, Wk=r.standard_normal((d, d)) / 2, Wv=r.standard_normal((d, d)) / 2)
+
+
+# ----------------------------------------------------------------------------- hand-worked cases
+
+def check_golden_eq3():
+    g = _load("eq3_link_history.json")
+    LP = orc.lime_link_history(_arr(g["E"]), None, _arr(g["LC"]), _arr(g["Wq"]), _arr(g["Wk"]), _arr(g["Wv"]),
+                               g["h"], g["scale"])
+    np.testing.assert_allclose(LP, _arr(g["LP"]), rtol=0, atol=1e-14)
+
+
+def check_golden_eq4():
+    g = _load("eq4_decoupled_candidates.json")
+    O = orc.lime_score_candidates(_arr(g["T"]), _arr(g["L"]), _arr(g["LP"]), None, None, None, g["h"], g["scale"])
+    np.testing.assert_allclose(O, _arr(g["O"]), rtol=0, atol=1e-14)
+
+
+def check_golden_xora():
+    g = _load("xora_two_heads.json")
+    OT, OS = orc.lime_xor_history(_arr(g["E"]), None, _arr(g["LC"]), _arr(g["Wq"]), _arr(g["Wk"]), _arr(g["Wv"]),
+                                  g["h"], g["scale"])
+    np.testing.assert_allclose(OT, _arr(g["OT"]), rtol=0, atol=1e-14)
+    np.testing.assert_allclose(OS, _arr(g["OS"]), rtol=0, atol=1e-14)
+    os_q, ot_q = orc.xora_quadratic(_arr(g["E"])[0], _arr(g["LC"]), _arr(g["Wq"]), _arr(g["Wk"]), _arr(g["Wv"]),
+                                    g["h"], g["scale"])
+    np.testing.assert_allclose(ot_q, _arr(g["OT"])[0], rtol=0, atol=1e-14)
+    np.testing.assert_allclose(os_q, _arr(g["OS"])[0], rtol=0, atol=1e-14)
+
+
+def check_golden_eq1_masked():
+    g = _load("eq1_target_attention_masked.json")
+    O = orc.mha_target_attention(_arr(g["T"]), _arr(g["E"]), g["lens"], _arr(g["Wq"]), _arr(g["Wk"]), _arr(g["Wv"]),
+                                 g["h"], g["scale"])
+    np.testing.assert_allclose(O, _arr(g["O"]), rtol=0, atol=1e-14)
+
+
+# ----------------------------------------------------------------------------- scalar brute force (Eq. 1)
+
+def _brute_attention(Q, K, V, Wq, Wk, Wv, h, scale, phi, denom=1.0):
+    """Eq. 1 for one user with scalar loops: no matmul, no vectorised exp."""
+    q, d = len(Q), len(Q[0])
+    n = len(K)
+    dh = d // h
+
+    def proj(X, W):
+        return [[sum(X[r][k] * W[k][c] for k in range(d)) for c in range(d)] for r in range(len(X))]
+
+    Qt, Kt, Vt = proj(Q, Wq), proj(K, Wk), proj(V, Wv)
+    out = [[0.0] * d for _ in range(q)]
+    for a in range(h):
+        for i in range(q):
+            s = [scale * sum(Qt[i][a * dh + t] * Kt[j][a * dh + t] for t in range(dh)) for j in range(n)]
+            if phi == "softmax":
+                mx = max(s)
+                e = [math.exp(x - mx) for x in s]
+                z = sum(e)
+                w = [x / z for x in e]
+            else:
+                w = [x / (1.0 + math.exp(-x)) / denom for x in s]
+            for t in range(dh):
+                out[i][a * dh + t] = sum(w[j] * Vt[j][a * dh + t] for j in range(n))
+    return np.array(out)
+
+
+def check_brute_force_all_paths():
+    p = _problem(11, B=2, N=7, C=5, d=8, m=3)
+    lens = [7, 4]
+    h, scale = 2, 0.37
+    W = (p["Wq"].tolist(), p["Wk"].tolist(), p["Wv"].tolist())
+    mha = orc.mha_target_attention(p["T"], p["E"], lens, p["Wq"], p["Wk"], p["Wv"], h, scale)
+    LP = orc.lime_link_history(p["E"], lens, p["L"], p["Wq"], p["Wk"], p["Wv"], h, scale)
+    O = orc.lime_score_candidates(p["T"], p["L"], LP, p["Wq"], p["Wk"], p["Wv"], h, scale)
+    OT, OS = orc.lime_xor_history(p["E"], lens, p["L"], p["Wq"], p["Wk"], p["Wv"], h, 0.8)
+    for b in range(2):
+        Eb = p["E"][b, : lens[b]].tolist()
+        Tb, Lb = p["T"][b].tolist(), p["L"].tolist()
+        np.testing.assert_allclose(mha[b], _brute_attention(Tb, Eb, Eb, *W, h, scale, "softmax"), atol=1e-12)
+        np.testing.assert_allclose(LP[b], _brute_attention(Lb, Eb, Eb, *W, h, scale, "softmax"), atol=1e-12)
+        np.testing.assert_allclose(O[b], _brute_attention(Tb, Lb, LP[b].tolist(), *W, h, scale, "softmax"), atol=1e-12)
+        np.testing.assert_allclose(OT[b], _brute_attention(Lb, Eb, Eb, *W, h, 0.8, "silu", denom=lens[b]), atol=1e-12)
+        np.testing.assert_allclose(OS[b, : lens[b]], _brute_attention(Eb, Lb, Lb, *W, h, 0.8, "silu", denom=3),
+                                   atol=1e-12)
+        assert not OS[b, lens[b]:].any()
+
+
+# ----------------------------------------------------------------------------- library routine
+
+def check_against_torch_sdpa():
+    import torch
+    import torch.nn.functional as F
+
+    p = _problem(5, B=2, N=33, C=9, d=16, m=6)
+    h, scale = 4, 0.41
+    t = {k: torch.tensor(v, dtype=torch.float64) for k, v in p.items()}
+
+    def heads(x):  # [r, d] -> [h, r, d/h]
+        return x.reshape(x.shape[0], h, -1).transpose(0, 1)
+
+    def sdpa(Q, K, V):
+        o = F.scaled_dot_product_attention(heads(Q @ t["Wq"]), heads(K @ t["Wk"]), heads(V @ t["Wv"]), scale=scale)
+        return o.transpose(0, 1).reshape(Q.shape[0], -1).numpy()
+
+    lens = [33, 20]
+    LP = orc.lime_link_history(p["E"], lens, p["L"], p["Wq"], p["Wk"], p["Wv"], h, scale)
+    O = orc.lime_score_candidates(p["T"], p["L"], LP, p["Wq"], p["Wk"], p["Wv"], h, scale)
+    A = orc.mha_target_attention(p["T"], p["E"], lens, p["Wq"], p["Wk"], p["Wv"], h, scale)
+    for b in range(2):
+        Eb = t["E"][b, : lens[b]]
+        np.testing.assert_allclose(LP[b], sdpa(t["L"], Eb, Eb), atol=1e-12)
+        np.testing.assert_allclose(O[b], sdpa(t["T"][b], t["L"], torch.tensor(LP[b])), atol=1e-12)
+        np.testing.assert_allclose(A[b], sdpa(t["T"][b], Eb, Eb), atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- closed forms
+
+def check_rows_sum_to_one():
+    p = _problem(3, B=3, N=12, C=6, d=8, m=4)
+    lens = [12, 5, 1]
+    _, W = orc.lime_link_history(p["E"], lens, p["L"], p["Wq"], p["Wk"], p["Wv"], 2, 1.3, return_weights=True)
+    for b, w in enumerate(W):
+        assert w.shape == (2, 4, lens[b])
+        np.testing.assert_allclose(w.sum(axis=-1), 1.0, atol=1e-14)
+        assert (w >= 0).all()
+    LP = _rand(4, 3, 4, 8)
+    _, W = orc.lime_score_candidates(p["T"], p["L"], LP, p["Wq"], p["Wk"], p["Wv"], 2, 1.3, return_weights=True)
+    for w in W:
+        np.testing.assert_allclose(w.sum(axis=-1), 1.0, atol=1e-14)
+    # masked form of the primitive: masked keys get weight exactly zero, the rest sums to one
+    M = np.zeros((4, 12), dtype=bool)
+    M[:, :5] = True
+    _, w = orc.mha(p["L"], p["E"][0], p["E"][0], M, p["Wq"], p["Wk"], p["Wv"], 2, 1.3, return_weights=True)
+    assert not w[:, :, 5:].any()
+    np.testing.assert_allclose(w.sum(axis=-1), 1.0, atol=1e-14)
+
+
+def check_uniform_attention_closed_form():
+    # W_Q = 0 makes every logit 0: softmax is uniform, so the output is the mean of the projected values.
+    p = _problem(7, B=2, N=9, C=4, d=8, m=3)
+    lens = [9, 6]
+    Z = np.zeros((8, 8))
+    LP = orc.lime_link_history(p["E"], lens, p["L"], Z, p["Wk"], p["Wv"], 2, 1.0)
+    for b in range(2):
+        mean_v = (p["E"][b, : lens[b]] @ p["Wv"]).mean(axis=0)
+        np.testing.assert_allclose(LP[b], np.tile(mean_v, (3, 1)), atol=1e-13)
+    LPin = _rand(8, 2, 3, 8)
+    O = orc.lime_score_candidates(p["T"], p["L"], LPin, Z, p["Wk"], p["Wv"], 2, 1.0)
+    for b in range(2):
+        np.testing.assert_allclose(O[b], np.tile((LPin[b] @ p["Wv"]).mean(axis=0), (4, 1)), atol=1e-13)
+    A = orc.mha_target_attention(p["T"], p["E"], lens, Z, p["Wk"], p["Wv"], 2, 1.0)
+    for b in range(2):
+        np.testing.assert_allclose(A[b], np.tile((p["E"][b, : lens[b]] @ p["Wv"]).mean(axis=0), (4, 1)), atol=1e-13)
+
+
+def check_identity_links_reduce_to_values():
+    # h = 1, d = N = m, E = L^C = c I, W_Q = W_K = I, scale c^2 >= 50: link i attends to item i only,
+    # so L^P = E W_V; scoring candidates against those links (keys L = E, values L^P) is then the same
+    # as full target attention over the history.
+    n, c = 6, 8.0
+    I = np.eye(n)
+    E = (c * I)[None]
+    Wv = _rand(9, n, n)
+    LP = orc.lime_link_history(E, None, c * I, I, I, Wv, 1, 1.0)
+    np.testing.assert_allclose(LP[0], c * Wv, atol=1e-12)
+    T = _rand(10, 1, 5, n)
+    Wq, Wk = _rand(12, n, n), _rand(13, n, n)
+    # decoupled attention with keys = raw links (= E) and values = L^P, value projection already applied
+    O = orc.lime_score_candidates(T, E[0], LP, Wq, Wk, None, 1, 0.3)
+    A = orc.mha_target_attention(T, E, None, Wq, Wk, Wv, 1, 0.3)
+    np.testing.assert_allclose(O, A, atol=1e-11)
+
+
+def check_m_equals_n_reduces_to_target_attention():
+    # Eq. 4 with L := E_b and L^P := E_b is Eq. 1 with K = V = E_b.
+    p = _problem(21, B=1, N=10, C=7, d=8, m=10)
+    O = orc.lime_score_candidates(p["T"], p["E"][0], p["E"], p["Wq"], p["Wk"], p["Wv"], 2, 0.6)
+    A = orc.mha_target_attention(p["T"], p["E"], None, p["Wq"], p["Wk"], p["Wv"], 2, 0.6)
+    np.testing.assert_allclose(O, A, atol=1e-13)
+
+
+def check_permutations():
+    p = _problem(31, B=1, N=11, C=8, d=8, m=4)
+    h, s = 2, 0.9
+    LP = orc.lime_link_history(p["E"], None, p["L"], p["Wq"], p["Wk"], p["Wv"], h, s)
+    perm = np.random.default_rng(1).permutation(8)
+    O = orc.lime_score_candidates(p["T"], p["L"], LP, p["Wq"], p["Wk"], p["Wv"], h, s)
+    Op = orc.lime_score_candidates(p["T"][:, perm], p["L"], LP, p["Wq"], p["Wk"], p["Wv"], h, s)
+    # per-row results must not depend on which other candidates are present
+    np.testing.assert_allclose(Op, O[:, perm], rtol=0, atol=1e-15)
+    one = orc.lime_score_candidates(p["T"][:, 3:4], p["L"], LP, p["Wq"], p["Wk"], p["Wv"], h, s)
+    np.testing.assert_allclose(one[0, 0], O[0, 3], rtol=0, atol=1e-15)
+    # no positional term anywhere: permuting the history leaves the link states unchanged
+    hperm = np.random.default_rng(2).permutation(11)
+    LPp = orc.lime_link_history(p["E"][:, hperm], None, p["L"], p["Wq"], p["Wk"], p["Wv"], h, s)
+    np.testing.assert_allclose(LPp, LP, atol=1e-13)
+    OT, _ = orc.lime_xor_history(p["E"], None, p["L"], p["Wq"], p["Wk"], p["Wv"], h)
+    OTp, OSp = orc.lime_xor_history(p["E"][:, hperm], None, p["L"], p["Wq"], p["Wk"], p["Wv"], h)
+    np.testing.assert_allclose(OTp, OT, atol=1e-13)
+    _, OS = orc.lime_xor_history(p["E"], None, p["L"], p["Wq"], p["Wk"], p["Wv"], h)
+    np.testing.assert_allclose(OSp, OS[:, hperm], atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- XORA
+
+def check_xor_truth_table():
+    # Algorithm 1 for every (i, j): attend iff exactly one index is a source; normaliser = other side's size.
+    for n_s, n_t in [(1, 1), (3, 2), (2, 5), (4, 4)]:
+        n = n_s + n_t
+        for i in range(n):
+            for j in range(n):
+                m, d = orc.xor_mask_and_denominator(i, j, n_s, n_t)
+                src_q, src_k = i < n_s, j < n_s
+                assert m == ((src_q and not src_k) or (src_k and not src_q))
+                assert d == (n_t if src_q else n_s)
+        M = np.array([[orc.xor_mask_and_denominator(i, j, n_s, n_t)[0] for j in range(n)] for i in range(n)])
+        # block structure of Eq. 7: zero diagonal blocks, all-ones off-diagonal blocks, symmetric
+        assert not M[:n_s, :n_s].any() and not M[n_s:, n_s:].any()
+        assert M[:n_s, n_s:].all() and M[n_s:, :n_s].all()
+        assert (M == M.T).all() and M.sum() == 2 * n_s * n_t
+
+
+def check_xor_block_equals_quadratic():
+    p = _problem(41, B=2, N=9, C=1, d=8, m=5)
+    lens = [9, 3]
+    for h in (1, 2, 4):
+        OT, OS = orc.lime_xor_history(p["E"], lens, p["L"], p["Wq"], p["Wk"], p["Wv"], h, 0.7)
+        for b in range(2):
+            os_q, ot_q = orc.xora_quadratic(p["E"][b, : lens[b]], p["L"], p["Wq"], p["Wk"], p["Wv"], h, 0.7)
+            np.testing.assert_allclose(OT[b], ot_q, atol=1e-13)
+            np.testing.assert_allclose(OS[b, : lens[b]], os_q, atol=1e-13)
+
+
+def check_xor_closed_forms():
+    p = _problem(43, B=1, N=6, C=1, d=4, m=3)
+    Z = np.zeros((4, 4))
+    # all logits zero: SiLU(0) = 0, both outputs vanish
+    OT, OS = orc.lime_xor_history(p["E"], None, p["L"], Z, p["Wk"], p["Wv"], 2)
+    assert not OT.any() and not OS.any()
+    # constant logit s: h = 1, every projected query and key equals u with <u, u> = s
+    d, s = 4, 1.7
+    u = np.full(d, math.sqrt(s / d))
+    E = np.tile(u, (1, 6, 1))
+    L = np.tile(u, (3, 1))
+    I = np.eye(d)
+    Wv = _rand(44, d, d)
+    OT, OS = orc.lime_xor_history(E, None, L, I, I, Wv, 1)
+    silu_s = s / (1.0 + math.exp(-s))
+    np.testing.assert_allclose(OT[0], np.tile(silu_s * (u @ Wv), (3, 1)), atol=1e-13)  # SiLU(s) * mean(V[S])
+    np.testing.assert_allclose(OS[0], np.tile(silu_s * (u @ Wv), (6, 1)), atol=1e-13)  # SiLU(s) * mean(V[T])
+    # SiLU is not normalised: doubling the history with copies leaves O[T] unchanged (mean, not sum)
+    E2 = np.concatenate([p["E"], p["E"]], axis=1)
+    a, _ = orc.lime_xor_history(p["E"], None, p["L"], p["Wq"], p["Wk"], p["Wv"], 2)
+    b, _ = orc.lime_xor_history(E2, None, p["L"], p["Wq"], p["Wk"], p["Wv"], 2)
+    np.testing.assert_allclose(a, b, atol=1e-13)
+
+
+def check_xor_zero_cross_dependence():
+    # Appendix H.2: O[T] does not depend on Q[S], K[T], V[T]; O[S] not on Q[T], K[S], V[S].
+    p = _problem(47, B=1, N=6, C=1, d=4, m=3)
+    Eb, Lb = p["E"][0], p["L"]
+    os0, ot0 = orc.xora_quadratic(Eb, Lb, p["Wq"], p["Wk"], p["Wv"], 2)
+
+    def quad_with(Qx, Kx, Vx):
+        # the quadratic form with separately perturbed query / key / value inputs, projections folded in
+        n_s, n_t = 6, 3
+        n = n_s + n_t
+        M = np.array([[orc.xor_mask_and_denominator(i, j, n_s, n_t)[0] for j in range(n)] for i in range(n)])
+        den = np.array([orc.xor_mask_and_denominator(i, 0, n_s, n_t)[1] for i in range(n)])
+        O = orc.mha(Qx, Kx, Vx, M, p["Wq"], p["Wk"], p["Wv"], 2, 1.0, "silu", denom=den)
+        return O[:n_s], O[n_s:]
+
+    X = np.concatenate([Eb, Lb])
+    bump_s = X.copy()
+    bump_s[:6] += 1.0  # perturb the source rows only
+    bump_t = X.copy()
+    bump_t[6:] += 1.0  # perturb the target rows only
+    _, ot = quad_with(bump_s, bump_t, bump_t)  # Q[S], K[T], V[T] changed
+    np.testing.assert_array_equal(ot, ot0)
+    os_, _ = quad_with(bump_t, bump_s, bump_s)  # Q[T], K[S], V[S] changed
+    np.testing.assert_array_equal(os_, os0)
+    # and the dependence that must be there is there
+    _, ot = quad_with(X, bump_s, X)
+    assert np.abs(ot - ot0).max() > 1e-3
+
+
+# ----------------------------------------------------------------------------- masks / ragged
+
+def check_ragged_masking():
+    p = _problem(51, B=3, N=10, C=4, d=8, m=3)
+    lens = [10, 4, 0]
+    h, s = 2, 0.5
+    clean = p["E"].copy()
+    for b in range(3):
+        clean[b, lens[b]:] = 0.0
+    outs = []
+    for poison in (0.0, np.nan, np.inf, 1e30):
+        E = clean.copy()
+        for b in range(3):
+            E[b, lens[b]:] = poison
+        LP = orc.lime_link_history(E, lens, p["L"], p["Wq"], p["Wk"], p["Wv"], h, s)
+        OT, OS = orc.lime_xor_history(E, lens, p["L"], p["Wq"], p["Wk"], p["Wv"], h)
+        A = orc.mha_target_attention(p["T"], E, lens, p["Wq"], p["Wk"], p["Wv"], h, s)
+        outs.append((LP, OT, OS, A))
+    for o in outs[1:]:
+        for x, y in zip(o, outs[0]):
+            np.testing.assert_array_equal(x, y)  # bit-identical whatever the padding holds
+    LP, OT, OS, A = outs[0]
+    assert np.isfinite(LP).all() and np.isfinite(OT).all() and np.isfinite(OS).all() and np.isfinite(A).all()
+    # empty history: zeros, no NaN
+    assert not LP[2].any() and not OT[2].any() and not OS[2].any() and not A[2].any()
+    # padded O[S] rows are exact zeros
+    assert not OS[1, 4:].any()
+    # equals the result on truncated tensors
+    LPt = orc.lime_link_history(clean[1:2, :4], None, p["L"], p["Wq"], p["Wk"], p["Wv"], h, s)
+    np.testing.assert_array_equal(LPt[0], LP[1])
+    # equals Eq. 1 with an explicit key mask inside the softmax on the zero-padded tensor
+    M = np.zeros((3, 10), dtype=bool)
+    M[:, :4] = True
+    viaM = orc.mha(p["L"], clean[1], clean[1], M, p["Wq"], p["Wk"], p["Wv"], h, s)
+    np.testing.assert_allclose(viaM, LP[1], atol=1e-14)
+    # per-user links
+    LCu = _rand(52, 3, 3, 8)
+    LPu = orc.lime_link_history(clean, lens, LCu, p["Wq"], p["Wk"], p["Wv"], h, s)
+    for b in range(2):
+        one = orc.lime_link_history(clean[b:b + 1], lens[b:b + 1], LCu[b], p["Wq"], p["Wk"], p["Wv"], h, s)
+        np.testing.assert_array_equal(one[0], LPu[b])
+
+
+def check_softmax_is_shift_invariant_and_stable():
+    # logits of a few hundred must not overflow; adding a constant to every logit changes nothing
+    S = np.array([[700.0, 699.0, -800.0], [1e4, 1e4, 1e4]])
+    A = orc.phi_softmax(S, np.ones_like(S, dtype=bool))
+    e = math.exp(-1.0)
+    np.testing.assert_allclose(A[0], [1 / (1 + e), e / (1 + e), 0.0], atol=1e-15)
+    np.testing.assert_allclose(A[1], [1 / 3] * 3, atol=1e-15)
+
+
+PINS = [
+    check_golden_eq3,
+    check_golden_eq4,
+    check_golden_xora,
+    check_golden_eq1_masked,
+    check_brute_force_all_paths,
+    check_against_torch_sdpa,
+    check_rows_sum_to_one,
+    check_uniform_attention_closed_form,
+    check_identity_links_reduce_to_values,
+    check_m_equals_n_reduces_to_target_attention,
+    check_permutations,
+    check_xor_truth_table,
+    check_xor_block_equals_quadratic,
+    check_xor_closed_forms,
+    check_xor_zero_cross_dependence,
+    check_ragged_masking,
+    check_softmax_is_shift_invariant_and_stable,
+]
+
+
+@pytest.mark.parametrize("pin", PINS, ids=lambda f: f.__name__)
+def test_pin(pin):
+    pin()
+
+
+# ----------------------------------------------------------------------------- planted mistakes
+
+def _pins_that_fail():
+    failed = []
+    for pin in PINS:
+        try:
+            with np.errstate(all="ignore"):
+                pin()
+        except Exception:  # noqa: BLE001 - any failure counts as "caught"
+            failed.append(pin.__name__)
+    return failed
+
+
+def _mut_project_transposed(X, W):
+    X = np.asarray(X, dtype=np.float64)
+    return X if W is None else X @ np.asarray(W, dtype=np.float64).T
+
+
+def _mut_silu_wrong_sign(x):
+    x = np.asarray(x, dtype=np.float64)
+    return x / (1.0 + np.exp(x))
+
+
+def _mut_softmax_ignores_mask(S, M):
+    S = np.asarray(S, dtype=np.float64)
+    e = np.exp(S - S.max(axis=1, keepdims=True))
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def _mut_softmax_mask_after(S, M):
+    # Eq. 1 read literally for softmax: normalise over all keys, then zero the masked ones
+    S = np.asarray(S, dtype=np.float64)
+    with np.errstate(all="ignore"):
+        S = np.nan_to_num(S, nan=0.0, posinf=0.0, neginf=0.0)
+        e = np.exp(S - S.max(axis=1, keepdims=True))
+    return np.where(M, e / e.sum(axis=1, keepdims=True), 0.0)
+
+
+def _mut_phi_silu_unnormalised(S, M, denom):
+    return np.where(M, _mut_free_silu(S), 0.0)
+
+
+def _mut_free_silu(x):
+    x = np.asarray(x, dtype=np.float64)
+    return x / (1.0 + np.exp(-x))
+
+
+def _mut_xor_mask_and(i, j, n_s, n_t):
+    # the formula printed beside Eq. 7 (a conjunction): both indices are sources
+    return bool(i < n_s and j < n_s), int(n_t if i < n_s else n_s)
+
+
+def _mut_xor_same_side_denominator(i, j, n_s, n_t):
+    return bool((i < n_s) != (j < n_s)), int(n_s if i < n_s else n_t)
+
+
+def _make_mha_mutant(kind):
+    real = orc.mha
+
+    def mutant(Q, K, V, M, Wq, Wk, Wv, h, scale, phi="softmax", denom=None, return_weights=False):
+        if kind == "no_heads":
+            return real(Q, K, V, M, Wq, Wk, Wv, 1, scale, phi, denom, return_weights)
+        if kind == "no_scale":
+            return real(Q, K, V, M, Wq, Wk, Wv, h, 1.0, phi, denom, return_weights)
+        if kind == "keys_from_values":
+            return real(Q, V, V, M, Wq, Wk, Wv, h, scale, phi, denom, return_weights)
+        if kind == "swap_wk_wv":
+            return real(Q, K, V, M, Wq, Wv, Wk, h, scale, phi, denom, return_weights)
+        raise AssertionError(kind)
+
+    return mutant
+
+
+MUTATIONS = [
+    ("project", _mut_project_transposed),
+    ("silu", _mut_silu_wrong_sign),
+    ("phi_softmax", _mut_softmax_ignores_mask),
+    ("phi_softmax", _mut_softmax_mask_after),
+    ("phi_silu", _mut_phi_silu_unnormalised),
+    ("xor_mask_and_denominator", _mut_xor_mask_and),
+    ("xor_mask_and_denominator", _mut_xor_same_side_denominator),
+    ("mha", "no_heads"),
+    ("mha", "no_scale"),
+    ("mha", "keys_from_values"),
+    ("mha", "swap_wk_wv"),
+]
+
+
+@pytest.mark.parametrize("name,mutant", MUTATIONS, ids=[f"{n}:{getattr(m, '__name__', m)}" for n, m in MUTATIONS])
+def test_planted_mistake_is_caught(monkeypatch, name, mutant):
+    """A plausible mistake planted in the oracle (on the CPU) must fail at least one pin."""
+    assert _pins_that_fail() == []
+    if isinstance(mutant, str):
+        mutant = _make_mha_mutant(mutant)
+    monkeypatch.setattr(orc, name, mutant)
+    assert _pins_that_fail(), f"mutation {name} survived every pin"
