@@ -1,0 +1,122 @@
+/*
+ * lime.h - C ABI of the MI355X (gfx950) LIME inference hot path, arXiv 2510.18239.
+ *
+ * Conventions common to every entry point
+ * ---------------------------------------
+ * Pointers.  Every tensor pointer is a DEVICE pointer owned by the caller.  The
+ *   library never allocates, frees, copies to the host or synchronises.  `lens`
+ *   is a device pointer too.  Outputs must not alias inputs.
+ * Layout.  Row-major, innermost dimension contiguous, no padding between rows:
+ *   E[B][N][d], T[B][C][d], L[m][d], LP[B][m][d], W[d_in][d_out] (so that the
+ *   projection of Eq. 1 is X~ = X W).
+ * dtype.  LIME_F32 (0) or LIME_BF16 (1); it applies to every tensor argument
+ *   and every output of the call.  Products are accumulated in fp32; bf16
+ *   outputs are rounded to nearest-even from the fp32 accumulators.
+ * Heads.  The d projected columns are cut into h contiguous blocks of d/h; heads
+ *   are independent and their outputs concatenated; there is no output
+ *   projection (theta = {W_Q, W_K, W_V} only, Eq. 1).
+ * scale.  Multiplies every logit before phi ("scaled softmax", Eq. 1).  Callers
+ *   normally pass (d/h)^-1/2 for the softmax paths and 1 for XORA (Algorithm 2
+ *   applies SiLU to the raw product).
+ * Ragged histories.  lens[b] in [0, N] is the number of valid history rows of
+ *   user b (NULL = all N).  Rows at or beyond lens[b] are never read into any
+ *   result: they may hold anything, NaN included.  The result for user b equals
+ *   the result on E[b] truncated to lens[b] rows; a user with lens[b] = 0 gets
+ *   all-zero outputs.  lens[b] outside [0, N] is a contract violation that is
+ *   not checked on the device.
+ * workspace.  Scratch device memory of at least lime_workspace_bytes(...) bytes,
+ *   256-byte aligned, private to the call until the stream has passed it.
+ * stream.  A hipStream_t passed as void* (NULL = the default stream).  All work
+ *   is enqueued on it, in order.
+ * Status.  0 LIME_OK; 1 LIME_INVALID_ARG (a required pointer is NULL, a
+ *   dimension is <= 0, d % h != 0, unknown dtype); 2 LIME_UNSUPPORTED (shape
+ *   outside the limits below); 3 LIME_WORKSPACE_TOO_SMALL; 4 LIME_LAUNCH_FAILED
+ *   (a HIP error; text in lime_last_error()).  Arguments are checked on the host
+ *   before anything is launched, so on any non-zero status nothing was enqueued
+ *   (except LIME_LAUNCH_FAILED, where earlier launches of the call may have been).
+ * Limits.  d/h <= 256.  The bf16 matrix-core (MFMA) kernels serve d/h in {32, 64}
+ *   with h in {1, 2, 4, 8}, d <= 256 and m a multiple of 32 up to 128; every other
+ *   shape, and all of fp32, runs on the general fp32-arithmetic kernels.
+ */
+#ifndef LIME_H_
+#define LIME_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { LIME_OK = 0, LIME_INVALID_ARG = 1, LIME_UNSUPPORTED = 2, LIME_WORKSPACE_TOO_SMALL = 3, LIME_LAUNCH_FAILED = 4 };
+enum { LIME_F32 = 0, LIME_BF16 = 1 };
+enum { LIME_OP_LINK_HISTORY = 0, LIME_OP_XOR_HISTORY = 1, LIME_OP_SCORE_CANDIDATES = 2, LIME_OP_MHA_TARGET = 3 };
+
+/*
+ * User-side link personalisation, Section 3.1 Eq. 3:
+ *   LP[b] = MHA(LC_b, E[b], E[b]; J; theta),  phi = softmax over the valid history rows.
+ * LC: contextualised links L^C (the output of Eq. 2, taken as given).  User b's links
+ *   start at LC + b * lc_user_stride elements: 0 = one [m][d] set shared by all users,
+ *   m*d = a [B][m][d] tensor.
+ * Out: LP[B][m][d].
+ */
+int32_t lime_link_history(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride,
+                          const void* Wq, const void* Wk, const void* Wv, void* LP,
+                          int32_t B, int32_t N, int32_t d, int32_t h, int32_t m,
+                          float scale, int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * One XOR-attention layer, Section 3.2 Eq. 6-7, Appendix H.1, Appendix I Algorithms 1-2.
+ * Source = the user's lens[b] valid history rows, target = the m links, one theta for both:
+ *   LP[b] = O[T] = (1/n_s) SiLU(scale * Q[T] K[S]^T) V[S],   n_s = lens[b]
+ *   OS[b] = O[S] = (1/n_t) SiLU(scale * Q[S] K[T]^T) V[T],   n_t = m
+ * with Q[S], K[S], V[S] = E[b] Wq, Wk, Wv and Q[T], K[T], V[T] = LC_b Wq, Wk, Wv, per head.
+ * Out: LP[B][m][d]; OS[B][N][d] when OS != NULL (rows >= lens[b] are written as zeros).
+ */
+int32_t lime_xor_history(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride,
+                         const void* Wq, const void* Wk, const void* Wv, void* LP, void* OS,
+                         int32_t B, int32_t N, int32_t d, int32_t h, int32_t m,
+                         float scale, int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * Candidate-side decoupled attention, Section 3.1 Eq. 4 and Section 3.3:
+ *   O[b] = MHA(T[b], L, LP[b]; J; theta),  phi = softmax over the m links;
+ * the keys are the raw, user-independent links L[m][d], the values the personalised
+ * links LP[B][m][d].  Each of Wq, Wk, Wv may be NULL (= identity), which yields the
+ * literal right-hand side phi(T L^t) L^P.
+ * Out: O[B][C][d].
+ */
+int32_t lime_score_candidates(const void* T, const void* L, const void* LP,
+                              const void* Wq, const void* Wk, const void* Wv, void* O,
+                              int32_t B, int32_t C, int32_t d, int32_t h, int32_t m,
+                              float scale, int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * Baseline: full target attention (the "MHA skyline", Section 4.1), Eq. 1 with the
+ * candidates as queries and the history as keys and values:
+ *   O[b] = MHA(T[b], E[b], E[b]; M; theta),  M = valid history rows, phi = softmax.
+ * Out: O[B][C][d].
+ */
+int32_t mha_target_attention(const void* T, const void* E, const int32_t* lens,
+                             const void* Wq, const void* Wk, const void* Wv, void* O,
+                             int32_t B, int32_t C, int32_t N, int32_t d, int32_t h,
+                             float scale, int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * Workspace size in bytes for `op` (LIME_OP_*) at the given shape; dimensions an op
+ * does not have are ignored.  `flags` bit 0: lime_xor_history will be asked for OS.
+ * Returns 0 for shapes the op would reject.
+ */
+size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t d, int32_t h, int32_t m,
+                            int32_t dtype, int32_t flags);
+
+/* Text of the calling thread's most recent non-zero status ("" if none).  Host memory, owned by the library. */
+const char* lime_last_error(void);
+
+/* "major.minor.patch" of the library.  Host memory, owned by the library. */
+const char* lime_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIME_H_ */

@@ -1,0 +1,207 @@
+"""ctypes binding of liblime_hip.so: argument marshalling only.
+
+Every function here has the name and the meaning of the C entry point it calls
+(see include/lime.h); tensors are torch CUDA tensors whose device pointers are
+handed through, work goes onto torch's current stream.  There is no fallback:
+if the library has not been built, or a call returns a non-zero status, an
+exception is raised.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblime_hip.so")
+
+LIME_F32, LIME_BF16 = 0, 1
+OP_LINK_HISTORY, OP_XOR_HISTORY, OP_SCORE_CANDIDATES, OP_MHA_TARGET = 0, 1, 2, 3
+STATUS_NAMES = {0: "LIME_OK", 1: "LIME_INVALID_ARG", 2: "LIME_UNSUPPORTED", 3: "LIME_WORKSPACE_TOO_SMALL",
+                4: "LIME_LAUNCH_FAILED"}
+
+_c = ctypes
+_vp, _i32, _i64, _f32, _sz = _c.c_void_p, _c.c_int32, _c.c_int64, _c.c_float, _c.c_size_t
+
+SIGNATURES = {
+    "lime_link_history": (_i32, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32, _i32,
+                                 _vp, _sz, _vp]),
+    "lime_xor_history": (_i32, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32,
+                                _i32, _vp, _sz, _vp]),
+    "lime_score_candidates": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32, _i32,
+                                     _vp, _sz, _vp]),
+    "mha_target_attention": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32, _i32,
+                                    _vp, _sz, _vp]),
+    "lime_workspace_bytes": (_sz, [_i32] * 9),
+    "lime_last_error": (_c.c_char_p, []),
+    "lime_version": (_c.c_char_p, []),
+}
+
+_lib = None
+
+
+class LimeError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {text}")
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built (python -c 'import __graft_entry__ as g; g.build()')."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first (python paper_2510_18239_amd/build.py); "
+                               "there is no CPU fallback")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def last_error() -> str:
+    return lib().lime_last_error().decode()
+
+
+def version() -> str:
+    return lib().lime_version().decode()
+
+
+def workspace_bytes(op: int, B=1, N=1, C=1, d=1, h=1, m=1, dtype=LIME_BF16, flags=0) -> int:
+    return int(lib().lime_workspace_bytes(op, B, N, C, d, h, m, dtype, flags))
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return LIME_F32
+    if t.dtype == torch.bfloat16:
+        return LIME_BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _check(*tensors):
+    first = next(t for t in tensors if t is not None)
+    for t in tensors:
+        if t is None:
+            continue
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous CUDA tensors")
+        if t.dtype != first.dtype or t.device != first.device:
+            raise ValueError("tensors must share dtype and device")
+    return first
+
+
+_workspaces: dict = {}
+
+
+def get_workspace(nbytes: int, device) -> torch.Tensor:
+    """A grow-only scratch buffer per device (caller-owned memory as far as the C ABI is concerned)."""
+    key = torch.device(device)
+    ws = _workspaces.get(key)
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=key)
+        _workspaces[key] = ws
+    return ws
+
+
+def _stream(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def _raise(status):
+    if status != 0:
+        raise LimeError(status, last_error())
+
+
+def _lens_arg(lens, B, device):
+    if lens is None:
+        return None
+    if lens.dtype != torch.int32 or not lens.is_cuda or lens.numel() != B or not lens.is_contiguous():
+        raise ValueError("lens must be a contiguous CUDA int32 tensor of B entries")
+    return lens
+
+
+def _history(fn_name, op, E, lens, LC, Wq, Wk, Wv, h, scale, LP, OS, workspace, stream, want_os):
+    first = _check(E, LC, Wq, Wk, Wv, LP, OS)
+    B, N, d = E.shape
+    if LC.dim() == 2:
+        m, stride = LC.shape[0], 0
+    else:
+        if LC.shape[0] != B:
+            raise ValueError("per-user links must be [B, m, d]")
+        m, stride = LC.shape[1], LC.shape[1] * LC.shape[2]
+    lens = _lens_arg(lens, B, E.device)
+    code = _dtype_code(first)
+    if LP is None:
+        LP = torch.empty((B, m, d), dtype=E.dtype, device=E.device)
+    if want_os and OS is None:
+        OS = torch.empty((B, N, d), dtype=E.dtype, device=E.device)
+    need = workspace_bytes(op, B=B, N=N, d=d, h=h, m=m, dtype=code, flags=1 if want_os else 0)
+    ws = workspace if workspace is not None else get_workspace(need, E.device)
+    fn = getattr(lib(), fn_name)
+    with torch.cuda.device(E.device):
+        if op == OP_LINK_HISTORY:
+            st = fn(_ptr(E), _ptr(lens), _ptr(LC), stride, _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(LP), B, N, d, h, m,
+                    float(scale), code, _ptr(ws), ws.numel(), _stream(stream))
+        else:
+            st = fn(_ptr(E), _ptr(lens), _ptr(LC), stride, _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(LP), _ptr(OS), B, N, d,
+                    h, m, float(scale), code, _ptr(ws), ws.numel(), _stream(stream))
+    _raise(st)
+    return LP, OS
+
+
+def lime_link_history(E, lens, LC, Wq, Wk, Wv, h, scale, LP=None, workspace=None, stream=None):
+    """LP[B, m, d] = MHA(LC, E, E) per user, softmax over the valid history rows (Eq. 3)."""
+    return _history("lime_link_history", OP_LINK_HISTORY, E, lens, LC, Wq, Wk, Wv, h, scale, LP, None, workspace,
+                    stream, False)[0]
+
+
+def lime_xor_history(E, lens, LC, Wq, Wk, Wv, h, scale=1.0, want_os=False, LP=None, OS=None, workspace=None,
+                     stream=None):
+    """One XORA layer (Eq. 6-7): returns (O[T] = link states [B, m, d], O[S] [B, N, d] or None)."""
+    return _history("lime_xor_history", OP_XOR_HISTORY, E, lens, LC, Wq, Wk, Wv, h, scale, LP, OS, workspace, stream,
+                    want_os or OS is not None)
+
+
+def lime_score_candidates(T, L, LP, Wq, Wk, Wv, h, scale, O=None, workspace=None, stream=None):
+    """O[B, C, d] = MHA(T, L, LP) per user, softmax over the m links (Eq. 4); W* may be None (identity)."""
+    first = _check(T, L, LP, Wq, Wk, Wv, O)
+    B, C, d = T.shape
+    m = L.shape[0]
+    code = _dtype_code(first)
+    if O is None:
+        O = torch.empty_like(T)
+    need = workspace_bytes(OP_SCORE_CANDIDATES, B=B, C=C, d=d, h=h, m=m, dtype=code)
+    ws = workspace if workspace is not None else get_workspace(need, T.device)
+    with torch.cuda.device(T.device):
+        st = lib().lime_score_candidates(_ptr(T), _ptr(L), _ptr(LP), _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(O), B, C, d,
+                                         h, m, float(scale), code, _ptr(ws), ws.numel(), _stream(stream))
+    _raise(st)
+    return O
+
+
+def mha_target_attention(T, E, lens, Wq, Wk, Wv, h, scale, O=None, workspace=None, stream=None):
+    """O[B, C, d] = MHA(T, E, E) per user over the valid history rows (Eq. 1; the baseline)."""
+    first = _check(T, E, Wq, Wk, Wv, O)
+    B, C, d = T.shape
+    N = E.shape[1]
+    lens = _lens_arg(lens, B, E.device)
+    code = _dtype_code(first)
+    if O is None:
+        O = torch.empty_like(T)
+    need = workspace_bytes(OP_MHA_TARGET, B=B, N=N, C=C, d=d, h=h, dtype=code)
+    ws = workspace if workspace is not None else get_workspace(need, T.device)
+    with torch.cuda.device(T.device):
+        st = lib().mha_target_attention(_ptr(T), _ptr(E), _ptr(lens), _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(O), B, C, N,
+                                        d, h, float(scale), code, _ptr(ws), ws.numel(), _stream(stream))
+    _raise(st)
+    return O

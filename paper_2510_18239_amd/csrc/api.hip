@@ -1,0 +1,230 @@
+// C ABI of the LIME hot path: argument checks, workspace planning, kernel dispatch.
+#include "../../include/lime.h"
+
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "common.hpp"
+
+namespace {
+
+thread_local char g_error[512] = "";
+
+int32_t fail(int32_t status, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_error, sizeof(g_error), fmt, ap);
+  va_end(ap);
+  return status;
+}
+
+#define LIME_HIP(expr)                                                                            \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess) return fail(LIME_LAUNCH_FAILED, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+constexpr int kMaxHeadDim = 256;
+constexpr int kMaxUsers = 65535;
+
+// Carves 256-byte aligned pieces out of the caller's workspace; with base == nullptr it only sizes.
+struct Arena {
+  char* base;
+  size_t used = 0;
+  explicit Arena(void* p) : base(static_cast<char*>(p)) {}
+  template <typename T>
+  T* take(size_t count) {
+    T* p = base ? reinterpret_cast<T*>(base + used) : nullptr;
+    used += lime::align_up(count * sizeof(T));
+    return p;
+  }
+};
+
+int32_t check_common(const char* fn, int32_t B, int32_t d, int32_t h, int32_t dtype) {
+  if (dtype != LIME_F32 && dtype != LIME_BF16) return fail(LIME_INVALID_ARG, "%s: unknown dtype %d", fn, dtype);
+  if (B <= 0 || d <= 0 || h <= 0) return fail(LIME_INVALID_ARG, "%s: B, d, h must be positive (B=%d d=%d h=%d)", fn, B, d, h);
+  if (d % h != 0) return fail(LIME_INVALID_ARG, "%s: d=%d is not a multiple of h=%d", fn, d, h);
+  if (d / h > kMaxHeadDim) return fail(LIME_UNSUPPORTED, "%s: d/h=%d exceeds %d", fn, d / h, kMaxHeadDim);
+  if (B > kMaxUsers) return fail(LIME_UNSUPPORTED, "%s: B=%d exceeds %d", fn, B, kMaxUsers);
+  return LIME_OK;
+}
+
+// ----------------------------------------------------------------------------- history side (Eq. 3, Eq. 7)
+struct HistoryPlan {
+  float *Qt, *Ks, *Vs;        // Q[T] = LC Wq; K[S] = E Wk; V[S] = E Wv
+  float *Qs, *Kt, *Vt;        // only for O[S]: Q[S] = E Wq; K[T] = LC Wk; V[T] = LC Wv
+  size_t bytes;
+};
+
+HistoryPlan plan_history(void* ws, int64_t B, int64_t N, int64_t d, int64_t m, bool per_user_links, bool want_os) {
+  Arena a(ws);
+  HistoryPlan p{};
+  const int64_t link_rows = (per_user_links ? B : 1) * m;
+  p.Qt = a.take<float>(link_rows * d);
+  p.Ks = a.take<float>(B * N * d);
+  p.Vs = a.take<float>(B * N * d);
+  if (want_os) {
+    p.Qs = a.take<float>(B * N * d);
+    p.Kt = a.take<float>(link_rows * d);
+    p.Vt = a.take<float>(link_rows * d);
+  }
+  p.bytes = a.used;
+  return p;
+}
+
+int32_t history_impl(const char* fn, int phi, const void* E, const int32_t* lens, const void* LC,
+                     int64_t lc_user_stride, const void* Wq, const void* Wk, const void* Wv, void* LP, void* OS,
+                     int32_t B, int32_t N, int32_t d, int32_t h, int32_t m, float scale, int32_t dtype,
+                     void* workspace, size_t ws_bytes, void* stream) {
+  if (int32_t st = check_common(fn, B, d, h, dtype)) return st;
+  if (N <= 0 || m <= 0) return fail(LIME_INVALID_ARG, "%s: N and m must be positive (N=%d m=%d)", fn, N, m);
+  if (!E || !LC || !Wq || !Wk || !Wv || !LP) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  if (lc_user_stride != 0 && lc_user_stride != static_cast<int64_t>(m) * d)
+    return fail(LIME_INVALID_ARG, "%s: lc_user_stride must be 0 or m*d (got %lld)", fn, static_cast<long long>(lc_user_stride));
+  const bool per_user = lc_user_stride != 0;
+  const bool want_os = OS != nullptr;
+  HistoryPlan p = plan_history(nullptr, B, N, d, m, per_user, want_os);
+  if (!workspace || ws_bytes < p.bytes)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, p.bytes, workspace ? ws_bytes : 0);
+  p = plan_history(workspace, B, N, d, m, per_user, want_os);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int64_t link_rows = (per_user ? B : 1) * static_cast<int64_t>(m);
+  const int64_t hist_rows = static_cast<int64_t>(B) * N;
+  const int64_t link_stride = per_user ? static_cast<int64_t>(m) * d : 0;
+
+  LIME_HIP(lime::generic_project(LC, Wq, p.Qt, link_rows, d, dtype, s));
+  LIME_HIP(lime::generic_project(E, Wk, p.Ks, hist_rows, d, dtype, s));
+  LIME_HIP(lime::generic_project(E, Wv, p.Vs, hist_rows, d, dtype, s));
+  lime::GenericAttention t{};
+  t.Q = p.Qt, t.K = p.Ks, t.V = p.Vs;
+  t.q_user_stride = link_stride, t.k_user_stride = t.v_user_stride = static_cast<int64_t>(N) * d;
+  t.O = LP, t.q_lens = nullptr, t.k_lens = lens;
+  t.B = B, t.q_rows = m, t.n_keys = N, t.d = d, t.h = h, t.scale = scale, t.phi = phi, t.dtype = dtype;
+  LIME_HIP(lime::generic_attention(t, s));
+  if (want_os) {
+    LIME_HIP(lime::generic_project(E, Wq, p.Qs, hist_rows, d, dtype, s));
+    LIME_HIP(lime::generic_project(LC, Wk, p.Kt, link_rows, d, dtype, s));
+    LIME_HIP(lime::generic_project(LC, Wv, p.Vt, link_rows, d, dtype, s));
+    lime::GenericAttention o{};
+    o.Q = p.Qs, o.K = p.Kt, o.V = p.Vt;
+    o.q_user_stride = static_cast<int64_t>(N) * d, o.k_user_stride = o.v_user_stride = link_stride;
+    o.O = OS, o.q_lens = lens, o.k_lens = nullptr;
+    o.B = B, o.q_rows = N, o.n_keys = m, o.d = d, o.h = h, o.scale = scale, o.phi = lime::kPhiSilu, o.dtype = dtype;
+    LIME_HIP(lime::generic_attention(o, s));
+  }
+  return LIME_OK;
+}
+
+// ----------------------------------------------------------------------------- candidate side (Eq. 4) and baseline (Eq. 1)
+struct QueryPlan {
+  float *Qt, *Kt, *Vt;
+  size_t bytes;
+};
+
+QueryPlan plan_queries(void* ws, int64_t q_rows_total, int64_t k_rows_total, int64_t v_rows_total, int64_t d) {
+  Arena a(ws);
+  QueryPlan p{};
+  p.Qt = a.take<float>(q_rows_total * d);
+  p.Kt = a.take<float>(k_rows_total * d);
+  p.Vt = a.take<float>(v_rows_total * d);
+  p.bytes = a.used;
+  return p;
+}
+
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+int32_t lime_link_history(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride, const void* Wq,
+                          const void* Wk, const void* Wv, void* LP, int32_t B, int32_t N, int32_t d, int32_t h,
+                          int32_t m, float scale, int32_t dtype, void* workspace, size_t ws_bytes, void* stream) {
+  return history_impl("lime_link_history", lime::kPhiSoftmax, E, lens, LC, lc_user_stride, Wq, Wk, Wv, LP, nullptr, B,
+                      N, d, h, m, scale, dtype, workspace, ws_bytes, stream);
+}
+
+int32_t lime_xor_history(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride, const void* Wq,
+                         const void* Wk, const void* Wv, void* LP, void* OS, int32_t B, int32_t N, int32_t d,
+                         int32_t h, int32_t m, float scale, int32_t dtype, void* workspace, size_t ws_bytes,
+                         void* stream) {
+  return history_impl("lime_xor_history", lime::kPhiSilu, E, lens, LC, lc_user_stride, Wq, Wk, Wv, LP, OS, B, N, d, h,
+                      m, scale, dtype, workspace, ws_bytes, stream);
+}
+
+int32_t lime_score_candidates(const void* T, const void* L, const void* LP, const void* Wq, const void* Wk,
+                              const void* Wv, void* O, int32_t B, int32_t C, int32_t d, int32_t h, int32_t m,
+                              float scale, int32_t dtype, void* workspace, size_t ws_bytes, void* stream) {
+  const char* fn = "lime_score_candidates";
+  if (int32_t st = check_common(fn, B, d, h, dtype)) return st;
+  if (C <= 0 || m <= 0) return fail(LIME_INVALID_ARG, "%s: C and m must be positive (C=%d m=%d)", fn, C, m);
+  if (!T || !L || !LP || !O) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  const int64_t q_rows = static_cast<int64_t>(B) * C, v_rows = static_cast<int64_t>(B) * m;
+  QueryPlan p = plan_queries(nullptr, q_rows, m, v_rows, d);
+  if (!workspace || ws_bytes < p.bytes)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, p.bytes, workspace ? ws_bytes : 0);
+  p = plan_queries(workspace, q_rows, m, v_rows, d);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  LIME_HIP(lime::generic_project(T, Wq, p.Qt, q_rows, d, dtype, s));
+  LIME_HIP(lime::generic_project(L, Wk, p.Kt, m, d, dtype, s));
+  LIME_HIP(lime::generic_project(LP, Wv, p.Vt, v_rows, d, dtype, s));
+  lime::GenericAttention a{};
+  a.Q = p.Qt, a.K = p.Kt, a.V = p.Vt;
+  a.q_user_stride = static_cast<int64_t>(C) * d, a.k_user_stride = 0, a.v_user_stride = static_cast<int64_t>(m) * d;
+  a.O = O, a.q_lens = nullptr, a.k_lens = nullptr;
+  a.B = B, a.q_rows = C, a.n_keys = m, a.d = d, a.h = h, a.scale = scale, a.phi = lime::kPhiSoftmax, a.dtype = dtype;
+  LIME_HIP(lime::generic_attention(a, s));
+  return LIME_OK;
+}
+
+int32_t mha_target_attention(const void* T, const void* E, const int32_t* lens, const void* Wq, const void* Wk,
+                             const void* Wv, void* O, int32_t B, int32_t C, int32_t N, int32_t d, int32_t h,
+                             float scale, int32_t dtype, void* workspace, size_t ws_bytes, void* stream) {
+  const char* fn = "mha_target_attention";
+  if (int32_t st = check_common(fn, B, d, h, dtype)) return st;
+  if (C <= 0 || N <= 0) return fail(LIME_INVALID_ARG, "%s: C and N must be positive (C=%d N=%d)", fn, C, N);
+  if (!T || !E || !Wq || !Wk || !Wv || !O) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  const int64_t q_rows = static_cast<int64_t>(B) * C, k_rows = static_cast<int64_t>(B) * N;
+  QueryPlan p = plan_queries(nullptr, q_rows, k_rows, k_rows, d);
+  if (!workspace || ws_bytes < p.bytes)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, p.bytes, workspace ? ws_bytes : 0);
+  p = plan_queries(workspace, q_rows, k_rows, k_rows, d);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  LIME_HIP(lime::generic_project(T, Wq, p.Qt, q_rows, d, dtype, s));
+  LIME_HIP(lime::generic_project(E, Wk, p.Kt, k_rows, d, dtype, s));
+  LIME_HIP(lime::generic_project(E, Wv, p.Vt, k_rows, d, dtype, s));
+  lime::GenericAttention a{};
+  a.Q = p.Qt, a.K = p.Kt, a.V = p.Vt;
+  a.q_user_stride = static_cast<int64_t>(C) * d, a.k_user_stride = a.v_user_stride = static_cast<int64_t>(N) * d;
+  a.O = O, a.q_lens = nullptr, a.k_lens = lens;
+  a.B = B, a.q_rows = C, a.n_keys = N, a.d = d, a.h = h, a.scale = scale, a.phi = lime::kPhiSoftmax, a.dtype = dtype;
+  LIME_HIP(lime::generic_attention(a, s));
+  return LIME_OK;
+}
+
+size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t d, int32_t h, int32_t m,
+                            int32_t dtype, int32_t flags) {
+  if (B <= 0 || d <= 0 || h <= 0 || d % h != 0 || d / h > kMaxHeadDim || B > kMaxUsers) return 0;
+  if (dtype != LIME_F32 && dtype != LIME_BF16) return 0;
+  switch (op) {
+    case LIME_OP_LINK_HISTORY:
+    case LIME_OP_XOR_HISTORY:
+      if (N <= 0 || m <= 0) return 0;
+      // sized for per-user links, the larger of the two link layouts
+      return plan_history(nullptr, B, N, d, m, true, op == LIME_OP_XOR_HISTORY && (flags & 1)).bytes;
+    case LIME_OP_SCORE_CANDIDATES:
+      if (C <= 0 || m <= 0) return 0;
+      return plan_queries(nullptr, static_cast<int64_t>(B) * C, m, static_cast<int64_t>(B) * m, d).bytes;
+    case LIME_OP_MHA_TARGET:
+      if (C <= 0 || N <= 0) return 0;
+      return plan_queries(nullptr, static_cast<int64_t>(B) * C, static_cast<int64_t>(B) * N, static_cast<int64_t>(B) * N, d).bytes;
+    default:
+      return 0;
+  }
+}
+
+const char* lime_last_error(void) { return g_error; }
+
+const char* lime_version(void) { return "0.1.0"; }
+
+#pragma GCC visibility pop
+}  // extern "C"

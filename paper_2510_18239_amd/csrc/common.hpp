@@ -1,0 +1,53 @@
+// Shared device helpers and the internal launcher interface of the LIME HIP library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace lime {
+
+// ----------------------------------------------------------------------------- storage types
+struct bf16_t {
+  uint16_t bits;
+};
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float(static_cast<uint32_t>(x.bits) << 16); }
+
+// fp32 -> bf16, round to nearest even; NaN stays NaN (quiet).
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x0040u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>(u >> 16);
+}
+
+__device__ __forceinline__ void store_as(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_as(bf16_t* p, float v) { p->bits = f32_to_bf16_bits(v); }
+
+constexpr int kPhiSoftmax = 0;
+constexpr int kPhiSilu = 1;
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// ----------------------------------------------------------------------------- general kernels (generic.hip)
+// Y[rows][d] (fp32) = X[rows][d] * W[d][d]; W == nullptr copies X (identity projection).
+hipError_t generic_project(const void* X, const void* W, float* Y, int64_t rows, int d, int dtype, hipStream_t s);
+
+struct GenericAttention {
+  const float* Q;      // [.][q_rows][d], user b at Q + b * q_user_stride
+  const float* K;      // [.][n_keys][d]
+  const float* V;      // [.][n_keys][d]
+  int64_t q_user_stride, k_user_stride, v_user_stride;  // in elements; 0 = shared by all users
+  void* O;             // [B][q_rows][d] in `dtype`
+  const int32_t* q_lens;  // nullable; query rows >= q_lens[b] are written as zeros
+  const int32_t* k_lens;  // nullable; keys >= k_lens[b] are masked
+  int B, q_rows, n_keys, d, h;
+  float scale;
+  int phi;    // kPhiSoftmax: softmax over valid keys; kPhiSilu: SiLU(logit) / (number of valid keys)
+  int dtype;  // of O
+};
+hipError_t generic_attention(const GenericAttention& a, hipStream_t s);
+
+}  // namespace lime

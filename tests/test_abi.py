@@ -1,0 +1,101 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+function include/lime.h declares, and rejects bad arguments before launching anything."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2510_18239_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x1000  # a non-NULL pointer that is never dereferenced: every call below fails its host-side checks
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "lime.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(\w+)\s*\([^;{]*\)\s*;", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"lime_link_history", "lime_xor_history", "lime_score_candidates", "mha_target_attention",
+            "lime_workspace_bytes", "lime_last_error", "lime_version"} <= set(names)
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(binding.SIGNATURES), "binding and header disagree"
+    assert re.fullmatch(r"\d+\.\d+\.\d+", binding.version())
+
+
+def test_missing_library_is_an_error(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        binding.lib()
+
+
+def _hist(fn, **kw):
+    a = dict(E=FAKE, lens=None, LC=FAKE, stride=0, Wq=FAKE, Wk=FAKE, Wv=FAKE, LP=FAKE, OS=None, B=2, N=8, d=8, h=2,
+             m=4, scale=1.0, dtype=1, ws=FAKE, ws_bytes=0, stream=None)
+    a.update(kw)
+    lib = binding.lib()
+    if fn == "lime_link_history":
+        return lib.lime_link_history(a["E"], a["lens"], a["LC"], a["stride"], a["Wq"], a["Wk"], a["Wv"], a["LP"],
+                                     a["B"], a["N"], a["d"], a["h"], a["m"], a["scale"], a["dtype"], a["ws"],
+                                     a["ws_bytes"], a["stream"])
+    return lib.lime_xor_history(a["E"], a["lens"], a["LC"], a["stride"], a["Wq"], a["Wk"], a["Wv"], a["LP"], a["OS"],
+                                a["B"], a["N"], a["d"], a["h"], a["m"], a["scale"], a["dtype"], a["ws"],
+                                a["ws_bytes"], a["stream"])
+
+
+@pytest.mark.parametrize("fn", ["lime_link_history", "lime_xor_history"])
+def test_history_argument_checks(fn):
+    assert _hist(fn) == 3 and "workspace" in binding.last_error()  # workspace of 0 bytes
+    assert _hist(fn, ws=None, ws_bytes=1 << 30) == 3
+    assert _hist(fn, E=None) == 1
+    assert _hist(fn, LP=None) == 1
+    assert _hist(fn, Wk=None) == 1
+    assert _hist(fn, B=0) == 1
+    assert _hist(fn, N=-3) == 1
+    assert _hist(fn, m=0) == 1
+    assert _hist(fn, d=9) == 1 and "multiple" in binding.last_error()
+    assert _hist(fn, dtype=7) == 1
+    assert _hist(fn, stride=5) == 1
+    assert _hist(fn, d=1024, h=2) == 2  # d/h = 512 > 256
+    assert _hist(fn, B=70000) == 2
+
+
+def test_candidate_and_baseline_argument_checks():
+    lib = binding.lib()
+
+    def cand(T=FAKE, L=FAKE, LP=FAKE, O=FAKE, B=1, C=4, d=8, h=2, m=4, dtype=1, ws=FAKE, ws_bytes=0):
+        return lib.lime_score_candidates(T, L, LP, None, None, None, O, B, C, d, h, m, 1.0, dtype, ws, ws_bytes, None)
+
+    assert cand() == 3
+    assert cand(T=None) == 1 and cand(L=None) == 1 and cand(LP=None) == 1 and cand(O=None) == 1
+    assert cand(C=0) == 1 and cand(m=0) == 1 and cand(h=3) == 1 and cand(dtype=-1) == 1
+    assert cand(d=2048, h=4) == 2
+
+    def mha(T=FAKE, E=FAKE, Wq=FAKE, O=FAKE, B=1, C=4, N=8, d=8, h=2, dtype=0, ws=FAKE, ws_bytes=0):
+        return lib.mha_target_attention(T, E, None, Wq, FAKE, FAKE, O, B, C, N, d, h, 1.0, dtype, ws, ws_bytes, None)
+
+    assert mha() == 3
+    assert mha(T=None) == 1 and mha(E=None) == 1 and mha(Wq=None) == 1 and mha(O=None) == 1
+    assert mha(N=0) == 1 and mha(C=0) == 1 and mha(h=0) == 1
+
+
+def test_workspace_query():
+    wb = binding.workspace_bytes
+    assert wb(binding.OP_LINK_HISTORY, B=2, N=100, d=64, h=4, m=16) > 0
+    assert wb(binding.OP_XOR_HISTORY, B=2, N=100, d=64, h=4, m=16, flags=1) >= wb(binding.OP_XOR_HISTORY, B=2, N=100,
+                                                                                    d=64, h=4, m=16, flags=0)
+    assert wb(binding.OP_SCORE_CANDIDATES, B=1, C=32768, d=256, h=4, m=64) > 0
+    assert wb(binding.OP_MHA_TARGET, B=1, C=10, N=10, d=8, h=2) > 0
+    assert wb(binding.OP_LINK_HISTORY, B=0, N=100, d=64, h=4, m=16) == 0
+    assert wb(binding.OP_LINK_HISTORY, B=1, N=100, d=64, h=5, m=16) == 0
+    assert wb(99, B=1, N=1, C=1, d=8, h=1, m=1) == 0
+    for op in range(4):
+        assert wb(op, B=3, N=50, C=70, d=32, h=2, m=8, dtype=0, flags=1) % 256 == 0
