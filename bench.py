@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the LIME inference hot path on one MI355X.
+
+A "step" is one LIME request of the headline workload: lime_link_history over the N-item
+history (Eq. 3) followed by lime_score_candidates over the C candidates (Eq. 4), at
+B=1, N=2048, C=32768, d=256, h=4, m=64, bf16, inputs resident in HBM.  Candidate and
+output buffers rotate through more memory than the 256 MiB last-level cache holds, so the
+candidate stream really comes from HBM.  Prints one JSON line.
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def parse_args():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=200)
+    p.add_argument("--warmup", type=int, default=20)
+    p.add_argument("--candidates", type=int, default=32768, help="C of the headline workload")
+    p.add_argument("--history", type=int, default=2048, help="N of the headline workload")
+    p.add_argument("--rotate-mib", type=int, default=544, help="candidate+output bytes to rotate through (0 = reuse one pair)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--extras", action="store_true", help="also time the XORA history pass, the C sweep and the MHA baseline")
+    return p.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (one MI355X per box); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2510_18239_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    cfg = dict(synth.CONFIGS[3])
+    cfg["C"], cfg["N"] = args.candidates, args.history
+    B, N, C, d, h, m = (cfg[k] for k in ("B", "N", "C", "d", "h", "m"))
+    w = synth.make_workload(3, **cfg)
+    scale = w.softmax_scale
+
+    def t(x):
+        return torch.from_numpy(x).to(torch.bfloat16).to(dev)
+
+    E, L, Wq, Wk, Wv = t(w.E), t(w.L), t(w.Wq), t(w.Wk), t(w.Wv)
+    pair_bytes = 2 * B * C * d * 2
+    n_pairs = max(1, -(-args.rotate_mib * (1 << 20) // pair_bytes)) if args.rotate_mib > 0 else 1
+    T0 = t(w.T)
+    Ts = [T0] + [T0.clone() for _ in range(n_pairs - 1)]
+    Os = [torch.empty_like(T0) for _ in range(n_pairs)]
+    LP = torch.empty((B, m, d), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(max(binding.workspace_bytes(binding.OP_LINK_HISTORY, B=B, N=N, d=d, h=h, m=m),
+                         binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=B, C=C, d=d, h=h, m=m)),
+                     dtype=torch.uint8, device=dev)
+
+    def step(i):
+        binding.lime_link_history(E, None, L, Wq, Wk, Wv, h, scale, LP=LP, workspace=ws)
+        binding.lime_score_candidates(Ts[i % n_pairs], L, LP, Wq, Wk, Wv, h, scale, O=Os[i % n_pairs], workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ---- the timed region: exactly K steps between two synchronisations
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    value = B * C / (ms_per_step * 1e-3)
+
+    # ---- per-call latencies (events on the launch stream) and the dominant kernel's own duration
+    def timed(fn, reps):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for i, (a, b) in enumerate(evs):
+            a.record()
+            fn(i)
+            b.record()
+        torch.cuda.synchronize()
+        return sorted(a.elapsed_time(b) for a, b in evs)
+
+    def pct(xs, q):
+        return xs[min(len(xs) - 1, int(q * len(xs)))]
+
+    reps = args.steps
+    lat_step = timed(step, reps)
+    lat_hist = timed(lambda i: binding.lime_link_history(E, None, L, Wq, Wk, Wv, h, scale, LP=LP, workspace=ws), reps)
+    binding.profile_enable(True)
+    binding.profile_collect(0)
+    lat_cand = timed(lambda i: binding.lime_score_candidates(Ts[i % n_pairs], L, LP, Wq, Wk, Wv, h, scale,
+                                                             O=Os[i % n_pairs], workspace=ws), reps)
+    kern_ms = binding.profile_collect(0)
+    binding.profile_enable(False)
+    kern_avg_ms = statistics.fmean(kern_ms) if kern_ms else float("nan")
+    algorithmic_bytes = 2 * B * C * d * 2  # read each candidate row once, write each output row once (bf16)
+    achieved = algorithmic_bytes / (kern_avg_ms * 1e-3) / 1e9 if kern_ms else None
+
+    out = {
+        "metric": "scored candidates/sec and p50 latency (ms) at N=2048, C=32768, 1 MI355X",
+        "value": value,
+        "unit": "candidates/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"configs[2] candidate sweep point: B={B} user, N={N}, C={C}, d={d}, h={h}, m={m}, "
+                               "bf16, embeddings and weights ~N(0,1/d); step = lime_link_history + lime_score_candidates",
+                   "rotating_buffer_pairs": n_pairs, "rotating_mib": n_pairs * pair_bytes / 2 ** 20},
+        "latency_ms": {"request_p50": pct(lat_step, 0.5), "request_p10": pct(lat_step, 0.1),
+                       "request_p90": pct(lat_step, 0.9), "lime_link_history_p50": pct(lat_hist, 0.5),
+                       "lime_score_candidates_p50": pct(lat_cand, 0.5)},
+        "candidates_per_s_candidate_call_only": B * C / (pct(lat_cand, 0.5) * 1e-3),
+        "roofline": {"bound": "hbm", "kernel": "queries_over_links_kernel<64,64,4,softmax>", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
+                     "avg_kernel_ms": kern_avg_ms, "launches_timed": len(kern_ms),
+                     "algorithmic_bytes_per_launch": algorithmic_bytes, "traffic": TRAFFIC_BYTES_PER_LAUNCH},
+    }
+
+    if args.extras:
+        out["extras"] = extras(binding, synth, torch, dev, timed, pct)
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, scale)
+
+    print(json.dumps(out))
+
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/); None until measured.
+TRAFFIC_BYTES_PER_LAUNCH = None
+
+
+def cpu_baseline(w, scale):
+    """The CPU oracle, as it stands, on the same workload (one full request), best of 3."""
+    from oracle import lime_oracle as orc
+
+    try:
+        from threadpoolctl import threadpool_info
+
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:  # noqa: BLE001
+        threads = os.cpu_count() or 1
+    best = float("inf")
+    for _ in range(3):
+        t0 = time.perf_counter()
+        LP = orc.lime_link_history(w.E, None, w.L, w.Wq, w.Wk, w.Wv, w.h, scale)
+        orc.lime_score_candidates(w.T, w.L, LP, w.Wq, w.Wk, w.Wv, w.h, scale)
+        best = min(best, time.perf_counter() - t0)
+    return {"value": w.B * w.C / best, "unit": "candidates/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"the full request (history N={w.N} + all C={w.C} candidates), numpy fp64, best of 3, {best:.3f} s"}
+
+
+def extras(binding, synth, torch, dev, timed, pct):
+    """Context numbers: latency vs C, the XORA history pass vs N, and LIME vs full target attention."""
+    res = {}
+
+    def t(x):
+        return torch.from_numpy(x).to(torch.bfloat16).to(dev)
+
+    # latency vs number of candidates (configs[2])
+    c3 = dict(synth.CONFIGS[3])
+    w = synth.make_workload(3, **c3)
+    E, L, Wq, Wk, Wv, T = t(w.E), t(w.L), t(w.Wq), t(w.Wk), t(w.Wv), t(w.T)
+    LP = binding.lime_link_history(E, None, L, Wq, Wk, Wv, w.h, w.softmax_scale)
+    sweep = {}
+    for C in [16 << i for i in range(12)]:
+        Tc = T[:, :C].contiguous()
+        O = torch.empty_like(Tc)
+        lat = timed(lambda i: binding.lime_score_candidates(Tc, L, LP, Wq, Wk, Wv, w.h, w.softmax_scale, O=O), 100)
+        sweep[C] = pct(lat, 0.5)
+    res["lime_score_candidates_p50_ms_vs_C"] = sweep
+    # XORA history pass vs N (configs[3])
+    c4 = dict(synth.CONFIGS[4])
+    xs = {}
+    for N in (2048, 4096, 8192, 16384):
+        c4["N"] = N
+        w4 = synth.make_workload(4, **c4)
+        E4, L4, q4, k4, v4 = t(w4.E), t(w4.L), t(w4.Wq), t(w4.Wk), t(w4.Wv)
+        lat = timed(lambda i: binding.lime_xor_history(E4, None, L4, q4, k4, v4, w4.h, 1.0), 50)
+        xs[N] = pct(lat, 0.5)
+    res["lime_xor_history_p50_ms_vs_N"] = xs
+    # LIME vs full target attention on identical inputs (configs[4])
+    c5 = dict(synth.CONFIGS[5])
+    c5["pad_value"] = 0.0
+    w5 = synth.make_workload(5, **c5)
+    E5, L5, q5, k5, v5, T5 = t(w5.E), t(w5.L), t(w5.Wq), t(w5.Wk), t(w5.Wv), t(w5.T)
+    lens5 = torch.from_numpy(w5.lens).to(dev)
+    s5 = w5.softmax_scale
+
+    def lime(i):
+        LP5 = binding.lime_link_history(E5, lens5, L5, q5, k5, v5, w5.h, s5)
+        binding.lime_score_candidates(T5, L5, LP5, q5, k5, v5, w5.h, s5)
+
+    lat_lime = timed(lime, 20)
+    lat_mha = timed(lambda i: binding.mha_target_attention(T5, E5, lens5, q5, k5, v5, w5.h, s5), 5)
+    res["config5_ms"] = {"lime_request_p50": pct(lat_lime, 0.5), "mha_target_attention_p50": pct(lat_mha, 0.5),
+                         "speedup": pct(lat_mha, 0.5) / pct(lat_lime, 0.5)}
+    return res
+
+
+if __name__ == "__main__":
+    main()

@@ -110,6 +110,19 @@ int32_t mha_target_attention(const void* T, const void* E, const int32_t* lens,
 size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t d, int32_t h, int32_t m,
                             int32_t dtype, int32_t flags);
 
+/*
+ * Per-kernel timing for benchmarks (callers that only want results never need it).
+ * lime_profile_enable(1): from now on every main kernel launched by the entry points above is
+ * bracketed by a pair of HIP events on its stream (kernel ids: 0 = the candidate-side kernel
+ * of lime_score_candidates and of O[S]; 1 = the links-over-history kernel of lime_link_history /
+ * lime_xor_history; 2 = the attention kernel of mha_target_attention; 3 = their K/V projection).
+ * lime_profile_collect(kernel, ms, capacity): waits for the recorded launches of that kernel,
+ * writes up to `capacity` durations in milliseconds to the HOST array `ms` in launch order,
+ * forgets them and returns how many it wrote.  Only the matrix-core kernels are instrumented.
+ */
+void lime_profile_enable(int32_t on);
+int32_t lime_profile_collect(int32_t kernel, float* ms, int32_t capacity);
+
 /* Text of the calling thread's most recent non-zero status ("" if none).  Host memory, owned by the library. */
 const char* lime_last_error(void);
 

@@ -35,6 +35,8 @@ SIGNATURES = {
     "mha_target_attention": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32, _i32,
                                     _vp, _sz, _vp]),
     "lime_workspace_bytes": (_sz, [_i32] * 9),
+    "lime_profile_enable": (None, [_i32]),
+    "lime_profile_collect": (_i32, [_i32, _c.POINTER(_c.c_float), _i32]),
     "lime_last_error": (_c.c_char_p, []),
     "lime_version": (_c.c_char_p, []),
 }
@@ -69,6 +71,17 @@ def last_error() -> str:
 
 def version() -> str:
     return lib().lime_version().decode()
+
+
+def profile_enable(on: bool) -> None:
+    lib().lime_profile_enable(1 if on else 0)
+
+
+def profile_collect(kernel: int, capacity: int = 65536) -> list[float]:
+    """Durations (ms) of the recorded launches of one kernel id since the last collect."""
+    buf = (_c.c_float * capacity)()
+    n = lib().lime_profile_collect(kernel, buf, capacity)
+    return [float(buf[i]) for i in range(n)]
 
 
 def workspace_bytes(op: int, B=1, N=1, C=1, d=1, h=1, m=1, dtype=LIME_BF16, flags=0) -> int:

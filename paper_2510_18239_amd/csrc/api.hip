@@ -4,7 +4,10 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <algorithm>
+
 #include "common.hpp"
+#include "mfma.hpp"
 
 namespace {
 
@@ -25,6 +28,10 @@ int32_t fail(int32_t status, const char* fmt, ...) {
   } while (0)
 
 constexpr int kMaxHeadDim = 256;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+template <typename... P>
+bool all_aligned16(P... p) { return (aligned16(p) && ...); }
 constexpr int kMaxUsers = 65535;
 
 // Carves 256-byte aligned pieces out of the caller's workspace; with base == nullptr it only sizes.
@@ -83,10 +90,15 @@ int32_t history_impl(const char* fn, int phi, const void* E, const int32_t* lens
     return fail(LIME_INVALID_ARG, "%s: lc_user_stride must be 0 or m*d (got %lld)", fn, static_cast<long long>(lc_user_stride));
   const bool per_user = lc_user_stride != 0;
   const bool want_os = OS != nullptr;
-  HistoryPlan p = plan_history(nullptr, B, N, d, m, per_user, want_os);
-  if (!workspace || ws_bytes < p.bytes)
-    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, p.bytes, workspace ? ws_bytes : 0);
-  p = plan_history(workspace, B, N, d, m, per_user, want_os);
+  // O[S] is "every history row attends over the m links": the candidate-side kernel with phi = SiLU/m
+  const bool os_on_mfma = want_os && dtype == LIME_BF16 && lime::queries_over_links_supported(d, h, m) &&
+                          all_aligned16(E, LC, Wq, Wk, Wv, OS, workspace);
+  HistoryPlan p = plan_history(nullptr, B, N, d, m, per_user, want_os && !os_on_mfma);
+  const size_t os_bytes = os_on_mfma ? lime::queries_over_links_workspace(B, d, m, per_user) : 0;
+  if (!workspace || ws_bytes < p.bytes + os_bytes)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, p.bytes + os_bytes,
+                workspace ? ws_bytes : 0);
+  p = plan_history(workspace, B, N, d, m, per_user, want_os && !os_on_mfma);
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int64_t link_rows = (per_user ? B : 1) * static_cast<int64_t>(m);
   const int64_t hist_rows = static_cast<int64_t>(B) * N;
@@ -101,7 +113,13 @@ int32_t history_impl(const char* fn, int phi, const void* E, const int32_t* lens
   t.O = LP, t.q_lens = nullptr, t.k_lens = lens;
   t.B = B, t.q_rows = m, t.n_keys = N, t.d = d, t.h = h, t.scale = scale, t.phi = phi, t.dtype = dtype;
   LIME_HIP(lime::generic_attention(t, s));
-  if (want_os) {
+  if (os_on_mfma) {
+    lime::QueriesOverLinks q{};
+    q.X = E, q.O = OS, q.Wq = Wq, q.Ksrc = LC, q.Wk = Wk, q.Vsrc = LC, q.Wv = Wv;
+    q.k_user_stride = q.v_user_stride = link_stride, q.row_lens = lens;
+    q.B = B, q.rows = N, q.d = d, q.h = h, q.m = m, q.scale = scale, q.phi = lime::kPhiSilu;
+    LIME_HIP(lime::queries_over_links(q, static_cast<char*>(workspace) + p.bytes, s));
+  } else if (want_os) {
     LIME_HIP(lime::generic_project(E, Wq, p.Qs, hist_rows, d, dtype, s));
     LIME_HIP(lime::generic_project(LC, Wk, p.Kt, link_rows, d, dtype, s));
     LIME_HIP(lime::generic_project(LC, Wv, p.Vt, link_rows, d, dtype, s));
@@ -159,11 +177,23 @@ int32_t lime_score_candidates(const void* T, const void* L, const void* LP, cons
   if (C <= 0 || m <= 0) return fail(LIME_INVALID_ARG, "%s: C and m must be positive (C=%d m=%d)", fn, C, m);
   if (!T || !L || !LP || !O) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
   const int64_t q_rows = static_cast<int64_t>(B) * C, v_rows = static_cast<int64_t>(B) * m;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (dtype == LIME_BF16 && lime::queries_over_links_supported(d, h, m) &&
+      all_aligned16(T, L, LP, Wq, Wk, Wv, O, workspace)) {
+    const size_t need = lime::queries_over_links_workspace(B, d, m, false);
+    if (!workspace || ws_bytes < need)
+      return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? ws_bytes : 0);
+    lime::QueriesOverLinks q{};
+    q.X = T, q.O = O, q.Wq = Wq, q.Ksrc = L, q.Wk = Wk, q.Vsrc = LP, q.Wv = Wv;
+    q.k_user_stride = 0, q.v_user_stride = static_cast<int64_t>(m) * d, q.row_lens = nullptr;
+    q.B = B, q.rows = C, q.d = d, q.h = h, q.m = m, q.scale = scale, q.phi = lime::kPhiSoftmax;
+    LIME_HIP(lime::queries_over_links(q, workspace, s));
+    return LIME_OK;
+  }
   QueryPlan p = plan_queries(nullptr, q_rows, m, v_rows, d);
   if (!workspace || ws_bytes < p.bytes)
     return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, p.bytes, workspace ? ws_bytes : 0);
   p = plan_queries(workspace, q_rows, m, v_rows, d);
-  hipStream_t s = static_cast<hipStream_t>(stream);
   LIME_HIP(lime::generic_project(T, Wq, p.Qt, q_rows, d, dtype, s));
   LIME_HIP(lime::generic_project(L, Wk, p.Kt, m, d, dtype, s));
   LIME_HIP(lime::generic_project(LP, Wv, p.Vt, v_rows, d, dtype, s));
@@ -210,10 +240,14 @@ size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t
     case LIME_OP_XOR_HISTORY:
       if (N <= 0 || m <= 0) return 0;
       // sized for per-user links, the larger of the two link layouts
-      return plan_history(nullptr, B, N, d, m, true, op == LIME_OP_XOR_HISTORY && (flags & 1)).bytes;
+      return plan_history(nullptr, B, N, d, m, true, op == LIME_OP_XOR_HISTORY && (flags & 1)).bytes +
+             (dtype == LIME_BF16 && lime::queries_over_links_supported(d, h, m)
+                  ? lime::queries_over_links_workspace(B, d, m, true) : size_t{0});
     case LIME_OP_SCORE_CANDIDATES:
       if (C <= 0 || m <= 0) return 0;
-      return plan_queries(nullptr, static_cast<int64_t>(B) * C, m, static_cast<int64_t>(B) * m, d).bytes;
+      return std::max(plan_queries(nullptr, static_cast<int64_t>(B) * C, m, static_cast<int64_t>(B) * m, d).bytes,
+                      dtype == LIME_BF16 && lime::queries_over_links_supported(d, h, m)
+                          ? lime::queries_over_links_workspace(B, d, m, false) : size_t{0});
     case LIME_OP_MHA_TARGET:
       if (C <= 0 || N <= 0) return 0;
       return plan_queries(nullptr, static_cast<int64_t>(B) * C, static_cast<int64_t>(B) * N, static_cast<int64_t>(B) * N, d).bytes;

@@ -31,6 +31,12 @@ constexpr int kPhiSilu = 1;
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+// ----------------------------------------------------------------------------- per-kernel timing (profile.hip)
+enum ProfiledKernel { kKernelQueriesOverLinks = 0, kKernelLinksOverHistory = 1, kKernelTargetAttention = 2,
+                      kKernelProjection = 3 };
+void profile_begin(int kernel, hipStream_t s);
+void profile_end(int kernel, hipStream_t s);
+
 // ----------------------------------------------------------------------------- general kernels (generic.hip)
 // Y[rows][d] (fp32) = X[rows][d] * W[d][d]; W == nullptr copies X (identity projection).
 hipError_t generic_project(const void* X, const void* W, float* Y, int64_t rows, int d, int dtype, hipStream_t s);

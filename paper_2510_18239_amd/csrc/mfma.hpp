@@ -1,0 +1,68 @@
+// bf16 matrix-core (MFMA) building blocks for gfx950 and the launcher interface of the
+// kernels built from them.
+//
+// All contractions use v_mfma_f32_32x32x16_bf16.  With lane = 32*g + n (n in [0,32), g in {0,1}):
+//   A fragment (32 x 16):  lane holds A[row n][k = 8g + t], t = 0..7
+//   B fragment (16 x 32):  lane holds B[k = 8g + t][col n]
+//   D accumulator (32x32): lane holds D[row 8j + 4g + r][col n] in register 4j + r (j, r in [0,4))
+// The two operand layouts are mirror images (lane <-> the index that is kept, slot <-> the index
+// that is summed), so a D block can be fed straight back as an operand whose summed index is D's
+// row index: registers 8f..8f+7 (f in {0,1}) of a D block form one 16-deep fragment in which slot t
+// of lane-half g stands for row 16f + chain_k(g, t).  The other operand of that product is laid
+// out in the same "chained" order; sums do not care about the order of their terms.
+#pragma once
+
+#include "common.hpp"
+
+namespace lime {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Row (within a 16-deep k-step) that slot t of lane-half g stands for in a chained fragment.
+__host__ __device__ constexpr int chain_k(int g, int t) { return 8 * (t >> 2) + 4 * g + (t & 3); }
+// Inverse: k in [0,16) -> lane-half and slot.
+__host__ __device__ constexpr int chain_g(int k) { return (k >> 2) & 1; }
+__host__ __device__ constexpr int chain_t(int k) { return 4 * (k >> 3) + (k & 3); }
+
+// Registers 8f..8f+7 of a D block as a bf16 fragment (round to nearest even).
+__device__ __forceinline__ bf16x8 pack_half(const f32x16& d, int f) {
+  bf16x8 r;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) r[t] = static_cast<__bf16>(d[8 * f + t]);
+  return r;
+}
+
+// Output-row permutation that makes a lane's 16 accumulator registers 16 consecutive columns:
+// the A-operand row `rho` of an output block carries column out_col(rho); lane-half g then holds
+// columns 16g .. 16g+15 of the 32-wide block in register order.
+__host__ __device__ constexpr int out_col(int rho) { return 16 * ((rho >> 2) & 1) + 4 * (rho >> 3) + (rho & 3); }
+__host__ __device__ constexpr int out_rho(int col) { return 8 * ((col >> 2) & 3) + 4 * (col >> 4) + (col & 3); }
+
+// ----------------------------------------------------------------------------- candidate-side kernel family
+// Fused "queries x few keys" attention: for every query row x (a candidate of Eq. 4, or a history
+// row for O[S] of Eq. 7): q = x Wq; per head w = phi(scale * q K~^T) over the m keys; out = w V~.
+struct QueriesOverLinks {
+  const void* X;        // [B][rows][d] bf16 query-side embeddings (T, or E for O[S])
+  void* O;              // [B][rows][d] bf16
+  const void* Wq;       // [d][d] bf16 or nullptr (identity)
+  const void* Ksrc;     // [.][m][d] bf16 rows that become keys   (L, or LC)
+  const void* Wk;       // nullable
+  const void* Vsrc;     // [.][m][d] bf16 rows that become values (LP, or LC)
+  const void* Wv;       // nullable
+  int64_t k_user_stride, v_user_stride;  // elements; 0 = shared
+  const int32_t* row_lens;               // nullable; rows >= row_lens[b] are written as zeros
+  int B, rows, d, h, m;
+  float scale;
+  int phi;              // kPhiSoftmax, or kPhiSilu with normaliser m
+};
+bool queries_over_links_supported(int d, int h, int m);
+size_t queries_over_links_workspace(int B, int d, int m, bool k_per_user);
+hipError_t queries_over_links(const QueriesOverLinks& a, void* workspace, hipStream_t s);
+
+}  // namespace lime

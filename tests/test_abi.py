@@ -22,6 +22,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"lime_link_history", "lime_xor_history", "lime_score_candidates", "mha_target_attention",
+            "lime_profile_enable", "lime_profile_collect",
             "lime_workspace_bytes", "lime_last_error", "lime_version"} <= set(names)
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
