@@ -90,29 +90,44 @@ int32_t history_impl(const char* fn, int phi, const void* E, const int32_t* lens
     return fail(LIME_INVALID_ARG, "%s: lc_user_stride must be 0 or m*d (got %lld)", fn, static_cast<long long>(lc_user_stride));
   const bool per_user = lc_user_stride != 0;
   const bool want_os = OS != nullptr;
-  // O[S] is "every history row attends over the m links": the candidate-side kernel with phi = SiLU/m
-  const bool os_on_mfma = want_os && dtype == LIME_BF16 && lime::queries_over_links_supported(d, h, m) &&
-                          all_aligned16(E, LC, Wq, Wk, Wv, OS, workspace);
-  HistoryPlan p = plan_history(nullptr, B, N, d, m, per_user, want_os && !os_on_mfma);
-  const size_t os_bytes = os_on_mfma ? lime::queries_over_links_workspace(B, d, m, per_user) : 0;
-  if (!workspace || ws_bytes < p.bytes + os_bytes)
-    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, p.bytes + os_bytes,
-                workspace ? ws_bytes : 0);
-  p = plan_history(workspace, B, N, d, m, per_user, want_os && !os_on_mfma);
+  // The matrix-core path: L^P / O[T] ("the m links attend over the history") on the fused history-side
+  // kernel, O[S] ("every history row attends over the m links") on the candidate-side kernel with SiLU/m.
+  const bool lp_on_mfma = dtype == LIME_BF16 && lime::links_over_history_supported(d, h, m) &&
+                          all_aligned16(E, LC, Wq, Wk, Wv, LP, OS, workspace);
+  const bool os_on_mfma = want_os && lp_on_mfma;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int64_t link_rows = (per_user ? B : 1) * static_cast<int64_t>(m);
   const int64_t hist_rows = static_cast<int64_t>(B) * N;
   const int64_t link_stride = per_user ? static_cast<int64_t>(m) * d : 0;
-
-  LIME_HIP(lime::generic_project(LC, Wq, p.Qt, link_rows, d, dtype, s));
-  LIME_HIP(lime::generic_project(E, Wk, p.Ks, hist_rows, d, dtype, s));
-  LIME_HIP(lime::generic_project(E, Wv, p.Vs, hist_rows, d, dtype, s));
-  lime::GenericAttention t{};
-  t.Q = p.Qt, t.K = p.Ks, t.V = p.Vs;
-  t.q_user_stride = link_stride, t.k_user_stride = t.v_user_stride = static_cast<int64_t>(N) * d;
-  t.O = LP, t.q_lens = nullptr, t.k_lens = lens;
-  t.B = B, t.q_rows = m, t.n_keys = N, t.d = d, t.h = h, t.scale = scale, t.phi = phi, t.dtype = dtype;
-  LIME_HIP(lime::generic_attention(t, s));
+  HistoryPlan p{};
+  if (lp_on_mfma) {
+    p.bytes = lime::links_over_history_workspace(B, N, d, h, m, per_user);
+    // (when L^P runs on the matrix cores, so does O[S]: same shape and alignment conditions)
+    const size_t os_bytes = os_on_mfma ? lime::queries_over_links_workspace(B, d, m, per_user) : 0;
+    if (!workspace || ws_bytes < p.bytes + os_bytes)
+      return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, p.bytes + os_bytes,
+                  workspace ? ws_bytes : 0);
+    lime::LinksOverHistory q{};
+    q.E = E, q.lens = lens, q.LC = LC, q.lc_user_stride = link_stride, q.Wq = Wq, q.Wk = Wk, q.Wv = Wv, q.LP = LP;
+    q.B = B, q.N = N, q.d = d, q.h = h, q.m = m, q.scale = scale, q.phi = phi;
+    LIME_HIP(lime::links_over_history(q, workspace, s));
+  } else {
+    p = plan_history(nullptr, B, N, d, m, per_user, want_os && !os_on_mfma);
+    const size_t os_bytes = os_on_mfma ? lime::queries_over_links_workspace(B, d, m, per_user) : 0;
+    if (!workspace || ws_bytes < p.bytes + os_bytes)
+      return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, p.bytes + os_bytes,
+                  workspace ? ws_bytes : 0);
+    p = plan_history(workspace, B, N, d, m, per_user, want_os && !os_on_mfma);
+    LIME_HIP(lime::generic_project(LC, Wq, p.Qt, link_rows, d, dtype, s));
+    LIME_HIP(lime::generic_project(E, Wk, p.Ks, hist_rows, d, dtype, s));
+    LIME_HIP(lime::generic_project(E, Wv, p.Vs, hist_rows, d, dtype, s));
+    lime::GenericAttention t{};
+    t.Q = p.Qt, t.K = p.Ks, t.V = p.Vs;
+    t.q_user_stride = link_stride, t.k_user_stride = t.v_user_stride = static_cast<int64_t>(N) * d;
+    t.O = LP, t.q_lens = nullptr, t.k_lens = lens;
+    t.B = B, t.q_rows = m, t.n_keys = N, t.d = d, t.h = h, t.scale = scale, t.phi = phi, t.dtype = dtype;
+    LIME_HIP(lime::generic_attention(t, s));
+  }
   if (os_on_mfma) {
     lime::QueriesOverLinks q{};
     q.X = E, q.O = OS, q.Wq = Wq, q.Ksrc = LC, q.Wk = Wk, q.Vsrc = LC, q.Wv = Wv;
@@ -240,9 +255,14 @@ size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t
     case LIME_OP_XOR_HISTORY:
       if (N <= 0 || m <= 0) return 0;
       // sized for per-user links, the larger of the two link layouts
-      return plan_history(nullptr, B, N, d, m, true, op == LIME_OP_XOR_HISTORY && (flags & 1)).bytes +
-             (dtype == LIME_BF16 && lime::queries_over_links_supported(d, h, m)
-                  ? lime::queries_over_links_workspace(B, d, m, true) : size_t{0});
+    {
+      const bool os = op == LIME_OP_XOR_HISTORY && (flags & 1);
+      size_t need = plan_history(nullptr, B, N, d, m, true, os).bytes;
+      if (dtype == LIME_BF16 && lime::links_over_history_supported(d, h, m))
+        need = std::max(need, lime::links_over_history_workspace(B, N, d, h, m, true) +
+                                  (os ? lime::queries_over_links_workspace(B, d, m, true) : size_t{0}));
+      return need;
+    }
     case LIME_OP_SCORE_CANDIDATES:
       if (C <= 0 || m <= 0) return 0;
       return std::max(plan_queries(nullptr, static_cast<int64_t>(B) * C, m, static_cast<int64_t>(B) * m, d).bytes,

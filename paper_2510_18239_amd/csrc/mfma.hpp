@@ -44,6 +44,31 @@ __device__ __forceinline__ bf16x8 pack_half(const f32x16& d, int f) {
 __host__ __device__ constexpr int out_col(int rho) { return 16 * ((rho >> 2) & 1) + 4 * (rho >> 3) + (rho & 3); }
 __host__ __device__ constexpr int out_rho(int col) { return 8 * ((col >> 2) & 3) + 4 * (col >> 4) + (col & 3); }
 
+// ----------------------------------------------------------------------------- operand packing (mfma_pack.hip)
+// One small kernel per call lays the stationary operands out in fragment order (units of bf16x8,
+// one per lane), so that the main kernels fetch each fragment with one 16-byte access per lane.
+//   weight image  [h][d/16][dh/32][64]: fragment (a, kk, mb), lane (n, g), slot t = W[16kk + 8g + t][a dh + 32mb + n]
+//     (the head-a slice of W^T as an A operand with natural k order; equally W as a B operand)
+//   kPackKeys     [U][h][dh/16][m/32][64]: fragment (u, a, kk, lb), lane (n, g), slot t
+//                   = (X_u W)[32lb + n][a dh + 16kk + chain_k(g, t)]   (rows kept, head columns summed in chained order)
+//   kPackValues   [U][h][m/16][dh/32][64]: fragment (u, a, kk, ob), lane (rho, g), slot t
+//                   = (X_u W)[16kk + chain_k(g, t)][a dh + 32ob + out_col(rho)]   (rows summed in chained order)
+struct PackWeight {
+  const void* W;   // [d][d] bf16, or nullptr for the identity
+  void* image;
+};
+constexpr int kPackKeys = 0, kPackValues = 1;
+struct PackProject {
+  const void* X;   // [users][m][d] bf16 rows to project
+  const void* W;   // [d][d] bf16, or nullptr for the identity
+  void* image;
+  int64_t user_stride;  // elements between users in X
+  int users;
+  int layout;      // kPackKeys or kPackValues
+};
+hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackProject* projections, int n_projections,
+                         int d, int h, int m, hipStream_t s);
+
 // ----------------------------------------------------------------------------- candidate-side kernel family
 // Fused "queries x few keys" attention: for every query row x (a candidate of Eq. 4, or a history
 // row for O[S] of Eq. 7): q = x Wq; per head w = phi(scale * q K~^T) over the m keys; out = w V~.
@@ -64,5 +89,23 @@ struct QueriesOverLinks {
 bool queries_over_links_supported(int d, int h, int m);
 size_t queries_over_links_workspace(int B, int d, int m, bool k_per_user);
 hipError_t queries_over_links(const QueriesOverLinks& a, void* workspace, hipStream_t s);
+
+// ----------------------------------------------------------------------------- history-side kernel family
+// Fused "few queries x many keys" attention: the m links attend over one user's N history rows;
+// keys and values are projected on the fly (K~ = E Wk, V~ = E Wv), queries are Q~ = LC Wq.
+struct LinksOverHistory {
+  const void* E;        // [B][N][d] bf16
+  const int32_t* lens;  // nullable
+  const void* LC;       // [.][m][d] bf16
+  int64_t lc_user_stride;
+  const void *Wq, *Wk, *Wv;  // [d][d] bf16, all required
+  void* LP;             // [B][m][d] bf16
+  int B, N, d, h, m;
+  float scale;
+  int phi;              // kPhiSoftmax, or kPhiSilu with normaliser lens[b]
+};
+bool links_over_history_supported(int d, int h, int m);
+size_t links_over_history_workspace(int B, int N, int d, int h, int m, bool q_per_user);
+hipError_t links_over_history(const LinksOverHistory& a, void* workspace, hipStream_t s);
 
 }  // namespace lime

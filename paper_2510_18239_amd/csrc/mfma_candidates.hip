@@ -19,66 +19,6 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-// ----------------------------------------------------------------------------- pack kernel
-// Fragment images (units of bf16x8, one per lane):
-//   WqA [h][d/16][dh/32][64]   : A[row = dh-column 32mb + n][k = 16kk + 8g + t]      = Wq[k][a dh + row]
-//   KA  [U][h][dh/16][m/32][64]: A[row = link 32lb + n][k = 16kk + chain_k(g, t)]    = K~[link][a dh + k]
-//   VA  [U][h][m/16][dh/32][64]: A[row rho -> column 32ob + out_col(rho)][k = link 16kk + chain_k(g, t)] = V~[link][a dh + col]
-struct PackArgs {
-  const bf16_t *Wq, *Ksrc, *Wk, *Vsrc, *Wv;
-  bf16_t *WqA, *KA, *VA;
-  int64_t k_user_stride, v_user_stride;
-  int d, dh, m, k_users, v_users;
-  int wq_blocks, k_blocks;  // block ranges of the three jobs
-};
-
-__device__ __forceinline__ float project_element(const bf16_t* __restrict__ x_row, const bf16_t* __restrict__ W,
-                                                 int d, int col) {
-  if (W == nullptr) return to_float(x_row[col]);
-  float acc = 0.f;
-  for (int k = 0; k < d; ++k) acc = fmaf(to_float(x_row[k]), to_float(W[static_cast<int64_t>(k) * d + col]), acc);
-  return acc;
-}
-
-__global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
-  const int d = p.d, dh = p.dh, m = p.m;
-  int blk = blockIdx.x;
-  if (blk < p.wq_blocks) {
-    const int idx = blk * 256 + threadIdx.x;  // (k, col)
-    if (idx >= d * d) return;
-    const int k = idx / d, col = idx % d;
-    const float v = p.Wq ? to_float(p.Wq[idx]) : (k == col ? 1.f : 0.f);
-    const int a = col / dh, c = col % dh, mb = c / 32, n = c % 32;
-    const int kk = k / 16, g = (k % 16) / 8, t = k % 8;
-    const int64_t frag = (static_cast<int64_t>(a) * (d / 16) + kk) * (dh / 32) + mb;
-    store_as(p.WqA + (frag * 64 + 32 * g + n) * 8 + t, v);
-    return;
-  }
-  blk -= p.wq_blocks;
-  if (blk < p.k_blocks) {
-    const int64_t idx = static_cast<int64_t>(blk) * 256 + threadIdx.x;  // (user, link, col)
-    if (idx >= static_cast<int64_t>(p.k_users) * m * d) return;
-    const int col = idx % d, link = (idx / d) % m, u = idx / (static_cast<int64_t>(d) * m);
-    const float v = project_element(p.Ksrc + u * p.k_user_stride + static_cast<int64_t>(link) * d, p.Wk, d, col);
-    const int a = col / dh, c = col % dh, kk = c / 16, kin = c % 16;
-    const int lb = link / 32, n = link % 32;
-    const int64_t frag = ((static_cast<int64_t>(u) * (d / dh) + a) * (dh / 16) + kk) * (m / 32) + lb;
-    store_as(p.KA + (frag * 64 + 32 * chain_g(kin) + n) * 8 + chain_t(kin), v);
-    return;
-  }
-  blk -= p.k_blocks;
-  {
-    const int64_t idx = static_cast<int64_t>(blk) * 256 + threadIdx.x;
-    if (idx >= static_cast<int64_t>(p.v_users) * m * d) return;
-    const int col = idx % d, link = (idx / d) % m, u = idx / (static_cast<int64_t>(d) * m);
-    const float v = project_element(p.Vsrc + u * p.v_user_stride + static_cast<int64_t>(link) * d, p.Wv, d, col);
-    const int a = col / dh, c = col % dh, ob = c / 32, rho = out_rho(c % 32);
-    const int kk = link / 16, kin = link % 16;
-    const int64_t frag = ((static_cast<int64_t>(u) * (d / dh) + a) * (m / 16) + kk) * (dh / 32) + ob;
-    store_as(p.VA + (frag * 64 + 32 * chain_g(kin) + rho) * 8 + chain_t(kin), v);
-  }
-}
-
 // ----------------------------------------------------------------------------- main kernel
 struct MainArgs {
   const bf16_t* X;
@@ -109,6 +49,21 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   bf16x8 ka[K2][LB], va[K3][MB];
   int cur_user = -1;
 
+  // The X fragments of the next tile are requested before the current tile is computed, so the
+  // memory latency hides behind the MFMA work of the one wavefront a SIMD holds.
+  auto x_row_ptr = [&](int64_t tile) {
+    const int b = static_cast<int>(tile / a.tiles_per_user);
+    const int row = static_cast<int>(tile % a.tiles_per_user) * 32 + n;
+    // rows past the end are clamped for the load; their columns of the products are never stored
+    return a.X + (static_cast<int64_t>(b) * a.rows + min(row, a.rows - 1)) * D + 8 * g;
+  };
+  bf16x8 xn[K1];
+  if (blockIdx.x < a.total_tiles) {
+    const bf16_t* xrow = x_row_ptr(blockIdx.x);
+#pragma unroll
+    for (int kk = 0; kk < K1; ++kk) xn[kk] = *reinterpret_cast<const bf16x8*>(xrow + 16 * kk);
+  }
+
   for (int64_t tile = blockIdx.x; tile < a.total_tiles; tile += gridDim.x) {
     const int b = static_cast<int>(tile / a.tiles_per_user);
     const int r0 = static_cast<int>(tile % a.tiles_per_user) * 32;
@@ -131,8 +86,14 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
     }
     const int row = r0 + n;
     const int rlen = a.row_lens ? min(a.row_lens[b], a.rows) : a.rows;
-    // rows past the end are clamped for the load; their columns of the products are never stored
-    const bf16_t* xrow = a.X + (static_cast<int64_t>(b) * a.rows + min(row, a.rows - 1)) * D + 8 * g;
+    bf16x8 x[K1];
+#pragma unroll
+    for (int kk = 0; kk < K1; ++kk) x[kk] = xn[kk];
+    if (tile + gridDim.x < a.total_tiles) {
+      const bf16_t* xrow = x_row_ptr(tile + gridDim.x);
+#pragma unroll
+      for (int kk = 0; kk < K1; ++kk) xn[kk] = *reinterpret_cast<const bf16x8*>(xrow + 16 * kk);
+    }
 
     // Q~^T = Wq_a^T X^T
     f32x16 acc1[MB];
@@ -142,9 +103,8 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
       for (int i = 0; i < 16; ++i) acc1[mb][i] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < K1; ++kk) {
-      const bf16x8 x = *reinterpret_cast<const bf16x8*>(xrow + 16 * kk);
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) acc1[mb] = mfma32(wq[kk][mb], x, acc1[mb]);
+      for (int mb = 0; mb < MB; ++mb) acc1[mb] = mfma32(wq[kk][mb], x[kk], acc1[mb]);
     }
     bf16x8 qf[K2];
 #pragma unroll
@@ -226,6 +186,17 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   }
 }
 
+int compute_units() {
+  static const int n = [] {
+    int dev = 0, cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0)
+      cu = 256;
+    return cu;
+  }();
+  return n;
+}
+
 template <int DH, int M, int H>
 hipError_t launch_main(const MainArgs& m, int phi, int grid, hipStream_t s) {
   if (phi == kPhiSoftmax)
@@ -282,19 +253,10 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
   bf16_t* KA = reinterpret_cast<bf16_t*>(ws + align_up(static_cast<size_t>(d) * d * 2));
   bf16_t* VA = reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(KA) +
                                          align_up(static_cast<size_t>(k_per_user ? q.B : 1) * m * d * 2));
-  PackArgs p{};
-  p.Wq = static_cast<const bf16_t*>(q.Wq), p.Ksrc = static_cast<const bf16_t*>(q.Ksrc);
-  p.Wk = static_cast<const bf16_t*>(q.Wk), p.Vsrc = static_cast<const bf16_t*>(q.Vsrc);
-  p.Wv = static_cast<const bf16_t*>(q.Wv);
-  p.WqA = WqA, p.KA = KA, p.VA = VA;
-  p.k_user_stride = q.k_user_stride, p.v_user_stride = q.v_user_stride;
-  p.d = d, p.dh = dh, p.m = m;
-  p.k_users = k_per_user ? q.B : 1, p.v_users = v_per_user ? q.B : 1;
-  p.wq_blocks = (d * d + 255) / 256;
-  p.k_blocks = static_cast<int>((static_cast<int64_t>(p.k_users) * m * d + 255) / 256);
-  const int v_blocks = static_cast<int>((static_cast<int64_t>(p.v_users) * m * d + 255) / 256);
-  hipLaunchKernelGGL(pack_kernel, dim3(p.wq_blocks + p.k_blocks + v_blocks), dim3(256), 0, s, p);
-  hipError_t e = hipGetLastError();
+  PackWeight wjob{q.Wq, WqA};
+  PackProject pjobs[2] = {{q.Ksrc, q.Wk, KA, q.k_user_stride, k_per_user ? q.B : 1, kPackKeys},
+                          {q.Vsrc, q.Wv, VA, q.v_user_stride, v_per_user ? q.B : 1, kPackValues}};
+  hipError_t e = pack_operands(&wjob, 1, pjobs, 2, d, h, m, s);
   if (e != hipSuccess) return e;
 
   MainArgs a{};
@@ -307,7 +269,10 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
   a.B = q.B, a.rows = q.rows, a.tiles_per_user = (q.rows + 31) / 32;
   a.total_tiles = static_cast<int64_t>(a.tiles_per_user) * q.B;
   a.scale = q.scale, a.inv_norm = 1.f / static_cast<float>(m);
-  const int grid = static_cast<int>(a.total_tiles < 512 ? a.total_tiles : 512);
+  // one resident workgroup per compute unit when the kernel needs most of the register file,
+  // two when its footprint is small (d/h = 32)
+  const int64_t resident = static_cast<int64_t>(compute_units()) * (dh == 32 && h <= 4 ? 2 : 1);
+  const int grid = static_cast<int>(a.total_tiles < resident ? a.total_tiles : resident);
   profile_begin(kKernelQueriesOverLinks, s);
   e = dh == 32 ? dispatch_h<32>(a, h, m, q.phi, grid, s) : dispatch_h<64>(a, h, m, q.phi, grid, s);
   profile_end(kKernelQueriesOverLinks, s);

@@ -1,0 +1,353 @@
+// User-side link personalisation on the matrix cores: the m links attend over the N history
+// rows, by softmax (Eq. 3) or by the target-to-source half of XORA, O[T] (Eq. 7, phi = SiLU/n_s).
+//
+// Design: one fused pass over E.  A workgroup has one wavefront per head and owns a chunk of one
+// user's history; wave a keeps the head-a slices of W_K^T and W_V and the projected link queries
+// Q~_a in fragment form (W_K^T in LDS when d = 256, otherwise in registers) and walks its chunk in
+// tiles of 32 items.  Per tile, with X = the 32 history rows read row-major as stored:
+//   K~^T (d/h x 32) = W_K,a^T . X^T     X is the B operand
+//   V~   (32 x d/h) = X . W_V,a         the same X registers are the A operand
+//   S^T  (32 x m)   = K~ . Q~_a^T       A operand = accumulators of the first product
+//   L^P^T(d/h x m) += V~^T . phi(S)^T   both operands are accumulators (of the 2nd and 3rd product)
+// so the projected keys and values never leave registers.  Each lane owns one link (column of
+// S^T and of L^P^T): the running softmax maximum, the running sum and the rescaling of the
+// accumulator are all lane-local, plus one exchange with lane ^ 32.  Rows at or beyond lens[b] are
+// replaced by zeros as they are loaded and masked out of phi, so their content is never used.
+// Every chunk writes an un-normalised partial (max, sum, accumulator); a small merge kernel
+// combines the chunks of a user in a fixed order (deterministic) and writes L^P.
+#include "mfma.hpp"
+
+namespace lime {
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct HistArgs {
+  const bf16_t* E;
+  const int32_t* lens;
+  const bf16x8 *WkA, *WvB, *QB;
+  int64_t qb_user_frags;  // size of one user's query image in bf16x8 units (0 = shared links)
+  float* part_acc;        // [B][chunks][h][m][dh]
+  float* part_ml;         // [B][chunks][h][m][2]  (running max, running sum)
+  int N, chunk_items, chunks;
+  float scale;
+};
+
+template <int DH, int M, int H, int PHI, bool WK_LDS>
+__global__ __launch_bounds__(64 * H) void links_over_history_kernel(HistArgs a) {
+  constexpr int D = DH * H;
+  constexpr int K1 = D / 16, MB = DH / 32;  // projections: k-steps over d, blocks over d/h
+  constexpr int K2 = DH / 16, LB = M / 32;  // scores: k-steps over d/h, blocks over links
+  extern __shared__ bf16x8 lds_wk[];
+  const int lane = threadIdx.x & 63, head = threadIdx.x >> 6;
+  const int n = lane & 31, g = lane >> 5;
+  const int b = blockIdx.y, chunk = blockIdx.x;
+  const int len = a.lens ? min(a.lens[b], a.N) : a.N;
+  const int i_begin = chunk * a.chunk_items;
+  if (i_begin >= len) return;  // uniform over the workgroup: nothing for this chunk
+  const int i_end = min(len, i_begin + a.chunk_items);
+
+  bf16x8 wk[WK_LDS ? 1 : K1][WK_LDS ? 1 : MB];
+  if (WK_LDS) {
+    for (int i = threadIdx.x; i < H * K1 * MB * 64; i += 64 * H) lds_wk[i] = a.WkA[i];
+    __syncthreads();
+  } else {
+#pragma unroll
+    for (int kk = 0; kk < K1; ++kk)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) wk[kk][mb] = a.WkA[((head * K1 + kk) * MB + mb) * 64 + lane];
+  }
+  bf16x8 wv[K1][MB];
+#pragma unroll
+  for (int kk = 0; kk < K1; ++kk)
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) wv[kk][mb] = a.WvB[((head * K1 + kk) * MB + mb) * 64 + lane];
+  bf16x8 qb[K2][LB];
+  {
+    const bf16x8* src = a.QB + b * a.qb_user_frags + static_cast<int64_t>(head) * K2 * LB * 64;
+#pragma unroll
+    for (int kk = 0; kk < K2; ++kk)
+#pragma unroll
+      for (int lb = 0; lb < LB; ++lb) qb[kk][lb] = src[(kk * LB + lb) * 64 + lane];
+  }
+
+  f32x16 acc[MB][LB];
+  float run_max[LB], run_sum[LB];
+#pragma unroll
+  for (int lb = 0; lb < LB; ++lb) {
+    run_max[lb] = -INFINITY;
+    run_sum[lb] = 0.f;
+#pragma unroll
+    for (int ob = 0; ob < MB; ++ob)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[ob][lb][i] = 0.f;
+  }
+
+  const bf16_t* Eb = a.E + static_cast<int64_t>(b) * a.N * D;
+  for (int i0 = i_begin; i0 < i_end; i0 += 32) {
+    const int item = i0 + n;
+    const bool live = item < i_end;
+    const bf16_t* xrow = Eb + static_cast<int64_t>(min(item, a.N - 1)) * D + 8 * g;
+
+    f32x16 d1[MB], d2[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) d1[mb][i] = d2[mb][i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < K1; ++kk) {
+      bf16x8 x = *reinterpret_cast<const bf16x8*>(xrow + 16 * kk);
+      if (!live) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) x[t] = static_cast<__bf16>(0.f);
+      }
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const bf16x8 w = WK_LDS ? lds_wk[((head * K1 + kk) * MB + mb) * 64 + lane] : wk[WK_LDS ? 0 : kk][WK_LDS ? 0 : mb];
+        d1[mb] = mfma32(w, x, d1[mb]);
+        d2[mb] = mfma32(x, wv[kk][mb], d2[mb]);
+      }
+    }
+    bf16x8 kf[K2], vf[MB][2];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      kf[2 * mb] = pack_half(d1[mb], 0);
+      kf[2 * mb + 1] = pack_half(d1[mb], 1);
+      vf[mb][0] = pack_half(d2[mb], 0);
+      vf[mb][1] = pack_half(d2[mb], 1);
+    }
+
+#pragma unroll
+    for (int lb = 0; lb < LB; ++lb) {
+      f32x16 sc;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sc[i] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < K2; ++kk) sc = mfma32(kf[kk], qb[kk][lb], sc);
+      // register 4j + r of this lane is item i0 + 8j + 4g + r
+      if (PHI == kPhiSoftmax) {
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const bool ok = i0 + 8 * (i >> 2) + 4 * g + (i & 3) < i_end;
+          sc[i] = ok ? sc[i] * a.scale : -INFINITY;
+          tmax = fmaxf(tmax, sc[i]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float new_max = fmaxf(run_max[lb], tmax);  // finite: the tile holds at least one valid item
+        const float alpha = __builtin_amdgcn_exp2f((run_max[lb] - new_max) * kLog2e);
+        float psum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          sc[i] = __builtin_amdgcn_exp2f((sc[i] - new_max) * kLog2e);
+          psum += sc[i];
+        }
+        run_sum[lb] = run_sum[lb] * alpha + psum;
+        run_max[lb] = new_max;
+#pragma unroll
+        for (int ob = 0; ob < MB; ++ob)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[ob][lb][i] *= alpha;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const bool ok = i0 + 8 * (i >> 2) + 4 * g + (i & 3) < i_end;
+          const float s = sc[i] * a.scale;
+          sc[i] = ok ? s / (1.f + __builtin_amdgcn_exp2f(-s * kLog2e)) : 0.f;
+        }
+      }
+      const bf16x8 p0 = pack_half(sc, 0), p1 = pack_half(sc, 1);
+#pragma unroll
+      for (int ob = 0; ob < MB; ++ob) {
+        acc[ob][lb] = mfma32(vf[ob][0], p0, acc[ob][lb]);
+        acc[ob][lb] = mfma32(vf[ob][1], p1, acc[ob][lb]);
+      }
+    }
+  }
+
+  // partials: lane (link n of block lb) holds head columns 32ob + 8j + 4g + r in register 4j + r
+  const int64_t slot = (static_cast<int64_t>(b) * a.chunks + chunk) * H + head;
+#pragma unroll
+  for (int lb = 0; lb < LB; ++lb) {
+    const int link = 32 * lb + n;
+    float* dst = a.part_acc + (slot * M + link) * DH + 4 * g;
+#pragma unroll
+    for (int ob = 0; ob < MB; ++ob)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float4 v = make_float4(acc[ob][lb][4 * j], acc[ob][lb][4 * j + 1], acc[ob][lb][4 * j + 2], acc[ob][lb][4 * j + 3]);
+        *reinterpret_cast<float4*>(dst + 32 * ob + 8 * j) = v;
+      }
+    const float total = run_sum[lb] + __shfl_xor(run_sum[lb], 32);
+    if (g == 0) {
+      float* ml = a.part_ml + (slot * M + link) * 2;
+      ml[0] = run_max[lb];
+      ml[1] = total;
+    }
+  }
+}
+
+struct MergeArgs {
+  const float* part_acc;
+  const float* part_ml;
+  const int32_t* lens;
+  bf16_t* LP;
+  int N, chunk_items, chunks, h, m, dh;
+};
+
+// One thread per output element LP[b][link][a dh + t]; chunks are combined in ascending order.
+template <int PHI>
+__global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
+  const int b = blockIdx.y;
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  const int d = a.h * a.dh;
+  if (idx >= a.m * d) return;
+  const int link = idx / d, col = idx % d, head = col / a.dh, t = col % a.dh;
+  const int len = a.lens ? min(a.lens[b], a.N) : a.N;
+  const int used = (len + a.chunk_items - 1) / a.chunk_items;  // chunks that hold at least one valid item
+  float out = 0.f;
+  if (used > 0) {
+    const int64_t stride = static_cast<int64_t>(a.h) * a.m;  // (head, link) slots per chunk
+    const int64_t first = (static_cast<int64_t>(b) * a.chunks * a.h + head) * a.m + link;
+    if (PHI == kPhiSoftmax) {
+      float gmax = -INFINITY;
+      for (int c = 0; c < used; ++c) gmax = fmaxf(gmax, a.part_ml[(first + c * stride) * 2]);
+      float num = 0.f, den = 0.f;
+      for (int c = 0; c < used; ++c) {
+        const int64_t s = first + c * stride;
+        const float w = __builtin_amdgcn_exp2f((a.part_ml[s * 2] - gmax) * kLog2e);
+        num = fmaf(w, a.part_acc[s * a.dh + t], num);
+        den = fmaf(w, a.part_ml[s * 2 + 1], den);
+      }
+      out = num / den;
+    } else {
+      float num = 0.f;
+      for (int c = 0; c < used; ++c) num += a.part_acc[(first + c * stride) * a.dh + t];
+      out = num / static_cast<float>(len);
+    }
+  }
+  store_as(a.LP + (static_cast<int64_t>(b) * a.m + link) * d + col, out);
+}
+
+int compute_units() {
+  static const int n = [] {
+    int dev = 0, cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0)
+      cu = 256;
+    return cu;
+  }();
+  return n;
+}
+
+template <int DH, int M, int H, int PHI>
+hipError_t launch_phi(const HistArgs& a, dim3 grid, hipStream_t s) {
+  constexpr bool kWkLds = DH * H >= 256;
+  constexpr size_t lds = kWkLds ? static_cast<size_t>(DH) * H * DH * H * 2 : 0;
+  auto kernel = links_over_history_kernel<DH, M, H, PHI, kWkLds>;
+  if (lds > 64 * 1024) {
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (attr != hipSuccess) return attr;
+  }
+  hipLaunchKernelGGL(kernel, grid, dim3(64 * H), lds, s, a);
+  return hipGetLastError();
+}
+
+template <int DH, int M, int H>
+hipError_t launch_main(const HistArgs& a, int phi, dim3 grid, hipStream_t s) {
+  return phi == kPhiSoftmax ? launch_phi<DH, M, H, kPhiSoftmax>(a, grid, s) : launch_phi<DH, M, H, kPhiSilu>(a, grid, s);
+}
+
+template <int DH, int H>
+hipError_t dispatch_m(const HistArgs& a, int links, int phi, dim3 grid, hipStream_t s) {
+  switch (links) {
+    case 32: return launch_main<DH, 32, H>(a, phi, grid, s);
+    case 64: return launch_main<DH, 64, H>(a, phi, grid, s);
+    case 96: return launch_main<DH, 96, H>(a, phi, grid, s);
+    case 128: return launch_main<DH, 128, H>(a, phi, grid, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <int DH>
+hipError_t dispatch_h(const HistArgs& a, int h, int links, int phi, dim3 grid, hipStream_t s) {
+  switch (h) {
+    case 1: return dispatch_m<DH, 1>(a, links, phi, grid, s);
+    case 2: return dispatch_m<DH, 2>(a, links, phi, grid, s);
+    case 4: return dispatch_m<DH, 4>(a, links, phi, grid, s);
+    case 8: if (DH == 32) return dispatch_m<32, 8>(a, links, phi, grid, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+struct Layout {
+  int chunk_items, chunks;
+  size_t wk, wv, qb, acc, ml, total;
+};
+
+Layout plan(int B, int N, int d, int h, int m, bool q_per_user) {
+  Layout l{};
+  const int tiles = (N + 31) / 32;
+  // aim at about one chunk per compute unit, at least two tiles per chunk so that the cost of
+  // fetching the stationary operands is shared
+  int chunk_tiles = static_cast<int>((static_cast<int64_t>(B) * tiles + compute_units() - 1) / compute_units());
+  if (chunk_tiles < 2) chunk_tiles = 2;
+  if (chunk_tiles > tiles) chunk_tiles = tiles;
+  l.chunk_items = chunk_tiles * 32;
+  l.chunks = (tiles + chunk_tiles - 1) / chunk_tiles;
+  l.wk = l.wv = align_up(static_cast<size_t>(d) * d * 2);
+  l.qb = align_up(static_cast<size_t>(q_per_user ? B : 1) * m * d * 2);
+  l.acc = align_up(static_cast<size_t>(B) * l.chunks * m * d * sizeof(float));
+  l.ml = align_up(static_cast<size_t>(B) * l.chunks * h * m * 2 * sizeof(float));
+  l.total = l.wk + l.wv + l.qb + l.acc + l.ml;
+  return l;
+}
+
+}  // namespace
+
+bool links_over_history_supported(int d, int h, int m) { return queries_over_links_supported(d, h, m); }
+
+size_t links_over_history_workspace(int B, int N, int d, int h, int m, bool q_per_user) {
+  return plan(B, N, d, h, m, q_per_user).total;
+}
+
+hipError_t links_over_history(const LinksOverHistory& q, void* workspace, hipStream_t s) {
+  const int d = q.d, h = q.h, m = q.m, dh = d / h;
+  const bool per_user = q.lc_user_stride != 0;
+  const Layout l = plan(q.B, q.N, d, h, m, per_user);
+  char* ws = static_cast<char*>(workspace);
+  void* WkA = ws;
+  void* WvB = ws + l.wk;
+  void* QB = ws + l.wk + l.wv;
+  float* part_acc = reinterpret_cast<float*>(ws + l.wk + l.wv + l.qb);
+  float* part_ml = reinterpret_cast<float*>(ws + l.wk + l.wv + l.qb + l.acc);
+
+  PackWeight wjobs[2] = {{q.Wk, WkA}, {q.Wv, WvB}};
+  PackProject pjob{q.LC, q.Wq, QB, q.lc_user_stride, per_user ? q.B : 1, kPackKeys};
+  hipError_t e = pack_operands(wjobs, 2, &pjob, 1, d, h, m, s);
+  if (e != hipSuccess) return e;
+
+  HistArgs a{};
+  a.E = static_cast<const bf16_t*>(q.E), a.lens = q.lens;
+  a.WkA = static_cast<const bf16x8*>(WkA), a.WvB = static_cast<const bf16x8*>(WvB);
+  a.QB = static_cast<const bf16x8*>(QB);
+  a.qb_user_frags = per_user ? static_cast<int64_t>(m) * d / 8 : 0;
+  a.part_acc = part_acc, a.part_ml = part_ml;
+  a.N = q.N, a.chunk_items = l.chunk_items, a.chunks = l.chunks, a.scale = q.scale;
+  const dim3 grid(l.chunks, q.B);
+  profile_begin(kKernelLinksOverHistory, s);
+  e = dh == 32 ? dispatch_h<32>(a, h, m, q.phi, grid, s) : dispatch_h<64>(a, h, m, q.phi, grid, s);
+  profile_end(kKernelLinksOverHistory, s);
+  if (e != hipSuccess) return e;
+
+  MergeArgs g{part_acc, part_ml, q.lens, static_cast<bf16_t*>(q.LP), q.N, l.chunk_items, l.chunks, h, m, dh};
+  const dim3 mgrid((m * d + 255) / 256, q.B);
+  if (q.phi == kPhiSoftmax)
+    hipLaunchKernelGGL(merge_kernel<kPhiSoftmax>, mgrid, dim3(256), 0, s, g);
+  else
+    hipLaunchKernelGGL(merge_kernel<kPhiSilu>, mgrid, dim3(256), 0, s, g);
+  return hipGetLastError();
+}
+
+}  // namespace lime

@@ -1,0 +1,149 @@
+// Operand packing for the matrix-core kernels: weight matrices and the small projected link
+// matrices (m rows) are written once per call in MFMA fragment order.
+#include "mfma.hpp"
+
+namespace lime {
+namespace {
+
+constexpr int kPackRows = 4;  // rows of X per block of a projection job
+constexpr int kMaxJobs = 2;
+
+struct PackArgs {
+  const bf16_t* w_src[kMaxJobs];
+  bf16x8* w_img[kMaxJobs];
+  const bf16_t* p_x[kMaxJobs];
+  const bf16_t* p_w[kMaxJobs];
+  bf16_t* p_img[kMaxJobs];
+  int64_t p_stride[kMaxJobs];
+  int p_layout[kMaxJobs];
+  int p_first_block[kMaxJobs + 1];  // block ranges of the projection jobs, after the weight jobs
+  int n_weights, blocks_per_weight;
+  int d, dh, m;
+};
+
+// Where element (row, col) of a projected [m][d] matrix goes in its fragment image (bf16 units).
+__device__ __forceinline__ int64_t keys_slot(int u, int row, int col, int d, int dh, int m) {
+  const int a = col / dh, c = col % dh, kk = c / 16, kin = c % 16;
+  const int64_t frag = ((static_cast<int64_t>(u) * (d / dh) + a) * (dh / 16) + kk) * (m / 32) + row / 32;
+  return (frag * 64 + 32 * chain_g(kin) + row % 32) * 8 + chain_t(kin);
+}
+__device__ __forceinline__ int64_t values_slot(int u, int row, int col, int d, int dh, int m) {
+  const int a = col / dh, c = col % dh, kk = row / 16, kin = row % 16;
+  const int64_t frag = ((static_cast<int64_t>(u) * (d / dh) + a) * (m / 16) + kk) * (dh / 32) + c / 32;
+  return (frag * 64 + 32 * chain_g(kin) + out_rho(c % 32)) * 8 + chain_t(kin);
+}
+
+__global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
+  extern __shared__ float smem[];
+  const int d = p.d, dh = p.dh, m = p.m, tid = threadIdx.x;
+  int blk = blockIdx.x;
+  if (blk < p.n_weights * p.blocks_per_weight) {
+    // one thread per (8 consecutive k, column): a 16-byte slot of the weight image
+    const int job = blk / p.blocks_per_weight;
+    const int idx = (blk % p.blocks_per_weight) * 256 + tid;
+    if (idx >= d * d / 8) return;
+    const bf16_t* W = p.w_src[job];
+    const int col = idx % d, k0 = (idx / d) * 8;
+    bf16x8 v;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const float x = W ? to_float(W[static_cast<int64_t>(k0 + t) * d + col]) : (k0 + t == col ? 1.f : 0.f);
+      v[t] = static_cast<__bf16>(x);
+    }
+    const int a = col / dh, c = col % dh, mb = c / 32, n = c % 32;
+    const int kk = k0 / 16, g = (k0 % 16) / 8;
+    const int64_t frag = (static_cast<int64_t>(a) * (d / 16) + kk) * (dh / 32) + mb;
+    p.w_img[job][frag * 64 + 32 * g + n] = v;
+    return;
+  }
+  blk -= p.n_weights * p.blocks_per_weight;
+  const int job = blk >= p.p_first_block[1] ? 1 : 0;
+  blk -= p.p_first_block[job];
+  const int groups = m / kPackRows;  // m is a multiple of 32
+  const int u = blk / groups, row0 = (blk % groups) * kPackRows;
+  const bf16_t* X = p.p_x[job] + u * p.p_stride[job] + static_cast<int64_t>(row0) * d;
+  const bf16_t* W = p.p_w[job];
+
+  // kPackRows rows of X times W: thread (cg, kc) owns 8 adjacent columns and every nkc-th k;
+  // the partial sums meet in LDS.
+  float* xs = smem;                    // [kPackRows][d]
+  float* out = xs + kPackRows * d;     // [kPackRows][d]
+  float* red = out + kPackRows * d;    // [nkc][kPackRows][d]
+  for (int i = tid; i < kPackRows * d; i += 256) xs[i] = to_float(X[i]);
+  __syncthreads();
+  if (W == nullptr) {
+    for (int i = tid; i < kPackRows * d; i += 256) out[i] = xs[i];
+  } else {
+    const int CG = d / 8, nkc = 256 / CG;
+    const int cg = tid % CG, kc = tid / CG;
+    float acc[kPackRows][8];
+#pragma unroll
+    for (int r = 0; r < kPackRows; ++r)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[r][j] = 0.f;
+#pragma unroll 16
+    for (int k = kc; k < d; k += nkc) {
+      const bf16x8 w = *reinterpret_cast<const bf16x8*>(W + static_cast<int64_t>(k) * d + 8 * cg);
+#pragma unroll
+      for (int r = 0; r < kPackRows; ++r) {
+        const float x = xs[r * d + k];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[r][j] = fmaf(x, static_cast<float>(w[j]), acc[r][j]);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < kPackRows; ++r)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) red[(kc * kPackRows + r) * d + 8 * cg + j] = acc[r][j];
+    __syncthreads();
+    for (int i = tid; i < kPackRows * d; i += 256) {
+      float sum = 0.f;
+      for (int c = 0; c < nkc; ++c) sum += red[c * kPackRows * d + i];
+      out[i] = sum;
+    }
+  }
+  __syncthreads();
+  bf16_t* img = p.p_img[job];
+  const bool keys = p.p_layout[job] == kPackKeys;
+  for (int i = tid; i < kPackRows * d; i += 256) {
+    const int row = row0 + i / d, col = i % d;
+    store_as(img + (keys ? keys_slot(u, row, col, d, dh, m) : values_slot(u, row, col, d, dh, m)), out[i]);
+  }
+}
+
+}  // namespace
+
+hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackProject* projections, int n_projections,
+                         int d, int h, int m, hipStream_t s) {
+  if (n_weights > kMaxJobs || n_projections > kMaxJobs) return hipErrorInvalidValue;
+  PackArgs p{};
+  p.d = d, p.dh = d / h, p.m = m;
+  p.n_weights = n_weights;
+  p.blocks_per_weight = (d * d / 8 + 255) / 256;
+  for (int i = 0; i < n_weights; ++i) {
+    p.w_src[i] = static_cast<const bf16_t*>(weights[i].W);
+    p.w_img[i] = static_cast<bf16x8*>(weights[i].image);
+  }
+  int blocks = 0;
+  for (int i = 0; i < kMaxJobs; ++i) {
+    p.p_first_block[i] = blocks;
+    if (i < n_projections) {
+      p.p_x[i] = static_cast<const bf16_t*>(projections[i].X);
+      p.p_w[i] = static_cast<const bf16_t*>(projections[i].W);
+      p.p_img[i] = static_cast<bf16_t*>(projections[i].image);
+      p.p_stride[i] = projections[i].user_stride;
+      p.p_layout[i] = projections[i].layout;
+      blocks += projections[i].users * (m / kPackRows);
+    }
+  }
+  p.p_first_block[kMaxJobs] = blocks;
+  if (n_projections < 2) p.p_first_block[1] = 0x7fffffff;
+  const int nkc = 256 / (d / 8);
+  const size_t lds = static_cast<size_t>(2 + nkc) * kPackRows * d * sizeof(float);
+  const int grid = n_weights * p.blocks_per_weight + blocks;
+  if (grid == 0) return hipSuccess;
+  hipLaunchKernelGGL(pack_kernel, dim3(grid), dim3(256), lds, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace lime
