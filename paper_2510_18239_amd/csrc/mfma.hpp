@@ -65,6 +65,7 @@ struct PackProject {
   int64_t user_stride;  // elements between users in X
   int users;
   int layout;      // kPackKeys or kPackValues
+  float sign;      // +1 or -1: multiplies every projected element (exact); lets kernels assume scale >= 0
 };
 hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackProject* projections, int n_projections,
                          int d, int h, int m, hipStream_t s);

@@ -5,7 +5,7 @@
 // per head.  Wave a keeps, as MFMA A-operand fragments in its registers, the head-a slices of
 // W_Q^T (d/h x d), of the projected keys K~ (m x d/h) and of the projected values V~^T (d/h x m).
 // For each tile of 32 query rows it chains three contractions without leaving registers:
-//   Q~^T (d/h x 32) = W_Q,a^T  . X^T        X rows are the B operand, read row-major as stored
+//   Q~^T (d/h x 32) = W_Q,a^T  . X^T        X rows are the B operand (staged once per tile through LDS)
 //   S^T  (m   x 32) = K~_a     . Q~^T       B operand = the accumulators of the first product
 //   O^T  (d/h x 32) = V~_a^T   . phi(S)^T   B operand = the accumulators of the second product
 // Every lane owns one query row (column of the transposed products), so the softmax over the m
@@ -26,8 +26,7 @@ struct MainArgs {
   const bf16x8 *WqA, *KA, *VA;
   int64_t ka_user_frags, va_user_frags;  // fragment-image size per user (0 = shared), in bf16x8 units
   const int32_t* row_lens;
-  int B, rows, tiles_per_user;
-  int64_t total_tiles;
+  int B, rows, tiles_per_user, total_tiles;
   float scale, inv_norm;
 };
 
@@ -37,150 +36,241 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   constexpr int K1 = D / 16, MB = DH / 32;   // first product: k-steps over d, row blocks over d/h
   constexpr int K2 = DH / 16, LB = M / 32;   // second: k-steps over d/h, row blocks over links
   constexpr int K3 = M / 16;                 // third: k-steps over links, row blocks over d/h (MB)
+  // A tile is 32 consecutive rows of X = 64 D contiguous bytes.  The H waves copy it cooperatively:
+  // each wave issues LW loads of 1 KiB (16 bytes per lane, fully coalesced) into a register ring that
+  // keeps P tiles in flight per workgroup (besides the two tiles parked in LDS), then parks the tile in LDS (row pitch padded by 16 bytes
+  // so that the fragment reads are free of bank conflicts) where all H waves read it.
+  constexpr int P = 2;
+  constexpr int LW = DH / 16;
+  // With d = 256 the W_Q^T slice alone is half of the register file; the second half of its k-steps
+  // lives in LDS instead (read once per tile), which keeps the kernel free of register spills.
+  constexpr int KL = D >= 256 ? K1 / 2 : 0;  // k-steps of W_Q^T kept in LDS
+  constexpr int KR = K1 - KL;                // k-steps kept in registers
+  constexpr int CPR = D / 8;            // 16-byte chunks per row of X
+  constexpr int PITCH = 2 * D + 16;     // LDS row pitch of an X tile, bytes
+  constexpr int OCPR = DH / 8;          // 16-byte chunks per row of one head's output slice
+  constexpr int OPITCH = 2 * DH + 16;   // LDS row pitch of a wave's output tile, bytes
+  __shared__ __attribute__((aligned(16))) unsigned char xs[2][32 * PITCH];
+  __shared__ __attribute__((aligned(16))) unsigned char os[H][32 * OPITCH];
+  __shared__ bf16x8 wq_lds[KL > 0 ? H * KL * MB * 64 : 1];
   const int lane = threadIdx.x & 63, head = threadIdx.x >> 6;
   const int n = lane & 31, g = lane >> 5;
+  const int64_t total_rows = static_cast<int64_t>(a.B) * a.rows;
+  // Each workgroup owns a contiguous run of tiles (neighbouring rows share pages and DRAM rows).
+  const int per_wg = (a.total_tiles + gridDim.x - 1) / gridDim.x;
+  const int first = blockIdx.x * per_wg;
+  const int last = min(first + per_wg, a.total_tiles);  // one past this workgroup's final tile
+  if (first >= last) return;  // uniform
 
-  bf16x8 wq[K1][MB];
+  // Rows past a user's last row are read from whatever follows (the next user's rows; zeros past the
+  // end of the tensor): every row is an independent column of the three products and such columns
+  // are never stored.
+  auto issue = [&](int tile, bf16x8 (&r)[LW]) {
+    const int tb = tile / a.tiles_per_user;
+    const int64_t row0 = static_cast<int64_t>(tb) * a.rows + (tile - tb * a.tiles_per_user) * 32;
 #pragma unroll
-  for (int kk = 0; kk < K1; ++kk)
+    for (int j = 0; j < LW; ++j) {
+      const int q = (head * LW + j) * 64 + lane;
+      const int64_t row = row0 + q / CPR;
+      bf16x8 v;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = static_cast<__bf16>(0.f);
+      if (row < total_rows) v = *reinterpret_cast<const bf16x8*>(a.X + row * D + (q % CPR) * 8);
+      r[j] = v;
+    }
+  };
+  auto park = [&](const bf16x8 (&r)[LW], unsigned char* buf) {
+#pragma unroll
+    for (int j = 0; j < LW; ++j) {
+      const int q = (head * LW + j) * 64 + lane;
+      *reinterpret_cast<bf16x8*>(buf + (q / CPR) * PITCH + (q % CPR) * 16) = r[j];
+    }
+  };
+
+  bf16x8 ring[P][LW];
+#pragma unroll
+  for (int p = 0; p < P; ++p)
+    if (first + p < last) issue(first + p, ring[p]);
+
+  bf16x8 wq[KR][MB];
+#pragma unroll
+  for (int kk = 0; kk < KR; ++kk)
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) wq[kk][mb] = a.WqA[((head * K1 + kk) * MB + mb) * 64 + lane];
-
-  bf16x8 ka[K2][LB], va[K3][MB];
-  int cur_user = -1;
-
-  // The X fragments of the next tile are requested before the current tile is computed, so the
-  // memory latency hides behind the MFMA work of the one wavefront a SIMD holds.
-  auto x_row_ptr = [&](int64_t tile) {
-    const int b = static_cast<int>(tile / a.tiles_per_user);
-    const int row = static_cast<int>(tile % a.tiles_per_user) * 32 + n;
-    // rows past the end are clamped for the load; their columns of the products are never stored
-    return a.X + (static_cast<int64_t>(b) * a.rows + min(row, a.rows - 1)) * D + 8 * g;
-  };
-  bf16x8 xn[K1];
-  if (blockIdx.x < a.total_tiles) {
-    const bf16_t* xrow = x_row_ptr(blockIdx.x);
+  if constexpr (KL > 0) {
+    bf16x8 tmp[KL * MB];
 #pragma unroll
-    for (int kk = 0; kk < K1; ++kk) xn[kk] = *reinterpret_cast<const bf16x8*>(xrow + 16 * kk);
+    for (int i = 0; i < KL * MB; ++i) tmp[i] = a.WqA[((head * K1 + KR) * MB + i) * 64 + lane];
+#pragma unroll
+    for (int i = 0; i < KL * MB; ++i) wq_lds[(head * KL * MB + i) * 64 + lane] = tmp[i];
+    // each wave reads back only what it wrote itself: no barrier needed
   }
 
-  for (int64_t tile = blockIdx.x; tile < a.total_tiles; tile += gridDim.x) {
-    const int b = static_cast<int>(tile / a.tiles_per_user);
-    const int r0 = static_cast<int>(tile % a.tiles_per_user) * 32;
-    if (b != cur_user) {
-      if (cur_user < 0 || a.ka_user_frags != 0) {
-        const bf16x8* src = a.KA + b * a.ka_user_frags + static_cast<int64_t>(head) * K2 * LB * 64;
-#pragma unroll
-        for (int kk = 0; kk < K2; ++kk)
-#pragma unroll
-          for (int lb = 0; lb < LB; ++lb) ka[kk][lb] = src[(kk * LB + lb) * 64 + lane];
-      }
-      if (cur_user < 0 || a.va_user_frags != 0) {
-        const bf16x8* src = a.VA + b * a.va_user_frags + static_cast<int64_t>(head) * K3 * MB * 64;
-#pragma unroll
-        for (int kk = 0; kk < K3; ++kk)
-#pragma unroll
-          for (int mb = 0; mb < MB; ++mb) va[kk][mb] = src[(kk * MB + mb) * 64 + lane];
-      }
-      cur_user = b;
-    }
-    const int row = r0 + n;
-    const int rlen = a.row_lens ? min(a.row_lens[b], a.rows) : a.rows;
-    bf16x8 x[K1];
-#pragma unroll
-    for (int kk = 0; kk < K1; ++kk) x[kk] = xn[kk];
-    if (tile + gridDim.x < a.total_tiles) {
-      const bf16_t* xrow = x_row_ptr(tile + gridDim.x);
-#pragma unroll
-      for (int kk = 0; kk < K1; ++kk) xn[kk] = *reinterpret_cast<const bf16x8*>(xrow + 16 * kk);
-    }
-
-    // Q~^T = Wq_a^T X^T
-    f32x16 acc1[MB];
+  // Q~^T = Wq_a^T X^T for the tile parked in `buf`; lane (n, g) reads X[row n][16kk + 8g ..]
+  f32x16 acc1[MB];
+  auto first_product = [&](const unsigned char* buf) {
+    const unsigned char* xrow = buf + n * PITCH + 16 * g;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc1[mb][i] = 0.f;
+    int wl = head * KL * MB * 64 + lane;
+    asm volatile("" : "+v"(wl));  // keeps the LDS reads of W_Q^T inside the tile loop
 #pragma unroll
     for (int kk = 0; kk < K1; ++kk) {
+      const bf16x8 x = *reinterpret_cast<const bf16x8*>(xrow + 32 * kk);
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) acc1[mb] = mfma32(wq[kk][mb], x[kk], acc1[mb]);
+      for (int mb = 0; mb < MB; ++mb) {
+        const bf16x8 w = kk < KR ? wq[kk < KR ? kk : 0][mb] : wq_lds[wl + ((kk - KR) * MB + mb) * 64];
+        acc1[mb] = mfma32(w, x, acc1[mb]);
+      }
     }
-    bf16x8 qf[K2];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-      qf[2 * mb] = pack_half(acc1[mb], 0);
-      qf[2 * mb + 1] = pack_half(acc1[mb], 1);
-    }
+  };
 
-    // S^T = K~_a Q~^T
-    f32x16 acc2[LB];
-#pragma unroll
-    for (int lb = 0; lb < LB; ++lb) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc2[lb][i] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < K2; ++kk) acc2[lb] = mfma32(ka[kk][lb], qf[kk], acc2[lb]);
-    }
-
-    // phi over the m links of this lane's query row (the other half of the links sits in lane ^ 32)
-    float inv = a.inv_norm;
+  // phi over the m links of this lane's query row (the other half of the links sits in lane ^ 32);
+  // returns the factor still to be applied to the weighted sum
+  f32x16 acc2[LB];
+  auto phi = [&]() -> float {
     if (PHI == kPhiSoftmax) {
-      float mx = -INFINITY;
+      const float c = a.scale * kLog2e;  // >= 0
+      float mx = acc2[0][0];
 #pragma unroll
       for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          acc2[lb][i] *= a.scale;
-          mx = fmaxf(mx, acc2[lb][i]);
-        }
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc2[lb][i]);
       mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float shift = -mx * c;  // exp2(raw * c + shift) = exp(scale * raw - max of the scaled logits)
       float sum = 0.f;
 #pragma unroll
       for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const float p = __builtin_amdgcn_exp2f((acc2[lb][i] - mx) * kLog2e);
-          acc2[lb][i] = p;
-          sum += p;
+          const float pr = __builtin_amdgcn_exp2f(fmaf(acc2[lb][i], c, shift));
+          acc2[lb][i] = pr;
+          sum += pr;
         }
       sum += __shfl_xor(sum, 32);
-      inv = 1.f / sum;
-    } else {
-#pragma unroll
-      for (int lb = 0; lb < LB; ++lb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float s = acc2[lb][i] * a.scale;
-          acc2[lb][i] = s / (1.f + __builtin_amdgcn_exp2f(-s * kLog2e));
-        }
+      return 1.f / sum;
     }
-    bf16x8 pf[K3];
 #pragma unroll
-    for (int lb = 0; lb < LB; ++lb) {
-      pf[2 * lb] = pack_half(acc2[lb], 0);
-      pf[2 * lb + 1] = pack_half(acc2[lb], 1);
-    }
+    for (int lb = 0; lb < LB; ++lb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float s = acc2[lb][i] * a.scale;
+        acc2[lb][i] = s / (1.f + __builtin_amdgcn_exp2f(-s * kLog2e));
+      }
+    return a.inv_norm;
+  };
 
-    // O^T = V~_a^T phi(S)^T, then the normaliser, then 16 consecutive output columns per lane and block
-    bf16_t* orow = a.O + (static_cast<int64_t>(b) * a.rows + row) * D + head * DH + 16 * g;
+  bf16x8 ka[K2][LB], va[K3][MB];
+  int cur_user = -1;
+
+  // Software pipeline: while the vector ALUs do phi of tile i, the matrix cores already run the
+  // first product of tile i+1, whose X rows were parked in the other LDS buffer.
+  park(ring[0], xs[0]);
+  __syncthreads();
+  if (first + P < last) issue(first + P, ring[0]);
+  first_product(xs[0]);
+
+  for (int base = first; base < last; base += P) {
 #pragma unroll
-    for (int ob = 0; ob < MB; ++ob) {
-      f32x16 acc3;
+    for (int p = 0; p < P; ++p) {
+      const int tile = base + p;
+      if (tile >= last) break;  // uniform over the workgroup
+      const bool has_next = tile + 1 < last;
+      const int b = tile / a.tiles_per_user;
+      const int r0 = (tile - b * a.tiles_per_user) * 32;
+      if (b != cur_user) {
+        if (cur_user < 0 || a.ka_user_frags != 0) {
+          const bf16x8* src = a.KA + b * a.ka_user_frags + static_cast<int64_t>(head) * K2 * LB * 64;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc3[i] = 0.f;
+          for (int kk = 0; kk < K2; ++kk)
 #pragma unroll
-      for (int kk = 0; kk < K3; ++kk) acc3 = mfma32(va[kk][ob], pf[kk], acc3);
-      if (row < a.rows) {
-        const bool live = row < rlen;
+            for (int lb = 0; lb < LB; ++lb) ka[kk][lb] = src[(kk * LB + lb) * 64 + lane];
+        }
+        if (cur_user < 0 || a.va_user_frags != 0) {
+          const bf16x8* src = a.VA + b * a.va_user_frags + static_cast<int64_t>(head) * K3 * MB * 64;
+#pragma unroll
+          for (int kk = 0; kk < K3; ++kk)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) va[kk][mb] = src[(kk * MB + mb) * 64 + lane];
+        }
+        cur_user = b;
+      }
+      const int rlen = a.row_lens ? min(a.row_lens[b], a.rows) : a.rows;
+
+      // S^T = K~_a Q~^T from this tile's first product
+      bf16x8 qf[K2];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        qf[2 * mb] = pack_half(acc1[mb], 0);
+        qf[2 * mb + 1] = pack_half(acc1[mb], 1);
+      }
+#pragma unroll
+      for (int lb = 0; lb < LB; ++lb) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc2[lb][i] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < K2; ++kk) acc2[lb] = mfma32(ka[kk][lb], qf[kk], acc2[lb]);
+      }
+
+      float inv;
+      if (has_next) {
+        // The buffer being overwritten was last read for the tile before this one; every wave has
+        // passed a barrier since.  The barrier below publishes the new tile.
+        unsigned char* nbuf = xs[(p + 1) & 1];
+        park(ring[(p + 1) % P], nbuf);
+        __syncthreads();
+        if (tile + P + 1 < last) issue(tile + P + 1, ring[(p + 1) % P]);
+        first_product(nbuf);
+        inv = phi();
+        // one MFMA of the next tile's first product, then a few vector-ALU operations of phi, and so on
+#pragma unroll
+        for (int i = 0; i < K1 * MB; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+        }
+      } else {
+        inv = phi();
+      }
+      bf16x8 pf[K3];
+#pragma unroll
+      for (int lb = 0; lb < LB; ++lb) {
+        pf[2 * lb] = pack_half(acc2[lb], 0);
+        pf[2 * lb + 1] = pack_half(acc2[lb], 1);
+      }
+
+      // O^T = V~_a^T phi(S)^T; lane (n, g) gets 16 consecutive columns per block.  The wave's 32 x d/h
+      // output tile goes through LDS so that whole 2*d/h-byte row segments are stored at once.
+      unsigned char* otile = os[head];
+#pragma unroll
+      for (int ob = 0; ob < MB; ++ob) {
+        f32x16 acc3;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc3[i] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < K3; ++kk) acc3 = mfma32(va[kk][ob], pf[kk], acc3);
         bf16x8 lo, hi;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-          lo[t] = static_cast<__bf16>(live ? acc3[t] * inv : 0.f);
-          hi[t] = static_cast<__bf16>(live ? acc3[8 + t] * inv : 0.f);
+          lo[t] = static_cast<__bf16>(acc3[t] * inv);
+          hi[t] = static_cast<__bf16>(acc3[8 + t] * inv);
         }
-        *reinterpret_cast<bf16x8*>(orow + 32 * ob) = lo;
-        *reinterpret_cast<bf16x8*>(orow + 32 * ob + 8) = hi;
+        unsigned char* dst = otile + n * OPITCH + (32 * ob + 16 * g) * 2;
+        *reinterpret_cast<bf16x8*>(dst) = lo;
+        *reinterpret_cast<bf16x8*>(dst + 16) = hi;
+      }
+#pragma unroll
+      for (int j = 0; j < LW; ++j) {
+        const int q = j * 64 + lane;
+        const int row = r0 + q / OCPR;
+        bf16x8 v = *reinterpret_cast<const bf16x8*>(otile + (q / OCPR) * OPITCH + (q % OCPR) * 16);
+        if (row >= rlen) {
+#pragma unroll
+          for (int t = 0; t < 8; ++t) v[t] = static_cast<__bf16>(0.f);
+        }
+        if (row < a.rows)
+          *reinterpret_cast<bf16x8*>(a.O + (static_cast<int64_t>(b) * a.rows + row) * D + head * DH + (q % OCPR) * 8) = v;
       }
     }
   }
@@ -254,8 +344,9 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
   bf16_t* VA = reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(KA) +
                                          align_up(static_cast<size_t>(k_per_user ? q.B : 1) * m * d * 2));
   PackWeight wjob{q.Wq, WqA};
-  PackProject pjobs[2] = {{q.Ksrc, q.Wk, KA, q.k_user_stride, k_per_user ? q.B : 1, kPackKeys},
-                          {q.Vsrc, q.Wv, VA, q.v_user_stride, v_per_user ? q.B : 1, kPackValues}};
+  // a negative logit scale is folded into the sign of the packed keys, so the kernel sees scale >= 0
+  PackProject pjobs[2] = {{q.Ksrc, q.Wk, KA, q.k_user_stride, k_per_user ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f},
+                          {q.Vsrc, q.Wv, VA, q.v_user_stride, v_per_user ? q.B : 1, kPackValues, 1.f}};
   hipError_t e = pack_operands(&wjob, 1, pjobs, 2, d, h, m, s);
   if (e != hipSuccess) return e;
 
@@ -267,12 +358,12 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
   a.va_user_frags = v_per_user ? static_cast<int64_t>(m) * d / 8 : 0;
   a.row_lens = q.row_lens;
   a.B = q.B, a.rows = q.rows, a.tiles_per_user = (q.rows + 31) / 32;
-  a.total_tiles = static_cast<int64_t>(a.tiles_per_user) * q.B;
-  a.scale = q.scale, a.inv_norm = 1.f / static_cast<float>(m);
+  a.total_tiles = a.tiles_per_user * q.B;  // the caller has checked that this fits an int
+  a.scale = fabsf(q.scale), a.inv_norm = 1.f / static_cast<float>(m);
   // one resident workgroup per compute unit when the kernel needs most of the register file,
   // two when its footprint is small (d/h = 32)
-  const int64_t resident = static_cast<int64_t>(compute_units()) * (dh == 32 && h <= 4 ? 2 : 1);
-  const int grid = static_cast<int>(a.total_tiles < resident ? a.total_tiles : resident);
+  const int resident = compute_units() * (dh == 32 && h <= 4 ? 2 : 1);
+  const int grid = a.total_tiles < resident ? a.total_tiles : resident;
   profile_begin(kKernelQueriesOverLinks, s);
   e = dh == 32 ? dispatch_h<32>(a, h, m, q.phi, grid, s) : dispatch_h<64>(a, h, m, q.phi, grid, s);
   profile_end(kKernelQueriesOverLinks, s);

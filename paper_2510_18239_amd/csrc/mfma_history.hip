@@ -49,7 +49,12 @@ __global__ __launch_bounds__(64 * H) void links_over_history_kernel(HistArgs a) 
 
   bf16x8 wk[WK_LDS ? 1 : K1][WK_LDS ? 1 : MB];
   if (WK_LDS) {
-    for (int i = threadIdx.x; i < H * K1 * MB * 64; i += 64 * H) lds_wk[i] = a.WkA[i];
+    // the whole W_K^T image (all heads): every thread moves K1*MB 16-byte pieces, loads first
+    bf16x8 tmp[K1 * MB];
+#pragma unroll
+    for (int it = 0; it < K1 * MB; ++it) tmp[it] = a.WkA[it * 64 * H + threadIdx.x];
+#pragma unroll
+    for (int it = 0; it < K1 * MB; ++it) lds_wk[it * 64 * H + threadIdx.x] = tmp[it];
     __syncthreads();
   } else {
 #pragma unroll
@@ -89,6 +94,11 @@ __global__ __launch_bounds__(64 * H) void links_over_history_kernel(HistArgs a) 
     const bool live = item < i_end;
     const bf16_t* xrow = Eb + static_cast<int64_t>(min(item, a.N - 1)) * D + 8 * g;
 
+    // The LDS copy of W_K^T must be re-read for every tile (that is the point of keeping it in LDS
+    // rather than in registers); an opaque base index stops the compiler from hoisting the reads.
+    int wk_base = head * K1 * MB * 64 + lane;
+    asm volatile("" : "+v"(wk_base));
+
     f32x16 d1[MB], d2[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -103,7 +113,7 @@ __global__ __launch_bounds__(64 * H) void links_over_history_kernel(HistArgs a) 
       }
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
-        const bf16x8 w = WK_LDS ? lds_wk[((head * K1 + kk) * MB + mb) * 64 + lane] : wk[WK_LDS ? 0 : kk][WK_LDS ? 0 : mb];
+        const bf16x8 w = WK_LDS ? lds_wk[wk_base + (kk * MB + mb) * 64] : wk[WK_LDS ? 0 : kk][WK_LDS ? 0 : mb];
         d1[mb] = mfma32(w, x, d1[mb]);
         d2[mb] = mfma32(x, wv[kk][mb], d2[mb]);
       }
@@ -209,20 +219,45 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
   if (used > 0) {
     const int64_t stride = static_cast<int64_t>(a.h) * a.m;  // (head, link) slots per chunk
     const int64_t first = (static_cast<int64_t>(b) * a.chunks * a.h + head) * a.m + link;
+    // all loads of a batch of chunks are issued before any is used: the partials were written by
+    // other compute units and every access is a long-latency miss
+    constexpr int kBatch = 16;
     if (PHI == kPhiSoftmax) {
-      float gmax = -INFINITY;
-      for (int c = 0; c < used; ++c) gmax = fmaxf(gmax, a.part_ml[(first + c * stride) * 2]);
-      float num = 0.f, den = 0.f;
-      for (int c = 0; c < used; ++c) {
-        const int64_t s = first + c * stride;
-        const float w = __builtin_amdgcn_exp2f((a.part_ml[s * 2] - gmax) * kLog2e);
-        num = fmaf(w, a.part_acc[s * a.dh + t], num);
-        den = fmaf(w, a.part_ml[s * 2 + 1], den);
+      float gmax = -INFINITY, num = 0.f, den = 0.f;
+      for (int c0 = 0; c0 < used; c0 += kBatch) {
+        float mx[kBatch], sm[kBatch], ac[kBatch];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+          const int64_t s = first + static_cast<int64_t>(min(c0 + i, used - 1)) * stride;
+          mx[i] = a.part_ml[s * 2];
+          sm[i] = a.part_ml[s * 2 + 1];
+          ac[i] = a.part_acc[s * a.dh + t];
+        }
+        float bmax = gmax;
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) bmax = fmaxf(bmax, mx[i]);
+        const float keep = __builtin_amdgcn_exp2f((gmax - bmax) * kLog2e);  // 0 on the first batch
+        num *= keep;
+        den *= keep;
+        gmax = bmax;
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+          const float w = c0 + i < used ? __builtin_amdgcn_exp2f((mx[i] - gmax) * kLog2e) : 0.f;
+          num = fmaf(w, ac[i], num);
+          den = fmaf(w, sm[i], den);
+        }
       }
       out = num / den;
     } else {
       float num = 0.f;
-      for (int c = 0; c < used; ++c) num += a.part_acc[(first + c * stride) * a.dh + t];
+      for (int c0 = 0; c0 < used; c0 += kBatch) {
+        float ac[kBatch];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i)
+          ac[i] = a.part_acc[(first + static_cast<int64_t>(min(c0 + i, used - 1)) * stride) * a.dh + t];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) num += c0 + i < used ? ac[i] : 0.f;
+      }
       out = num / static_cast<float>(len);
     }
   }
@@ -324,7 +359,7 @@ hipError_t links_over_history(const LinksOverHistory& q, void* workspace, hipStr
   float* part_ml = reinterpret_cast<float*>(ws + l.wk + l.wv + l.qb + l.acc);
 
   PackWeight wjobs[2] = {{q.Wk, WkA}, {q.Wv, WvB}};
-  PackProject pjob{q.LC, q.Wq, QB, q.lc_user_stride, per_user ? q.B : 1, kPackKeys};
+  PackProject pjob{q.LC, q.Wq, QB, q.lc_user_stride, per_user ? q.B : 1, kPackKeys, 1.f};
   hipError_t e = pack_operands(wjobs, 2, &pjob, 1, d, h, m, s);
   if (e != hipSuccess) return e;
 

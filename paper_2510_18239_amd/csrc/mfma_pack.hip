@@ -5,7 +5,7 @@
 namespace lime {
 namespace {
 
-constexpr int kPackRows = 4;  // rows of X per block of a projection job
+constexpr int kPackRows = 1;  // rows of X per block of a projection job (more blocks, shorter critical path)
 constexpr int kMaxJobs = 2;
 
 struct PackArgs {
@@ -16,6 +16,7 @@ struct PackArgs {
   bf16_t* p_img[kMaxJobs];
   int64_t p_stride[kMaxJobs];
   int p_layout[kMaxJobs];
+  float p_sign[kMaxJobs];
   int p_first_block[kMaxJobs + 1];  // block ranges of the projection jobs, after the weight jobs
   int n_weights, blocks_per_weight;
   int d, dh, m;
@@ -105,9 +106,10 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
   __syncthreads();
   bf16_t* img = p.p_img[job];
   const bool keys = p.p_layout[job] == kPackKeys;
+  const float sign = p.p_sign[job];
   for (int i = tid; i < kPackRows * d; i += 256) {
     const int row = row0 + i / d, col = i % d;
-    store_as(img + (keys ? keys_slot(u, row, col, d, dh, m) : values_slot(u, row, col, d, dh, m)), out[i]);
+    store_as(img + (keys ? keys_slot(u, row, col, d, dh, m) : values_slot(u, row, col, d, dh, m)), sign * out[i]);
   }
 }
 
@@ -133,6 +135,7 @@ hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackPro
       p.p_img[i] = static_cast<bf16_t*>(projections[i].image);
       p.p_stride[i] = projections[i].user_stride;
       p.p_layout[i] = projections[i].layout;
+      p.p_sign[i] = projections[i].sign;
       blocks += projections[i].users * (m / kPackRows);
     }
   }
