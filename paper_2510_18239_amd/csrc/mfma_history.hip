@@ -1,10 +1,13 @@
 // User-side link personalisation on the matrix cores: the m links attend over the N history
 // rows, by softmax (Eq. 3) or by the target-to-source half of XORA, O[T] (Eq. 7, phi = SiLU/n_s).
 //
-// Design: one fused pass over E.  A workgroup has one wavefront per head and owns a chunk of one
-// user's history; wave a keeps the head-a slices of W_K^T and W_V and the projected link queries
-// Q~_a in fragment form (W_K^T in LDS when d = 256, otherwise in registers) and walks its chunk in
-// tiles of 32 items.  Per tile, with X = the 32 history rows read row-major as stored:
+// Design: one fused pass over E.  A workgroup is a single wavefront that owns one head of a chunk
+// of one user's history (histories are short next to the chip: many small workgroups keep every
+// compute unit busy and each fetches only its own head's operands).  The wave keeps the head's
+// slices of W_K^T and W_V and the projected link queries Q~_a in fragment form (W_K^T in LDS when
+// d = 256, otherwise in registers) and walks its chunk in tiles of 32 items, requesting the next
+// tile's rows before it computes the current one.  Per tile, with X = the 32 history rows read
+// row-major as stored:
 //   K~^T (d/h x 32) = W_K,a^T . X^T     X is the B operand
 //   V~   (32 x d/h) = X . W_V,a         the same X registers are the A operand
 //   S^T  (32 x m)   = K~ . Q~_a^T       A operand = accumulators of the first product
@@ -34,12 +37,12 @@ struct HistArgs {
 };
 
 template <int DH, int M, int H, int PHI, bool WK_LDS>
-__global__ __launch_bounds__(64 * H) void links_over_history_kernel(HistArgs a) {
+__global__ __launch_bounds__(64) void links_over_history_kernel(HistArgs a) {
   constexpr int D = DH * H;
   constexpr int K1 = D / 16, MB = DH / 32;  // projections: k-steps over d, blocks over d/h
   constexpr int K2 = DH / 16, LB = M / 32;  // scores: k-steps over d/h, blocks over links
   extern __shared__ bf16x8 lds_wk[];
-  const int lane = threadIdx.x & 63, head = threadIdx.x >> 6;
+  const int lane = threadIdx.x, head = blockIdx.z;
   const int n = lane & 31, g = lane >> 5;
   const int b = blockIdx.y, chunk = blockIdx.x;
   const int len = a.lens ? min(a.lens[b], a.N) : a.N;
@@ -49,13 +52,12 @@ __global__ __launch_bounds__(64 * H) void links_over_history_kernel(HistArgs a) 
 
   bf16x8 wk[WK_LDS ? 1 : K1][WK_LDS ? 1 : MB];
   if (WK_LDS) {
-    // the whole W_K^T image (all heads): every thread moves K1*MB 16-byte pieces, loads first
+    // this head's W_K^T image: the lane moves exactly the K1*MB fragments it will read back itself
     bf16x8 tmp[K1 * MB];
 #pragma unroll
-    for (int it = 0; it < K1 * MB; ++it) tmp[it] = a.WkA[it * 64 * H + threadIdx.x];
+    for (int it = 0; it < K1 * MB; ++it) tmp[it] = a.WkA[(head * K1 * MB + it) * 64 + lane];
 #pragma unroll
-    for (int it = 0; it < K1 * MB; ++it) lds_wk[it * 64 * H + threadIdx.x] = tmp[it];
-    __syncthreads();
+    for (int it = 0; it < K1 * MB; ++it) lds_wk[it * 64 + lane] = tmp[it];
   } else {
 #pragma unroll
     for (int kk = 0; kk < K1; ++kk)
@@ -89,14 +91,30 @@ __global__ __launch_bounds__(64 * H) void links_over_history_kernel(HistArgs a) 
   }
 
   const bf16_t* Eb = a.E + static_cast<int64_t>(b) * a.N * D;
-  for (int i0 = i_begin; i0 < i_end; i0 += 32) {
+  // rows at or beyond the end of the chunk are replaced by zeros (their content is never used)
+  auto load_tile = [&](int i0, bf16x8 (&x)[K1]) {
     const int item = i0 + n;
-    const bool live = item < i_end;
     const bf16_t* xrow = Eb + static_cast<int64_t>(min(item, a.N - 1)) * D + 8 * g;
+#pragma unroll
+    for (int kk = 0; kk < K1; ++kk) {
+      bf16x8 v;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = static_cast<__bf16>(0.f);
+      if (item < i_end) v = *reinterpret_cast<const bf16x8*>(xrow + 16 * kk);
+      x[kk] = v;
+    }
+  };
+  bf16x8 xnext[K1];
+  load_tile(i_begin, xnext);
+  for (int i0 = i_begin; i0 < i_end; i0 += 32) {
+    bf16x8 x[K1];
+#pragma unroll
+    for (int kk = 0; kk < K1; ++kk) x[kk] = xnext[kk];
+    if (i0 + 32 < i_end) load_tile(i0 + 32, xnext);
 
     // The LDS copy of W_K^T must be re-read for every tile (that is the point of keeping it in LDS
     // rather than in registers); an opaque base index stops the compiler from hoisting the reads.
-    int wk_base = head * K1 * MB * 64 + lane;
+    int wk_base = lane;
     asm volatile("" : "+v"(wk_base));
 
     f32x16 d1[MB], d2[MB];
@@ -106,16 +124,11 @@ __global__ __launch_bounds__(64 * H) void links_over_history_kernel(HistArgs a) 
       for (int i = 0; i < 16; ++i) d1[mb][i] = d2[mb][i] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < K1; ++kk) {
-      bf16x8 x = *reinterpret_cast<const bf16x8*>(xrow + 16 * kk);
-      if (!live) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) x[t] = static_cast<__bf16>(0.f);
-      }
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
         const bf16x8 w = WK_LDS ? lds_wk[wk_base + (kk * MB + mb) * 64] : wk[WK_LDS ? 0 : kk][WK_LDS ? 0 : mb];
-        d1[mb] = mfma32(w, x, d1[mb]);
-        d2[mb] = mfma32(x, wv[kk][mb], d2[mb]);
+        d1[mb] = mfma32(w, x[kk], d1[mb]);
+        d2[mb] = mfma32(x[kk], wv[kk][mb], d2[mb]);
       }
     }
     bf16x8 kf[K2], vf[MB][2];
@@ -278,14 +291,14 @@ int compute_units() {
 template <int DH, int M, int H, int PHI>
 hipError_t launch_phi(const HistArgs& a, dim3 grid, hipStream_t s) {
   constexpr bool kWkLds = DH * H >= 256;
-  constexpr size_t lds = kWkLds ? static_cast<size_t>(DH) * H * DH * H * 2 : 0;
+  constexpr size_t lds = kWkLds ? static_cast<size_t>(DH) * H * DH * 2 : 0;  // one head's slice of W_K^T
   auto kernel = links_over_history_kernel<DH, M, H, PHI, kWkLds>;
   if (lds > 64 * 1024) {
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (attr != hipSuccess) return attr;
   }
-  hipLaunchKernelGGL(kernel, grid, dim3(64 * H), lds, s, a);
+  hipLaunchKernelGGL(kernel, grid, dim3(64), lds, s, a);
   return hipGetLastError();
 }
 
@@ -324,9 +337,10 @@ struct Layout {
 Layout plan(int B, int N, int d, int h, int m, bool q_per_user) {
   Layout l{};
   const int tiles = (N + 31) / 32;
-  // aim at about one chunk per compute unit, at least two tiles per chunk so that the cost of
-  // fetching the stationary operands is shared
-  int chunk_tiles = static_cast<int>((static_cast<int64_t>(B) * tiles + compute_units() - 1) / compute_units());
+  // every (chunk, head) pair is a one-wave workgroup and a compute unit runs four of them at once;
+  // aim at one round of workgroups, at least two tiles per chunk so that the cost of fetching the
+  // stationary operands is shared and the merge stays small
+  int chunk_tiles = static_cast<int>((static_cast<int64_t>(B) * tiles * h + 4 * compute_units() - 1) / (4 * compute_units()));
   if (chunk_tiles < 2) chunk_tiles = 2;
   if (chunk_tiles > tiles) chunk_tiles = tiles;
   l.chunk_items = chunk_tiles * 32;
@@ -370,7 +384,7 @@ hipError_t links_over_history(const LinksOverHistory& q, void* workspace, hipStr
   a.qb_user_frags = per_user ? static_cast<int64_t>(m) * d / 8 : 0;
   a.part_acc = part_acc, a.part_ml = part_ml;
   a.N = q.N, a.chunk_items = l.chunk_items, a.chunks = l.chunks, a.scale = q.scale;
-  const dim3 grid(l.chunks, q.B);
+  const dim3 grid(l.chunks, q.B, h);
   profile_begin(kKernelLinksOverHistory, s);
   e = dh == 32 ? dispatch_h<32>(a, h, m, q.phi, grid, s) : dispatch_h<64>(a, h, m, q.phi, grid, s);
   profile_end(kKernelLinksOverHistory, s);

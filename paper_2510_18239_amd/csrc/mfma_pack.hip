@@ -70,26 +70,39 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
   float* xs = smem;                    // [kPackRows][d]
   float* out = xs + kPackRows * d;     // [kPackRows][d]
   float* red = out + kPackRows * d;    // [nkc][kPackRows][d]
+  // Every load this block needs is issued before the first wait: the row of X and, per thread, up to
+  // kMaxK 16-byte pieces of W (one global round trip instead of one per k-step).
+  constexpr int kMaxK = 32;  // d / nkc = d^2 / 2048 k-steps per thread; 32 at d = 256
+  const int CG = d / 8, nkc = 256 / CG;
+  const int cg = tid % CG, kc = tid / CG;
+  bf16x8 wreg[kMaxK];
+  if (W != nullptr) {
+#pragma unroll
+    for (int it = 0; it < kMaxK; ++it) {
+      const int k = kc + it * nkc;
+      if (k < d) wreg[it] = *reinterpret_cast<const bf16x8*>(W + static_cast<int64_t>(k) * d + 8 * cg);
+    }
+  }
   for (int i = tid; i < kPackRows * d; i += 256) xs[i] = to_float(X[i]);
   __syncthreads();
   if (W == nullptr) {
     for (int i = tid; i < kPackRows * d; i += 256) out[i] = xs[i];
   } else {
-    const int CG = d / 8, nkc = 256 / CG;
-    const int cg = tid % CG, kc = tid / CG;
     float acc[kPackRows][8];
 #pragma unroll
     for (int r = 0; r < kPackRows; ++r)
 #pragma unroll
       for (int j = 0; j < 8; ++j) acc[r][j] = 0.f;
-#pragma unroll 16
-    for (int k = kc; k < d; k += nkc) {
-      const bf16x8 w = *reinterpret_cast<const bf16x8*>(W + static_cast<int64_t>(k) * d + 8 * cg);
 #pragma unroll
-      for (int r = 0; r < kPackRows; ++r) {
-        const float x = xs[r * d + k];
+    for (int it = 0; it < kMaxK; ++it) {
+      const int k = kc + it * nkc;
+      if (k < d) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[r][j] = fmaf(x, static_cast<float>(w[j]), acc[r][j]);
+        for (int r = 0; r < kPackRows; ++r) {
+          const float x = xs[r * d + k];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) acc[r][j] = fmaf(x, static_cast<float>(wreg[it][j]), acc[r][j]);
+        }
       }
     }
 #pragma unroll

@@ -197,3 +197,38 @@ def test_status_codes_on_device_arguments():
     with pytest.raises(binding.LimeError) as e:
         binding.lime_link_history(g.E, None, g.L, g.Wq, g.Wk, g.Wv, 3, 1.0)
     assert e.value.status == 1
+
+
+def test_hip_graph_replay_matches_eager():
+    """The whole request captured in a HIP graph: every replay, with eager work in between, must give
+    the bits of the eager run (the library enqueues kernels only: no memsets, no allocations)."""
+    w = _sharp(workload=39, B=2, N=300, C=400, d=256, h=4, m=64, dtype="bf16", len_range=(50, 300), pad_value=0.0)
+    g = DeviceWorkload(w)
+    s = w.softmax_scale
+    LP = torch.empty((2, 64, 256), dtype=torch.bfloat16, device="cuda")
+    O = torch.empty_like(g.T)
+    XT = torch.empty_like(LP)
+    ws = torch.empty(max(binding.workspace_bytes(binding.OP_XOR_HISTORY, B=2, N=300, d=256, h=4, m=64),
+                         binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=2, C=400, d=256, h=4, m=64)),
+                     dtype=torch.uint8, device="cuda")
+
+    def request():
+        binding.lime_link_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, 4, s, LP=LP, workspace=ws)
+        binding.lime_score_candidates(g.T, g.L, LP, g.Wq, g.Wk, g.Wv, 4, s, O=O, workspace=ws)
+        binding.lime_xor_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, 4, s, LP=XT, workspace=ws)
+
+    request()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (LP, O, XT)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        request()
+    for _ in range(4):
+        for t in (LP, O, XT):
+            t.fill_(7.0)
+        ws.random_(0, 255)  # the workspace carries nothing from one call to the next
+        (torch.randn(1000, device="cuda") * 2).sum().item()  # unrelated eager work and a synchronisation
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((LP, O, XT), want):
+            assert torch.equal(got, ref)
