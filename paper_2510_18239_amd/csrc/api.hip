@@ -32,6 +32,8 @@ constexpr int kMaxHeadDim = 256;
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 template <typename... P>
 bool all_aligned16(P... p) { return (aligned16(p) && ...); }
+// the matrix-core kernels index 32-row tiles with an int
+bool fits_tiles(int64_t users, int64_t rows) { return users * ((rows + 31) / 32) < (int64_t{1} << 31); }
 constexpr int kMaxUsers = 65535;
 
 // Carves 256-byte aligned pieces out of the caller's workspace; with base == nullptr it only sizes.
@@ -93,7 +95,7 @@ int32_t history_impl(const char* fn, int phi, const void* E, const int32_t* lens
   // The matrix-core path: L^P / O[T] ("the m links attend over the history") on the fused history-side
   // kernel, O[S] ("every history row attends over the m links") on the candidate-side kernel with SiLU/m.
   const bool lp_on_mfma = dtype == LIME_BF16 && lime::links_over_history_supported(d, h, m) &&
-                          all_aligned16(E, LC, Wq, Wk, Wv, LP, OS, workspace);
+                          all_aligned16(E, LC, Wq, Wk, Wv, LP, OS, workspace) && fits_tiles(B, N);
   const bool os_on_mfma = want_os && lp_on_mfma;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int64_t link_rows = (per_user ? B : 1) * static_cast<int64_t>(m);
@@ -194,7 +196,7 @@ int32_t lime_score_candidates(const void* T, const void* L, const void* LP, cons
   const int64_t q_rows = static_cast<int64_t>(B) * C, v_rows = static_cast<int64_t>(B) * m;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == LIME_BF16 && lime::queries_over_links_supported(d, h, m) &&
-      all_aligned16(T, L, LP, Wq, Wk, Wv, O, workspace)) {
+      all_aligned16(T, L, LP, Wq, Wk, Wv, O, workspace) && fits_tiles(B, C)) {
     const size_t need = lime::queries_over_links_workspace(B, d, m, false);
     if (!workspace || ws_bytes < need)
       return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? ws_bytes : 0);
@@ -229,11 +231,20 @@ int32_t mha_target_attention(const void* T, const void* E, const int32_t* lens, 
   if (C <= 0 || N <= 0) return fail(LIME_INVALID_ARG, "%s: C and N must be positive (C=%d N=%d)", fn, C, N);
   if (!T || !E || !Wq || !Wk || !Wv || !O) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
   const int64_t q_rows = static_cast<int64_t>(B) * C, k_rows = static_cast<int64_t>(B) * N;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (dtype == LIME_BF16 && lime::target_attention_supported(d, h) && all_aligned16(T, E, Wq, Wk, Wv, O, workspace) &&
+      fits_tiles(B, C) && fits_tiles(B, N)) {
+    const size_t need = lime::target_attention_workspace(B, C, N, d);
+    if (!workspace || ws_bytes < need)
+      return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? ws_bytes : 0);
+    lime::TargetAttention q{T, E, lens, Wq, Wk, Wv, O, B, C, N, d, h, scale};
+    LIME_HIP(lime::target_attention(q, workspace, s));
+    return LIME_OK;
+  }
   QueryPlan p = plan_queries(nullptr, q_rows, k_rows, k_rows, d);
   if (!workspace || ws_bytes < p.bytes)
     return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, p.bytes, workspace ? ws_bytes : 0);
   p = plan_queries(workspace, q_rows, k_rows, k_rows, d);
-  hipStream_t s = static_cast<hipStream_t>(stream);
   LIME_HIP(lime::generic_project(T, Wq, p.Qt, q_rows, d, dtype, s));
   LIME_HIP(lime::generic_project(E, Wk, p.Kt, k_rows, d, dtype, s));
   LIME_HIP(lime::generic_project(E, Wv, p.Vt, k_rows, d, dtype, s));
@@ -270,7 +281,9 @@ size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t
                           ? lime::queries_over_links_workspace(B, d, m, false) : size_t{0});
     case LIME_OP_MHA_TARGET:
       if (C <= 0 || N <= 0) return 0;
-      return plan_queries(nullptr, static_cast<int64_t>(B) * C, static_cast<int64_t>(B) * N, static_cast<int64_t>(B) * N, d).bytes;
+      return std::max(plan_queries(nullptr, static_cast<int64_t>(B) * C, static_cast<int64_t>(B) * N, static_cast<int64_t>(B) * N, d).bytes,
+                      dtype == LIME_BF16 && lime::target_attention_supported(d, h)
+                          ? lime::target_attention_workspace(B, C, N, d) : size_t{0});
     default:
       return 0;
   }

@@ -56,6 +56,7 @@ __host__ __device__ constexpr int out_rho(int col) { return 8 * ((col >> 2) & 3)
 struct PackWeight {
   const void* W;   // [d][d] bf16, or nullptr for the identity
   void* image;
+  float sign = 1.f;  // +1 or -1, multiplies every element (exact)
 };
 constexpr int kPackKeys = 0, kPackValues = 1;
 struct PackProject {
@@ -90,6 +91,20 @@ struct QueriesOverLinks {
 bool queries_over_links_supported(int d, int h, int m);
 size_t queries_over_links_workspace(int B, int d, int m, bool k_per_user);
 hipError_t queries_over_links(const QueriesOverLinks& a, void* workspace, hipStream_t s);
+
+// ----------------------------------------------------------------------------- baseline: full target attention
+struct TargetAttention {
+  const void* T;        // [B][C][d] bf16
+  const void* E;        // [B][N][d] bf16
+  const int32_t* lens;  // nullable
+  const void *Wq, *Wk, *Wv;
+  void* O;              // [B][C][d] bf16
+  int B, C, N, d, h;
+  float scale;
+};
+bool target_attention_supported(int d, int h);
+size_t target_attention_workspace(int B, int C, int N, int d);
+hipError_t target_attention(const TargetAttention& a, void* workspace, hipStream_t s);
 
 // ----------------------------------------------------------------------------- history-side kernel family
 // Fused "few queries x many keys" attention: the m links attend over one user's N history rows;

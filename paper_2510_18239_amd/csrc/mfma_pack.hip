@@ -6,11 +6,12 @@ namespace lime {
 namespace {
 
 constexpr int kPackRows = 1;  // rows of X per block of a projection job (more blocks, shorter critical path)
-constexpr int kMaxJobs = 2;
+constexpr int kMaxJobs = 3;
 
 struct PackArgs {
   const bf16_t* w_src[kMaxJobs];
   bf16x8* w_img[kMaxJobs];
+  float w_sign[kMaxJobs];
   const bf16_t* p_x[kMaxJobs];
   const bf16_t* p_w[kMaxJobs];
   bf16_t* p_img[kMaxJobs];
@@ -49,7 +50,7 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       const float x = W ? to_float(W[static_cast<int64_t>(k0 + t) * d + col]) : (k0 + t == col ? 1.f : 0.f);
-      v[t] = static_cast<__bf16>(x);
+      v[t] = static_cast<__bf16>(x * p.w_sign[job]);
     }
     const int a = col / dh, c = col % dh, mb = c / 32, n = c % 32;
     const int kk = k0 / 16, g = (k0 % 16) / 8;
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
     return;
   }
   blk -= p.n_weights * p.blocks_per_weight;
-  const int job = blk >= p.p_first_block[1] ? 1 : 0;
+  const int job = blk >= p.p_first_block[2] ? 2 : (blk >= p.p_first_block[1] ? 1 : 0);
   blk -= p.p_first_block[job];
   const int groups = m / kPackRows;  // m is a multiple of 32
   const int u = blk / groups, row0 = (blk % groups) * kPackRows;
@@ -138,6 +139,7 @@ hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackPro
   for (int i = 0; i < n_weights; ++i) {
     p.w_src[i] = static_cast<const bf16_t*>(weights[i].W);
     p.w_img[i] = static_cast<bf16x8*>(weights[i].image);
+    p.w_sign[i] = weights[i].sign;
   }
   int blocks = 0;
   for (int i = 0; i < kMaxJobs; ++i) {
@@ -153,7 +155,8 @@ hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackPro
     }
   }
   p.p_first_block[kMaxJobs] = blocks;
-  if (n_projections < 2) p.p_first_block[1] = 0x7fffffff;
+  for (int i = n_projections; i < kMaxJobs; ++i)
+    if (i > 0) p.p_first_block[i] = 0x7fffffff;
   const int nkc = 256 / (d / 8);
   const size_t lds = static_cast<size_t>(2 + nkc) * kPackRows * d * sizeof(float);
   const int grid = n_weights * p.blocks_per_weight + blocks;
