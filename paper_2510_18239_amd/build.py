@@ -14,6 +14,8 @@ OBJ_DIR = os.path.join(HERE, "_build")
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # accumulators of MFMA chains are consumed by vector-ALU code right away: keep them in VGPRs
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-Wall", "-Wno-unused-function",
 ]
 

@@ -163,7 +163,24 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   };
 
   bf16x8 ka[K2][LB], va[K3][MB];
-  int cur_user = -1;
+  auto load_user = [&](int b, bool keys, bool values) {
+    if (keys) {
+      const bf16x8* src = a.KA + b * a.ka_user_frags + static_cast<int64_t>(head) * K2 * LB * 64;
+#pragma unroll
+      for (int kk = 0; kk < K2; ++kk)
+#pragma unroll
+        for (int lb = 0; lb < LB; ++lb) ka[kk][lb] = src[(kk * LB + lb) * 64 + lane];
+    }
+    if (values) {
+      const bf16x8* src = a.VA + b * a.va_user_frags + static_cast<int64_t>(head) * K3 * MB * 64;
+#pragma unroll
+      for (int kk = 0; kk < K3; ++kk)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) va[kk][mb] = src[(kk * MB + mb) * 64 + lane];
+    }
+  };
+  int cur_user = first / a.tiles_per_user;
+  load_user(cur_user, true, true);  // requested with everything else, long before their first use
 
   // Software pipeline: while the vector ALUs do phi of tile i, the matrix cores already run the
   // first product of tile i+1, whose X rows were parked in the other LDS buffer.
@@ -181,20 +198,7 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
       const int b = tile / a.tiles_per_user;
       const int r0 = (tile - b * a.tiles_per_user) * 32;
       if (b != cur_user) {
-        if (cur_user < 0 || a.ka_user_frags != 0) {
-          const bf16x8* src = a.KA + b * a.ka_user_frags + static_cast<int64_t>(head) * K2 * LB * 64;
-#pragma unroll
-          for (int kk = 0; kk < K2; ++kk)
-#pragma unroll
-            for (int lb = 0; lb < LB; ++lb) ka[kk][lb] = src[(kk * LB + lb) * 64 + lane];
-        }
-        if (cur_user < 0 || a.va_user_frags != 0) {
-          const bf16x8* src = a.VA + b * a.va_user_frags + static_cast<int64_t>(head) * K3 * MB * 64;
-#pragma unroll
-          for (int kk = 0; kk < K3; ++kk)
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) va[kk][mb] = src[(kk * MB + mb) * 64 + lane];
-        }
+        load_user(b, a.ka_user_frags != 0, a.va_user_frags != 0);
         cur_user = b;
       }
       const int rlen = a.row_lens ? min(a.row_lens[b], a.rows) : a.rows;
