@@ -116,13 +116,26 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
       for (int i = 0; i < 16; ++i) acc1[mb][i] = 0.f;
     int wl = head * KL * MB * 64 + lane;
     asm volatile("" : "+v"(wl));  // keeps the LDS reads of W_Q^T inside the tile loop
+    // fragment reads run kAhead k-steps ahead of the MFMAs that use them (one wave per SIMD: nobody
+    // else covers the LDS latency)
+    constexpr int kAhead = 3;
+    bf16x8 xq[K1], wl_frag[KL > 0 ? KL : 1][MB];
+    auto fetch = [&](int kk) {
+      xq[kk] = *reinterpret_cast<const bf16x8*>(xrow + 32 * kk);
+      if (kk >= KR) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) wl_frag[KL > 0 ? kk - KR : 0][mb] = wq_lds[wl + ((kk - KR) * MB + mb) * 64];
+      }
+    };
+#pragma unroll
+    for (int kk = 0; kk < kAhead && kk < K1; ++kk) fetch(kk);
 #pragma unroll
     for (int kk = 0; kk < K1; ++kk) {
-      const bf16x8 x = *reinterpret_cast<const bf16x8*>(xrow + 32 * kk);
+      if (kk + kAhead < K1) fetch(kk + kAhead);
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
-        const bf16x8 w = kk < KR ? wq[kk < KR ? kk : 0][mb] : wq_lds[wl + ((kk - KR) * MB + mb) * 64];
-        acc1[mb] = mfma32(w, x, acc1[mb]);
+        const bf16x8 w = kk < KR ? wq[kk < KR ? kk : 0][mb] : wl_frag[kk >= KR ? kk - KR : 0][mb];
+        acc1[mb] = mfma32(w, xq[kk], acc1[mb]);
       }
     }
   };

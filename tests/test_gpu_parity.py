@@ -232,3 +232,47 @@ def test_hip_graph_replay_matches_eager():
         torch.cuda.synchronize()
         for got, ref in zip((LP, O, XT), want):
             assert torch.equal(got, ref)
+
+
+@pytest.mark.parametrize("scale", [-0.2, 0.0])
+@pytest.mark.parametrize("dtype,d,h,m", [("bf16", 256, 4, 64), ("bf16", 128, 4, 64), ("fp32", 64, 2, 16)])
+def test_negative_and_zero_logit_scale(scale, dtype, d, h, m):
+    """The scale is an arbitrary float: a negative one prefers the smallest raw logits, zero gives
+    uniform attention (and SiLU(0) = 0)."""
+    w = _sharp(workload=40, B=2, N=150, C=90, d=d, h=h, m=m, dtype=dtype, len_range=(40, 150), pad_value=np.nan)
+    g = DeviceWorkload(w)
+    LP = binding.lime_link_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, h, scale)
+    assert_close(host(LP), orc.lime_link_history(w.E, w.lens, w.L, w.Wq, w.Wk, w.Wv, h, scale), dtype, "LP")
+    O = binding.lime_score_candidates(g.T, g.L, LP, g.Wq, g.Wk, g.Wv, h, scale)
+    assert_close(host(O), orc.lime_score_candidates(w.T, w.L, host(LP), w.Wq, w.Wk, w.Wv, h, scale), dtype, "O")
+    OT, OS = binding.lime_xor_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, h, scale, want_os=True)
+    rt, rs = orc.lime_xor_history(w.E, w.lens, w.L, w.Wq, w.Wk, w.Wv, h, scale)
+    assert_close(host(OT), rt, dtype, "O[T]")
+    assert_close(host(OS), rs, dtype, "O[S]")
+    A = binding.mha_target_attention(g.T, g.E, g.lens, g.Wq, g.Wk, g.Wv, h, scale)
+    assert_close(host(A), orc.mha_target_attention(w.T, w.E, w.lens, w.Wq, w.Wk, w.Wv, h, scale), dtype, "MHA")
+
+
+def test_unaligned_pointers_take_the_general_kernels():
+    """bf16 tensors that are not 16-byte aligned are served (by the general kernels) with the same results."""
+    w = _sharp(workload=41, B=2, N=100, C=70, d=128, h=4, m=64, dtype="bf16", len_range=(30, 100), pad_value=0.0)
+    g = DeviceWorkload(w)
+    s = w.softmax_scale
+
+    def shifted(t):
+        buf = torch.empty(t.numel() + 8, dtype=t.dtype, device=t.device)
+        v = buf[1:1 + t.numel()].view(t.shape)
+        v.copy_(t)
+        assert v.data_ptr() % 16 != 0
+        return v
+
+    E2, T2 = shifted(g.E), shifted(g.T)
+    LP_a = binding.lime_link_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, 4, s)
+    LP_b = binding.lime_link_history(E2, g.lens, g.L, g.Wq, g.Wk, g.Wv, 4, s)
+    ref = orc.lime_link_history(w.E, w.lens, w.L, w.Wq, w.Wk, w.Wv, 4, s)
+    assert_close(host(LP_a), ref, "bf16", "aligned LP")
+    assert_close(host(LP_b), ref, "bf16", "unaligned LP")
+    O_b = binding.lime_score_candidates(T2, g.L, LP_a, g.Wq, g.Wk, g.Wv, 4, s)
+    assert_close(host(O_b), orc.lime_score_candidates(w.T, w.L, host(LP_a), w.Wq, w.Wk, w.Wv, 4, s), "bf16", "unaligned O")
+    A_b = binding.mha_target_attention(T2, E2, g.lens, g.Wq, g.Wk, g.Wv, 4, s)
+    assert_close(host(A_b), orc.mha_target_attention(w.T, w.E, w.lens, w.Wq, w.Wk, w.Wv, 4, s), "bf16", "unaligned MHA")
