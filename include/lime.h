@@ -50,7 +50,8 @@ extern "C" {
 
 enum { LIME_OK = 0, LIME_INVALID_ARG = 1, LIME_UNSUPPORTED = 2, LIME_WORKSPACE_TOO_SMALL = 3, LIME_LAUNCH_FAILED = 4 };
 enum { LIME_F32 = 0, LIME_BF16 = 1 };
-enum { LIME_OP_LINK_HISTORY = 0, LIME_OP_XOR_HISTORY = 1, LIME_OP_SCORE_CANDIDATES = 2, LIME_OP_MHA_TARGET = 3 };
+enum { LIME_OP_LINK_HISTORY = 0, LIME_OP_XOR_HISTORY = 1, LIME_OP_SCORE_CANDIDATES = 2, LIME_OP_MHA_TARGET = 3,
+       LIME_OP_BUILD_QK_CACHE = 4, LIME_OP_SCORE_CACHED = 5 };
 
 /*
  * User-side link personalisation, Section 3.1 Eq. 3:
@@ -103,6 +104,22 @@ int32_t mha_target_attention(const void* T, const void* E, const int32_t* lens,
                              float scale, int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
 
 /*
+ * The three-stage inference of Section 3.3 ("QK cache").  The attention weights of Eq. 4 depend on the
+ * candidate and on the raw links only, not on the user, so they can be computed ahead of time:
+ *   lime_build_qk_cache:  W[b][c][a][i] = softmax over the m links i of scale * <(T[b][c] Wq)_a, (L Wk)[i]_a>
+ *     (offline item side).  Out: W[B][C][h][m] in `dtype`.  Wq, Wk may be NULL (identity).
+ *   lime_score_candidates_cached:  O[b][c][head a] = sum_i W[b][c][a][i] * (LP[b] Wv)[i][head a]
+ *     (online: a lookup and a weighted sum of the personalised links).  Wv may be NULL.  Out: O[B][C][d].
+ * Chaining the two equals lime_score_candidates up to the storage rounding of W.
+ */
+int32_t lime_build_qk_cache(const void* T, const void* L, const void* Wq, const void* Wk, void* W,
+                            int32_t B, int32_t C, int32_t d, int32_t h, int32_t m,
+                            float scale, int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
+int32_t lime_score_candidates_cached(const void* W, const void* LP, const void* Wv, void* O,
+                                     int32_t B, int32_t C, int32_t d, int32_t h, int32_t m,
+                                     int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
+
+/*
  * Workspace size in bytes for `op` (LIME_OP_*) at the given shape; dimensions an op
  * does not have are ignored.  `flags` bit 0: lime_xor_history will be asked for OS.
  * Returns 0 for shapes the op would reject.
@@ -115,7 +132,8 @@ size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t
  * lime_profile_enable(1): from now on every main kernel launched by the entry points above is
  * bracketed by a pair of HIP events on its stream (kernel ids: 0 = the candidate-side kernel
  * of lime_score_candidates and of O[S]; 1 = the links-over-history kernel of lime_link_history /
- * lime_xor_history; 2 = the attention kernel of mha_target_attention; 3 = their K/V projection).
+ * lime_xor_history; 2 = the attention kernel of mha_target_attention; 3 = their K/V projection; 4 = the kernel of
+ * lime_score_candidates_cached).
  * lime_profile_collect(kernel, ms, capacity): waits for the recorded launches of that kernel,
  * writes up to `capacity` durations in milliseconds to the HOST array `ms` in launch order,
  * forgets them and returns how many it wrote.  Only the matrix-core kernels are instrumented.

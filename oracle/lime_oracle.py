@@ -50,6 +50,8 @@ __all__ = [
     "xora_quadratic",
     "lime_score_candidates",
     "mha_target_attention",
+    "qk_cache",
+    "lime_score_candidates_cached",
 ]
 
 
@@ -270,4 +272,44 @@ def mha_target_attention(T, E, lens, Wq, Wk, Wv, h, scale):
             continue
         Eb = E[b, : lens[b]]
         O[b] = mha(T[b], Eb, Eb, None, Wq, Wk, Wv, h, scale, "softmax")
+    return O
+
+
+def qk_cache(T, L, Wq, Wk, h, scale):
+    """The user-independent attention weights phi(T L^t) of Eq. 4 (the "QK cache" of Section 3.3):
+    W[b, c, a, i] = softmax over the m links i of scale * <(T[b, c] W_Q)_a, (L W_K)[i]_a>.
+
+    T [B, C, d]; L [m, d].  Returns [B, C, h, m].
+    """
+    T = _f64(T)
+    B, C, d = T.shape
+    Kt = project(L, Wk)
+    m = Kt.shape[0]
+    dh = d // h
+    W = np.zeros((B, C, h, m))
+    for b in range(B):
+        Qt = project(T[b], Wq)
+        for a in range(h):
+            cols = slice(a * dh, (a + 1) * dh)
+            S = scale * (Qt[:, cols] @ Kt[:, cols].T)
+            W[b, :, a, :] = phi_softmax(S, np.ones_like(S, dtype=bool))
+    return W
+
+
+def lime_score_candidates_cached(W, LP, Wv, h):
+    """Online half of the three-stage inference of Section 3.3: the cached weights are looked up and the
+    interaction is a weighted sum of the personalised links, O[b, c, head a] = sum_i W[b, c, a, i] (L^P[b] W_V)[i, head a].
+
+    W [B, C, h, m]; LP [B, m, d].  Returns [B, C, d].
+    """
+    W, LP = _f64(W), _f64(LP)
+    B, C, _, m = W.shape
+    d = LP.shape[2]
+    dh = d // h
+    O = np.zeros((B, C, d))
+    for b in range(B):
+        Vt = project(LP[b], Wv)
+        for a in range(h):
+            cols = slice(a * dh, (a + 1) * dh)
+            O[b][:, cols] = W[b, :, a, :] @ Vt[:, cols]
     return O

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblime_hip.so")
 
 LIME_F32, LIME_BF16 = 0, 1
-OP_LINK_HISTORY, OP_XOR_HISTORY, OP_SCORE_CANDIDATES, OP_MHA_TARGET = 0, 1, 2, 3
+OP_LINK_HISTORY, OP_XOR_HISTORY, OP_SCORE_CANDIDATES, OP_MHA_TARGET, OP_BUILD_QK_CACHE, OP_SCORE_CACHED = range(6)
 STATUS_NAMES = {0: "LIME_OK", 1: "LIME_INVALID_ARG", 2: "LIME_UNSUPPORTED", 3: "LIME_WORKSPACE_TOO_SMALL",
                 4: "LIME_LAUNCH_FAILED"}
 
@@ -34,6 +34,8 @@ SIGNATURES = {
                                      _vp, _sz, _vp]),
     "mha_target_attention": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32, _i32,
                                     _vp, _sz, _vp]),
+    "lime_build_qk_cache": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32, _i32, _vp, _sz, _vp]),
+    "lime_score_candidates_cached": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _sz, _vp]),
     "lime_workspace_bytes": (_sz, [_i32] * 9),
     "lime_profile_enable": (None, [_i32]),
     "lime_profile_collect": (_i32, [_i32, _c.POINTER(_c.c_float), _i32]),
@@ -216,5 +218,39 @@ def mha_target_attention(T, E, lens, Wq, Wk, Wv, h, scale, O=None, workspace=Non
     with torch.cuda.device(T.device):
         st = lib().mha_target_attention(_ptr(T), _ptr(E), _ptr(lens), _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(O), B, C, N,
                                         d, h, float(scale), code, _ptr(ws), ws.numel(), _stream(stream))
+    _raise(st)
+    return O
+
+
+def lime_build_qk_cache(T, L, Wq, Wk, h, scale, W=None, workspace=None, stream=None):
+    """W[B, C, h, m] = softmax over the links of the scaled candidate-link logits (Section 3.3, offline side)."""
+    first = _check(T, L, Wq, Wk, W)
+    B, C, d = T.shape
+    m = L.shape[0]
+    code = _dtype_code(first)
+    if W is None:
+        W = torch.empty((B, C, h, m), dtype=T.dtype, device=T.device)
+    need = workspace_bytes(OP_BUILD_QK_CACHE, B=B, C=C, d=d, h=h, m=m, dtype=code)
+    ws = workspace if workspace is not None else get_workspace(need, T.device)
+    with torch.cuda.device(T.device):
+        st = lib().lime_build_qk_cache(_ptr(T), _ptr(L), _ptr(Wq), _ptr(Wk), _ptr(W), B, C, d, h, m, float(scale), code,
+                                       _ptr(ws), ws.numel(), _stream(stream))
+    _raise(st)
+    return W
+
+
+def lime_score_candidates_cached(W, LP, Wv, O=None, workspace=None, stream=None):
+    """O[B, C, d] = cached weights W[B, C, h, m] times the projected link states (Section 3.3, online side)."""
+    first = _check(W, LP, Wv, O)
+    B, C, h, m = W.shape
+    d = LP.shape[2]
+    code = _dtype_code(first)
+    if O is None:
+        O = torch.empty((B, C, d), dtype=W.dtype, device=W.device)
+    need = workspace_bytes(OP_SCORE_CACHED, B=B, C=C, d=d, h=h, m=m, dtype=code)
+    ws = workspace if workspace is not None else get_workspace(need, W.device)
+    with torch.cuda.device(W.device):
+        st = lib().lime_score_candidates_cached(_ptr(W), _ptr(LP), _ptr(Wv), _ptr(O), B, C, d, h, m, code, _ptr(ws),
+                                                ws.numel(), _stream(stream))
     _raise(st)
     return O

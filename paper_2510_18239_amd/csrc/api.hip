@@ -257,6 +257,64 @@ int32_t mha_target_attention(const void* T, const void* E, const int32_t* lens, 
   return LIME_OK;
 }
 
+int32_t lime_build_qk_cache(const void* T, const void* L, const void* Wq, const void* Wk, void* W, int32_t B, int32_t C,
+                            int32_t d, int32_t h, int32_t m, float scale, int32_t dtype, void* workspace,
+                            size_t ws_bytes, void* stream) {
+  const char* fn = "lime_build_qk_cache";
+  if (int32_t st = check_common(fn, B, d, h, dtype)) return st;
+  if (C <= 0 || m <= 0) return fail(LIME_INVALID_ARG, "%s: C and m must be positive (C=%d m=%d)", fn, C, m);
+  if (!T || !L || !W) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int64_t q_rows = static_cast<int64_t>(B) * C;
+  if (dtype == LIME_BF16 && lime::queries_over_links_supported(d, h, m) && all_aligned16(T, L, Wq, Wk, W, workspace) &&
+      fits_tiles(B, C) && (m * 2) % 16 == 0) {
+    const size_t need = lime::queries_over_links_workspace(B, d, m, false);
+    if (!workspace || ws_bytes < need)
+      return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? ws_bytes : 0);
+    lime::QueriesOverLinks q{};
+    q.X = T, q.O = nullptr, q.Wq = Wq, q.Ksrc = L, q.Wk = Wk, q.Vsrc = nullptr, q.Wv = nullptr;
+    q.k_user_stride = 0, q.v_user_stride = 0, q.row_lens = nullptr;
+    q.B = B, q.rows = C, q.d = d, q.h = h, q.m = m, q.scale = scale, q.phi = lime::kPhiSoftmax, q.weights_out = W;
+    LIME_HIP(lime::queries_over_links(q, workspace, s));
+    return LIME_OK;
+  }
+  QueryPlan p = plan_queries(nullptr, q_rows, m, 0, d);
+  if (!workspace || ws_bytes < p.bytes)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, p.bytes, workspace ? ws_bytes : 0);
+  p = plan_queries(workspace, q_rows, m, 0, d);
+  LIME_HIP(lime::generic_project(T, Wq, p.Qt, q_rows, d, dtype, s));
+  LIME_HIP(lime::generic_project(L, Wk, p.Kt, m, d, dtype, s));
+  LIME_HIP(lime::generic_qk_weights(p.Qt, p.Kt, W, q_rows, d, h, m, scale, dtype, s));
+  return LIME_OK;
+}
+
+int32_t lime_score_candidates_cached(const void* W, const void* LP, const void* Wv, void* O, int32_t B, int32_t C,
+                                     int32_t d, int32_t h, int32_t m, int32_t dtype, void* workspace, size_t ws_bytes,
+                                     void* stream) {
+  const char* fn = "lime_score_candidates_cached";
+  if (int32_t st = check_common(fn, B, d, h, dtype)) return st;
+  if (C <= 0 || m <= 0) return fail(LIME_INVALID_ARG, "%s: C and m must be positive (C=%d m=%d)", fn, C, m);
+  if (!W || !LP || !O) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (dtype == LIME_BF16 && lime::queries_over_links_supported(d, h, m) && all_aligned16(W, LP, Wv, O, workspace) &&
+      fits_tiles(B, C)) {
+    const size_t need = lime::cached_candidates_workspace(B, d, m);
+    if (!workspace || ws_bytes < need)
+      return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? ws_bytes : 0);
+    lime::CachedCandidates q{W, LP, Wv, O, B, C, d, h, m};
+    LIME_HIP(lime::cached_candidates(q, workspace, s));
+    return LIME_OK;
+  }
+  const int64_t v_rows = static_cast<int64_t>(B) * m;
+  QueryPlan p = plan_queries(nullptr, 0, 0, v_rows, d);
+  if (!workspace || ws_bytes < p.bytes)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, p.bytes, workspace ? ws_bytes : 0);
+  p = plan_queries(workspace, 0, 0, v_rows, d);
+  LIME_HIP(lime::generic_project(LP, Wv, p.Vt, v_rows, d, dtype, s));
+  LIME_HIP(lime::generic_cached_sum(W, p.Vt, O, B, C, d, h, m, dtype, s));
+  return LIME_OK;
+}
+
 size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t d, int32_t h, int32_t m,
                             int32_t dtype, int32_t flags) {
   if (B <= 0 || d <= 0 || h <= 0 || d % h != 0 || d / h > kMaxHeadDim || B > kMaxUsers) return 0;
@@ -284,6 +342,16 @@ size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t
       return std::max(plan_queries(nullptr, static_cast<int64_t>(B) * C, static_cast<int64_t>(B) * N, static_cast<int64_t>(B) * N, d).bytes,
                       dtype == LIME_BF16 && lime::target_attention_supported(d, h)
                           ? lime::target_attention_workspace(B, C, N, d) : size_t{0});
+    case LIME_OP_BUILD_QK_CACHE:
+      if (C <= 0 || m <= 0) return 0;
+      return std::max(plan_queries(nullptr, static_cast<int64_t>(B) * C, m, 0, d).bytes,
+                      dtype == LIME_BF16 && lime::queries_over_links_supported(d, h, m)
+                          ? lime::queries_over_links_workspace(B, d, m, false) : size_t{0});
+    case LIME_OP_SCORE_CACHED:
+      if (C <= 0 || m <= 0) return 0;
+      return std::max(plan_queries(nullptr, 0, 0, static_cast<int64_t>(B) * m, d).bytes,
+                      dtype == LIME_BF16 && lime::queries_over_links_supported(d, h, m)
+                          ? lime::cached_candidates_workspace(B, d, m) : size_t{0});
     default:
       return 0;
   }

@@ -33,7 +33,7 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 // ----------------------------------------------------------------------------- per-kernel timing (profile.hip)
 enum ProfiledKernel { kKernelQueriesOverLinks = 0, kKernelLinksOverHistory = 1, kKernelTargetAttention = 2,
-                      kKernelProjection = 3 };
+                      kKernelProjection = 3, kKernelCachedCandidates = 4 };
 void profile_begin(int kernel, hipStream_t s);
 void profile_end(int kernel, hipStream_t s);
 
@@ -55,5 +55,12 @@ struct GenericAttention {
   int dtype;  // of O
 };
 hipError_t generic_attention(const GenericAttention& a, hipStream_t s);
+
+// QK cache (Section 3.3): W[rows][h][m] = softmax over m of scale * <Q[row]_head, K[i]_head> (Q, K projected, fp32);
+// and the online weighted sum O[b][c][col] = sum_i W[b][c][head(col)][i] * V[b][i][col] (V projected, fp32).
+hipError_t generic_qk_weights(const float* Q, const float* K, void* W, int64_t rows, int d, int h, int m, float scale,
+                              int dtype, hipStream_t s);
+hipError_t generic_cached_sum(const void* W, const float* V, void* O, int B, int C, int d, int h, int m, int dtype,
+                              hipStream_t s);
 
 }  // namespace lime

@@ -199,7 +199,83 @@ hipError_t launch_attention(const AttnDev& dev, int B, int h, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ----------------------------------------------------------------------------- QK cache (Section 3.3)
+// One wave per (user, candidate, head): weights = softmax over the m links of the scaled logits.
+template <typename OutT>
+__global__ __launch_bounds__(256) void qk_weights_kernel(const float* __restrict__ Q, const float* __restrict__ K,
+                                                         OutT* __restrict__ W, int64_t rows, int d, int h, int m,
+                                                         float scale) {
+  const int lane = threadIdx.x & 63;
+  const int64_t item = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);  // (row, head)
+  if (item >= rows * h) return;
+  const int64_t row = item / h;
+  const int head = static_cast<int>(item % h), dh = d / h;
+  const float* q = Q + row * d + head * dh;
+  float mx = -INFINITY;
+  for (int i = lane; i < m; i += 64) {
+    const float* k = K + static_cast<int64_t>(i) * d + head * dh;
+    float s = 0.f;
+    for (int t = 0; t < dh; ++t) s = fmaf(q[t], k[t], s);
+    mx = fmaxf(mx, s * scale);
+  }
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  float sum = 0.f;
+  for (int i = lane; i < m; i += 64) {
+    const float* k = K + static_cast<int64_t>(i) * d + head * dh;
+    float s = 0.f;
+    for (int t = 0; t < dh; ++t) s = fmaf(q[t], k[t], s);
+    sum += expf(s * scale - mx);
+  }
+  for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+  for (int i = lane; i < m; i += 64) {
+    const float* k = K + static_cast<int64_t>(i) * d + head * dh;
+    float s = 0.f;
+    for (int t = 0; t < dh; ++t) s = fmaf(q[t], k[t], s);
+    store_as(W + (row * h + head) * m + i, expf(s * scale - mx) / sum);
+  }
+}
+
+// One thread per output element: O[b][c][col] = sum_i W[b][c][head(col)][i] * V[b][i][col].
+template <typename T>
+__global__ __launch_bounds__(256) void cached_sum_kernel(const T* __restrict__ W, const float* __restrict__ V,
+                                                         T* __restrict__ O, int64_t total, int C, int d, int h, int m) {
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int col = static_cast<int>(idx % d);
+  const int64_t row = idx / d, b = row / C;
+  const int head = col / (d / h);
+  const T* w = W + (row * h + head) * m;
+  const float* v = V + b * m * d + col;
+  float acc = 0.f;
+  for (int i = 0; i < m; ++i) acc = fmaf(to_float(w[i]), v[static_cast<int64_t>(i) * d], acc);
+  store_as(O + idx, acc);
+}
+
 }  // namespace
+
+hipError_t generic_qk_weights(const float* Q, const float* K, void* W, int64_t rows, int d, int h, int m, float scale,
+                              int dtype, hipStream_t s) {
+  const int64_t items = rows * h;
+  dim3 grid(static_cast<unsigned>((items + 3) / 4));
+  if (dtype == 0)
+    hipLaunchKernelGGL(qk_weights_kernel<float>, grid, dim3(256), 0, s, Q, K, static_cast<float*>(W), rows, d, h, m, scale);
+  else
+    hipLaunchKernelGGL(qk_weights_kernel<bf16_t>, grid, dim3(256), 0, s, Q, K, static_cast<bf16_t*>(W), rows, d, h, m, scale);
+  return hipGetLastError();
+}
+
+hipError_t generic_cached_sum(const void* W, const float* V, void* O, int B, int C, int d, int h, int m, int dtype,
+                              hipStream_t s) {
+  const int64_t total = static_cast<int64_t>(B) * C * d;
+  dim3 grid(static_cast<unsigned>((total + 255) / 256));
+  if (dtype == 0)
+    hipLaunchKernelGGL(cached_sum_kernel<float>, grid, dim3(256), 0, s, static_cast<const float*>(W), V,
+                       static_cast<float*>(O), total, C, d, h, m);
+  else
+    hipLaunchKernelGGL(cached_sum_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t*>(W), V,
+                       static_cast<bf16_t*>(O), total, C, d, h, m);
+  return hipGetLastError();
+}
 
 hipError_t generic_project(const void* X, const void* W, float* Y, int64_t rows, int d, int dtype, hipStream_t s) {
   if (rows <= 0) return hipSuccess;

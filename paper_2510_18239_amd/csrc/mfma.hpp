@@ -58,14 +58,16 @@ struct PackWeight {
   void* image;
   float sign = 1.f;  // +1 or -1, multiplies every element (exact)
 };
-constexpr int kPackKeys = 0, kPackValues = 1;
+//   kPackValuesNatural: as kPackValues with the rows summed in natural order, 16kk + 8g + t (for a B operand
+//                   that is read row-major from memory rather than taken from accumulators)
+constexpr int kPackKeys = 0, kPackValues = 1, kPackValuesNatural = 2;
 struct PackProject {
   const void* X;   // [users][m][d] bf16 rows to project
   const void* W;   // [d][d] bf16, or nullptr for the identity
   void* image;
   int64_t user_stride;  // elements between users in X
   int users;
-  int layout;      // kPackKeys or kPackValues
+  int layout;      // kPackKeys, kPackValues or kPackValuesNatural
   float sign;      // +1 or -1: multiplies every projected element (exact); lets kernels assume scale >= 0
 };
 hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackProject* projections, int n_projections,
@@ -87,10 +89,22 @@ struct QueriesOverLinks {
   int B, rows, d, h, m;
   float scale;
   int phi;              // kPhiSoftmax, or kPhiSilu with normaliser m
+  void* weights_out;    // when set: write the attention weights [B][rows][h][m] instead of O (Vsrc, Wv unused)
 };
 bool queries_over_links_supported(int d, int h, int m);
 size_t queries_over_links_workspace(int B, int d, int m, bool k_per_user);
 hipError_t queries_over_links(const QueriesOverLinks& a, void* workspace, hipStream_t s);
+
+// ----------------------------------------------------------------------------- QK-cache scoring (mfma_cached.hip)
+struct CachedCandidates {
+  const void* W;    // [B][C][h][m] bf16 cached attention weights
+  const void* LP;   // [B][m][d] bf16
+  const void* Wv;   // nullable
+  void* O;          // [B][C][d] bf16
+  int B, C, d, h, m;
+};
+size_t cached_candidates_workspace(int B, int d, int m);
+hipError_t cached_candidates(const CachedCandidates& a, void* workspace, hipStream_t s);
 
 // ----------------------------------------------------------------------------- baseline: full target attention
 struct TargetAttention {

@@ -28,9 +28,12 @@ struct MainArgs {
   const int32_t* row_lens;
   int B, rows, tiles_per_user, total_tiles;
   float scale, inv_norm;
+  bf16_t* Wout;  // WEIGHTS variant only
 };
 
-template <int DH, int M, int H, int PHI>
+// WEIGHTS: stop after phi and write the normalised attention weights [rows][h][m] (the QK cache of
+// Section 3.3) instead of the weighted sum.
+template <int DH, int M, int H, int PHI, bool WEIGHTS>
 __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) {
   constexpr int D = DH * H;
   constexpr int K1 = D / 16, MB = DH / 32;   // first product: k-steps over d, row blocks over d/h
@@ -193,7 +196,7 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
     }
   };
   int cur_user = first / a.tiles_per_user;
-  load_user(cur_user, true, true);  // requested with everything else, long before their first use
+  load_user(cur_user, true, !WEIGHTS);  // requested with everything else, long before their first use
 
   // Software pipeline: while the vector ALUs do phi of tile i, the matrix cores already run the
   // first product of tile i+1, whose X rows were parked in the other LDS buffer.
@@ -211,7 +214,7 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
       const int b = tile / a.tiles_per_user;
       const int r0 = (tile - b * a.tiles_per_user) * 32;
       if (b != cur_user) {
-        load_user(b, a.ka_user_frags != 0, a.va_user_frags != 0);
+        load_user(b, a.ka_user_frags != 0, !WEIGHTS && a.va_user_frags != 0);
         cur_user = b;
       }
       const int rlen = a.row_lens ? min(a.row_lens[b], a.rows) : a.rows;
@@ -250,6 +253,22 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
       } else {
         inv = phi();
       }
+      if constexpr (WEIGHTS) {
+        // register 4j + r of block lb is link 32 lb + 8 j + 4 g + r of this lane's query row
+        const int row = r0 + n;
+        if (row < a.rows) {
+          bf16_t* wrow = a.Wout + ((static_cast<int64_t>(b) * a.rows + row) * H + head) * M + 4 * g;
+#pragma unroll
+          for (int lb = 0; lb < LB; ++lb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              bf16x4 v;
+#pragma unroll
+              for (int r = 0; r < 4; ++r) v[r] = static_cast<__bf16>(acc2[lb][4 * j + r] * inv);
+              *reinterpret_cast<bf16x4*>(wrow + 32 * lb + 8 * j) = v;
+            }
+        }
+      } else {
       bf16x8 pf[K3];
 #pragma unroll
       for (int lb = 0; lb < LB; ++lb) {
@@ -289,6 +308,7 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
         if (row < a.rows)
           *reinterpret_cast<bf16x8*>(a.O + (static_cast<int64_t>(b) * a.rows + row) * D + head * DH + (q % OCPR) * 8) = v;
       }
+      }
     }
   }
 }
@@ -306,10 +326,12 @@ int compute_units() {
 
 template <int DH, int M, int H>
 hipError_t launch_main(const MainArgs& m, int phi, int grid, hipStream_t s) {
-  if (phi == kPhiSoftmax)
-    hipLaunchKernelGGL((queries_over_links_kernel<DH, M, H, kPhiSoftmax>), dim3(grid), dim3(64 * H), 0, s, m);
+  if (m.Wout != nullptr)
+    hipLaunchKernelGGL((queries_over_links_kernel<DH, M, H, kPhiSoftmax, true>), dim3(grid), dim3(64 * H), 0, s, m);
+  else if (phi == kPhiSoftmax)
+    hipLaunchKernelGGL((queries_over_links_kernel<DH, M, H, kPhiSoftmax, false>), dim3(grid), dim3(64 * H), 0, s, m);
   else
-    hipLaunchKernelGGL((queries_over_links_kernel<DH, M, H, kPhiSilu>), dim3(grid), dim3(64 * H), 0, s, m);
+    hipLaunchKernelGGL((queries_over_links_kernel<DH, M, H, kPhiSilu, false>), dim3(grid), dim3(64 * H), 0, s, m);
   return hipGetLastError();
 }
 
@@ -364,7 +386,7 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
   // a negative logit scale is folded into the sign of the packed keys, so the kernel sees scale >= 0
   PackProject pjobs[2] = {{q.Ksrc, q.Wk, KA, q.k_user_stride, k_per_user ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f},
                           {q.Vsrc, q.Wv, VA, q.v_user_stride, v_per_user ? q.B : 1, kPackValues, 1.f}};
-  hipError_t e = pack_operands(&wjob, 1, pjobs, 2, d, h, m, s);
+  hipError_t e = pack_operands(&wjob, 1, pjobs, q.weights_out ? 1 : 2, d, h, m, s);
   if (e != hipSuccess) return e;
 
   MainArgs a{};
@@ -374,6 +396,7 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
   a.ka_user_frags = k_per_user ? static_cast<int64_t>(m) * d / 8 : 0;
   a.va_user_frags = v_per_user ? static_cast<int64_t>(m) * d / 8 : 0;
   a.row_lens = q.row_lens;
+  a.Wout = static_cast<bf16_t*>(q.weights_out);
   a.B = q.B, a.rows = q.rows, a.tiles_per_user = (q.rows + 31) / 32;
   a.total_tiles = a.tiles_per_user * q.B;  // the caller has checked that this fits an int
   a.scale = fabsf(q.scale), a.inv_norm = 1.f / static_cast<float>(m);

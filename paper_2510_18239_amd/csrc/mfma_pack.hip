@@ -29,10 +29,11 @@ __device__ __forceinline__ int64_t keys_slot(int u, int row, int col, int d, int
   const int64_t frag = ((static_cast<int64_t>(u) * (d / dh) + a) * (dh / 16) + kk) * (m / 32) + row / 32;
   return (frag * 64 + 32 * chain_g(kin) + row % 32) * 8 + chain_t(kin);
 }
-__device__ __forceinline__ int64_t values_slot(int u, int row, int col, int d, int dh, int m) {
+__device__ __forceinline__ int64_t values_slot(int u, int row, int col, int d, int dh, int m, bool chained) {
   const int a = col / dh, c = col % dh, kk = row / 16, kin = row % 16;
   const int64_t frag = ((static_cast<int64_t>(u) * (d / dh) + a) * (m / 16) + kk) * (dh / 32) + c / 32;
-  return (frag * 64 + 32 * chain_g(kin) + out_rho(c % 32)) * 8 + chain_t(kin);
+  const int g = chained ? chain_g(kin) : kin / 8, t = chained ? chain_t(kin) : kin % 8;
+  return (frag * 64 + 32 * g + out_rho(c % 32)) * 8 + t;
 }
 
 __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
   const float sign = p.p_sign[job];
   for (int i = tid; i < kPackRows * d; i += 256) {
     const int row = row0 + i / d, col = i % d;
-    store_as(img + (keys ? keys_slot(u, row, col, d, dh, m) : values_slot(u, row, col, d, dh, m)), sign * out[i]);
+    store_as(img + (keys ? keys_slot(u, row, col, d, dh, m) : values_slot(u, row, col, d, dh, m, p.p_layout[job] == kPackValues)), sign * out[i]);
   }
 }
 

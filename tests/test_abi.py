@@ -22,7 +22,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"lime_link_history", "lime_xor_history", "lime_score_candidates", "mha_target_attention",
-            "lime_profile_enable", "lime_profile_collect",
+            "lime_profile_enable", "lime_profile_collect", "lime_build_qk_cache", "lime_score_candidates_cached",
             "lime_workspace_bytes", "lime_last_error", "lime_version"} <= set(names)
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
@@ -100,3 +100,23 @@ def test_workspace_query():
     assert wb(99, B=1, N=1, C=1, d=8, h=1, m=1) == 0
     for op in range(4):
         assert wb(op, B=3, N=50, C=70, d=32, h=2, m=8, dtype=0, flags=1) % 256 == 0
+
+
+def test_qk_cache_argument_checks():
+    lib = binding.lib()
+
+    def build(T=FAKE, L=FAKE, W=FAKE, C=4, d=8, h=2, m=4, dtype=1, ws=FAKE, ws_bytes=0):
+        return lib.lime_build_qk_cache(T, L, None, None, W, 1, C, d, h, m, 1.0, dtype, ws, ws_bytes, None)
+
+    assert build() == 3
+    assert build(T=None) == 1 and build(L=None) == 1 and build(W=None) == 1
+    assert build(C=0) == 1 and build(m=-1) == 1 and build(h=3) == 1 and build(dtype=5) == 1
+
+    def score(W=FAKE, LP=FAKE, O=FAKE, C=4, d=8, h=2, m=4, dtype=0, ws=FAKE, ws_bytes=0):
+        return lib.lime_score_candidates_cached(W, LP, None, O, 1, C, d, h, m, dtype, ws, ws_bytes, None)
+
+    assert score() == 3
+    assert score(W=None) == 1 and score(LP=None) == 1 and score(O=None) == 1
+    assert score(C=0) == 1 and score(m=0) == 1 and score(d=7) == 1
+    assert binding.workspace_bytes(binding.OP_BUILD_QK_CACHE, B=1, C=100, d=256, h=4, m=64) > 0
+    assert binding.workspace_bytes(binding.OP_SCORE_CACHED, B=2, C=100, d=256, h=4, m=64) > 0

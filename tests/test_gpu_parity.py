@@ -276,3 +276,28 @@ def test_unaligned_pointers_take_the_general_kernels():
     assert_close(host(O_b), orc.lime_score_candidates(w.T, w.L, host(LP_a), w.Wq, w.Wk, w.Wv, 4, s), "bf16", "unaligned O")
     A_b = binding.mha_target_attention(T2, E2, g.lens, g.Wq, g.Wk, g.Wv, 4, s)
     assert_close(host(A_b), orc.mha_target_attention(w.T, w.E, w.lens, w.Wq, w.Wk, w.Wv, 4, s), "bf16", "unaligned MHA")
+
+
+@pytest.mark.parametrize("dtype,d,h,m,C", [("bf16", 256, 4, 64, 1000), ("bf16", 128, 4, 64, 333), ("bf16", 256, 4, 128, 200),
+                                           ("fp32", 64, 2, 16, 77), ("bf16", 96, 3, 20, 50)])
+def test_qk_cache_path(dtype, d, h, m, C):
+    """Section 3.3: the cached attention weights and the online weighted sum, against the oracle, and
+    chained against the direct candidate call."""
+    w = _sharp(workload=42, B=2, N=8, C=C, d=d, h=h, m=m, dtype=dtype)
+    g = DeviceWorkload(w)
+    s = w.softmax_scale
+    LPv = synth.per_user_links(42, 2, m, d, dtype, gain=w.meta["gain"])
+    LP = dev(LPv, dtype)
+    W = binding.lime_build_qk_cache(g.T, g.L, g.Wq, g.Wk, h, s)
+    assert W.shape == (2, C, h, m)
+    W_ref = orc.qk_cache(w.T, w.L, w.Wq, w.Wk, h, s)
+    assert_close(host(W), W_ref, dtype, "cached weights")
+    sums = host(W).sum(axis=-1)
+    assert np.abs(sums - 1.0).max() <= (2e-2 if dtype == "bf16" else 1e-4)
+    # the online half is checked on the weights the GPU stored (they travel in the storage type)
+    O = binding.lime_score_candidates_cached(W, LP, g.Wv)
+    assert_close(host(O), orc.lime_score_candidates_cached(host(W), LPv, w.Wv, h), dtype, "cached O")
+    # and the chain against Eq. 4 evaluated directly
+    assert_close(host(O), orc.lime_score_candidates(w.T, w.L, LPv, w.Wq, w.Wk, w.Wv, h, s), dtype, "cached chain", 2.0)
+    direct = binding.lime_score_candidates(g.T, g.L, LP, g.Wq, g.Wk, g.Wv, h, s)
+    assert_close(host(O), host(direct).astype(np.float64), dtype, "cached vs direct on the GPU", 2.0)

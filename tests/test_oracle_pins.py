@@ -386,6 +386,34 @@ def check_softmax_is_shift_invariant_and_stable():
     np.testing.assert_allclose(A[1], [1 / 3] * 3, atol=1e-15)
 
 
+def check_qk_cache_path():
+    # Section 3.3: looking the weights up and summing the personalised links is Eq. 4 itself
+    p = _problem(61, B=2, N=5, C=9, d=8, m=4)
+    LP = _rand(62, 2, 4, 8)
+    h, s = 2, 0.8
+    W = orc.qk_cache(p["T"], p["L"], p["Wq"], p["Wk"], h, s)
+    assert W.shape == (2, 9, 2, 4)
+    np.testing.assert_allclose(W.sum(axis=-1), 1.0, atol=1e-14)
+    assert (W >= 0).all()
+    direct = orc.lime_score_candidates(p["T"], p["L"], LP, p["Wq"], p["Wk"], p["Wv"], h, s)
+    np.testing.assert_allclose(orc.lime_score_candidates_cached(W, LP, p["Wv"], h), direct, atol=1e-13)
+    # the cache does not depend on the user's link states or on W_V
+    np.testing.assert_array_equal(W, orc.qk_cache(p["T"], p["L"], p["Wq"], p["Wk"], h, s))
+    # hand case of the Eq. 4 fixture: logits [ln2, 0] -> weights [2/3, 1/3]; values [[3, 0], [0, 6]] -> [2, 2]
+    g = _load("eq4_decoupled_candidates.json")
+    Wg = orc.qk_cache(_arr(g["T"]), _arr(g["L"]), None, None, 1, 1.0)
+    np.testing.assert_allclose(Wg[0, 0, 0], [2 / 3, 1 / 3], atol=1e-15)
+    np.testing.assert_allclose(orc.lime_score_candidates_cached(Wg, _arr(g["LP"]), None, 1), _arr(g["O"]), atol=1e-14)
+    # brute force of the weighted sum with scalar loops
+    Vt = (LP[1] @ p["Wv"]).tolist()
+    out = orc.lime_score_candidates_cached(W, LP, p["Wv"], h)
+    for c in range(9):
+        for col in range(8):
+            a = col // 4
+            want = sum(W[1, c, a, i] * Vt[i][col] for i in range(4))
+            assert abs(out[1, c, col] - want) < 1e-13
+
+
 PINS = [
     check_golden_eq3,
     check_golden_eq4,
@@ -404,6 +432,7 @@ PINS = [
     check_xor_zero_cross_dependence,
     check_ragged_masking,
     check_softmax_is_shift_invariant_and_stable,
+    check_qk_cache_path,
 ]
 
 
