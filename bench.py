@@ -223,6 +223,24 @@ def extras(binding, synth, torch, dev, timed, pct):
         lat = timed(lambda i: binding.lime_score_candidates(Tc, L, LP, Wq, Wk, Wv, w.h, w.softmax_scale, O=O), 100)
         sweep[C] = pct(lat, 0.5)
     res["lime_score_candidates_p50_ms_vs_C"] = sweep
+    # the QK-cache path of Section 3.3 at the headline shape: weights in, weighted sum out, cold buffers
+    C = T.shape[1]
+    n = 17
+    Wc = binding.lime_build_qk_cache(T, L, Wq, Wk, w.h, w.softmax_scale)
+    Ws = [Wc] + [Wc.clone() for _ in range(n - 1)]
+    Oc = [torch.empty_like(T) for _ in range(n)]
+    binding.profile_enable(True)
+    binding.profile_collect(4)
+    lat = timed(lambda i: binding.lime_score_candidates_cached(Ws[i % n], LP, Wv, O=Oc[i % n]), 200)
+    k = binding.profile_collect(4)
+    binding.profile_enable(False)
+    overhead = pct(timed(lambda i: None, 200), 0.5)
+    kavg = sum(k) / len(k) - overhead
+    nbytes = Wc.numel() * 2 + T.numel() * 2
+    res["qk_cache_path"] = {"lime_score_candidates_cached_p50_ms": pct(lat, 0.5), "kernel_avg_ms": kavg,
+                            "algorithmic_bytes": nbytes, "achieved_GBps": nbytes / (kavg * 1e-3) / 1e9,
+                            "frac_of_hbm_peak": nbytes / (kavg * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    del Ws, Oc
     # XORA history pass vs N (configs[3])
     c4 = dict(synth.CONFIGS[4])
     xs = {}

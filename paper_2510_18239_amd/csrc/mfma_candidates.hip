@@ -172,10 +172,10 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
     for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const float s = acc2[lb][i] * a.scale;
-        acc2[lb][i] = s / (1.f + __builtin_amdgcn_exp2f(-s * kLog2e));
+        // SiLU(scale * s) = scale * s * sigmoid(scale * s); `scale` is part of the final factor
+        acc2[lb][i] = acc2[lb][i] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-acc2[lb][i] * (a.scale * kLog2e)));
       }
-    return a.inv_norm;
+    return a.inv_norm * a.scale;
   };
 
   bf16x8 ka[K2][LB], va[K3][MB];

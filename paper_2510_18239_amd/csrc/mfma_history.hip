@@ -36,13 +36,22 @@ struct HistArgs {
   float scale;
 };
 
-template <int DH, int M, int H, int PHI, bool WK_LDS>
-__global__ __launch_bounds__(64) void links_over_history_kernel(HistArgs a) {
+// COOP = false: a workgroup is one wave (one head of one chunk; grid.z = heads) that reads its rows
+// straight from memory, one tile ahead.  COOP = true (long histories, d <= 128): a workgroup is h waves
+// (all heads of one chunk) that copy each tile once, cooperatively and several tiles ahead, through a
+// register ring into LDS, as the candidate-side kernel does.
+template <int DH, int M, int H, int PHI, bool WK_LDS, bool COOP>
+__global__ __launch_bounds__(COOP ? 64 * H : 64) void links_over_history_kernel(HistArgs a) {
   constexpr int D = DH * H;
   constexpr int K1 = D / 16, MB = DH / 32;  // projections: k-steps over d, blocks over d/h
   constexpr int K2 = DH / 16, LB = M / 32;  // scores: k-steps over d/h, blocks over links
+  constexpr int P = 4;                      // COOP: tiles in flight per workgroup
+  constexpr int LW = DH / 16;               // COOP: 1 KiB loads per wave and tile
+  constexpr int CPR = D / 8, PITCH = 2 * D + 16;
+  static_assert(!(COOP && WK_LDS), "the cooperative variant keeps W_K^T in registers");
   extern __shared__ bf16x8 lds_wk[];
-  const int lane = threadIdx.x, head = blockIdx.z;
+  __shared__ __attribute__((aligned(16))) unsigned char xs[COOP ? 2 : 1][COOP ? 32 * PITCH : 16];
+  const int lane = threadIdx.x & 63, head = COOP ? threadIdx.x >> 6 : blockIdx.z;
   const int n = lane & 31, g = lane >> 5;
   const int b = blockIdx.y, chunk = blockIdx.x;
   const int len = a.lens ? min(a.lens[b], a.N) : a.N;
@@ -104,14 +113,21 @@ __global__ __launch_bounds__(64) void links_over_history_kernel(HistArgs a) {
       x[kk] = v;
     }
   };
-  bf16x8 xnext[K1];
-  load_tile(i_begin, xnext);
-  for (int i0 = i_begin; i0 < i_end; i0 += 32) {
-    bf16x8 x[K1];
+  // COOP: this wave's share of a tile (32 rows = 64 D contiguous bytes), 16 bytes per lane and load
+  auto issue = [&](int i0, bf16x8 (&r)[LW]) {
 #pragma unroll
-    for (int kk = 0; kk < K1; ++kk) x[kk] = xnext[kk];
-    if (i0 + 32 < i_end) load_tile(i0 + 32, xnext);
+    for (int j = 0; j < LW; ++j) {
+      const int q = (head * LW + j) * 64 + lane;
+      const int item = i0 + q / CPR;
+      bf16x8 v;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = static_cast<__bf16>(0.f);
+      if (item < i_end) v = *reinterpret_cast<const bf16x8*>(Eb + static_cast<int64_t>(item) * D + (q % CPR) * 8);
+      r[j] = v;
+    }
+  };
 
+  auto process_tile = [&](int i0, const bf16x8 (&x)[K1]) {
     // The LDS copy of W_K^T must be re-read for every tile (that is the point of keeping it in LDS
     // rather than in registers); an opaque base index stops the compiler from hoisting the reads.
     int wk_base = lane;
@@ -147,36 +163,44 @@ __global__ __launch_bounds__(64) void links_over_history_kernel(HistArgs a) {
       for (int i = 0; i < 16; ++i) sc[i] = 0.f;
 #pragma unroll
       for (int kk = 0; kk < K2; ++kk) sc = mfma32(kf[kk], qb[kk][lb], sc);
-      // register 4j + r of this lane is item i0 + 8j + 4g + r
+      // register 4j + r of this lane is item i0 + 8j + 4g + r; only a chunk's last tile can be ragged
+      const float c = a.scale * kLog2e;  // >= 0: a negative scale is folded into the sign of the packed queries
+      const bool ragged = i0 + 32 > i_end;  // uniform
       if (PHI == kPhiSoftmax) {
-        float tmax = -INFINITY;
+        if (ragged) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const bool ok = i0 + 8 * (i >> 2) + 4 * g + (i & 3) < i_end;
-          sc[i] = ok ? sc[i] * a.scale : -INFINITY;
-          tmax = fmaxf(tmax, sc[i]);
+          for (int i = 0; i < 16; ++i)
+            if (i0 + 8 * (i >> 2) + 4 * g + (i & 3) >= i_end) sc[i] = -INFINITY;
         }
+        float tmax = sc[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, sc[i]);
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
         const float new_max = fmaxf(run_max[lb], tmax);  // finite: the tile holds at least one valid item
-        const float alpha = __builtin_amdgcn_exp2f((run_max[lb] - new_max) * kLog2e);
+        if (__any(new_max > run_max[lb])) {  // uniform; after the first tiles the maximum rarely moves
+          const float alpha = run_max[lb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((run_max[lb] - new_max) * c);
+          run_sum[lb] *= alpha;
+          run_max[lb] = new_max;
+#pragma unroll
+          for (int ob = 0; ob < MB; ++ob)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[ob][lb][i] *= alpha;
+        }
+        const float shift = -new_max * c;  // exp2(raw * c + shift) = exp(scale * raw - running maximum)
         float psum = 0.f;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          sc[i] = __builtin_amdgcn_exp2f((sc[i] - new_max) * kLog2e);
+          const float pr = __builtin_amdgcn_exp2f(fmaf(sc[i], c, shift));
+          sc[i] = ragged && sc[i] == -INFINITY ? 0.f : pr;  // (the select also covers scale = 0)
           psum += sc[i];
         }
-        run_sum[lb] = run_sum[lb] * alpha + psum;
-        run_max[lb] = new_max;
-#pragma unroll
-        for (int ob = 0; ob < MB; ++ob)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) acc[ob][lb][i] *= alpha;
+        run_sum[lb] += psum;
       } else {
+        // SiLU(scale * s) = scale * s * sigmoid(scale * s); the factor `scale` is applied by the merge
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const bool ok = i0 + 8 * (i >> 2) + 4 * g + (i & 3) < i_end;
-          const float s = sc[i] * a.scale;
-          sc[i] = ok ? s / (1.f + __builtin_amdgcn_exp2f(-s * kLog2e)) : 0.f;
+          const float pr = sc[i] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-sc[i] * c));
+          sc[i] = ragged && i0 + 8 * (i >> 2) + 4 * g + (i & 3) >= i_end ? 0.f : pr;
         }
       }
       const bf16x8 p0 = pack_half(sc, 0), p1 = pack_half(sc, 1);
@@ -185,6 +209,44 @@ __global__ __launch_bounds__(64) void links_over_history_kernel(HistArgs a) {
         acc[ob][lb] = mfma32(vf[ob][0], p0, acc[ob][lb]);
         acc[ob][lb] = mfma32(vf[ob][1], p1, acc[ob][lb]);
       }
+    }
+  };
+
+  if constexpr (COOP) {
+    bf16x8 ring[P][LW];
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+      if (i_begin + 32 * p < i_end) issue(i_begin + 32 * p, ring[p]);
+    for (int base = i_begin; base < i_end; base += 32 * P) {
+#pragma unroll
+      for (int p = 0; p < P; ++p) {
+        const int i0 = base + 32 * p;
+        if (i0 >= i_end) break;  // uniform over the workgroup
+        unsigned char* buf = xs[p & 1];
+#pragma unroll
+        for (int j = 0; j < LW; ++j) {
+          const int q = (head * LW + j) * 64 + lane;
+          *reinterpret_cast<bf16x8*>(buf + (q / CPR) * PITCH + (q % CPR) * 16) = ring[p][j];
+        }
+        // a wave arrives here only after it has finished reading the tile before the previous one,
+        // which is the one this buffer held
+        __syncthreads();
+        if (i0 + 32 * P < i_end) issue(i0 + 32 * P, ring[p]);
+        bf16x8 x[K1];
+#pragma unroll
+        for (int kk = 0; kk < K1; ++kk) x[kk] = *reinterpret_cast<const bf16x8*>(buf + n * PITCH + 32 * kk + 16 * g);
+        process_tile(i0, x);
+      }
+    }
+  } else {
+    bf16x8 xnext[K1];
+    load_tile(i_begin, xnext);
+    for (int i0 = i_begin; i0 < i_end; i0 += 32) {
+      bf16x8 x[K1];
+#pragma unroll
+      for (int kk = 0; kk < K1; ++kk) x[kk] = xnext[kk];
+      if (i0 + 32 < i_end) load_tile(i0 + 32, xnext);
+      process_tile(i0, x);
     }
   }
 
@@ -204,7 +266,7 @@ __global__ __launch_bounds__(64) void links_over_history_kernel(HistArgs a) {
     const float total = run_sum[lb] + __shfl_xor(run_sum[lb], 32);
     if (g == 0) {
       float* ml = a.part_ml + (slot * M + link) * 2;
-      ml[0] = run_max[lb];
+      ml[0] = run_max[lb] * a.scale;  // the merge works on scaled logits
       ml[1] = total;
     }
   }
@@ -216,6 +278,7 @@ struct MergeArgs {
   const int32_t* lens;
   bf16_t* LP;
   int N, chunk_items, chunks, h, m, dh;
+  float scale;  // |logit scale|: the factor the SiLU partials still lack
 };
 
 // One thread per output element LP[b][link][a dh + t]; chunks are combined in ascending order.
@@ -271,7 +334,7 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
 #pragma unroll
         for (int i = 0; i < kBatch; ++i) num += c0 + i < used ? ac[i] : 0.f;
       }
-      out = num / static_cast<float>(len);
+      out = num * a.scale / static_cast<float>(len);
     }
   }
   store_as(a.LP + (static_cast<int64_t>(b) * a.m + link) * d + col, out);
@@ -289,58 +352,71 @@ int compute_units() {
 }
 
 template <int DH, int M, int H, int PHI>
-hipError_t launch_phi(const HistArgs& a, dim3 grid, hipStream_t s) {
+hipError_t launch_phi(const HistArgs& a, int users, bool coop, hipStream_t s) {
   constexpr bool kWkLds = DH * H >= 256;
+  if constexpr (!kWkLds && H > 1) {
+    if (coop) {
+      hipLaunchKernelGGL((links_over_history_kernel<DH, M, H, PHI, false, true>), dim3(a.chunks, users), dim3(64 * H), 0,
+                         s, a);
+      return hipGetLastError();
+    }
+  }
   constexpr size_t lds = kWkLds ? static_cast<size_t>(DH) * H * DH * 2 : 0;  // one head's slice of W_K^T
-  auto kernel = links_over_history_kernel<DH, M, H, PHI, kWkLds>;
+  auto kernel = links_over_history_kernel<DH, M, H, PHI, kWkLds, false>;
   if (lds > 64 * 1024) {
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (attr != hipSuccess) return attr;
   }
-  hipLaunchKernelGGL(kernel, grid, dim3(64), lds, s, a);
+  hipLaunchKernelGGL(kernel, dim3(a.chunks, users, H), dim3(64), lds, s, a);
   return hipGetLastError();
 }
 
 template <int DH, int M, int H>
-hipError_t launch_main(const HistArgs& a, int phi, dim3 grid, hipStream_t s) {
-  return phi == kPhiSoftmax ? launch_phi<DH, M, H, kPhiSoftmax>(a, grid, s) : launch_phi<DH, M, H, kPhiSilu>(a, grid, s);
+hipError_t launch_main(const HistArgs& a, int phi, int users, bool coop, hipStream_t s) {
+  return phi == kPhiSoftmax ? launch_phi<DH, M, H, kPhiSoftmax>(a, users, coop, s)
+                            : launch_phi<DH, M, H, kPhiSilu>(a, users, coop, s);
 }
 
 template <int DH, int H>
-hipError_t dispatch_m(const HistArgs& a, int links, int phi, dim3 grid, hipStream_t s) {
+hipError_t dispatch_m(const HistArgs& a, int links, int phi, int users, bool coop, hipStream_t s) {
   switch (links) {
-    case 32: return launch_main<DH, 32, H>(a, phi, grid, s);
-    case 64: return launch_main<DH, 64, H>(a, phi, grid, s);
-    case 96: return launch_main<DH, 96, H>(a, phi, grid, s);
-    case 128: return launch_main<DH, 128, H>(a, phi, grid, s);
+    case 32: return launch_main<DH, 32, H>(a, phi, users, coop, s);
+    case 64: return launch_main<DH, 64, H>(a, phi, users, coop, s);
+    case 96: return launch_main<DH, 96, H>(a, phi, users, coop, s);
+    case 128: return launch_main<DH, 128, H>(a, phi, users, coop, s);
   }
   return hipErrorInvalidValue;
 }
 
 template <int DH>
-hipError_t dispatch_h(const HistArgs& a, int h, int links, int phi, dim3 grid, hipStream_t s) {
+hipError_t dispatch_h(const HistArgs& a, int h, int links, int phi, int users, bool coop, hipStream_t s) {
   switch (h) {
-    case 1: return dispatch_m<DH, 1>(a, links, phi, grid, s);
-    case 2: return dispatch_m<DH, 2>(a, links, phi, grid, s);
-    case 4: return dispatch_m<DH, 4>(a, links, phi, grid, s);
-    case 8: if (DH == 32) return dispatch_m<32, 8>(a, links, phi, grid, s);
+    case 1: return dispatch_m<DH, 1>(a, links, phi, users, coop, s);
+    case 2: return dispatch_m<DH, 2>(a, links, phi, users, coop, s);
+    case 4: return dispatch_m<DH, 4>(a, links, phi, users, coop, s);
+    case 8: if (DH == 32) return dispatch_m<32, 8>(a, links, phi, users, coop, s);
   }
   return hipErrorInvalidValue;
 }
 
 struct Layout {
   int chunk_items, chunks;
+  bool coop;  // h-wave workgroups that stage each tile once through LDS (long histories, d <= 128)
   size_t wk, wv, qb, acc, ml, total;
 };
 
 Layout plan(int B, int N, int d, int h, int m, bool q_per_user) {
   Layout l{};
   const int tiles = (N + 31) / 32;
-  // every (chunk, head) pair is a one-wave workgroup and a compute unit runs four of them at once;
-  // aim at one round of workgroups, at least two tiles per chunk so that the cost of fetching the
-  // stationary operands is shared and the merge stays small
-  int chunk_tiles = static_cast<int>((static_cast<int64_t>(B) * tiles * h + 4 * compute_units() - 1) / (4 * compute_units()));
+  // Short histories: every (chunk, head) pair is a one-wave workgroup and a compute unit runs four of
+  // them at once (eight when d/h = 32); aim at one round of workgroups.  Long histories with d <= 128
+  // (at least four tiles per compute unit): h-wave workgroups, two per compute unit.  At least two
+  // tiles per chunk so that the stationary operands are fetched for more than one tile and the merge
+  // stays small.
+  l.coop = d <= 128 && h > 1 && static_cast<int64_t>(B) * tiles >= 4 * static_cast<int64_t>(compute_units());
+  const int64_t slots = static_cast<int64_t>(l.coop ? 2 : (d / h == 32 ? 8 : 4)) * compute_units();
+  int chunk_tiles = static_cast<int>((static_cast<int64_t>(B) * tiles * (l.coop ? 1 : h) + slots - 1) / slots);
   if (chunk_tiles < 2) chunk_tiles = 2;
   if (chunk_tiles > tiles) chunk_tiles = tiles;
   l.chunk_items = chunk_tiles * 32;
@@ -373,7 +449,8 @@ hipError_t links_over_history(const LinksOverHistory& q, void* workspace, hipStr
   float* part_ml = reinterpret_cast<float*>(ws + l.wk + l.wv + l.qb + l.acc);
 
   PackWeight wjobs[2] = {{q.Wk, WkA}, {q.Wv, WvB}};
-  PackProject pjob{q.LC, q.Wq, QB, q.lc_user_stride, per_user ? q.B : 1, kPackKeys, 1.f};
+  // a negative logit scale is folded into the sign of the packed queries, so the kernels see scale >= 0
+  PackProject pjob{q.LC, q.Wq, QB, q.lc_user_stride, per_user ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f};
   hipError_t e = pack_operands(wjobs, 2, &pjob, 1, d, h, m, s);
   if (e != hipSuccess) return e;
 
@@ -383,14 +460,13 @@ hipError_t links_over_history(const LinksOverHistory& q, void* workspace, hipStr
   a.QB = static_cast<const bf16x8*>(QB);
   a.qb_user_frags = per_user ? static_cast<int64_t>(m) * d / 8 : 0;
   a.part_acc = part_acc, a.part_ml = part_ml;
-  a.N = q.N, a.chunk_items = l.chunk_items, a.chunks = l.chunks, a.scale = q.scale;
-  const dim3 grid(l.chunks, q.B, h);
+  a.N = q.N, a.chunk_items = l.chunk_items, a.chunks = l.chunks, a.scale = fabsf(q.scale);
   profile_begin(kKernelLinksOverHistory, s);
-  e = dh == 32 ? dispatch_h<32>(a, h, m, q.phi, grid, s) : dispatch_h<64>(a, h, m, q.phi, grid, s);
+  e = dh == 32 ? dispatch_h<32>(a, h, m, q.phi, q.B, l.coop, s) : dispatch_h<64>(a, h, m, q.phi, q.B, l.coop, s);
   profile_end(kKernelLinksOverHistory, s);
   if (e != hipSuccess) return e;
 
-  MergeArgs g{part_acc, part_ml, q.lens, static_cast<bf16_t*>(q.LP), q.N, l.chunk_items, l.chunks, h, m, dh};
+  MergeArgs g{part_acc, part_ml, q.lens, static_cast<bf16_t*>(q.LP), q.N, l.chunk_items, l.chunks, h, m, dh, fabsf(q.scale)};
   const dim3 mgrid((m * d + 255) / 256, q.B);
   if (q.phi == kPhiSoftmax)
     hipLaunchKernelGGL(merge_kernel<kPhiSoftmax>, mgrid, dim3(256), 0, s, g);
