@@ -190,17 +190,20 @@ __global__ __launch_bounds__(COOP ? 64 * H : 64) void links_over_history_kernel(
         float psum = 0.f;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const float pr = __builtin_amdgcn_exp2f(fmaf(sc[i], c, shift));
-          sc[i] = ragged && sc[i] == -INFINITY ? 0.f : pr;  // (the select also covers scale = 0)
+          const float raw = sc[i];
+          sc[i] = __builtin_amdgcn_exp2f(fmaf(raw, c, shift));
+          if (ragged && raw == -INFINITY) sc[i] = 0.f;  // (explicit: also right for scale = 0)
           psum += sc[i];
         }
         run_sum[lb] += psum;
       } else {
         // SiLU(scale * s) = scale * s * sigmoid(scale * s); the factor `scale` is applied by the merge
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float pr = sc[i] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-sc[i] * c));
-          sc[i] = ragged && i0 + 8 * (i >> 2) + 4 * g + (i & 3) >= i_end ? 0.f : pr;
+        for (int i = 0; i < 16; ++i) sc[i] = sc[i] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-sc[i] * c));
+        if (ragged) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (i0 + 8 * (i >> 2) + 4 * g + (i & 3) >= i_end) sc[i] = 0.f;
         }
       }
       const bf16x8 p0 = pack_half(sc, 0), p1 = pack_half(sc, 1);
