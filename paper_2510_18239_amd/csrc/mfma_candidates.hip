@@ -45,9 +45,10 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   // so that the fragment reads are free of bank conflicts) where all H waves read it.
   constexpr int P = 2;
   constexpr int LW = DH / 16;
-  // With d = 256 the W_Q^T slice alone is half of the register file; the second half of its k-steps
-  // lives in LDS instead (read once per tile), which keeps the kernel free of register spills.
-  constexpr int KL = D >= 256 ? K1 / 2 : 0;  // k-steps of W_Q^T kept in LDS
+  // With d = 256 the W_Q^T slice alone is a quarter of the register file; with many links (whose
+  // logits and weights need registers too) the second half of its k-steps lives in LDS instead and is
+  // read once per tile, which keeps the kernel free of register spills.
+  constexpr int KL = (D >= 256 && M >= 128) ? K1 / 2 : 0;  // k-steps of W_Q^T kept in LDS
   constexpr int KR = K1 - KL;                // k-steps kept in registers
   constexpr int CPR = D / 8;            // 16-byte chunks per row of X
   constexpr int PITCH = 2 * D + 16;     // LDS row pitch of an X tile, bytes
@@ -109,72 +110,92 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
     // each wave reads back only what it wrote itself: no barrier needed
   }
 
-  // Q~^T = Wq_a^T X^T for the tile parked in `buf`; lane (n, g) reads X[row n][16kk + 8g ..]
+  // Q~^T = Wq_a^T X^T for the tile parked in `buf`; lane (n, g) reads X[row n][16kk + 8g ..].
+  // Fragment reads run kAhead k-steps ahead of the MFMAs that use them (one wave per SIMD: nobody else
+  // covers the LDS latency).  first_begin() clears the accumulators and starts the reads, first_mfma(i)
+  // issues MFMA i of the K1 * MB, so that the caller can put other work between them.
   f32x16 acc1[MB];
-  auto first_product = [&](const unsigned char* buf) {
-    const unsigned char* xrow = buf + n * PITCH + 16 * g;
+  constexpr int kAhead = 3;
+  constexpr int NM = K1 * MB;
+  bf16x8 xq[K1], wl_frag[KL > 0 ? KL : 1][MB];
+  const unsigned char* xrow = nullptr;
+  int wl = 0;
+  auto fetch = [&](int kk) {
+    xq[kk] = *reinterpret_cast<const bf16x8*>(xrow + 32 * kk);
+    if (kk >= KR) {
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) wl_frag[KL > 0 ? kk - KR : 0][mb] = wq_lds[wl + ((kk - KR) * MB + mb) * 64];
+    }
+  };
+  auto first_begin = [&](const unsigned char* buf) {
+    xrow = buf + n * PITCH + 16 * g;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc1[mb][i] = 0.f;
-    int wl = head * KL * MB * 64 + lane;
+    wl = head * KL * MB * 64 + lane;
     asm volatile("" : "+v"(wl));  // keeps the LDS reads of W_Q^T inside the tile loop
-    // fragment reads run kAhead k-steps ahead of the MFMAs that use them (one wave per SIMD: nobody
-    // else covers the LDS latency)
-    constexpr int kAhead = 3;
-    bf16x8 xq[K1], wl_frag[KL > 0 ? KL : 1][MB];
-    auto fetch = [&](int kk) {
-      xq[kk] = *reinterpret_cast<const bf16x8*>(xrow + 32 * kk);
-      if (kk >= KR) {
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) wl_frag[KL > 0 ? kk - KR : 0][mb] = wq_lds[wl + ((kk - KR) * MB + mb) * 64];
-      }
-    };
 #pragma unroll
     for (int kk = 0; kk < kAhead && kk < K1; ++kk) fetch(kk);
+  };
+  auto first_mfma = [&](int i) {
+    const int kk = i / MB, mb = i % MB;
+    if (mb == 0 && kk + kAhead < K1) fetch(kk + kAhead);
+    const bf16x8 w = kk < KR ? wq[kk < KR ? kk : 0][mb] : wl_frag[kk >= KR ? kk - KR : 0][mb];
+    acc1[mb] = mfma32(w, xq[kk], acc1[mb]);
+  };
+  auto first_product = [&](const unsigned char* buf) {
+    first_begin(buf);
 #pragma unroll
-    for (int kk = 0; kk < K1; ++kk) {
-      if (kk + kAhead < K1) fetch(kk + kAhead);
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        const bf16x8 w = kk < KR ? wq[kk < KR ? kk : 0][mb] : wl_frag[kk >= KR ? kk - KR : 0][mb];
-        acc1[mb] = mfma32(w, xq[kk], acc1[mb]);
-      }
-    }
+    for (int i = 0; i < NM; ++i) first_mfma(i);
   };
 
-  // phi over the m links of this lane's query row (the other half of the links sits in lane ^ 32);
-  // returns the factor still to be applied to the weighted sum
+  // phi over the m links of this lane's query row (the other half of the links sits in lane ^ 32), cut
+  // into steps so that the tile loop can put one matrix instruction of the next tile between them:
+  // softmax = kMaxSteps partial maxima, the exchange with lane ^ 32, kGapSteps empty steps that cover the
+  // exchange's latency, then one step per pair of links (exponential, running sum, bf16 rounding into the
+  // B fragments `pf` of the third product).  phi_finish() returns the factor still owed to the weighted sum.
   f32x16 acc2[LB];
-  auto phi = [&]() -> float {
-    if (PHI == kPhiSoftmax) {
-      const float c = a.scale * kLog2e;  // >= 0
-      float mx = acc2[0][0];
+  bf16x8 pf[K3];
+  constexpr int kPairs = LB * 8;
+  constexpr int kMaxSteps = PHI == kPhiSoftmax ? LB * 2 : 0;
+  constexpr int kGapSteps = PHI == kPhiSoftmax ? 2 : 0;
+  constexpr int kPairStep0 = PHI == kPhiSoftmax ? kMaxSteps + 1 + kGapSteps : 0;
+  constexpr int NV = kPairStep0 + kPairs;
+  const float phi_c = a.scale * kLog2e;  // >= 0
+  float phi_mx = 0.f, phi_other = 0.f, phi_shift = 0.f, phi_sum = 0.f;
+  auto phi_step = [&](int st) {
+    if (PHI == kPhiSoftmax && st < kMaxSteps) {
+      const int lb = st / 2, i0 = (st % 2) * 8;
+      if (st == 0) phi_mx = acc2[0][0];
 #pragma unroll
-      for (int lb = 0; lb < LB; ++lb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc2[lb][i]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float shift = -mx * c;  // exp2(raw * c + shift) = exp(scale * raw - max of the scaled logits)
-      float sum = 0.f;
-#pragma unroll
-      for (int lb = 0; lb < LB; ++lb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float pr = __builtin_amdgcn_exp2f(fmaf(acc2[lb][i], c, shift));
-          acc2[lb][i] = pr;
-          sum += pr;
+      for (int i = 0; i < 8; ++i) phi_mx = fmaxf(phi_mx, acc2[lb][i0 + i]);
+    } else if (PHI == kPhiSoftmax && st == kMaxSteps) {
+      phi_other = __shfl_xor(phi_mx, 32);
+    } else if (st >= kPairStep0) {
+      const int e = st - kPairStep0, lb = e / 8, i = (e % 8) * 2;
+      float p0, p1;
+      if (PHI == kPhiSoftmax) {
+        if (e == 0) {
+          phi_shift = -fmaxf(phi_mx, phi_other) * phi_c;  // exp2(raw * c + shift) = exp(scale * raw - max scaled logit)
+          phi_sum = 0.f;
         }
-      sum += __shfl_xor(sum, 32);
-      return 1.f / sum;
-    }
-#pragma unroll
-    for (int lb = 0; lb < LB; ++lb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
+        p0 = __builtin_amdgcn_exp2f(fmaf(acc2[lb][i], phi_c, phi_shift));
+        p1 = __builtin_amdgcn_exp2f(fmaf(acc2[lb][i + 1], phi_c, phi_shift));
+        phi_sum += p0;
+        phi_sum += p1;
+      } else {
         // SiLU(scale * s) = scale * s * sigmoid(scale * s); `scale` is part of the final factor
-        acc2[lb][i] = acc2[lb][i] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-acc2[lb][i] * (a.scale * kLog2e)));
+        p0 = acc2[lb][i] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-acc2[lb][i] * phi_c));
+        p1 = acc2[lb][i + 1] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-acc2[lb][i + 1] * phi_c));
       }
+      acc2[lb][i] = p0, acc2[lb][i + 1] = p1;
+      pf[2 * lb + (i >> 3)][i & 7] = static_cast<__bf16>(p0);
+      pf[2 * lb + (i >> 3)][(i & 7) + 1] = static_cast<__bf16>(p1);
+    }
+  };
+  auto phi_finish = [&]() -> float {
+    if (PHI == kPhiSoftmax) return 1.f / (phi_sum + __shfl_xor(phi_sum, 32));
     return a.inv_norm * a.scale;
   };
 
@@ -242,17 +263,22 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
         park(ring[(p + 1) % P], nbuf);
         __syncthreads();
         if (tile + P + 1 < last) issue(tile + P + 1, ring[(p + 1) % P]);
-        first_product(nbuf);
-        inv = phi();
-        // one MFMA of the next tile's first product, then a few vector-ALU operations of phi, and so on
+        // one MFMA of the next tile's first product, then its share of phi's steps, and so on; the
+        // fences keep the compiler from regrouping them
+        first_begin(nbuf);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < K1 * MB; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+        for (int i = 0; i < NM; ++i) {
+          first_mfma(i);
+#pragma unroll
+          for (int st = i * NV / NM; st < (i + 1) * NV / NM; ++st) phi_step(st);
+          __builtin_amdgcn_sched_barrier(0);
         }
       } else {
-        inv = phi();
+#pragma unroll
+        for (int st = 0; st < NV; ++st) phi_step(st);
       }
+      inv = phi_finish();
       if constexpr (WEIGHTS) {
         // register 4j + r of block lb is link 32 lb + 8 j + 4 g + r of this lane's query row
         const int row = r0 + n;
@@ -269,38 +295,42 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
             }
         }
       } else {
-      bf16x8 pf[K3];
-#pragma unroll
-      for (int lb = 0; lb < LB; ++lb) {
-        pf[2 * lb] = pack_half(acc2[lb], 0);
-        pf[2 * lb + 1] = pack_half(acc2[lb], 1);
-      }
-
       // O^T = V~_a^T phi(S)^T; lane (n, g) gets 16 consecutive columns per block.  The wave's 32 x d/h
       // output tile goes through LDS so that whole 2*d/h-byte row segments are stored at once.
       unsigned char* otile = os[head];
+      f32x16 acc3[MB];
 #pragma unroll
       for (int ob = 0; ob < MB; ++ob) {
-        f32x16 acc3;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc3[i] = 0.f;
+        for (int i = 0; i < 16; ++i) acc3[ob][i] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < K3; ++kk) acc3 = mfma32(va[kk][ob], pf[kk], acc3);
+        for (int kk = 0; kk < K3; ++kk) acc3[ob] = mfma32(va[kk][ob], pf[kk], acc3[ob]);
+      }
+#pragma unroll
+      for (int ob = 0; ob < MB; ++ob) {
         bf16x8 lo, hi;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-          lo[t] = static_cast<__bf16>(acc3[t] * inv);
-          hi[t] = static_cast<__bf16>(acc3[8 + t] * inv);
+          lo[t] = static_cast<__bf16>(acc3[ob][t] * inv);
+          hi[t] = static_cast<__bf16>(acc3[ob][8 + t] * inv);
         }
         unsigned char* dst = otile + n * OPITCH + (32 * ob + 16 * g) * 2;
         *reinterpret_cast<bf16x8*>(dst) = lo;
         *reinterpret_cast<bf16x8*>(dst + 16) = hi;
       }
+      // all reads of the staged tile first, then the stores: one LDS round trip instead of LW
+      bf16x8 ov[LW];
+#pragma unroll
+      for (int j = 0; j < LW; ++j) {
+        const int q = j * 64 + lane;
+        ov[j] = *reinterpret_cast<const bf16x8*>(otile + (q / OCPR) * OPITCH + (q % OCPR) * 16);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int j = 0; j < LW; ++j) {
         const int q = j * 64 + lane;
         const int row = r0 + q / OCPR;
-        bf16x8 v = *reinterpret_cast<const bf16x8*>(otile + (q / OCPR) * OPITCH + (q % OCPR) * 16);
+        bf16x8 v = ov[j];
         if (row >= rlen) {
 #pragma unroll
           for (int t = 0; t < 8; ++t) v[t] = static_cast<__bf16>(0.f);
