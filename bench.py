@@ -5,12 +5,19 @@ A "step" is one LIME request of the headline workload: lime_link_history over th
 history (Eq. 3) followed by lime_score_candidates over the C candidates (Eq. 4), at
 B=1, N=2048, C=32768, d=256, h=4, m=64, bf16, inputs resident in HBM.  Candidate and
 output buffers rotate through more memory than the 256 MiB last-level cache holds, so the
-candidate stream really comes from HBM.  Prints one JSON line.
+candidate stream really comes from HBM.
+
+Throughput is that of a serving loop: every request is one captured HIP graph (five kernels), and
+requests of different users are independent, so the loop keeps --streams of them in flight, each on
+its own stream with its own link states and workspace; the small kernels of one request then run
+beside the candidate kernel of another.  Latency is that of one request alone on an idle GPU.
+Prints one JSON line.
 """
 
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
 import statistics
@@ -32,7 +39,8 @@ def parse_args():
     p.add_argument("--candidates", type=int, default=32768, help="C of the headline workload")
     p.add_argument("--history", type=int, default=2048, help="N of the headline workload")
     p.add_argument("--rotate-mib", type=int, default=544, help="candidate+output bytes to rotate through (0 = reuse one pair)")
-    p.add_argument("--eager", action="store_true", help="launch every kernel from the host instead of replaying a captured HIP graph")
+    p.add_argument("--streams", type=int, default=4, help="requests kept in flight (one stream, link-state buffer and workspace each)")
+    p.add_argument("--eager", action="store_true", help="launch every kernel from the host, on one stream, instead of replaying captured HIP graphs")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--extras", action="store_true", help="also time the XORA history pass, the C sweep and the MHA baseline")
     return p.parse_args()
@@ -68,35 +76,62 @@ def main():
     T0 = t(w.T)
     Ts = [T0] + [T0.clone() for _ in range(n_pairs - 1)]
     Os = [torch.empty_like(T0) for _ in range(n_pairs)]
-    LP = torch.empty((B, m, d), dtype=torch.bfloat16, device=dev)
-    ws = torch.empty(max(binding.workspace_bytes(binding.OP_LINK_HISTORY, B=B, N=N, d=d, h=h, m=m),
-                         binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=B, C=C, d=d, h=h, m=m)),
-                     dtype=torch.uint8, device=dev)
+    ws_bytes = max(binding.workspace_bytes(binding.OP_LINK_HISTORY, B=B, N=N, d=d, h=h, m=m),
+                   binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=B, C=C, d=d, h=h, m=m))
+    n_streams = 1 if args.eager else max(1, args.streams)
+    # one slot per request in flight: link states and workspace are private to a request
+    slots = [(torch.empty((B, m, d), dtype=torch.bfloat16, device=dev),
+              torch.empty(ws_bytes, dtype=torch.uint8, device=dev)) for _ in range(n_streams)]
+    LP, ws = slots[0]
 
-    def step(i):
-        binding.lime_link_history(E, None, L, Wq, Wk, Wv, h, scale, LP=LP, workspace=ws)
-        binding.lime_score_candidates(Ts[i % n_pairs], L, LP, Wq, Wk, Wv, h, scale, O=Os[i % n_pairs], workspace=ws)
+    def step(i, slot=0, stream=None):
+        lp, wsp = slots[slot]
+        binding.lime_link_history(E, None, L, Wq, Wk, Wv, h, scale, LP=lp, workspace=wsp, stream=stream)
+        binding.lime_score_candidates(Ts[i % n_pairs], L, lp, Wq, Wk, Wv, h, scale, O=Os[i % n_pairs], workspace=wsp,
+                                      stream=stream)
 
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
 
-    # A serving loop replays one captured HIP graph per request (five kernel launches, no host work
-    # between them); one graph per rotating buffer pair.  --eager times host-side launches instead.
     run = step
+    run_single = step
     if not args.eager:
-        graphs = []
-        for j in range(n_pairs):
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g):
-                step(j)
-            graphs.append(g)
+        # One captured HIP graph per (buffer pair, stream); graphs are launched with hipGraphLaunch directly
+        # (torch's replay() costs more host time per launch than a request takes on the GPU).
+        hip = HipGraphs()
+        pool = [hip.stream() for _ in range(2 * n_streams)]
+        streams = pool[:n_streams]
+        n_graphs = max(n_streams, n_pairs // n_streams * n_streams)
+        graphs = [hip.capture(streams[j % n_streams], lambda st, j=j: step(j, j % n_streams, st)) for j in range(n_graphs)]
+        single = [hip.capture(streams[0], lambda st, j=j: step(j, 0, st)) for j in range(n_pairs)]
         torch.cuda.synchronize()
 
         def run(i):
-            graphs[i % n_pairs].replay()
+            hip.launch(graphs[i % n_graphs], streams[i % n_streams])
 
-        for i in range(args.warmup):
+        def run_single(i):
+            hip.launch(single[i % n_pairs], streams[0])
+
+        # The runtime multiplexes streams onto a few hardware queues (4 here) and the first streams a
+        # process creates do not always land on different ones; two requests on one queue run one after
+        # the other.  Try the first and the second half of the pool briefly and keep the faster half.
+        def probe(cand):
+            nonlocal streams
+            streams = cand
+            for i in range(6 * n_graphs):
+                run(i)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(20 * n_graphs):
+                run(i)
+            torch.cuda.synchronize()
+            return time.perf_counter() - t0
+
+        halves = [pool[:n_streams], pool[n_streams:]]
+        probe_ms = [probe(c) * 1e3 for c in halves] if n_streams > 1 else [0.0, 0.0]
+        streams = halves[0] if probe_ms[0] <= probe_ms[1] else halves[1]
+        for i in range(max(args.warmup, n_graphs)):
             run(i)
         torch.cuda.synchronize()
 
@@ -104,10 +139,21 @@ def main():
     t0 = time.perf_counter()
     for i in range(args.steps):
         run(i)
+    host_ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps  # time the launches alone took
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
     value = B * C / (ms_per_step * 1e-3)
+
+    # the same loop with one request in flight (one stream)
+    for i in range(args.warmup):
+        run_single(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        run_single(i)
+    torch.cuda.synchronize()
+    ms_per_step_single = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # ---- per-call latencies (events on the launch stream) and the dominant kernel's own duration
     def timed(fn, reps):
@@ -123,7 +169,10 @@ def main():
         return xs[min(len(xs) - 1, int(q * len(xs)))]
 
     reps = args.steps
-    lat_step = timed(run, reps)
+    if args.eager:
+        lat_step = timed(run, reps)
+    else:
+        lat_step = hip.timed(lambda i: run_single(i), streams[0], reps)
     lat_hist = timed(lambda i: binding.lime_link_history(E, None, L, Wq, Wk, Wv, h, scale, LP=LP, workspace=ws), reps)
     binding.profile_enable(True)
     binding.profile_collect(0)
@@ -155,11 +204,15 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"configs[2] candidate sweep point: B={B} user, N={N}, C={C}, d={d}, h={h}, m={m}, "
                                "bf16, embeddings and weights ~N(0,1/d); step = lime_link_history + lime_score_candidates",
-                   "launch": "eager" if args.eager else "hipGraph replay (one graph per request)",
+                   "launch": "eager, one stream" if args.eager else
+                             f"one HIP graph per request, {n_streams} requests in flight on {n_streams} streams",
+                   "stream_probe_ms": None if args.eager else probe_ms,
                    "rotating_buffer_pairs": n_pairs, "rotating_mib": n_pairs * pair_bytes / 2 ** 20},
         "latency_ms": {"request_p50": pct(lat_step, 0.5), "request_p10": pct(lat_step, 0.1),
                        "request_p90": pct(lat_step, 0.9), "lime_link_history_p50": pct(lat_hist, 0.5),
                        "lime_score_candidates_p50": pct(lat_cand, 0.5)},
+        "host_launch_ms_per_step": host_ms_per_step,
+        "one_request_in_flight": {"ms_per_step": ms_per_step_single, "candidates_per_s": B * C / (ms_per_step_single * 1e-3)},
         "candidates_per_s_candidate_call_only": B * C / (pct(lat_cand, 0.5) * 1e-3),
         "roofline": {"bound": "hbm", "kernel": "queries_over_links_kernel<64,64,4,softmax>", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
@@ -176,6 +229,67 @@ def main():
         out["cpu_baseline"] = cpu_baseline(w, scale)
 
     print(json.dumps(out))
+
+
+class HipGraphs:
+    """Stream capture, instantiation and launch of HIP graphs through the HIP runtime's C API."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.keep = []
+
+    def check(self, err, what):
+        if err != 0:
+            raise RuntimeError(f"{what} failed with HIP error {err}")
+
+    def stream(self):
+        st = ctypes.c_void_p()
+        self.check(self.hip.hipStreamCreateWithFlags(ctypes.byref(st), 1), "hipStreamCreateWithFlags")  # non-blocking
+        return st
+
+    def capture(self, stream, fn):
+        """Records what fn(stream_handle) enqueues on `stream` and returns the executable graph."""
+
+        class Handle:  # what the binding expects of a stream object
+            cuda_stream = stream.value
+
+        self.check(self.hip.hipStreamBeginCapture(stream, 2), "hipStreamBeginCapture")  # relaxed mode
+        try:
+            fn(Handle)
+        finally:
+            graph = ctypes.c_void_p()
+            err = self.hip.hipStreamEndCapture(stream, ctypes.byref(graph))
+        self.check(err, "hipStreamEndCapture")
+        exe = ctypes.c_void_p()
+        self.check(self.hip.hipGraphInstantiate(ctypes.byref(exe), graph, None, None, 0), "hipGraphInstantiate")
+        self.keep.append(graph)
+        return exe
+
+    def launch(self, exe, stream):
+        err = self.hip.hipGraphLaunch(exe, stream)
+        if err != 0:
+            self.check(err, "hipGraphLaunch")
+
+    def timed(self, fn, stream, reps):
+        """Sorted durations (ms) of fn(i), each between two events recorded on `stream`."""
+        evs = []
+        for _ in range(2 * reps):
+            ev = ctypes.c_void_p()
+            self.check(self.hip.hipEventCreate(ctypes.byref(ev)), "hipEventCreate")
+            evs.append(ev)
+        for i in range(reps):
+            self.check(self.hip.hipEventRecord(evs[2 * i], stream), "hipEventRecord")
+            fn(i)
+            self.check(self.hip.hipEventRecord(evs[2 * i + 1], stream), "hipEventRecord")
+        self.check(self.hip.hipStreamSynchronize(stream), "hipStreamSynchronize")
+        out = []
+        for i in range(reps):
+            ms = ctypes.c_float()
+            self.check(self.hip.hipEventElapsedTime(ctypes.byref(ms), evs[2 * i], evs[2 * i + 1]), "hipEventElapsedTime")
+            out.append(ms.value)
+        for ev in evs:
+            self.hip.hipEventDestroy(ev)
+        return sorted(out)
 
 
 # HBM bytes per launch of the dominant kernel at the default workload, from the rocprofv3 --pmc FETCH_SIZE

@@ -234,6 +234,40 @@ def test_hip_graph_replay_matches_eager():
             assert torch.equal(got, ref)
 
 
+def test_concurrent_requests_on_separate_streams():
+    """Requests of different users in flight at once, each on its own stream with its own link states and
+    workspace (how the benchmark's serving loop runs them): the library keeps no state between calls, so
+    every request must give the bits it gives when it runs alone."""
+    n = 4
+    ws_list, inputs, want = [], [], []
+    for k in range(n):
+        w = _sharp(workload=60 + k, B=1, N=700 + 64 * k, C=3000 + 100 * k, d=256, h=4, m=64, dtype="bf16")
+        g = DeviceWorkload(w)
+        LP = binding.lime_link_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, 4, w.softmax_scale)
+        O = binding.lime_score_candidates(g.T, g.L, LP, g.Wq, g.Wk, g.Wv, 4, w.softmax_scale)
+        torch.cuda.synchronize()
+        want.append((LP.clone(), O.clone()))
+        inputs.append((w, g))
+        ws_list.append(torch.empty(max(binding.workspace_bytes(binding.OP_LINK_HISTORY, B=1, N=w.N, d=256, h=4, m=64),
+                                       binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=1, C=w.C, d=256, h=4, m=64)),
+                                   dtype=torch.uint8, device="cuda"))
+    streams = [torch.cuda.Stream() for _ in range(n)]
+    got = [(torch.empty_like(lp), torch.empty_like(o)) for lp, o in want]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for k in range(n):
+            w, g = inputs[k]
+            LP, O = got[k]
+            binding.lime_link_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, 4, w.softmax_scale, LP=LP,
+                                      workspace=ws_list[k], stream=streams[k])
+            binding.lime_score_candidates(g.T, g.L, LP, g.Wq, g.Wk, g.Wv, 4, w.softmax_scale, O=O,
+                                          workspace=ws_list[k], stream=streams[k])
+    torch.cuda.synchronize()
+    for k in range(n):
+        assert torch.equal(got[k][0], want[k][0]), f"link states of request {k}"
+        assert torch.equal(got[k][1], want[k][1]), f"candidate outputs of request {k}"
+
+
 @pytest.mark.parametrize("scale", [-0.2, 0.0])
 @pytest.mark.parametrize("dtype,d,h,m", [("bf16", 256, 4, 64), ("bf16", 128, 4, 64), ("fp32", 64, 2, 16)])
 def test_negative_and_zero_logit_scale(scale, dtype, d, h, m):
