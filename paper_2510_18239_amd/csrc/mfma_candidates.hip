@@ -69,19 +69,42 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   // Rows past a user's last row are read from whatever follows (the next user's rows; zeros past the
   // end of the tensor): every row is an independent column of the three products and such columns
   // are never stored.
-  auto issue = [&](int tile, bf16x8 (&r)[LW]) {
-    const int tb = tile / a.tiles_per_user;
-    const int64_t row0 = static_cast<int64_t>(tb) * a.rows + (tile - tb * a.tiles_per_user) * 32;
+  // A tile is named by (user, first row); the byte offsets of a lane's pieces inside a tile never change,
+  // so that a load is one scalar base plus a per-lane offset.
+  int xoff[LW], ooff[LW];
 #pragma unroll
-    for (int j = 0; j < LW; ++j) {
-      const int q = (head * LW + j) * 64 + lane;
-      const int64_t row = row0 + q / CPR;
-      bf16x8 v;
+  for (int j = 0; j < LW; ++j) {
+    const int q = (head * LW + j) * 64 + lane;
+    xoff[j] = ((q / CPR) * D + (q % CPR) * 8) * 2;
+    const int o = j * 64 + lane;
+    ooff[j] = ((o / OCPR) * D + (o % OCPR) * 8) * 2;
+  }
+  auto issue = [&](int tb, int tr0, bf16x8 (&r)[LW]) {
+    const int64_t row0 = static_cast<int64_t>(tb) * a.rows + tr0;
+    const unsigned char* base = reinterpret_cast<const unsigned char*>(a.X) + row0 * (2 * D);
+    if (row0 + 32 <= total_rows) {  // uniform: the whole tile lies inside the tensor
 #pragma unroll
-      for (int t = 0; t < 8; ++t) v[t] = static_cast<__bf16>(0.f);
-      if (row < total_rows) v = *reinterpret_cast<const bf16x8*>(a.X + row * D + (q % CPR) * 8);
-      r[j] = v;
+      for (int j = 0; j < LW; ++j) r[j] = *reinterpret_cast<const bf16x8*>(base + xoff[j]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < LW; ++j) {
+        const int q = (head * LW + j) * 64 + lane;
+        bf16x8 v;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] = static_cast<__bf16>(0.f);
+        if (row0 + q / CPR < total_rows) v = *reinterpret_cast<const bf16x8*>(base + xoff[j]);
+        r[j] = v;
+      }
     }
+  };
+  // (user, first row) of a tile index, and of the tile after a given one
+  auto locate = [&](int tile, int& tb, int& tr0) {
+    tb = tile / a.tiles_per_user;
+    tr0 = (tile - tb * a.tiles_per_user) * 32;
+  };
+  auto advance = [&](int& tb, int& tr0) {
+    tr0 += 32;
+    if (tr0 >= a.rows) tr0 = 0, ++tb;
   };
   auto park = [&](const bf16x8 (&r)[LW], unsigned char* buf) {
 #pragma unroll
@@ -92,9 +115,15 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   };
 
   bf16x8 ring[P][LW];
+  int ib, ir0;  // the next tile to request
+  locate(first, ib, ir0);
+  const int b_first = ib, r0_first = ir0;
 #pragma unroll
   for (int p = 0; p < P; ++p)
-    if (first + p < last) issue(first + p, ring[p]);
+    if (first + p < last) {
+      issue(ib, ir0, ring[p]);
+      advance(ib, ir0);
+    }
 
   bf16x8 wq[KR][MB];
 #pragma unroll
@@ -218,13 +247,18 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   };
   int cur_user = first / a.tiles_per_user;
   load_user(cur_user, true, !WEIGHTS);  // requested with everything else, long before their first use
+  int rlen = a.row_lens ? min(a.row_lens[cur_user], a.rows) : a.rows;
 
   // Software pipeline: while the vector ALUs do phi of tile i, the matrix cores already run the
   // first product of tile i+1, whose X rows were parked in the other LDS buffer.
   park(ring[0], xs[0]);
   __syncthreads();
-  if (first + P < last) issue(first + P, ring[0]);
+  if (first + P < last) {
+    issue(ib, ir0, ring[0]);
+    advance(ib, ir0);
+  }
   first_product(xs[0]);
+  int b = b_first, r0 = r0_first;  // the tile being computed
 
   for (int base = first; base < last; base += P) {
 #pragma unroll
@@ -232,13 +266,22 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
       const int tile = base + p;
       if (tile >= last) break;  // uniform over the workgroup
       const bool has_next = tile + 1 < last;
-      const int b = tile / a.tiles_per_user;
-      const int r0 = (tile - b * a.tiles_per_user) * 32;
       if (b != cur_user) {
+        // A new user's operands are waited for right here, inside the rare branch: left pending, they
+        // would make every tile wait for all of its outstanding loads and stores before the second product.
         load_user(b, a.ka_user_frags != 0, !WEIGHTS && a.va_user_frags != 0);
+        rlen = a.row_lens ? min(a.row_lens[b], a.rows) : a.rows;
         cur_user = b;
+#pragma unroll
+        for (int kk = 0; kk < K2; ++kk)
+#pragma unroll
+          for (int lb = 0; lb < LB; ++lb) asm volatile("" : "+v"(ka[kk][lb]));
+#pragma unroll
+        for (int kk = 0; kk < K3; ++kk)
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) asm volatile("" : "+v"(va[kk][mb]));
+        asm volatile("" : "+v"(rlen));
       }
-      const int rlen = a.row_lens ? min(a.row_lens[b], a.rows) : a.rows;
 
       // S^T = K~_a Q~^T from this tile's first product
       bf16x8 qf[K2];
@@ -262,7 +305,10 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
         unsigned char* nbuf = xs[(p + 1) & 1];
         park(ring[(p + 1) % P], nbuf);
         __syncthreads();
-        if (tile + P + 1 < last) issue(tile + P + 1, ring[(p + 1) % P]);
+        if (tile + P + 1 < last) {
+          issue(ib, ir0, ring[(p + 1) % P]);
+          advance(ib, ir0);
+        }
         // one MFMA of the next tile's first product, then its share of phi's steps, and so on; the
         // fences keep the compiler from regrouping them
         first_begin(nbuf);
@@ -326,19 +372,25 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
         ov[j] = *reinterpret_cast<const bf16x8*>(otile + (q / OCPR) * OPITCH + (q % OCPR) * 16);
       }
       __builtin_amdgcn_sched_barrier(0);
+      unsigned char* obase = reinterpret_cast<unsigned char*>(a.O) +
+                             ((static_cast<int64_t>(b) * a.rows + r0) * D + head * DH) * 2;
+      if (r0 + 32 <= min(rlen, a.rows)) {  // uniform: every row of the tile is stored as computed
 #pragma unroll
-      for (int j = 0; j < LW; ++j) {
-        const int q = j * 64 + lane;
-        const int row = r0 + q / OCPR;
-        bf16x8 v = ov[j];
-        if (row >= rlen) {
+        for (int j = 0; j < LW; ++j) *reinterpret_cast<bf16x8*>(obase + ooff[j]) = ov[j];
+      } else {
 #pragma unroll
-          for (int t = 0; t < 8; ++t) v[t] = static_cast<__bf16>(0.f);
+        for (int j = 0; j < LW; ++j) {
+          const int row = r0 + (j * 64 + lane) / OCPR;
+          bf16x8 v = ov[j];
+          if (row >= rlen) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) v[t] = static_cast<__bf16>(0.f);
+          }
+          if (row < a.rows) *reinterpret_cast<bf16x8*>(obase + ooff[j]) = v;
         }
-        if (row < a.rows)
-          *reinterpret_cast<bf16x8*>(a.O + (static_cast<int64_t>(b) * a.rows + row) * D + head * DH + (q % OCPR) * 8) = v;
       }
       }
+      advance(b, r0);
     }
   }
 }
