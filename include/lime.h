@@ -111,6 +111,11 @@ int32_t mha_target_attention(const void* T, const void* E, const int32_t* lens,
  *   lime_score_candidates_cached:  O[b][c][head a] = sum_i W[b][c][a][i] * (LP[b] Wv)[i][head a]
  *     (online: a lookup and a weighted sum of the personalised links).  Wv may be NULL.  Out: O[B][C][d].
  * Chaining the two equals lime_score_candidates up to the storage rounding of W.
+ *   lime_score_candidates_gathered:  the same online stage when the cache is one table for the whole item corpus,
+ *     Wtable[n_items][h][m] (lime_build_qk_cache with B = 1 and T = the corpus), and a request names its candidates
+ *     by id:  O[b][c][head a] = sum_i Wtable[ids[b][c]][a][i] * (LP[b] Wv)[i][head a].  ids: device int32 [B][C];
+ *     an id outside [0, n_items) is checked on the device and gives an all-zero output row.  Workspace size as for
+ *     LIME_OP_SCORE_CACHED.
  */
 int32_t lime_build_qk_cache(const void* T, const void* L, const void* Wq, const void* Wk, void* W,
                             int32_t B, int32_t C, int32_t d, int32_t h, int32_t m,
@@ -118,6 +123,9 @@ int32_t lime_build_qk_cache(const void* T, const void* L, const void* Wq, const 
 int32_t lime_score_candidates_cached(const void* W, const void* LP, const void* Wv, void* O,
                                      int32_t B, int32_t C, int32_t d, int32_t h, int32_t m,
                                      int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
+int32_t lime_score_candidates_gathered(const void* Wtable, const int32_t* ids, int32_t n_items, const void* LP,
+                                       const void* Wv, void* O, int32_t B, int32_t C, int32_t d, int32_t h, int32_t m,
+                                       int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
 
 /*
  * Workspace size in bytes for `op` (LIME_OP_*) at the given shape; dimensions an op
@@ -133,7 +141,7 @@ size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t
  * bracketed by a pair of HIP events on its stream (kernel ids: 0 = the candidate-side kernel
  * of lime_score_candidates and of O[S]; 1 = the links-over-history kernel of lime_link_history /
  * lime_xor_history; 2 = the attention kernel of mha_target_attention; 3 = their K/V projection; 4 = the kernel of
- * lime_score_candidates_cached).
+ * lime_score_candidates_cached and lime_score_candidates_gathered).
  * lime_profile_collect(kernel, ms, capacity): waits for the recorded launches of that kernel,
  * writes up to `capacity` durations in milliseconds to the HOST array `ms` in launch order,
  * forgets them and returns how many it wrote.  Only the matrix-core kernels are instrumented.

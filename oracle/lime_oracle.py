@@ -313,3 +313,28 @@ def lime_score_candidates_cached(W, LP, Wv, h):
             cols = slice(a * dh, (a + 1) * dh)
             O[b][:, cols] = W[b, :, a, :] @ Vt[:, cols]
     return O
+
+
+def lime_score_candidates_gathered(Wtable, ids, LP, Wv, h):
+    """The online stage of Section 3.3 when the cached weights are one table for the whole item corpus and a
+    request names its candidates by id: O[b, c] is the weighted sum of user b's projected link states with the
+    weights in row ids[b, c] of the table; an id outside the table gives a zero row.
+
+    Wtable [n_items, h, m]; ids [B, C] integers; LP [B, m, d].  Returns [B, C, d].
+    """
+    Wtable, LP = _f64(Wtable), _f64(LP)
+    ids = np.asarray(ids)
+    n_items, _, m = Wtable.shape
+    B, C = ids.shape
+    d = LP.shape[2]
+    dh = d // h
+    O = np.zeros((B, C, d))
+    for b in range(B):
+        Vt = project(LP[b], Wv)
+        for c in range(C):
+            i = int(ids[b, c])
+            if not 0 <= i < n_items:
+                continue
+            for a in range(h):
+                O[b, c, a * dh:(a + 1) * dh] = Wtable[i, a] @ Vt[:, a * dh:(a + 1) * dh]
+    return O

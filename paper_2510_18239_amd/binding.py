@@ -36,6 +36,8 @@ SIGNATURES = {
                                     _vp, _sz, _vp]),
     "lime_build_qk_cache": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32, _i32, _vp, _sz, _vp]),
     "lime_score_candidates_cached": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _sz, _vp]),
+    "lime_score_candidates_gathered": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _sz,
+                                              _vp]),
     "lime_workspace_bytes": (_sz, [_i32] * 9),
     "lime_profile_enable": (None, [_i32]),
     "lime_profile_collect": (_i32, [_i32, _c.POINTER(_c.c_float), _i32]),
@@ -252,5 +254,25 @@ def lime_score_candidates_cached(W, LP, Wv, O=None, workspace=None, stream=None)
     with torch.cuda.device(W.device):
         st = lib().lime_score_candidates_cached(_ptr(W), _ptr(LP), _ptr(Wv), _ptr(O), B, C, d, h, m, code, _ptr(ws),
                                                 ws.numel(), _stream(stream))
+    _raise(st)
+    return O
+
+
+def lime_score_candidates_gathered(Wtable, ids, LP, Wv, O=None, workspace=None, stream=None):
+    """O[B, C, d] from a corpus-wide table of cached weights Wtable[n_items, h, m] and candidate ids [B, C] (int32):
+    row ids[b, c] of the table times the projected link states of user b; ids outside the table give zero rows."""
+    first = _check(Wtable, LP, Wv, O)
+    assert ids.dtype == torch.int32 and ids.is_contiguous() and ids.device == Wtable.device, "ids: contiguous int32 on the device"
+    n_items, h, m = Wtable.shape
+    B, C = ids.shape
+    d = LP.shape[2]
+    code = _dtype_code(first)
+    if O is None:
+        O = torch.empty((B, C, d), dtype=Wtable.dtype, device=Wtable.device)
+    need = workspace_bytes(OP_SCORE_CACHED, B=B, C=C, d=d, h=h, m=m, dtype=code)
+    ws = workspace if workspace is not None else get_workspace(need, Wtable.device)
+    with torch.cuda.device(Wtable.device):
+        st = lib().lime_score_candidates_gathered(_ptr(Wtable), _ptr(ids), n_items, _ptr(LP), _ptr(Wv), _ptr(O), B, C, d,
+                                                  h, m, code, _ptr(ws), ws.numel(), _stream(stream))
     _raise(st)
     return O

@@ -288,10 +288,13 @@ int32_t lime_build_qk_cache(const void* T, const void* L, const void* Wq, const 
   return LIME_OK;
 }
 
-int32_t lime_score_candidates_cached(const void* W, const void* LP, const void* Wv, void* O, int32_t B, int32_t C,
-                                     int32_t d, int32_t h, int32_t m, int32_t dtype, void* workspace, size_t ws_bytes,
-                                     void* stream) {
-  const char* fn = "lime_score_candidates_cached";
+namespace {
+
+// Shared by the two online entry points of the QK-cache path: weights either per (user, candidate) or gathered
+// from a table by id.
+int32_t cached_impl(const char* fn, const void* W, const int32_t* ids, int32_t n_items, const void* LP, const void* Wv,
+                    void* O, int32_t B, int32_t C, int32_t d, int32_t h, int32_t m, int32_t dtype, void* workspace,
+                    size_t ws_bytes, void* stream) {
   if (int32_t st = check_common(fn, B, d, h, dtype)) return st;
   if (C <= 0 || m <= 0) return fail(LIME_INVALID_ARG, "%s: C and m must be positive (C=%d m=%d)", fn, C, m);
   if (!W || !LP || !O) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
@@ -301,7 +304,7 @@ int32_t lime_score_candidates_cached(const void* W, const void* LP, const void* 
     const size_t need = lime::cached_candidates_workspace(B, d, m);
     if (!workspace || ws_bytes < need)
       return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? ws_bytes : 0);
-    lime::CachedCandidates q{W, LP, Wv, O, B, C, d, h, m};
+    lime::CachedCandidates q{W, ids, n_items, LP, Wv, O, B, C, d, h, m};
     LIME_HIP(lime::cached_candidates(q, workspace, s));
     return LIME_OK;
   }
@@ -311,8 +314,26 @@ int32_t lime_score_candidates_cached(const void* W, const void* LP, const void* 
     return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, p.bytes, workspace ? ws_bytes : 0);
   p = plan_queries(workspace, 0, 0, v_rows, d);
   LIME_HIP(lime::generic_project(LP, Wv, p.Vt, v_rows, d, dtype, s));
-  LIME_HIP(lime::generic_cached_sum(W, p.Vt, O, B, C, d, h, m, dtype, s));
+  LIME_HIP(lime::generic_cached_sum(W, ids, n_items, p.Vt, O, B, C, d, h, m, dtype, s));
   return LIME_OK;
+}
+
+}  // namespace
+
+int32_t lime_score_candidates_cached(const void* W, const void* LP, const void* Wv, void* O, int32_t B, int32_t C,
+                                     int32_t d, int32_t h, int32_t m, int32_t dtype, void* workspace, size_t ws_bytes,
+                                     void* stream) {
+  return cached_impl("lime_score_candidates_cached", W, nullptr, 0, LP, Wv, O, B, C, d, h, m, dtype, workspace, ws_bytes,
+                     stream);
+}
+
+int32_t lime_score_candidates_gathered(const void* Wtable, const int32_t* ids, int32_t n_items, const void* LP,
+                                       const void* Wv, void* O, int32_t B, int32_t C, int32_t d, int32_t h, int32_t m,
+                                       int32_t dtype, void* workspace, size_t ws_bytes, void* stream) {
+  const char* fn = "lime_score_candidates_gathered";
+  if (!ids) return fail(LIME_INVALID_ARG, "%s: ids is NULL", fn);
+  if (n_items <= 0) return fail(LIME_INVALID_ARG, "%s: n_items must be positive (%d)", fn, n_items);
+  return cached_impl(fn, Wtable, ids, n_items, LP, Wv, O, B, C, d, h, m, dtype, workspace, ws_bytes, stream);
 }
 
 size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t d, int32_t h, int32_t m,

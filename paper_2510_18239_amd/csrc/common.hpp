@@ -57,10 +57,11 @@ struct GenericAttention {
 hipError_t generic_attention(const GenericAttention& a, hipStream_t s);
 
 // QK cache (Section 3.3): W[rows][h][m] = softmax over m of scale * <Q[row]_head, K[i]_head> (Q, K projected, fp32);
-// and the online weighted sum O[b][c][col] = sum_i W[b][c][head(col)][i] * V[b][i][col] (V projected, fp32).
+// and the online weighted sum O[b][c][col] = sum_i W[b][c][head(col)][i] * V[b][i][col] (V projected, fp32);
+// with ids (nullable) the weight row of (b, c) is row ids[b][c] of a table of n_items rows.
 hipError_t generic_qk_weights(const float* Q, const float* K, void* W, int64_t rows, int d, int h, int m, float scale,
                               int dtype, hipStream_t s);
-hipError_t generic_cached_sum(const void* W, const float* V, void* O, int B, int C, int d, int h, int m, int dtype,
-                              hipStream_t s);
+hipError_t generic_cached_sum(const void* W, const int32_t* ids, int n_items, const float* V, void* O, int B, int C,
+                              int d, int h, int m, int dtype, hipStream_t s);
 
 }  // namespace lime

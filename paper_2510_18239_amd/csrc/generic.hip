@@ -235,16 +235,27 @@ __global__ __launch_bounds__(256) void qk_weights_kernel(const float* __restrict
   }
 }
 
-// One thread per output element: O[b][c][col] = sum_i W[b][c][head(col)][i] * V[b][i][col].
+// One thread per output element: O[b][c][col] = sum_i W[b][c][head(col)][i] * V[b][i][col]; with ids, the
+// weight row is row ids[b][c] of a table of n_items rows, and an id outside the table gives zero.
 template <typename T>
-__global__ __launch_bounds__(256) void cached_sum_kernel(const T* __restrict__ W, const float* __restrict__ V,
-                                                         T* __restrict__ O, int64_t total, int C, int d, int h, int m) {
+__global__ __launch_bounds__(256) void cached_sum_kernel(const T* __restrict__ W, const int32_t* __restrict__ ids,
+                                                         int n_items, const float* __restrict__ V, T* __restrict__ O,
+                                                         int64_t total, int C, int d, int h, int m) {
   const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   if (idx >= total) return;
   const int col = static_cast<int>(idx % d);
   const int64_t row = idx / d, b = row / C;
   const int head = col / (d / h);
-  const T* w = W + (row * h + head) * m;
+  int64_t wrow = row;
+  if (ids != nullptr) {
+    const int id = ids[row];
+    if (static_cast<unsigned>(id) >= static_cast<unsigned>(n_items)) {
+      store_as(O + idx, 0.f);
+      return;
+    }
+    wrow = id;
+  }
+  const T* w = W + (wrow * h + head) * m;
   const float* v = V + b * m * d + col;
   float acc = 0.f;
   for (int i = 0; i < m; ++i) acc = fmaf(to_float(w[i]), v[static_cast<int64_t>(i) * d], acc);
@@ -264,15 +275,15 @@ hipError_t generic_qk_weights(const float* Q, const float* K, void* W, int64_t r
   return hipGetLastError();
 }
 
-hipError_t generic_cached_sum(const void* W, const float* V, void* O, int B, int C, int d, int h, int m, int dtype,
-                              hipStream_t s) {
+hipError_t generic_cached_sum(const void* W, const int32_t* ids, int n_items, const float* V, void* O, int B, int C,
+                              int d, int h, int m, int dtype, hipStream_t s) {
   const int64_t total = static_cast<int64_t>(B) * C * d;
   dim3 grid(static_cast<unsigned>((total + 255) / 256));
   if (dtype == 0)
-    hipLaunchKernelGGL(cached_sum_kernel<float>, grid, dim3(256), 0, s, static_cast<const float*>(W), V,
+    hipLaunchKernelGGL(cached_sum_kernel<float>, grid, dim3(256), 0, s, static_cast<const float*>(W), ids, n_items, V,
                        static_cast<float*>(O), total, C, d, h, m);
   else
-    hipLaunchKernelGGL(cached_sum_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t*>(W), V,
+    hipLaunchKernelGGL(cached_sum_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t*>(W), ids, n_items, V,
                        static_cast<bf16_t*>(O), total, C, d, h, m);
   return hipGetLastError();
 }

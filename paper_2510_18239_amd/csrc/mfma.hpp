@@ -97,7 +97,9 @@ hipError_t queries_over_links(const QueriesOverLinks& a, void* workspace, hipStr
 
 // ----------------------------------------------------------------------------- QK-cache scoring (mfma_cached.hip)
 struct CachedCandidates {
-  const void* W;    // [B][C][h][m] bf16 cached attention weights
+  const void* W;    // [B][C][h][m] bf16 cached attention weights; with ids: the table [n_items][h][m]
+  const int32_t* ids;  // nullable: [B][C] rows of the table; an id outside [0, n_items) gives a zero output row
+  int n_items;
   const void* LP;   // [B][m][d] bf16
   const void* Wv;   // nullable
   void* O;          // [B][C][d] bf16

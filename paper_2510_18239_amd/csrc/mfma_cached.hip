@@ -12,14 +12,18 @@ namespace lime {
 namespace {
 
 struct CachedArgs {
-  const bf16_t* W;   // [B][rows][h][m]
+  const bf16_t* W;   // [B][rows][h][m], or the table [n_items][h][m] when ids are given
+  const int32_t* ids;  // nullable: [B][rows]
+  int n_items;
   bf16_t* O;         // [B][rows][d]
   const bf16x8* VA;  // values image, natural k order
   int64_t va_user_frags;
   int rows, tiles_per_user, total_tiles;
 };
 
-template <int DH, int M, int H>
+// GATHER: the weight row of candidate (b, c) is row ids[b][c] of a table shared by all users (the
+// corpus-wide cache); the ids of a tile are fetched one tile before its weights.
+template <int DH, int M, int H, bool GATHER>
 __global__ __launch_bounds__(64 * H) void cached_candidates_kernel(CachedArgs a) {
   constexpr int D = DH * H, MB = DH / 32, K3 = M / 16;
   const int lane = threadIdx.x & 63, head = threadIdx.x >> 6;
@@ -29,22 +33,37 @@ __global__ __launch_bounds__(64 * H) void cached_candidates_kernel(CachedArgs a)
   const int last = min(first + per_wg, a.total_tiles);
   if (first >= last) return;
 
-  auto load_weights = [&](int tile, bf16x8 (&p)[K3]) {
+  auto load_id = [&](int tile) -> int {
+    const int b = tile / a.tiles_per_user;
+    const int row = min((tile - b * a.tiles_per_user) * 32 + n, a.rows - 1);
+    return a.ids[static_cast<int64_t>(b) * a.rows + row];
+  };
+  // `id` is used by the gathering variant only; an id outside the table reads row 0 and is zeroed at the store
+  auto load_weights = [&](int tile, int id, bf16x8 (&p)[K3]) {
     const int b = tile / a.tiles_per_user;
     const int row = min((tile - b * a.tiles_per_user) * 32 + n, a.rows - 1);  // clamped; such columns are not stored
-    const bf16_t* src = a.W + ((static_cast<int64_t>(b) * a.rows + row) * H + head) * M + 8 * g;
+    const int64_t wrow = GATHER ? (static_cast<unsigned>(id) < static_cast<unsigned>(a.n_items) ? id : 0)
+                                : static_cast<int64_t>(b) * a.rows + row;
+    const bf16_t* src = a.W + (wrow * H + head) * M + 8 * g;
 #pragma unroll
     for (int kk = 0; kk < K3; ++kk) p[kk] = *reinterpret_cast<const bf16x8*>(src + 16 * kk);
   };
 
   bf16x8 va[K3][MB], pn[K3];
-  load_weights(first, pn);
+  int id_next = GATHER ? load_id(first) : 0;  // id of the tile whose weights are in flight
+  load_weights(first, id_next, pn);
+  int id_ahead = GATHER && first + 1 < last ? load_id(first + 1) : 0;
   int cur_user = -1;
   for (int tile = first; tile < last; ++tile) {
     bf16x8 p[K3];
 #pragma unroll
     for (int kk = 0; kk < K3; ++kk) p[kk] = pn[kk];
-    if (tile + 1 < last) load_weights(tile + 1, pn);
+    const int id = id_next;
+    if (tile + 1 < last) {
+      id_next = id_ahead;
+      load_weights(tile + 1, id_next, pn);
+      if (GATHER && tile + 2 < last) id_ahead = load_id(tile + 2);
+    }
     const int b = tile / a.tiles_per_user;
     const int row = (tile - b * a.tiles_per_user) * 32 + n;
     if (b != cur_user && (cur_user < 0 || a.va_user_frags != 0)) {
@@ -64,6 +83,10 @@ __global__ __launch_bounds__(64 * H) void cached_candidates_kernel(CachedArgs a)
       for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
       for (int kk = 0; kk < K3; ++kk) acc = mfma32(va[kk][ob], p[kk], acc);
+      if (GATHER && static_cast<unsigned>(id) >= static_cast<unsigned>(a.n_items)) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+      }
       if (row < a.rows) {
         *reinterpret_cast<bf16x8*>(orow + 32 * ob) = pack_half(acc, 0);
         *reinterpret_cast<bf16x8*>(orow + 32 * ob + 8) = pack_half(acc, 1);
@@ -83,13 +106,21 @@ int compute_units() {
   return n;
 }
 
+template <int DH, int M, int H>
+void launch(const CachedArgs& a, int grid, hipStream_t s) {
+  if (a.ids != nullptr)
+    hipLaunchKernelGGL((cached_candidates_kernel<DH, M, H, true>), dim3(grid), dim3(64 * H), 0, s, a);
+  else
+    hipLaunchKernelGGL((cached_candidates_kernel<DH, M, H, false>), dim3(grid), dim3(64 * H), 0, s, a);
+}
+
 template <int DH, int H>
 hipError_t dispatch_m(const CachedArgs& a, int m, int grid, hipStream_t s) {
   switch (m) {
-    case 32: hipLaunchKernelGGL((cached_candidates_kernel<DH, 32, H>), dim3(grid), dim3(64 * H), 0, s, a); break;
-    case 64: hipLaunchKernelGGL((cached_candidates_kernel<DH, 64, H>), dim3(grid), dim3(64 * H), 0, s, a); break;
-    case 96: hipLaunchKernelGGL((cached_candidates_kernel<DH, 96, H>), dim3(grid), dim3(64 * H), 0, s, a); break;
-    case 128: hipLaunchKernelGGL((cached_candidates_kernel<DH, 128, H>), dim3(grid), dim3(64 * H), 0, s, a); break;
+    case 32: launch<DH, 32, H>(a, grid, s); break;
+    case 64: launch<DH, 64, H>(a, grid, s); break;
+    case 96: launch<DH, 96, H>(a, grid, s); break;
+    case 128: launch<DH, 128, H>(a, grid, s); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -115,7 +146,7 @@ hipError_t cached_candidates(const CachedCandidates& q, void* workspace, hipStre
   PackProject pjob{q.LP, q.Wv, workspace, static_cast<int64_t>(m) * d, q.B, kPackValuesNatural, 1.f};
   hipError_t e = pack_operands(nullptr, 0, &pjob, 1, d, h, m, s);
   if (e != hipSuccess) return e;
-  CachedArgs a{static_cast<const bf16_t*>(q.W), static_cast<bf16_t*>(q.O), static_cast<const bf16x8*>(workspace),
+  CachedArgs a{static_cast<const bf16_t*>(q.W), q.ids, q.n_items, static_cast<bf16_t*>(q.O), static_cast<const bf16x8*>(workspace),
                static_cast<int64_t>(m) * d / 8, q.C, (q.C + 31) / 32, ((q.C + 31) / 32) * q.B};
   // small register footprint: several workgroups per compute unit hide the memory latency
   const int resident = compute_units() * 4;

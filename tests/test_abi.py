@@ -23,6 +23,7 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"lime_link_history", "lime_xor_history", "lime_score_candidates", "mha_target_attention",
             "lime_profile_enable", "lime_profile_collect", "lime_build_qk_cache", "lime_score_candidates_cached",
+            "lime_score_candidates_gathered",
             "lime_workspace_bytes", "lime_last_error", "lime_version"} <= set(names)
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
@@ -118,5 +119,11 @@ def test_qk_cache_argument_checks():
     assert score() == 3
     assert score(W=None) == 1 and score(LP=None) == 1 and score(O=None) == 1
     assert score(C=0) == 1 and score(m=0) == 1 and score(d=7) == 1
+    def gathered(W=FAKE, ids=FAKE, n_items=10, LP=FAKE, O=FAKE, C=4, d=8, h=2, m=4, dtype=0, ws=FAKE, ws_bytes=0):
+        return lib.lime_score_candidates_gathered(W, ids, n_items, LP, None, O, 1, C, d, h, m, dtype, ws, ws_bytes, None)
+
+    assert gathered() == 3
+    assert gathered(ids=None) == 1 and gathered(n_items=0) == 1 and gathered(W=None) == 1 and gathered(O=None) == 1
+    assert gathered(C=0) == 1 and gathered(h=3) == 1
     assert binding.workspace_bytes(binding.OP_BUILD_QK_CACHE, B=1, C=100, d=256, h=4, m=64) > 0
     assert binding.workspace_bytes(binding.OP_SCORE_CACHED, B=2, C=100, d=256, h=4, m=64) > 0

@@ -335,3 +335,33 @@ def test_qk_cache_path(dtype, d, h, m, C):
     assert_close(host(O), orc.lime_score_candidates(w.T, w.L, LPv, w.Wq, w.Wk, w.Wv, h, s), dtype, "cached chain", 2.0)
     direct = binding.lime_score_candidates(g.T, g.L, LP, g.Wq, g.Wk, g.Wv, h, s)
     assert_close(host(O), host(direct).astype(np.float64), dtype, "cached vs direct on the GPU", 2.0)
+
+
+@pytest.mark.parametrize("dtype,d,h,m,n_items,C", [("bf16", 256, 4, 64, 5000, 1000), ("bf16", 128, 4, 64, 700, 333),
+                                                   ("bf16", 256, 4, 128, 300, 95), ("fp32", 64, 2, 16, 90, 77),
+                                                   ("bf16", 96, 3, 20, 60, 50)])
+def test_gathered_qk_cache(dtype, d, h, m, n_items, C):
+    """Section 3.3 with one cache table for the item corpus and candidates named by id (repeats, a ragged
+    last tile, ids outside the table): against the oracle on the table the GPU stored, and against Eq. 4
+    evaluated on the gathered embeddings."""
+    B = 3
+    w = _sharp(workload=44, B=1, N=8, C=n_items, d=d, h=h, m=m, dtype=dtype)  # T[0] is the corpus
+    g = DeviceWorkload(w)
+    s = w.softmax_scale
+    LPv = synth.per_user_links(44, B, m, d, dtype, gain=w.meta["gain"])
+    LP = dev(LPv, dtype)
+    table = binding.lime_build_qk_cache(g.T, g.L, g.Wq, g.Wk, h, s)[0]
+    rng = np.random.default_rng(4400 + n_items)
+    ids = rng.integers(0, n_items, size=(B, C)).astype(np.int32)
+    ids[0, :4] = ids[0, 4]           # repeats
+    ids[1, 1], ids[2, C - 1], ids[2, 0] = -1, n_items, np.iinfo(np.int32).max  # outside the table
+    O = binding.lime_score_candidates_gathered(table, torch.from_numpy(ids).cuda(), LP, g.Wv)
+    assert O.shape == (B, C, d)
+    ref = orc.lime_score_candidates_gathered(host(table), ids, LPv, w.Wv, h)
+    assert_close(host(O), ref, dtype, "gathered O")
+    got = host(O)
+    assert not got[1, 1].any() and not got[2, C - 1].any() and not got[2, 0].any()
+    assert np.array_equal(got[0, 0], got[0, 4])
+    valid = (ids >= 0) & (ids < n_items)
+    chain = orc.lime_score_candidates(w.T[0][np.where(valid, ids, 0)], w.L, LPv, w.Wq, w.Wk, w.Wv, h, s)
+    assert_close(got[valid], chain[valid], dtype, "gathered chain", 2.0)

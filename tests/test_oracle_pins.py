@@ -414,7 +414,34 @@ def check_qk_cache_path():
             assert abs(out[1, c, col] - want) < 1e-13
 
 
+def check_gathered_cache():
+    # one cache for the corpus, candidates named by id: the same as scoring the gathered embeddings with Eq. 4
+    p = _problem(71, B=1, N=3, C=11, d=8, m=4)  # T[0] plays the corpus of 11 items
+    corpus = p["T"][0]
+    LP = _rand(72, 3, 4, 8)
+    h, s = 2, 0.7
+    table = orc.qk_cache(corpus[None], p["L"], p["Wq"], p["Wk"], h, s)[0]
+    ids = np.array([[0, 10, 3, 3, 7], [5, 5, 5, 1, 0], [9, 8, 2, 6, 4]])
+    got = orc.lime_score_candidates_gathered(table, ids, LP, p["Wv"], h)
+    want = orc.lime_score_candidates(corpus[ids], p["L"], LP, p["Wq"], p["Wk"], p["Wv"], h, s)
+    np.testing.assert_allclose(got, want, atol=1e-13)
+    # equal ids give equal rows; the identity gather is the ungathered stage
+    np.testing.assert_array_equal(got[0, 2], got[0, 3])
+    all_ids = np.tile(np.arange(11), (3, 1))
+    np.testing.assert_allclose(orc.lime_score_candidates_gathered(table, all_ids, LP, p["Wv"], h),
+                               orc.lime_score_candidates_cached(np.tile(table[None], (3, 1, 1, 1)), LP, p["Wv"], h), atol=1e-14)
+    # ids outside the table: zero rows, the others untouched
+    bad = ids.copy()
+    bad[1, 2], bad[2, 0] = -1, 11
+    out = orc.lime_score_candidates_gathered(table, bad, LP, p["Wv"], h)
+    assert not out[1, 2].any() and not out[2, 0].any()
+    mask = np.ones(ids.shape, bool)
+    mask[1, 2] = mask[2, 0] = False
+    np.testing.assert_array_equal(out[mask], got[mask])
+
+
 PINS = [
+    check_gathered_cache,
     check_golden_eq3,
     check_golden_eq4,
     check_golden_xora,
