@@ -5,7 +5,8 @@
 namespace lime {
 namespace {
 
-constexpr int kPackRows = 1;  // rows of X per block of a projection job (more blocks, shorter critical path)
+constexpr int kPackRows = 4;   // rows of X per block of a projection job
+constexpr int kPackCols = 32;  // columns of W per block
 constexpr int kMaxJobs = 3;
 
 struct PackArgs {
@@ -62,33 +63,34 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
   blk -= p.n_weights * p.blocks_per_weight;
   const int job = blk >= p.p_first_block[2] ? 2 : (blk >= p.p_first_block[1] ? 1 : 0);
   blk -= p.p_first_block[job];
-  const int groups = m / kPackRows;  // m is a multiple of 32
-  const int u = blk / groups, row0 = (blk % groups) * kPackRows;
+  // A block computes kPackRows rows x kPackCols columns of X W: it fetches only its column slice of W
+  // (d x kPackCols), so that no compute unit has to take in the whole matrix.  Thread (cg, kc) owns 8
+  // adjacent columns and every nkc-th k; the partial sums meet in LDS.
+  const int slices = d / kPackCols, groups = m / kPackRows;  // d is a multiple of 32, m of 32
+  const int slice = blk % slices, rg = (blk / slices) % groups, u = blk / (slices * groups);
+  const int row0 = rg * kPackRows, col0 = slice * kPackCols;
   const bf16_t* X = p.p_x[job] + u * p.p_stride[job] + static_cast<int64_t>(row0) * d;
   const bf16_t* W = p.p_w[job];
 
-  // kPackRows rows of X times W: thread (cg, kc) owns 8 adjacent columns and every nkc-th k;
-  // the partial sums meet in LDS.
-  float* xs = smem;                    // [kPackRows][d]
-  float* out = xs + kPackRows * d;     // [kPackRows][d]
-  float* red = out + kPackRows * d;    // [nkc][kPackRows][d]
-  // Every load this block needs is issued before the first wait: the row of X and, per thread, up to
-  // kMaxK 16-byte pieces of W (one global round trip instead of one per k-step).
-  constexpr int kMaxK = 32;  // d / nkc = d^2 / 2048 k-steps per thread; 32 at d = 256
-  const int CG = d / 8, nkc = 256 / CG;
+  float* xs = smem;                          // [kPackRows][d]
+  float* out = xs + kPackRows * d;           // [kPackRows][kPackCols]
+  float* red = out + kPackRows * kPackCols;  // [nkc][kPackRows][kPackCols]
+  constexpr int CG = kPackCols / 8, nkc = 256 / CG;
+  constexpr int kMaxK = 256 / nkc;  // k-steps per thread at the largest d (256)
   const int cg = tid % CG, kc = tid / CG;
+  // every load this block needs is issued before the first wait
   bf16x8 wreg[kMaxK];
   if (W != nullptr) {
 #pragma unroll
     for (int it = 0; it < kMaxK; ++it) {
       const int k = kc + it * nkc;
-      if (k < d) wreg[it] = *reinterpret_cast<const bf16x8*>(W + static_cast<int64_t>(k) * d + 8 * cg);
+      if (k < d) wreg[it] = *reinterpret_cast<const bf16x8*>(W + static_cast<int64_t>(k) * d + col0 + 8 * cg);
     }
   }
   for (int i = tid; i < kPackRows * d; i += 256) xs[i] = to_float(X[i]);
   __syncthreads();
   if (W == nullptr) {
-    for (int i = tid; i < kPackRows * d; i += 256) out[i] = xs[i];
+    for (int i = tid; i < kPackRows * kPackCols; i += 256) out[i] = xs[(i / kPackCols) * d + col0 + i % kPackCols];
   } else {
     float acc[kPackRows][8];
 #pragma unroll
@@ -110,11 +112,12 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
 #pragma unroll
     for (int r = 0; r < kPackRows; ++r)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) red[(kc * kPackRows + r) * d + 8 * cg + j] = acc[r][j];
+      for (int j = 0; j < 8; ++j) red[(kc * kPackRows + r) * kPackCols + 8 * cg + j] = acc[r][j];
     __syncthreads();
-    for (int i = tid; i < kPackRows * d; i += 256) {
+    for (int i = tid; i < kPackRows * kPackCols; i += 256) {
       float sum = 0.f;
-      for (int c = 0; c < nkc; ++c) sum += red[c * kPackRows * d + i];
+#pragma unroll 8
+      for (int c = 0; c < nkc; ++c) sum += red[c * kPackRows * kPackCols + i];
       out[i] = sum;
     }
   }
@@ -122,8 +125,8 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
   bf16_t* img = p.p_img[job];
   const bool keys = p.p_layout[job] == kPackKeys;
   const float sign = p.p_sign[job];
-  for (int i = tid; i < kPackRows * d; i += 256) {
-    const int row = row0 + i / d, col = i % d;
+  for (int i = tid; i < kPackRows * kPackCols; i += 256) {
+    const int row = row0 + i / kPackCols, col = col0 + i % kPackCols;
     store_as(img + (keys ? keys_slot(u, row, col, d, dh, m) : values_slot(u, row, col, d, dh, m, p.p_layout[job] == kPackValues)), sign * out[i]);
   }
 }
@@ -152,14 +155,14 @@ hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackPro
       p.p_stride[i] = projections[i].user_stride;
       p.p_layout[i] = projections[i].layout;
       p.p_sign[i] = projections[i].sign;
-      blocks += projections[i].users * (m / kPackRows);
+      blocks += projections[i].users * (m / kPackRows) * (d / kPackCols);
     }
   }
   p.p_first_block[kMaxJobs] = blocks;
   for (int i = n_projections; i < kMaxJobs; ++i)
     if (i > 0) p.p_first_block[i] = 0x7fffffff;
-  const int nkc = 256 / (d / 8);
-  const size_t lds = static_cast<size_t>(2 + nkc) * kPackRows * d * sizeof(float);
+  constexpr int nkc = 256 / (kPackCols / 8);
+  const size_t lds = (static_cast<size_t>(kPackRows) * d + static_cast<size_t>(1 + nkc) * kPackRows * kPackCols) * sizeof(float);
   const int grid = n_weights * p.blocks_per_weight + blocks;
   if (grid == 0) return hipSuccess;
   hipLaunchKernelGGL(pack_kernel, dim3(grid), dim3(256), lds, s, p);
