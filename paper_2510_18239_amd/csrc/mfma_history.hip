@@ -87,6 +87,14 @@ __global__ __launch_bounds__(COOP ? 64 * H : 64) void links_over_history_kernel(
       for (int lb = 0; lb < LB; ++lb) qb[kk][lb] = src[(kk * LB + lb) * 64 + lane];
   }
 
+  if constexpr (!COOP) {
+    // W_V only ever feeds the matrix cores, which read AGPRs as readily as VGPRs: pinned there, it leaves the
+    // VGPRs to the values the vector ALUs touch and needs no copies.
+#pragma unroll
+    for (int kk = 0; kk < K1; ++kk)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) asm volatile("" : "+a"(wv[kk][mb]));
+  }
   f32x16 acc[MB][LB];
   float run_max[LB], run_sum[LB];
 #pragma unroll
@@ -138,11 +146,24 @@ __global__ __launch_bounds__(COOP ? 64 * H : 64) void links_over_history_kernel(
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) d1[mb][i] = d2[mb][i] = 0.f;
+    // the LDS reads run kAhead k-steps ahead of the MFMAs that use them (one wave per SIMD: nobody else
+    // covers the LDS latency)
+    constexpr int kAhead = 3;
+    bf16x8 wkf[WK_LDS ? K1 : 1][MB];
+    auto fetch = [&](int kk) {
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) wkf[WK_LDS ? kk : 0][mb] = lds_wk[wk_base + (kk * MB + mb) * 64];
+    };
+    if (WK_LDS) {
+#pragma unroll
+      for (int kk = 0; kk < kAhead && kk < K1; ++kk) fetch(kk);
+    }
 #pragma unroll
     for (int kk = 0; kk < K1; ++kk) {
+      if (WK_LDS && kk + kAhead < K1) fetch(kk + kAhead);
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
-        const bf16x8 w = WK_LDS ? lds_wk[wk_base + (kk * MB + mb) * 64] : wk[WK_LDS ? 0 : kk][WK_LDS ? 0 : mb];
+        const bf16x8 w = WK_LDS ? wkf[WK_LDS ? kk : 0][mb] : wk[WK_LDS ? 0 : kk][WK_LDS ? 0 : mb];
         d1[mb] = mfma32(w, x[kk], d1[mb]);
         d2[mb] = mfma32(x[kk], wv[kk][mb], d2[mb]);
       }
