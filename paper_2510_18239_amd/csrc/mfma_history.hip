@@ -45,12 +45,12 @@ __global__ __launch_bounds__(COOP ? 64 * H : 64) void links_over_history_kernel(
   constexpr int D = DH * H;
   constexpr int K1 = D / 16, MB = DH / 32;  // projections: k-steps over d, blocks over d/h
   constexpr int K2 = DH / 16, LB = M / 32;  // scores: k-steps over d/h, blocks over links
-  constexpr int P = 4;                      // COOP: tiles in flight per workgroup
+  constexpr int P = WK_LDS ? (M >= 128 ? 1 : 2) : 4;  // COOP: tiles in flight per workgroup (registers permitting)
+  constexpr int NXS = COOP ? (WK_LDS ? 1 : 2) : 1;  // COOP: LDS tile buffers (one when W_K^T fills the LDS)
   constexpr int LW = DH / 16;               // COOP: 1 KiB loads per wave and tile
   constexpr int CPR = D / 8, PITCH = 2 * D + 16;
-  static_assert(!(COOP && WK_LDS), "the cooperative variant keeps W_K^T in registers");
-  extern __shared__ bf16x8 lds_wk[];
-  __shared__ __attribute__((aligned(16))) unsigned char xs[COOP ? 2 : 1][COOP ? 32 * PITCH : 16];
+  extern __shared__ bf16x8 lds_wk_all[];
+  __shared__ __attribute__((aligned(16))) unsigned char xs[NXS][COOP ? 32 * PITCH : 16];
   const int lane = threadIdx.x & 63, head = COOP ? threadIdx.x >> 6 : blockIdx.z;
   const int n = lane & 31, g = lane >> 5;
   const int b = blockIdx.y, chunk = blockIdx.x;
@@ -59,6 +59,7 @@ __global__ __launch_bounds__(COOP ? 64 * H : 64) void links_over_history_kernel(
   if (i_begin >= len) return;  // uniform over the workgroup: nothing for this chunk
   const int i_end = min(len, i_begin + a.chunk_items);
 
+  bf16x8* lds_wk = lds_wk_all + (COOP ? head * K1 * MB * 64 : 0);  // this wave's slice
   bf16x8 wk[WK_LDS ? 1 : K1][WK_LDS ? 1 : MB];
   if (WK_LDS) {
     // this head's W_K^T image: the lane moves exactly the K1*MB fragments it will read back itself
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(COOP ? 64 * H : 64) void links_over_history_kernel(
       for (int lb = 0; lb < LB; ++lb) qb[kk][lb] = src[(kk * LB + lb) * 64 + lane];
   }
 
-  if constexpr (!COOP) {
+  if constexpr ((!COOP && M < 128) || (COOP && WK_LDS)) {  // (not where the accumulators of 128 links need the room)
     // W_V only ever feeds the matrix cores, which read AGPRs as readily as VGPRs: pinned there, it leaves the
     // VGPRs to the values the vector ALUs touch and needs no copies.
 #pragma unroll
@@ -246,19 +247,20 @@ __global__ __launch_bounds__(COOP ? 64 * H : 64) void links_over_history_kernel(
       for (int p = 0; p < P; ++p) {
         const int i0 = base + 32 * p;
         if (i0 >= i_end) break;  // uniform over the workgroup
-        unsigned char* buf = xs[p & 1];
+        unsigned char* buf = xs[NXS == 2 ? p & 1 : 0];
 #pragma unroll
         for (int j = 0; j < LW; ++j) {
           const int q = (head * LW + j) * 64 + lane;
           *reinterpret_cast<bf16x8*>(buf + (q / CPR) * PITCH + (q % CPR) * 16) = ring[p][j];
         }
-        // a wave arrives here only after it has finished reading the tile before the previous one,
-        // which is the one this buffer held
+        // with two buffers a wave arrives here only after it has finished reading the tile before the
+        // previous one, which is the one this buffer held; with one, a second barrier follows the reads
         __syncthreads();
         if (i0 + 32 * P < i_end) issue(i0 + 32 * P, ring[p]);
         bf16x8 x[K1];
 #pragma unroll
         for (int kk = 0; kk < K1; ++kk) x[kk] = *reinterpret_cast<const bf16x8*>(buf + n * PITCH + 32 * kk + 16 * g);
+        if (NXS == 1) __syncthreads();
         process_tile(i0, x);
       }
     }
@@ -378,21 +380,27 @@ int compute_units() {
 template <int DH, int M, int H, int PHI>
 hipError_t launch_phi(const HistArgs& a, int users, bool coop, hipStream_t s) {
   constexpr bool kWkLds = DH * H >= 256;
-  if constexpr (!kWkLds && H > 1) {
+  constexpr size_t slice = kWkLds ? static_cast<size_t>(DH) * H * DH * 2 : 0;  // one head's slice of W_K^T
+  if constexpr (H > 1 && !(kWkLds && H > 4)) {  // (eight waves of d = 256 would not fit the register file)
     if (coop) {
-      hipLaunchKernelGGL((links_over_history_kernel<DH, M, H, PHI, false, true>), dim3(a.chunks, users), dim3(64 * H), 0,
-                         s, a);
+      constexpr size_t lds = slice * H;
+      auto kernel = links_over_history_kernel<DH, M, H, PHI, kWkLds, true>;
+      if (lds > 64 * 1024) {
+        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (attr != hipSuccess) return attr;
+      }
+      hipLaunchKernelGGL(kernel, dim3(a.chunks, users), dim3(64 * H), lds, s, a);
       return hipGetLastError();
     }
   }
-  constexpr size_t lds = kWkLds ? static_cast<size_t>(DH) * H * DH * 2 : 0;  // one head's slice of W_K^T
   auto kernel = links_over_history_kernel<DH, M, H, PHI, kWkLds, false>;
-  if (lds > 64 * 1024) {
+  if (slice > 64 * 1024) {
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(slice));
     if (attr != hipSuccess) return attr;
   }
-  hipLaunchKernelGGL(kernel, dim3(a.chunks, users, H), dim3(64), lds, s, a);
+  hipLaunchKernelGGL(kernel, dim3(a.chunks, users, H), dim3(64), slice, s, a);
   return hipGetLastError();
 }
 
@@ -438,8 +446,9 @@ Layout plan(int B, int N, int d, int h, int m, bool q_per_user) {
   // (at least four tiles per compute unit): h-wave workgroups, two per compute unit.  At least two
   // tiles per chunk so that the stationary operands are fetched for more than one tile and the merge
   // stays small.
-  l.coop = d <= 128 && h > 1 && static_cast<int64_t>(B) * tiles >= 4 * static_cast<int64_t>(compute_units());
-  const int64_t slots = static_cast<int64_t>(l.coop ? 2 : (d / h == 32 ? 8 : 4)) * compute_units();
+  l.coop = h > 1 && !(d >= 256 && h > 4) && static_cast<int64_t>(B) * tiles >= 4 * static_cast<int64_t>(compute_units());
+  // (at d = 256 the cooperative workgroup keeps all of W_K^T in LDS and is alone on its compute unit)
+  const int64_t slots = static_cast<int64_t>(l.coop ? (d >= 256 ? 1 : 2) : (d / h == 32 ? 8 : 4)) * compute_units();
   int chunk_tiles = static_cast<int>((static_cast<int64_t>(B) * tiles * (l.coop ? 1 : h) + slots - 1) / slots);
   if (chunk_tiles < 2) chunk_tiles = 2;
   if (chunk_tiles > tiles) chunk_tiles = tiles;
