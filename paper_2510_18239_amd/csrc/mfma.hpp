@@ -38,6 +38,19 @@ __device__ __forceinline__ bf16x8 pack_half(const f32x16& d, int f) {
   return r;
 }
 
+// Reductions over the lane pair (n, n + 32), which together hold one row of an accumulator block.
+// v_permlane32_swap exchanges the wave's halves in the vector ALU (no LDS round trip): with both operands x it
+// returns (x of the low half, x of the high half) in every lane, so both lanes of a pair compute the same bits.
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float pair_max(float x) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float pair_sum(float x) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // Output-row permutation that makes a lane's 16 accumulator registers 16 consecutive columns:
 // the A-operand row `rho` of an output block carries column out_col(rho); lane-half g then holds
 // columns 16g .. 16g+15 of the 32-wide block in register order.

@@ -181,18 +181,17 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
 
   // phi over the m links of this lane's query row (the other half of the links sits in lane ^ 32), cut
   // into steps so that the tile loop can put one matrix instruction of the next tile between them:
-  // softmax = kMaxSteps partial maxima, the exchange with lane ^ 32, kGapSteps empty steps that cover the
-  // exchange's latency, then one step per pair of links (exponential, running sum, bf16 rounding into the
-  // B fragments `pf` of the third product).  phi_finish() returns the factor still owed to the weighted sum.
+  // softmax = kMaxSteps partial maxima, the exchange with lane ^ 32, then one step per pair of links
+  // (exponential, running sum, bf16 rounding into the B fragments `pf` of the third product).
+  // phi_finish() returns the factor still owed to the weighted sum.
   f32x16 acc2[LB];
   bf16x8 pf[K3];
   constexpr int kPairs = LB * 8;
   constexpr int kMaxSteps = PHI == kPhiSoftmax ? LB * 2 : 0;
-  constexpr int kGapSteps = PHI == kPhiSoftmax ? 2 : 0;
-  constexpr int kPairStep0 = PHI == kPhiSoftmax ? kMaxSteps + 1 + kGapSteps : 0;
+  constexpr int kPairStep0 = PHI == kPhiSoftmax ? kMaxSteps + 1 : 0;
   constexpr int NV = kPairStep0 + kPairs;
   const float phi_c = a.scale * kLog2e;  // >= 0
-  float phi_mx = 0.f, phi_other = 0.f, phi_shift = 0.f, phi_sum = 0.f;
+  float phi_mx = 0.f, phi_shift = 0.f, phi_sum = 0.f;
   auto phi_step = [&](int st) {
     if (PHI == kPhiSoftmax && st < kMaxSteps) {
       const int lb = st / 2, i0 = (st % 2) * 8;
@@ -200,13 +199,13 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
 #pragma unroll
       for (int i = 0; i < 8; ++i) phi_mx = fmaxf(phi_mx, acc2[lb][i0 + i]);
     } else if (PHI == kPhiSoftmax && st == kMaxSteps) {
-      phi_other = __shfl_xor(phi_mx, 32);
+      phi_mx = pair_max(phi_mx);
     } else if (st >= kPairStep0) {
       const int e = st - kPairStep0, lb = e / 8, i = (e % 8) * 2;
       float p0, p1;
       if (PHI == kPhiSoftmax) {
         if (e == 0) {
-          phi_shift = -fmaxf(phi_mx, phi_other) * phi_c;  // exp2(raw * c + shift) = exp(scale * raw - max scaled logit)
+          phi_shift = -phi_mx * phi_c;  // exp2(raw * c + shift) = exp(scale * raw - max scaled logit)
           phi_sum = 0.f;
         }
         p0 = __builtin_amdgcn_exp2f(fmaf(acc2[lb][i], phi_c, phi_shift));
@@ -224,7 +223,7 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
     }
   };
   auto phi_finish = [&]() -> float {
-    if (PHI == kPhiSoftmax) return 1.f / (phi_sum + __shfl_xor(phi_sum, 32));
+    if (PHI == kPhiSoftmax) return 1.f / pair_sum(phi_sum);
     return a.inv_norm * a.scale;
   };
 

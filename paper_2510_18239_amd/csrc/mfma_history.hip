@@ -197,7 +197,7 @@ __global__ __launch_bounds__(COOP ? 64 * H : 64) void links_over_history_kernel(
         float tmax = sc[0];
 #pragma unroll
         for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, sc[i]);
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        tmax = pair_max(tmax);
         const float new_max = fmaxf(run_max[lb], tmax);  // finite: the tile holds at least one valid item
         if (__any(new_max > run_max[lb])) {  // uniform; after the first tiles the maximum rarely moves
           const float alpha = run_max[lb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((run_max[lb] - new_max) * c);
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(COOP ? 64 * H : 64) void links_over_history_kernel(
         float4 v = make_float4(acc[ob][lb][4 * j], acc[ob][lb][4 * j + 1], acc[ob][lb][4 * j + 2], acc[ob][lb][4 * j + 3]);
         *reinterpret_cast<float4*>(dst + 32 * ob + 8 * j) = v;
       }
-    const float total = run_sum[lb] + __shfl_xor(run_sum[lb], 32);
+    const float total = pair_sum(run_sum[lb]);
     if (g == 0) {
       float* ml = a.part_ml + (slot * M + link) * 2;
       ml[0] = run_max[lb] * a.scale;  // the merge works on scaled logits

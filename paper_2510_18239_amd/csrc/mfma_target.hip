@@ -189,7 +189,7 @@ __global__ __launch_bounds__(256) void target_attention_kernel(AttnArgs a) {
       float tmax = sc[0];
 #pragma unroll
       for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, sc[i]);
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      tmax = pair_max(tmax);
       const float new_max = fmaxf(run_max[qb], tmax);  // finite: the tile holds at least one valid item
       const float alpha = run_max[qb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((run_max[qb] - new_max) * c);
       const float shift = -new_max * c;
@@ -218,7 +218,7 @@ __global__ __launch_bounds__(256) void target_attention_kernel(AttnArgs a) {
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int q = q0 + 32 * qb + n;
-    const float total = run_sum[qb] + __shfl_xor(run_sum[qb], 32);
+    const float total = pair_sum(run_sum[qb]);
     const float inv = tiles > 0 ? 1.f / total : 0.f;
     if (q >= a.C) continue;
     bf16_t* orow = a.O + (static_cast<int64_t>(b) * a.C + q) * D + head * DH + 4 * g;
