@@ -337,9 +337,29 @@ def extras(binding, synth, torch, dev, timed, pct):
         lat = timed(lambda i: binding.lime_score_candidates(Tc, L, LP, Wq, Wk, Wv, w.h, w.softmax_scale, O=O), 100)
         sweep[C] = pct(lat, 0.5)
     res["lime_score_candidates_p50_ms_vs_C"] = sweep
-    # the QK-cache path of Section 3.3 at the headline shape: weights in, weighted sum out, cold buffers
+    # what the machine does for a plain copy of the same footprint (16 MiB in, 16 MiB out, cold buffers), and the
+    # candidate call with warm buffers (one pair, resident in the last-level cache) next to the cold headline figure
     C = T.shape[1]
     n = 17
+    Tc = [T] + [T.clone() for _ in range(n - 1)]
+    Oc = [torch.empty_like(T) for _ in range(n)]
+    overhead = pct(timed(lambda i: None, 200), 0.5)
+    copy = timed(lambda i: Oc[i % n].copy_(Tc[i % n]), 200)
+    nbytes = 2 * T.numel() * 2
+    res["plain_copy_same_footprint"] = {"p50_ms_between_events": pct(copy, 0.5), "event_pair_overhead_ms": overhead,
+                                        "GBps": nbytes / ((pct(copy, 0.5) - overhead) * 1e-3) / 1e9}
+    binding.profile_enable(True)
+    for label, pairs in (("cold", n), ("warm", 1)):
+        binding.profile_collect(0)
+        timed(lambda i: binding.lime_score_candidates(Tc[i % pairs], L, LP, Wq, Wk, Wv, w.h, w.softmax_scale,
+                                                      O=Oc[i % pairs]), 200)
+        k = binding.profile_collect(0)
+        kavg = sum(k) / len(k) - overhead
+        res[f"candidate_kernel_{label}"] = {"kernel_avg_ms": kavg, "GBps": nbytes / (kavg * 1e-3) / 1e9,
+                                            "frac_of_hbm_peak": nbytes / (kavg * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    binding.profile_enable(False)
+    del Tc, Oc
+    # the QK-cache path of Section 3.3 at the headline shape: weights in, weighted sum out, cold buffers
     Wc = binding.lime_build_qk_cache(T, L, Wq, Wk, w.h, w.softmax_scale)
     Ws = [Wc] + [Wc.clone() for _ in range(n - 1)]
     Oc = [torch.empty_like(T) for _ in range(n)]
