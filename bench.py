@@ -358,6 +358,29 @@ def extras(binding, synth, torch, dev, timed, pct):
         res[f"candidate_kernel_{label}"] = {"kernel_avg_ms": kavg, "GBps": nbytes / (kavg * 1e-3) / 1e9,
                                             "frac_of_hbm_peak": nbytes / (kavg * 1e-3) / 1e9 / HBM_PEAK_GBS}
     binding.profile_enable(False)
+    # the request on operands prepared once per model (lime_prepare): four kernels instead of five, no weight packing
+    prepared = binding.lime_prepare(L, L, Wq, Wk, Wv, Wq, Wk, w.h, w.softmax_scale, w.softmax_scale)
+    hip = HipGraphs()
+    st = hip.stream()
+    LPp = torch.empty_like(LP)
+    ws_bytes = max(binding.workspace_bytes(binding.OP_LINK_HISTORY, B=w.B, N=w.N, d=w.d, h=w.h, m=w.m),
+                   binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=w.B, C=C, d=w.d, h=w.h, m=w.m))
+    wsp = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def prepared_request(j, stream):
+        binding.lime_link_history_prepared(E, None, prepared, w.h, w.m, w.softmax_scale, LP=LPp, workspace=wsp, stream=stream)
+        binding.lime_score_candidates_prepared(Tc[j], LPp, Wv, prepared, w.h, w.softmax_scale, O=Oc[j], workspace=wsp,
+                                               stream=stream)
+
+    graphs = [hip.capture(st, lambda stream, j=j: prepared_request(j, stream)) for j in range(n)]
+    torch.cuda.synchronize()
+    lat = hip.timed(lambda i: hip.launch(graphs[i % n], st), st, 200)
+    t0 = time.perf_counter()
+    for i in range(400):
+        hip.launch(graphs[i % n], st)
+    torch.cuda.synchronize()
+    res["prepared_operands"] = {"request_p50_ms": pct(lat, 0.5),
+                                "one_request_in_flight_ms_per_step": (time.perf_counter() - t0) * 1e3 / 400}
     del Tc, Oc
     # the QK-cache path of Section 3.3 at the headline shape: weights in, weighted sum out, cold buffers
     Wc = binding.lime_build_qk_cache(T, L, Wq, Wk, w.h, w.softmax_scale)

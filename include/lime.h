@@ -128,6 +128,32 @@ int32_t lime_score_candidates_gathered(const void* Wtable, const int32_t* ids, i
                                        int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
 
 /*
+ * Operands prepared once per model (Section 3.3: what does not depend on the user can be computed ahead of time).
+ * Every call above transposes the weights and projects the m links again; with static weights and shared links
+ * that work is the same for every request.  lime_prepare does it once into `prepared`, a device buffer of
+ * lime_prepared_bytes(d, h, m, dtype) bytes owned by the caller, 256-byte aligned, which holds: for the history
+ * stage the W_K^T / W_V images and Q~ = LC Wq_hist (signed by scale_hist); for the candidate stage the W_Q^T image
+ * and K~ = L Wk_cand (signed by scale_cand).  Wq_cand and Wk_cand may be NULL (identity).
+ *   lime_link_history_prepared      = lime_link_history (xor_attention = 0) or the LP output of lime_xor_history
+ *                                     (xor_attention != 0) with shared links LC[m][d];
+ *   lime_score_candidates_prepared  = lime_score_candidates;
+ * bit for bit, when given the scale passed to lime_prepare for that stage (only |scale| is read here).  Wv of the
+ * candidate stage is still applied per request (the values are the user's link states).  bf16 matrix-core
+ * shapes only (see Limits); anything else: lime_prepared_bytes returns 0 and the calls return LIME_UNSUPPORTED.
+ * Workspace sizes as for LIME_OP_LINK_HISTORY and LIME_OP_SCORE_CANDIDATES.
+ */
+size_t lime_prepared_bytes(int32_t d, int32_t h, int32_t m, int32_t dtype);
+int32_t lime_prepare(const void* LC, const void* L, const void* Wq_hist, const void* Wk_hist, const void* Wv_hist,
+                     const void* Wq_cand, const void* Wk_cand, float scale_hist, float scale_cand,
+                     void* prepared, size_t prepared_bytes, int32_t d, int32_t h, int32_t m, int32_t dtype, void* stream);
+int32_t lime_link_history_prepared(const void* E, const int32_t* lens, const void* prepared, void* LP,
+                                   int32_t B, int32_t N, int32_t d, int32_t h, int32_t m, float scale,
+                                   int32_t xor_attention, int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
+int32_t lime_score_candidates_prepared(const void* T, const void* LP, const void* Wv, const void* prepared, void* O,
+                                       int32_t B, int32_t C, int32_t d, int32_t h, int32_t m, float scale,
+                                       int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
+
+/*
  * Workspace size in bytes for `op` (LIME_OP_*) at the given shape; dimensions an op
  * does not have are ignored.  `flags` bit 0: lime_xor_history will be asked for OS.
  * Returns 0 for shapes the op would reject.

@@ -36,6 +36,12 @@ SIGNATURES = {
                                     _vp, _sz, _vp]),
     "lime_build_qk_cache": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32, _i32, _vp, _sz, _vp]),
     "lime_score_candidates_cached": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _sz, _vp]),
+    "lime_prepared_bytes": (_sz, [_i32, _i32, _i32, _i32]),
+    "lime_prepare": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _vp, _sz, _i32, _i32, _i32, _i32, _vp]),
+    "lime_link_history_prepared": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32, _i32, _i32, _vp, _sz,
+                                          _vp]),
+    "lime_score_candidates_prepared": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32, _i32, _vp,
+                                              _sz, _vp]),
     "lime_score_candidates_gathered": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _sz,
                                               _vp]),
     "lime_workspace_bytes": (_sz, [_i32] * 9),
@@ -274,5 +280,55 @@ def lime_score_candidates_gathered(Wtable, ids, LP, Wv, O=None, workspace=None, 
     with torch.cuda.device(Wtable.device):
         st = lib().lime_score_candidates_gathered(_ptr(Wtable), _ptr(ids), n_items, _ptr(LP), _ptr(Wv), _ptr(O), B, C, d,
                                                   h, m, code, _ptr(ws), ws.numel(), _stream(stream))
+    _raise(st)
+    return O
+
+
+def lime_prepare(LC, L, Wq_hist, Wk_hist, Wv_hist, Wq_cand, Wk_cand, h, scale_hist, scale_cand, stream=None):
+    """Packs what depends on the model only (weights, shared links [m, d]) once; returns the prepared buffer."""
+    first = _check(LC, L, Wq_hist, Wk_hist, Wv_hist, Wq_cand, Wk_cand)
+    m, d = LC.shape
+    code = _dtype_code(first)
+    need = lib().lime_prepared_bytes(d, h, m, code)
+    if need == 0:
+        raise LimeError(2, "lime_prepare: shape or dtype without prepared operands")
+    prepared = torch.empty(need, dtype=torch.uint8, device=LC.device)
+    with torch.cuda.device(LC.device):
+        st = lib().lime_prepare(_ptr(LC), _ptr(L), _ptr(Wq_hist), _ptr(Wk_hist), _ptr(Wv_hist), _ptr(Wq_cand),
+                                _ptr(Wk_cand), float(scale_hist), float(scale_cand), _ptr(prepared), need, d, h, m, code,
+                                _stream(stream))
+    _raise(st)
+    return prepared
+
+
+def lime_link_history_prepared(E, lens, prepared, h, m, scale, xor_attention=False, LP=None, workspace=None, stream=None):
+    """lime_link_history (or the link states of lime_xor_history) on operands prepared by lime_prepare."""
+    first = _check(E, LP)
+    B, N, d = E.shape
+    code = _dtype_code(first)
+    if LP is None:
+        LP = torch.empty((B, m, d), dtype=E.dtype, device=E.device)
+    need = workspace_bytes(OP_LINK_HISTORY, B=B, N=N, d=d, h=h, m=m, dtype=code)
+    ws = workspace if workspace is not None else get_workspace(need, E.device)
+    with torch.cuda.device(E.device):
+        st = lib().lime_link_history_prepared(_ptr(E), _ptr(lens), _ptr(prepared), _ptr(LP), B, N, d, h, m, float(scale),
+                                              int(bool(xor_attention)), code, _ptr(ws), ws.numel(), _stream(stream))
+    _raise(st)
+    return LP
+
+
+def lime_score_candidates_prepared(T, LP, Wv, prepared, h, scale, O=None, workspace=None, stream=None):
+    """lime_score_candidates on operands prepared by lime_prepare (the user's link states LP are projected per call)."""
+    first = _check(T, LP, Wv, O)
+    B, C, d = T.shape
+    m = LP.shape[1]
+    code = _dtype_code(first)
+    if O is None:
+        O = torch.empty_like(T)
+    need = workspace_bytes(OP_SCORE_CANDIDATES, B=B, C=C, d=d, h=h, m=m, dtype=code)
+    ws = workspace if workspace is not None else get_workspace(need, T.device)
+    with torch.cuda.device(T.device):
+        st = lib().lime_score_candidates_prepared(_ptr(T), _ptr(LP), _ptr(Wv), _ptr(prepared), _ptr(O), B, C, d, h, m,
+                                                  float(scale), code, _ptr(ws), ws.numel(), _stream(stream))
     _raise(st)
     return O

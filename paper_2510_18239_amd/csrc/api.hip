@@ -336,6 +336,71 @@ int32_t lime_score_candidates_gathered(const void* Wtable, const int32_t* ids, i
   return cached_impl(fn, Wtable, ids, n_items, LP, Wv, O, B, C, d, h, m, dtype, workspace, ws_bytes, stream);
 }
 
+// ----------------------------------------------------------------------------- operands prepared once per model
+size_t lime_prepared_bytes(int32_t d, int32_t h, int32_t m, int32_t dtype) {
+  if (d <= 0 || h <= 0 || m <= 0 || d % h != 0 || dtype != LIME_BF16) return 0;
+  if (!lime::queries_over_links_supported(d, h, m)) return 0;
+  return lime::prepared_layout(d, m).total;
+}
+
+int32_t lime_prepare(const void* LC, const void* L, const void* Wq_hist, const void* Wk_hist, const void* Wv_hist,
+                     const void* Wq_cand, const void* Wk_cand, float scale_hist, float scale_cand, void* prepared,
+                     size_t prepared_bytes, int32_t d, int32_t h, int32_t m, int32_t dtype, void* stream) {
+  const char* fn = "lime_prepare";
+  if (int32_t st = check_common(fn, 1, d, h, dtype)) return st;
+  if (m <= 0) return fail(LIME_INVALID_ARG, "%s: m must be positive (m=%d)", fn, m);
+  if (!LC || !L || !Wq_hist || !Wk_hist || !Wv_hist || !prepared)
+    return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  const size_t need = lime_prepared_bytes(d, h, m, dtype);
+  if (need == 0 || !all_aligned16(LC, L, Wq_hist, Wk_hist, Wv_hist, Wq_cand, Wk_cand, prepared))
+    return fail(LIME_UNSUPPORTED, "%s: prepared operands exist for the bf16 matrix-core shapes and 16-byte aligned pointers only", fn);
+  if (prepared_bytes < need)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: prepared buffer of %zu bytes needed, %zu given", fn, need, prepared_bytes);
+  lime::PrepareOperands p{LC, L, Wq_hist, Wk_hist, Wv_hist, Wq_cand, Wk_cand, scale_hist, scale_cand, d, h, m};
+  LIME_HIP(lime::prepare_operands(p, prepared, static_cast<hipStream_t>(stream)));
+  return LIME_OK;
+}
+
+int32_t lime_link_history_prepared(const void* E, const int32_t* lens, const void* prepared, void* LP, int32_t B,
+                                   int32_t N, int32_t d, int32_t h, int32_t m, float scale, int32_t xor_attention,
+                                   int32_t dtype, void* workspace, size_t ws_bytes, void* stream) {
+  const char* fn = "lime_link_history_prepared";
+  if (int32_t st = check_common(fn, B, d, h, dtype)) return st;
+  if (N <= 0 || m <= 0) return fail(LIME_INVALID_ARG, "%s: N and m must be positive (N=%d m=%d)", fn, N, m);
+  if (!E || !prepared || !LP) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  if (lime_prepared_bytes(d, h, m, dtype) == 0 || !all_aligned16(E, prepared, LP, workspace) || !fits_tiles(B, N))
+    return fail(LIME_UNSUPPORTED, "%s: prepared operands exist for the bf16 matrix-core shapes and 16-byte aligned pointers only", fn);
+  const size_t need = lime::links_over_history_workspace(B, N, d, h, m, false);
+  if (!workspace || ws_bytes < need)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? ws_bytes : 0);
+  lime::LinksOverHistory q{};
+  q.E = E, q.lens = lens, q.LP = LP, q.prepared = prepared;
+  q.B = B, q.N = N, q.d = d, q.h = h, q.m = m, q.scale = scale;
+  q.phi = xor_attention ? lime::kPhiSilu : lime::kPhiSoftmax;
+  LIME_HIP(lime::links_over_history(q, workspace, static_cast<hipStream_t>(stream)));
+  return LIME_OK;
+}
+
+int32_t lime_score_candidates_prepared(const void* T, const void* LP, const void* Wv, const void* prepared, void* O,
+                                       int32_t B, int32_t C, int32_t d, int32_t h, int32_t m, float scale,
+                                       int32_t dtype, void* workspace, size_t ws_bytes, void* stream) {
+  const char* fn = "lime_score_candidates_prepared";
+  if (int32_t st = check_common(fn, B, d, h, dtype)) return st;
+  if (C <= 0 || m <= 0) return fail(LIME_INVALID_ARG, "%s: C and m must be positive (C=%d m=%d)", fn, C, m);
+  if (!T || !LP || !prepared || !O) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  if (lime_prepared_bytes(d, h, m, dtype) == 0 || !all_aligned16(T, LP, Wv, prepared, O, workspace) || !fits_tiles(B, C))
+    return fail(LIME_UNSUPPORTED, "%s: prepared operands exist for the bf16 matrix-core shapes and 16-byte aligned pointers only", fn);
+  const size_t need = lime::queries_over_links_workspace(B, d, m, false);
+  if (!workspace || ws_bytes < need)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? ws_bytes : 0);
+  lime::QueriesOverLinks q{};
+  q.X = T, q.O = O, q.Vsrc = LP, q.Wv = Wv, q.prepared = prepared;
+  q.k_user_stride = 0, q.v_user_stride = static_cast<int64_t>(m) * d, q.row_lens = nullptr;
+  q.B = B, q.rows = C, q.d = d, q.h = h, q.m = m, q.scale = scale, q.phi = lime::kPhiSoftmax;
+  LIME_HIP(lime::queries_over_links(q, workspace, static_cast<hipStream_t>(stream)));
+  return LIME_OK;
+}
+
 size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t d, int32_t h, int32_t m,
                             int32_t dtype, int32_t flags) {
   if (B <= 0 || d <= 0 || h <= 0 || d % h != 0 || d / h > kMaxHeadDim || B > kMaxUsers) return 0;

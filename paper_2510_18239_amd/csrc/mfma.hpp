@@ -86,6 +86,25 @@ struct PackProject {
 hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackProject* projections, int n_projections,
                          int d, int h, int m, hipStream_t s);
 
+// ----------------------------------------------------------------------------- operands prepared once per model
+// What the two stages need of the model alone -- weights and shared links, not the user -- packed once into a
+// caller-owned buffer: for the history stage the W_K^T and W_V images and the projected link queries
+// Q~ = L^C W_Q; for the candidate stage the W_Q^T image and the projected link keys K~ = L W_K.  The signs of
+// the two logit scales are folded in.  The stages then skip their own packing of these.
+struct PreparedLayout {
+  size_t wk, wv, qb, wq, ka, total;  // byte offsets of the five images, and the size of the buffer
+};
+PreparedLayout prepared_layout(int d, int m);
+struct PrepareOperands {
+  const void* LC;   // [m][d] shared contextualised links (history-stage queries)
+  const void* L;    // [m][d] raw links (candidate-stage keys)
+  const void *Wq_hist, *Wk_hist, *Wv_hist;  // history-stage weights, all required
+  const void *Wq_cand, *Wk_cand;            // candidate-stage weights, nullable = identity
+  float scale_hist, scale_cand;
+  int d, h, m;
+};
+hipError_t prepare_operands(const PrepareOperands& p, void* prepared, hipStream_t s);
+
 // ----------------------------------------------------------------------------- candidate-side kernel family
 // Fused "queries x few keys" attention: for every query row x (a candidate of Eq. 4, or a history
 // row for O[S] of Eq. 7): q = x Wq; per head w = phi(scale * q K~^T) over the m keys; out = w V~.
@@ -103,6 +122,7 @@ struct QueriesOverLinks {
   float scale;
   int phi;              // kPhiSoftmax, or kPhiSilu with normaliser m
   void* weights_out;    // when set: write the attention weights [B][rows][h][m] instead of O (Vsrc, Wv unused)
+  const void* prepared; // when set: W_Q^T and K~ come from this prepared buffer (Wq, Ksrc, Wk unused; shared keys)
 };
 bool queries_over_links_supported(int d, int h, int m);
 size_t queries_over_links_workspace(int B, int d, int m, bool k_per_user);
@@ -148,6 +168,7 @@ struct LinksOverHistory {
   int B, N, d, h, m;
   float scale;
   int phi;              // kPhiSoftmax, or kPhiSilu with normaliser lens[b]
+  const void* prepared; // when set: W_K^T, W_V and Q~ come from this prepared buffer (LC, Wq, Wk, Wv unused)
 };
 bool links_over_history_supported(int d, int h, int m);
 size_t links_over_history_workspace(int B, int N, int d, int h, int m, bool q_per_user);

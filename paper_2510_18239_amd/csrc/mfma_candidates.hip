@@ -467,7 +467,15 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
   // a negative logit scale is folded into the sign of the packed keys, so the kernel sees scale >= 0
   PackProject pjobs[2] = {{q.Ksrc, q.Wk, KA, q.k_user_stride, k_per_user ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f},
                           {q.Vsrc, q.Wv, VA, q.v_user_stride, v_per_user ? q.B : 1, kPackValues, 1.f}};
-  hipError_t e = pack_operands(&wjob, 1, pjobs, q.weights_out ? 1 : 2, d, h, m, s);
+  hipError_t e;
+  if (q.prepared != nullptr) {  // only the user's values are left to pack
+    const PreparedLayout l = prepared_layout(d, m);
+    WqA = reinterpret_cast<bf16_t*>(const_cast<char*>(static_cast<const char*>(q.prepared)) + l.wq);
+    KA = reinterpret_cast<bf16_t*>(const_cast<char*>(static_cast<const char*>(q.prepared)) + l.ka);
+    e = pack_operands(nullptr, 0, pjobs + 1, 1, d, h, m, s);
+  } else {
+    e = pack_operands(&wjob, 1, pjobs, q.weights_out ? 1 : 2, d, h, m, s);
+  }
   if (e != hipSuccess) return e;
 
   MainArgs a{};

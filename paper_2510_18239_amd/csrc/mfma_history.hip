@@ -481,11 +481,18 @@ hipError_t links_over_history(const LinksOverHistory& q, void* workspace, hipStr
   float* part_acc = reinterpret_cast<float*>(ws + l.wk + l.wv + l.qb);
   float* part_ml = reinterpret_cast<float*>(ws + l.wk + l.wv + l.qb + l.acc);
 
-  PackWeight wjobs[2] = {{q.Wk, WkA}, {q.Wv, WvB}};
-  // a negative logit scale is folded into the sign of the packed queries, so the kernels see scale >= 0
-  PackProject pjob{q.LC, q.Wq, QB, q.lc_user_stride, per_user ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f};
-  hipError_t e = pack_operands(wjobs, 2, &pjob, 1, d, h, m, s);
-  if (e != hipSuccess) return e;
+  hipError_t e = hipSuccess;
+  if (q.prepared != nullptr) {  // nothing to pack
+    const PreparedLayout pl = prepared_layout(d, m);
+    char* base = const_cast<char*>(static_cast<const char*>(q.prepared));
+    WkA = base + pl.wk, WvB = base + pl.wv, QB = base + pl.qb;
+  } else {
+    PackWeight wjobs[2] = {{q.Wk, WkA}, {q.Wv, WvB}};
+    // a negative logit scale is folded into the sign of the packed queries, so the kernels see scale >= 0
+    PackProject pjob{q.LC, q.Wq, QB, q.lc_user_stride, per_user ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f};
+    e = pack_operands(wjobs, 2, &pjob, 1, d, h, m, s);
+    if (e != hipSuccess) return e;
+  }
 
   HistArgs a{};
   a.E = static_cast<const bf16_t*>(q.E), a.lens = q.lens;

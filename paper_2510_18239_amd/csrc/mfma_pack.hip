@@ -169,4 +169,20 @@ hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackPro
   return hipGetLastError();
 }
 
+PreparedLayout prepared_layout(int d, int m) {
+  PreparedLayout l{};
+  const size_t w = align_up(static_cast<size_t>(d) * d * 2), links = align_up(static_cast<size_t>(m) * d * 2);
+  l.wk = 0, l.wv = w, l.qb = 2 * w, l.wq = 2 * w + links, l.ka = 3 * w + links, l.total = 3 * w + 2 * links;
+  return l;
+}
+
+hipError_t prepare_operands(const PrepareOperands& p, void* prepared, hipStream_t s) {
+  const PreparedLayout l = prepared_layout(p.d, p.m);
+  char* base = static_cast<char*>(prepared);
+  PackWeight wjobs[3] = {{p.Wk_hist, base + l.wk}, {p.Wv_hist, base + l.wv}, {p.Wq_cand, base + l.wq}};
+  PackProject pjobs[2] = {{p.LC, p.Wq_hist, base + l.qb, 0, 1, kPackKeys, p.scale_hist < 0.f ? -1.f : 1.f},
+                          {p.L, p.Wk_cand, base + l.ka, 0, 1, kPackKeys, p.scale_cand < 0.f ? -1.f : 1.f}};
+  return pack_operands(wjobs, 3, pjobs, 2, p.d, p.h, p.m, s);
+}
+
 }  // namespace lime

@@ -23,7 +23,8 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"lime_link_history", "lime_xor_history", "lime_score_candidates", "mha_target_attention",
             "lime_profile_enable", "lime_profile_collect", "lime_build_qk_cache", "lime_score_candidates_cached",
-            "lime_score_candidates_gathered",
+            "lime_score_candidates_gathered", "lime_prepared_bytes", "lime_prepare", "lime_link_history_prepared",
+            "lime_score_candidates_prepared",
             "lime_workspace_bytes", "lime_last_error", "lime_version"} <= set(names)
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
@@ -127,3 +128,35 @@ def test_qk_cache_argument_checks():
     assert gathered(C=0) == 1 and gathered(h=3) == 1
     assert binding.workspace_bytes(binding.OP_BUILD_QK_CACHE, B=1, C=100, d=256, h=4, m=64) > 0
     assert binding.workspace_bytes(binding.OP_SCORE_CACHED, B=2, C=100, d=256, h=4, m=64) > 0
+
+
+def test_prepared_operand_argument_checks():
+    lib = binding.lib()
+    size = lib.lime_prepared_bytes(256, 4, 64, 1)
+    assert size == 3 * 256 * 256 * 2 + 2 * 64 * 256 * 2
+    assert lib.lime_prepared_bytes(256, 4, 64, 0) == 0      # fp32 has no matrix-core path
+    assert lib.lime_prepared_bytes(96, 3, 20, 1) == 0       # neither has this shape
+    assert lib.lime_prepared_bytes(256, 3, 64, 1) == 0 and lib.lime_prepared_bytes(0, 1, 64, 1) == 0
+
+    def prepare(LC=FAKE, L=FAKE, Wq=FAKE, prepared=FAKE, nbytes=0, d=256, h=4, m=64, dtype=1):
+        return lib.lime_prepare(LC, L, Wq, FAKE, FAKE, None, None, 1.0, 1.0, prepared, nbytes, d, h, m, dtype, None)
+
+    assert prepare() == 3
+    assert prepare(LC=None) == 1 and prepare(L=None) == 1 and prepare(Wq=None) == 1 and prepare(prepared=None) == 1
+    assert prepare(h=3) == 1 and prepare(m=0) == 1
+    assert prepare(dtype=0) == 2 and prepare(d=96, h=3, m=20) == 2 and prepare(LC=FAKE + 2) == 2
+    assert "prepared" in binding.last_error()
+
+    def hist(E=FAKE, prepared=FAKE, LP=FAKE, B=1, N=64, d=256, h=4, m=64, dtype=1, ws=FAKE, ws_bytes=0):
+        return lib.lime_link_history_prepared(E, None, prepared, LP, B, N, d, h, m, 1.0, 0, dtype, ws, ws_bytes, None)
+
+    assert hist() == 3
+    assert hist(E=None) == 1 and hist(prepared=None) == 1 and hist(LP=None) == 1 and hist(N=0) == 1
+    assert hist(dtype=0) == 2 and hist(d=96, h=3, m=20) == 2 and hist(E=FAKE + 4) == 2
+
+    def cand(T=FAKE, LP=FAKE, prepared=FAKE, O=FAKE, B=1, C=64, d=256, h=4, m=64, dtype=1, ws=FAKE, ws_bytes=0):
+        return lib.lime_score_candidates_prepared(T, LP, None, prepared, O, B, C, d, h, m, 1.0, dtype, ws, ws_bytes, None)
+
+    assert cand() == 3
+    assert cand(T=None) == 1 and cand(LP=None) == 1 and cand(prepared=None) == 1 and cand(O=None) == 1 and cand(C=0) == 1
+    assert cand(dtype=0) == 2 and cand(d=128, h=4, m=20) == 2

@@ -365,3 +365,28 @@ def test_gathered_qk_cache(dtype, d, h, m, n_items, C):
     valid = (ids >= 0) & (ids < n_items)
     chain = orc.lime_score_candidates(w.T[0][np.where(valid, ids, 0)], w.L, LPv, w.Wq, w.Wk, w.Wv, h, s)
     assert_close(got[valid], chain[valid], dtype, "gathered chain", 2.0)
+
+
+@pytest.mark.parametrize("B,N,C,d,h,m,ragged", [(1, 2048, 4096, 256, 4, 64, False), (3, 777, 500, 256, 4, 64, True),
+                                                (5, 300, 333, 128, 4, 64, True), (2, 4100, 100, 256, 4, 128, True),
+                                                (40, 1024, 64, 128, 4, 32, True)])
+def test_prepared_operands_give_the_same_bits(B, N, C, d, h, m, ragged):
+    """The stages on operands packed once by lime_prepare (Section 3.3: what does not depend on the user is
+    computed ahead of time) run the same kernels on the same images as the per-call entry points: equal bits,
+    for softmax and XORA link states and for the candidate stage, with a negative scale for one of them."""
+    w = _sharp(workload=70 + B, B=B, N=N, C=C, d=d, h=h, m=m, dtype="bf16", len_range=(N // 3, N) if ragged else None,
+               pad_value=float("nan") if ragged else 0.0)
+    g = DeviceWorkload(w)
+    s_h, s_c = w.softmax_scale, -0.5 * w.softmax_scale
+    prepared = binding.lime_prepare(g.L, g.L, g.Wq, g.Wk, g.Wv, g.Wq, g.Wk, h, s_h, s_c)
+    LP = binding.lime_link_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, h, s_h)
+    LP_p = binding.lime_link_history_prepared(g.E, g.lens, prepared, h, m, s_h)
+    assert torch.equal(LP, LP_p)
+    XT, _ = binding.lime_xor_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, h, s_h)
+    XT_p = binding.lime_link_history_prepared(g.E, g.lens, prepared, h, m, s_h, xor_attention=True)
+    assert torch.equal(XT, XT_p)
+    O = binding.lime_score_candidates(g.T, g.L, LP, g.Wq, g.Wk, g.Wv, h, s_c)
+    O_p = binding.lime_score_candidates_prepared(g.T, LP, g.Wv, prepared, h, s_c)
+    assert torch.equal(O, O_p)
+    # and against the oracle, so that the equality is not one of two wrong results
+    assert_close(host(O_p), orc.lime_score_candidates(w.T, w.L, host(LP), w.Wq, w.Wk, w.Wv, h, s_c), "bf16", "prepared O")
