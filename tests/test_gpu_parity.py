@@ -390,3 +390,24 @@ def test_prepared_operands_give_the_same_bits(B, N, C, d, h, m, ragged):
     assert torch.equal(O, O_p)
     # and against the oracle, so that the equality is not one of two wrong results
     assert_close(host(O_p), orc.lime_score_candidates(w.T, w.L, host(LP), w.Wq, w.Wk, w.Wv, h, s_c), "bf16", "prepared O")
+
+
+@pytest.mark.parametrize("d,h,m,B,N", [(256, 4, 64, 40, 1024), (256, 4, 128, 36, 1000), (128, 4, 64, 70, 600)])
+def test_cooperative_history_kernels_on_edge_lengths(d, h, m, B, N):
+    """Enough users x tiles for the cooperative history kernels (at d = 256 the variant with all W_K slices in
+    LDS and one tile buffer), with the lengths that stress them: empty users, one item, one short of / exactly /
+    one past a tile, a chunk boundary, the full history; padding rows hold NaN."""
+    w = _sharp(workload=90 + m, B=B, N=N, C=8, d=d, h=h, m=m, dtype="bf16", len_range=(1, N), pad_value=np.nan)
+    special = [0, 1, 31, 32, 33, 255, 256, 257, N - 1, N, 0, N]
+    w.lens[:len(special)] = special
+    for b, n in enumerate(special):
+        w.E[b, n:] = np.nan
+        w.E[b, :n] = np.nan_to_num(w.E[b, :n], nan=0.0)  # rows that became valid after the length change
+    g = DeviceWorkload(w)
+    s = w.softmax_scale
+    LP = binding.lime_link_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, h, s)
+    assert_close(host(LP), orc.lime_link_history(w.E, w.lens, w.L, w.Wq, w.Wk, w.Wv, h, s), "bf16", "LP")
+    assert not host(LP)[0].any() and not host(LP)[10].any()
+    OT, _ = binding.lime_xor_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, h, s)
+    OT_ref, _ = orc.lime_xor_history(w.E, w.lens, w.L, w.Wq, w.Wk, w.Wv, h, s, want_os=False)
+    assert_close(host(OT), OT_ref, "bf16", "O[T]")
