@@ -12,6 +12,8 @@
 // links is a reduction over the lane's own registers plus one exchange with lane ^ 32.
 // A small pack kernel computes K~ = Ksrc Wk and V~ = Vsrc Wv once per call and lays all three
 // stationary operands out in fragment order, so the main kernel loads them with 16-byte accesses.
+#include <type_traits>
+
 #include "mfma.hpp"
 
 namespace lime {
@@ -125,11 +127,27 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
       advance(ib, ir0);
     }
 
+  // Every workgroup wants the same W_Q^T fragments; asked for in the same order by all compute units at once,
+  // the requests queue up at one cache channel after another.  The workgroups of an XCD (consecutive
+  // workgroups go to different XCDs) therefore start at different k-steps.  The destination registers and the
+  // order of the products stay the same: kRot copies of the load sequence, chosen by a uniform switch.
   bf16x8 wq[KR][MB];
+  constexpr int kRot = KR >= 8 ? 4 : 1;
+  auto load_wq = [&](auto rot_tag) {
+    constexpr int start = decltype(rot_tag)::value * (KR / kRot);
 #pragma unroll
-  for (int kk = 0; kk < KR; ++kk)
+    for (int i = 0; i < KR; ++i) {
+      const int kk = (i + start) % KR;
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) wq[kk][mb] = a.WqA[((head * K1 + kk) * MB + mb) * 64 + lane];
+      for (int mb = 0; mb < MB; ++mb) wq[kk][mb] = a.WqA[((head * K1 + kk) * MB + mb) * 64 + lane];
+    }
+  };
+  switch (kRot == 1 ? 0 : (blockIdx.x / 8) % kRot) {
+    case 1: load_wq(std::integral_constant<int, 1>{}); break;
+    case 2: load_wq(std::integral_constant<int, 2>{}); break;
+    case 3: load_wq(std::integral_constant<int, 3>{}); break;
+    default: load_wq(std::integral_constant<int, 0>{}); break;
+  }
   if constexpr (KL > 0) {
     bf16x8 tmp[KL * MB];
 #pragma unroll
