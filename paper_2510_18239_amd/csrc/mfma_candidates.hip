@@ -43,8 +43,9 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   constexpr int K3 = M / 16;                 // third: k-steps over links, row blocks over d/h (MB)
   // A tile is 32 consecutive rows of X = 64 D contiguous bytes.  The H waves copy it cooperatively:
   // each wave issues LW loads of 1 KiB (16 bytes per lane, fully coalesced) into a register ring that
-  // keeps P tiles in flight per workgroup (besides the two tiles parked in LDS), then parks the tile in LDS (row pitch padded by 16 bytes
-  // so that the fragment reads are free of bank conflicts) where all H waves read it.
+  // keeps P tiles in flight per workgroup (besides the two tiles parked in LDS), then parks the tile in
+  // LDS (row pitch padded by 16 bytes so that the fragment reads are free of bank conflicts) where all
+  // H waves read it.
   constexpr int P = 2;
   constexpr int LW = DH / 16;
   // With d = 256 the W_Q^T slice alone is a quarter of the register file; with many links (whose
