@@ -7,11 +7,12 @@ B=1, N=2048, C=32768, d=256, h=4, m=64, bf16, inputs resident in HBM.  Candidate
 output buffers rotate through more memory than the 256 MiB last-level cache holds, so the
 candidate stream really comes from HBM.
 
-Throughput is that of a serving loop: every request is one captured HIP graph (five kernels), and
-requests of different users are independent, so the loop keeps --streams of them in flight, each on
-its own stream with its own link states and workspace; the small kernels of one request then run
-beside the candidate kernel of another.  Latency is that of one request alone on an idle GPU.
-Prints one JSON line.
+Throughput is that of a serving loop: a request is two C-ABI calls (five kernels) launched from the
+host with arguments marshalled once, and requests of different users are independent, so the loop
+keeps --streams of them in flight, each on its own stream with its own link states and workspace;
+the small kernels of one request then run beside the candidate kernel of another.  (--graphs replays
+one captured HIP graph per request instead; on this runtime that costs 4-8 us more per request.)
+Latency is that of one request alone on an idle GPU.  Prints one JSON line.
 """
 
 from __future__ import annotations
@@ -40,7 +41,7 @@ def parse_args():
     p.add_argument("--history", type=int, default=2048, help="N of the headline workload")
     p.add_argument("--rotate-mib", type=int, default=544, help="candidate+output bytes to rotate through (0 = reuse one pair)")
     p.add_argument("--streams", type=int, default=4, help="requests kept in flight (one stream, link-state buffer and workspace each)")
-    p.add_argument("--eager", action="store_true", help="launch every kernel from the host, on one stream, instead of replaying captured HIP graphs")
+    p.add_argument("--graphs", action="store_true", help="replay one captured HIP graph per request instead of launching its five kernels from the host")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--extras", action="store_true", help="also time the XORA history pass, the C sweep and the MHA baseline")
     return p.parse_args()
@@ -78,7 +79,7 @@ def main():
     Os = [torch.empty_like(T0) for _ in range(n_pairs)]
     ws_bytes = max(binding.workspace_bytes(binding.OP_LINK_HISTORY, B=B, N=N, d=d, h=h, m=m),
                    binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=B, C=C, d=d, h=h, m=m))
-    n_streams = 1 if args.eager else max(1, args.streams)
+    n_streams = max(1, args.streams)
     # one slot per request in flight: link states and workspace are private to a request
     slots = [(torch.empty((B, m, d), dtype=torch.bfloat16, device=dev),
               torch.empty(ws_bytes, dtype=torch.uint8, device=dev)) for _ in range(n_streams)]
@@ -94,14 +95,12 @@ def main():
         step(i)
     torch.cuda.synchronize()
 
-    run = step
-    run_single = step
-    if not args.eager:
-        # One captured HIP graph per (buffer pair, stream); graphs are launched with hipGraphLaunch directly
-        # (torch's replay() costs more host time per launch than a request takes on the GPU).
-        hip = HipGraphs()
-        pool = [hip.stream() for _ in range(2 * n_streams)]
-        streams = pool[:n_streams]
+    hip = HipRuntime()
+    pool = [hip.stream() for _ in range(2 * n_streams)]
+    streams = pool[:n_streams]
+    if args.graphs:
+        # One captured HIP graph per (buffer pair, stream), launched with hipGraphLaunch directly (torch's
+        # replay() costs more host time per launch than a request takes on the GPU).
         n_graphs = max(n_streams, n_pairs // n_streams * n_streams)
         graphs = [hip.capture(streams[j % n_streams], lambda st, j=j: step(j, j % n_streams, st)) for j in range(n_graphs)]
         single = [hip.capture(streams[0], lambda st, j=j: step(j, 0, st)) for j in range(n_pairs)]
@@ -112,28 +111,48 @@ def main():
 
         def run_single(i):
             hip.launch(single[i % n_pairs], streams[0])
+    else:
+        # The two C-ABI calls of a request, launched from the host with their arguments marshalled once (what a
+        # C++ server does; the Python wrappers' per-call checks alone would cost more host time than a request
+        # takes on the GPU when several are in flight).  The stream is the last argument of both calls.
+        lib = binding.lib()
+        ptr = lambda x: ctypes.c_void_p(x.data_ptr())  # noqa: E731
+        hist_args = [(ptr(E), None, ptr(L), 0, ptr(Wq), ptr(Wk), ptr(Wv), ptr(lp), B, N, d, h, m, scale, binding.LIME_BF16,
+                      ptr(wsp), ws_bytes) for lp, wsp in slots]
+        cand_args = [[(ptr(Ts[j]), ptr(L), ptr(lp), ptr(Wq), ptr(Wk), ptr(Wv), ptr(Os[j]), B, C, d, h, m, scale,
+                       binding.LIME_BF16, ptr(wsp), ws_bytes) for j in range(n_pairs)] for lp, wsp in slots]
 
-        # The runtime multiplexes streams onto a few hardware queues (4 here) and the first streams a
-        # process creates do not always land on different ones; two requests on one queue run one after
-        # the other.  Try the first and the second half of the pool briefly and keep the faster half.
-        def probe(cand):
-            nonlocal streams
-            streams = cand
-            for i in range(6 * n_graphs):
-                run(i)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for i in range(20 * n_graphs):
-                run(i)
-            torch.cuda.synchronize()
-            return time.perf_counter() - t0
+        def request(i, slot, stream):
+            if lib.lime_link_history(*hist_args[slot], stream) or lib.lime_score_candidates(*cand_args[slot][i % n_pairs], stream):
+                raise RuntimeError(binding.last_error())
 
-        halves = [pool[:n_streams], pool[n_streams:]]
-        probe_ms = [probe(c) * 1e3 for c in halves] if n_streams > 1 else [0.0, 0.0]
-        streams = halves[0] if probe_ms[0] <= probe_ms[1] else halves[1]
-        for i in range(max(args.warmup, n_graphs)):
+        def run(i):
+            request(i, i % n_streams, streams[i % n_streams])
+
+        def run_single(i):
+            request(i, 0, streams[0])
+
+    # The runtime multiplexes streams onto a few hardware queues (4 here) and the first streams a process
+    # creates do not always land on different ones; two requests on one queue run one after the other.
+    # Try the first and the second half of the pool briefly and keep the faster half.
+    def probe(cand):
+        nonlocal streams
+        streams = cand
+        for i in range(100):
             run(i)
         torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(320):
+            run(i)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    halves = [pool[:n_streams], pool[n_streams:]]
+    probe_ms = [probe(c) * 1e3 for c in halves] if n_streams > 1 else [0.0, 0.0]
+    streams = halves[0] if probe_ms[0] <= probe_ms[1] else halves[1]
+    for i in range(max(args.warmup, 2 * n_pairs)):
+        run(i)
+    torch.cuda.synchronize()
 
     # ---- the timed region: exactly K steps between two synchronisations
     t0 = time.perf_counter()
@@ -169,10 +188,7 @@ def main():
         return xs[min(len(xs) - 1, int(q * len(xs)))]
 
     reps = args.steps
-    if args.eager:
-        lat_step = timed(run, reps)
-    else:
-        lat_step = hip.timed(lambda i: run_single(i), streams[0], reps)
+    lat_step = hip.timed(run_single, streams[0], reps)
     lat_hist = timed(lambda i: binding.lime_link_history(E, None, L, Wq, Wk, Wv, h, scale, LP=LP, workspace=ws), reps)
     binding.profile_enable(True)
     binding.profile_collect(0)
@@ -204,9 +220,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"configs[2] candidate sweep point: B={B} user, N={N}, C={C}, d={d}, h={h}, m={m}, "
                                "bf16, embeddings and weights ~N(0,1/d); step = lime_link_history + lime_score_candidates",
-                   "launch": "eager, one stream" if args.eager else
-                             f"one HIP graph per request, {n_streams} requests in flight on {n_streams} streams",
-                   "stream_probe_ms": None if args.eager else probe_ms,
+                   "launch": ("one HIP graph per request" if args.graphs else "the two calls of a request launched from the host")
+                             + f", {n_streams} requests in flight on {n_streams} streams",
+                   "stream_probe_ms": probe_ms,
                    "rotating_buffer_pairs": n_pairs, "rotating_mib": n_pairs * pair_bytes / 2 ** 20},
         "latency_ms": {"request_p50": pct(lat_step, 0.5), "request_p10": pct(lat_step, 0.1),
                        "request_p90": pct(lat_step, 0.9), "lime_link_history_p50": pct(lat_hist, 0.5),
@@ -231,8 +247,8 @@ def main():
     print(json.dumps(out))
 
 
-class HipGraphs:
-    """Stream capture, instantiation and launch of HIP graphs through the HIP runtime's C API."""
+class HipRuntime:
+    """Streams, events and graphs (capture, instantiation, launch) through the HIP runtime's C API."""
 
     def __init__(self):
         self.hip = ctypes.CDLL("libamdhip64.so")
@@ -360,8 +376,12 @@ def extras(binding, synth, torch, dev, timed, pct):
     binding.profile_enable(False)
     # the request on operands prepared once per model (lime_prepare): four kernels instead of five, no weight packing
     prepared = binding.lime_prepare(L, L, Wq, Wk, Wv, Wq, Wk, w.h, w.softmax_scale, w.softmax_scale)
-    hip = HipGraphs()
+    hip = HipRuntime()
     st = hip.stream()
+
+    class st_handle:  # what the binding expects of a stream object
+        cuda_stream = st.value
+
     LPp = torch.empty_like(LP)
     ws_bytes = max(binding.workspace_bytes(binding.OP_LINK_HISTORY, B=w.B, N=w.N, d=w.d, h=w.h, m=w.m),
                    binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=w.B, C=C, d=w.d, h=w.h, m=w.m))
@@ -372,12 +392,11 @@ def extras(binding, synth, torch, dev, timed, pct):
         binding.lime_score_candidates_prepared(Tc[j], LPp, Wv, prepared, w.h, w.softmax_scale, O=Oc[j], workspace=wsp,
                                                stream=stream)
 
-    graphs = [hip.capture(st, lambda stream, j=j: prepared_request(j, stream)) for j in range(n)]
     torch.cuda.synchronize()
-    lat = hip.timed(lambda i: hip.launch(graphs[i % n], st), st, 200)
+    lat = hip.timed(lambda i: prepared_request(i % n, st_handle), st, 200)
     t0 = time.perf_counter()
     for i in range(400):
-        hip.launch(graphs[i % n], st)
+        prepared_request(i % n, st_handle)
     torch.cuda.synchronize()
     res["prepared_operands"] = {"request_p50_ms": pct(lat, 0.5),
                                 "one_request_in_flight_ms_per_step": (time.perf_counter() - t0) * 1e3 / 400}
