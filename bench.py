@@ -195,6 +195,12 @@ def main():
     lat_cand = timed(lambda i: binding.lime_score_candidates(Ts[i % n_pairs], L, LP, Wq, Wk, Wv, h, scale,
                                                              O=Os[i % n_pairs], workspace=ws), reps)
     kern_ms = binding.profile_collect(0)
+    # and the same kernel inside the serving loop itself: the K steps of the timed region once more, in the
+    # same launch configuration, with the event pairs switched on (they cost time: this pass is not `value`)
+    for i in range(args.steps):
+        run(i)
+    torch.cuda.synchronize()
+    kern_loop_ms = binding.profile_collect(0)
     binding.profile_enable(False)
     # An event pair has a cost of its own (about 4.4 us here) that a 17 us kernel cannot ignore: measure it
     # with nothing between the two records and take it off, so that the figure is the kernel's own duration.
@@ -234,6 +240,7 @@ def main():
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
                      "avg_kernel_ms": kern_avg_ms, "avg_kernel_ms_between_events": kern_raw_ms,
                      "event_pair_overhead_ms": event_overhead_ms, "launches_timed": len(kern_ms),
+                     "avg_kernel_ms_in_serving_loop": (statistics.fmean(kern_loop_ms) - event_overhead_ms) if kern_loop_ms else None,
                      "algorithmic_bytes_per_launch": algorithmic_bytes,
                      "traffic": TRAFFIC_BYTES_PER_LAUNCH if (B, C, d) == (1, 32768, 256) else None},
     }
