@@ -133,11 +133,15 @@ int32_t lime_score_candidates_gathered(const void* Wtable, const int32_t* ids, i
  * that work is the same for every request.  lime_prepare does it once into `prepared`, a device buffer of
  * lime_prepared_bytes(d, h, m, dtype) bytes owned by the caller, 256-byte aligned, which holds: for the history
  * stage the W_K^T / W_V images and Q~ = LC Wq_hist (signed by scale_hist); for the candidate stage the W_Q^T image
- * and K~ = L Wk_cand (signed by scale_cand).  Wq_cand and Wk_cand may be NULL (identity).
+ * and K~ = L Wk_cand (signed by scale_cand) or, when m <= d/h, their product per head G_a = Wq_cand,a K~_a^T
+ * (d x m: the logits of head a are T G_a, one contraction instead of two).  Wq_cand and Wk_cand may be NULL
+ * (identity).
  *   lime_link_history_prepared      = lime_link_history (xor_attention = 0) or the LP output of lime_xor_history
  *                                     (xor_attention != 0) with shared links LC[m][d];
  *   lime_score_candidates_prepared  = lime_score_candidates;
- * bit for bit, when given the scale passed to lime_prepare for that stage (only |scale| is read here).  Wv of the
+ * bit for bit, when given the scale passed to lime_prepare for that stage (only |scale| is read here), except
+ * that with m <= d/h the candidate stage rounds G instead of the projected queries to bf16: its outputs then agree
+ * with lime_score_candidates within the bf16 tolerance, not bit for bit.  Wv of the
  * candidate stage is still applied per request (the values are the user's link states).  bf16 matrix-core
  * shapes only (see Limits); anything else: lime_prepared_bytes returns 0 and the calls return LIME_UNSUPPORTED.
  * Workspace sizes as for LIME_OP_LINK_HISTORY and LIME_OP_SCORE_CANDIDATES.

@@ -83,8 +83,19 @@ struct PackProject {
   int layout;      // kPackKeys, kPackValues or kPackValuesNatural
   float sign;      // +1 or -1: multiplies every projected element (exact); lets kernels assume scale >= 0
 };
+//   score image   [h][d/16][m/32][64]: fragment (a, kk, lb), lane (n, g), slot t = G_a[16kk + 8g + t][32lb + n] with
+//                   G_a = W_Q[:, head a] (L W_K)[:, head a]^T  (d x m): the logits of head a are X G_a, so when the keys
+//                   do not depend on the user (Section 3.3) the query projection and the key product collapse into one
+//                   contraction over d.  Same shape as a weight image with the m links in place of the head's columns.
+struct PackScore {
+  const void* Wq;    // [d][d] bf16, or nullptr for the identity
+  const void* Ksrc;  // [m][d] bf16 rows that become keys (shared by all users)
+  const void* Wk;    // [d][d] bf16, or nullptr for the identity
+  void* image;
+  float sign;        // +1 or -1
+};
 hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackProject* projections, int n_projections,
-                         int d, int h, int m, hipStream_t s);
+                         int d, int h, int m, hipStream_t s, const PackScore* score = nullptr);
 
 // ----------------------------------------------------------------------------- operands prepared once per model
 // What the two stages need of the model alone -- weights and shared links, not the user -- packed once into a
@@ -125,6 +136,7 @@ struct QueriesOverLinks {
   const void* prepared; // when set: W_Q^T and K~ come from this prepared buffer (Wq, Ksrc, Wk unused; shared keys)
 };
 bool queries_over_links_supported(int d, int h, int m);
+bool fused_scores(int d, int h, int m, bool k_per_user);  // whether the kernel takes the score image G
 size_t queries_over_links_workspace(int B, int d, int m, bool k_per_user);
 hipError_t queries_over_links(const QueriesOverLinks& a, void* workspace, hipStream_t s);
 

@@ -12,6 +12,11 @@
 // links is a reduction over the lane's own registers plus one exchange with lane ^ 32.
 // A small pack kernel computes K~ = Ksrc Wk and V~ = Vsrc Wv once per call and lays all three
 // stationary operands out in fragment order, so the main kernel loads them with 16-byte accesses.
+//
+// FUSED: when the keys are the same for every user (the candidate side of LIME: links and weights are model
+// parameters, Section 3.3) and there are no more links than head columns, the first two products collapse into
+//   S^T  (m   x 32) = G_a^T    . X^T,       G_a = W_Q,a K~_a^T  (d x m), built once per model by lime_prepare,
+// which saves the second product, the bf16 rounding of Q~ and the registers of K~.
 #include <type_traits>
 
 #include "mfma.hpp"
@@ -25,21 +30,23 @@ constexpr float kLog2e = 1.4426950408889634f;
 struct MainArgs {
   const bf16_t* X;
   bf16_t* O;
-  const bf16x8 *WqA, *KA, *VA;
+  const bf16x8 *WqA, *KA, *VA;  // FUSED: WqA is the image of G and KA is unused
   int64_t ka_user_frags, va_user_frags;  // fragment-image size per user (0 = shared), in bf16x8 units
   const int32_t* row_lens;
   int B, rows, tiles_per_user, total_tiles;
   float scale, inv_norm;
   bf16_t* Wout;  // WEIGHTS variant only
+  bool fused;
 };
 
 // WEIGHTS: stop after phi and write the normalised attention weights [rows][h][m] (the QK cache of
 // Section 3.3) instead of the weighted sum.
-template <int DH, int M, int H, int PHI, bool WEIGHTS>
+template <int DH, int M, int H, int PHI, bool WEIGHTS, bool FUSED>
 __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) {
   constexpr int D = DH * H;
   constexpr int K1 = D / 16, MB = DH / 32;   // first product: k-steps over d, row blocks over d/h
   constexpr int K2 = DH / 16, LB = M / 32;   // second: k-steps over d/h, row blocks over links
+  constexpr int FB = FUSED ? LB : MB;        // row blocks of the first product (FUSED: over links)
   constexpr int K3 = M / 16;                 // third: k-steps over links, row blocks over d/h (MB)
   // A tile is 32 consecutive rows of X = 64 D contiguous bytes.  The H waves copy it cooperatively:
   // each wave issues LW loads of 1 KiB (16 bytes per lane, fully coalesced) into a register ring that
@@ -52,6 +59,7 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   // logits and weights need registers too) the second half of its k-steps lives in LDS instead and is
   // read once per tile, which keeps the kernel free of register spills.
   constexpr int KL = (D >= 256 && M >= 128) ? K1 / 2 : 0;  // k-steps of W_Q^T kept in LDS
+  static_assert(!FUSED || (KL == 0 && M <= DH), "the fused form is for few links");
   constexpr int KR = K1 - KL;                // k-steps kept in registers
   constexpr int CPR = D / 8;            // 16-byte chunks per row of X
   constexpr int PITCH = 2 * D + 16;     // LDS row pitch of an X tile, bytes
@@ -59,7 +67,7 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   constexpr int OPITCH = 2 * DH + 16;   // LDS row pitch of a wave's output tile, bytes
   __shared__ __attribute__((aligned(16))) unsigned char xs[2][32 * PITCH];
   __shared__ __attribute__((aligned(16))) unsigned char os[H][32 * OPITCH];
-  __shared__ bf16x8 wq_lds[KL > 0 ? H * KL * MB * 64 : 1];
+  __shared__ bf16x8 wq_lds[KL > 0 ? H * KL * FB * 64 : 1];
   const int lane = threadIdx.x & 63, head = threadIdx.x >> 6;
   const int n = lane & 31, g = lane >> 5;
   const int64_t total_rows = static_cast<int64_t>(a.B) * a.rows;
@@ -132,7 +140,7 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   // the requests queue up at one cache channel after another.  The workgroups of an XCD (consecutive
   // workgroups go to different XCDs) therefore start at different k-steps.  The destination registers and the
   // order of the products stay the same: kRot copies of the load sequence, chosen by a uniform switch.
-  bf16x8 wq[KR][MB];
+  bf16x8 wq[KR][FB];
   constexpr int kRot = KR >= 8 ? 4 : 1;
   auto load_wq = [&](auto rot_tag) {
     constexpr int start = decltype(rot_tag)::value * (KR / kRot);
@@ -140,7 +148,7 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
     for (int i = 0; i < KR; ++i) {
       const int kk = (i + start) % KR;
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) wq[kk][mb] = a.WqA[((head * K1 + kk) * MB + mb) * 64 + lane];
+      for (int mb = 0; mb < FB; ++mb) wq[kk][mb] = a.WqA[((head * K1 + kk) * FB + mb) * 64 + lane];
     }
   };
   switch (kRot == 1 ? 0 : (blockIdx.x / 8) % kRot) {
@@ -150,44 +158,44 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
     default: load_wq(std::integral_constant<int, 0>{}); break;
   }
   if constexpr (KL > 0) {
-    bf16x8 tmp[KL * MB];
+    bf16x8 tmp[KL * FB];
 #pragma unroll
-    for (int i = 0; i < KL * MB; ++i) tmp[i] = a.WqA[((head * K1 + KR) * MB + i) * 64 + lane];
+    for (int i = 0; i < KL * FB; ++i) tmp[i] = a.WqA[((head * K1 + KR) * FB + i) * 64 + lane];
 #pragma unroll
-    for (int i = 0; i < KL * MB; ++i) wq_lds[(head * KL * MB + i) * 64 + lane] = tmp[i];
+    for (int i = 0; i < KL * FB; ++i) wq_lds[(head * KL * FB + i) * 64 + lane] = tmp[i];
     // each wave reads back only what it wrote itself: no barrier needed
   }
 
   // Q~^T = Wq_a^T X^T for the tile parked in `buf`; lane (n, g) reads X[row n][16kk + 8g ..].
   // Fragment reads run kAhead k-steps ahead of the MFMAs that use them (one wave per SIMD: nobody else
   // covers the LDS latency).  first_begin() clears the accumulators and starts the reads, first_mfma(i)
-  // issues MFMA i of the K1 * MB, so that the caller can put other work between them.
-  f32x16 acc1[MB];
+  // issues MFMA i of the K1 * FB, so that the caller can put other work between them.
+  f32x16 acc1[FB];
   constexpr int kAhead = 3;
-  constexpr int NM = K1 * MB;
-  bf16x8 xq[K1], wl_frag[KL > 0 ? KL : 1][MB];
+  constexpr int NM = K1 * FB;
+  bf16x8 xq[K1], wl_frag[KL > 0 ? KL : 1][FB];
   const unsigned char* xrow = nullptr;
   int wl = 0;
   auto fetch = [&](int kk) {
     xq[kk] = *reinterpret_cast<const bf16x8*>(xrow + 32 * kk);
     if (kk >= KR) {
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) wl_frag[KL > 0 ? kk - KR : 0][mb] = wq_lds[wl + ((kk - KR) * MB + mb) * 64];
+      for (int mb = 0; mb < FB; ++mb) wl_frag[KL > 0 ? kk - KR : 0][mb] = wq_lds[wl + ((kk - KR) * FB + mb) * 64];
     }
   };
   auto first_begin = [&](const unsigned char* buf) {
     xrow = buf + n * PITCH + 16 * g;
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
+    for (int mb = 0; mb < FB; ++mb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc1[mb][i] = 0.f;
-    wl = head * KL * MB * 64 + lane;
+    wl = head * KL * FB * 64 + lane;
     asm volatile("" : "+v"(wl));  // keeps the LDS reads of W_Q^T inside the tile loop
 #pragma unroll
     for (int kk = 0; kk < kAhead && kk < K1; ++kk) fetch(kk);
   };
   auto first_mfma = [&](int i) {
-    const int kk = i / MB, mb = i % MB;
+    const int kk = i / FB, mb = i % FB;
     if (mb == 0 && kk + kAhead < K1) fetch(kk + kAhead);
     const bf16x8 w = kk < KR ? wq[kk < KR ? kk : 0][mb] : wl_frag[kk >= KR ? kk - KR : 0][mb];
     acc1[mb] = mfma32(w, xq[kk], acc1[mb]);
@@ -264,7 +272,7 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
     }
   };
   int cur_user = first / a.tiles_per_user;
-  load_user(cur_user, true, !WEIGHTS);  // requested with everything else, long before their first use
+  load_user(cur_user, !FUSED, !WEIGHTS);  // requested with everything else, long before their first use
   int rlen = a.row_lens ? min(a.row_lens[cur_user], a.rows) : a.rows;
 
   // Software pipeline: while the vector ALUs do phi of tile i, the matrix cores already run the
@@ -287,7 +295,7 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
       if (b != cur_user) {
         // A new user's operands are waited for right here, inside the rare branch: left pending, they
         // would make every tile wait for all of its outstanding loads and stores before the second product.
-        load_user(b, a.ka_user_frags != 0, !WEIGHTS && a.va_user_frags != 0);
+        load_user(b, !FUSED && a.ka_user_frags != 0, !WEIGHTS && a.va_user_frags != 0);
         rlen = a.row_lens ? min(a.row_lens[b], a.rows) : a.rows;
         cur_user = b;
 #pragma unroll
@@ -301,19 +309,25 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
         asm volatile("" : "+v"(rlen));
       }
 
-      // S^T = K~_a Q~^T from this tile's first product
-      bf16x8 qf[K2];
+      if constexpr (FUSED) {
+        // the first product already is S^T; the next tile's accumulates in the other set of registers
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        qf[2 * mb] = pack_half(acc1[mb], 0);
-        qf[2 * mb + 1] = pack_half(acc1[mb], 1);
-      }
+        for (int lb = 0; lb < LB; ++lb) acc2[lb] = acc1[lb];
+      } else {
+        // S^T = K~_a Q~^T from this tile's first product
+        bf16x8 qf[K2];
 #pragma unroll
-      for (int lb = 0; lb < LB; ++lb) {
+        for (int mb = 0; mb < MB; ++mb) {
+          qf[2 * mb] = pack_half(acc1[mb], 0);
+          qf[2 * mb + 1] = pack_half(acc1[mb], 1);
+        }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc2[lb][i] = 0.f;
+        for (int lb = 0; lb < LB; ++lb) {
 #pragma unroll
-        for (int kk = 0; kk < K2; ++kk) acc2[lb] = mfma32(ka[kk][lb], qf[kk], acc2[lb]);
+          for (int i = 0; i < 16; ++i) acc2[lb][i] = 0.f;
+#pragma unroll
+          for (int kk = 0; kk < K2; ++kk) acc2[lb] = mfma32(ka[kk][lb], qf[kk], acc2[lb]);
+        }
       }
 
       float inv;
@@ -424,15 +438,24 @@ int compute_units() {
   return n;
 }
 
+template <int DH, int M, int H, bool FUSED>
+hipError_t launch_form(const MainArgs& m, int phi, int grid, hipStream_t s) {
+  if (m.Wout != nullptr)
+    hipLaunchKernelGGL((queries_over_links_kernel<DH, M, H, kPhiSoftmax, true, FUSED>), dim3(grid), dim3(64 * H), 0, s, m);
+  else if (phi == kPhiSoftmax)
+    hipLaunchKernelGGL((queries_over_links_kernel<DH, M, H, kPhiSoftmax, false, FUSED>), dim3(grid), dim3(64 * H), 0, s, m);
+  else
+    hipLaunchKernelGGL((queries_over_links_kernel<DH, M, H, kPhiSilu, false, FUSED>), dim3(grid), dim3(64 * H), 0, s, m);
+  return hipGetLastError();
+}
+
 template <int DH, int M, int H>
 hipError_t launch_main(const MainArgs& m, int phi, int grid, hipStream_t s) {
-  if (m.Wout != nullptr)
-    hipLaunchKernelGGL((queries_over_links_kernel<DH, M, H, kPhiSoftmax, true>), dim3(grid), dim3(64 * H), 0, s, m);
-  else if (phi == kPhiSoftmax)
-    hipLaunchKernelGGL((queries_over_links_kernel<DH, M, H, kPhiSoftmax, false>), dim3(grid), dim3(64 * H), 0, s, m);
-  else
-    hipLaunchKernelGGL((queries_over_links_kernel<DH, M, H, kPhiSilu, false>), dim3(grid), dim3(64 * H), 0, s, m);
-  return hipGetLastError();
+  if (m.fused) {
+    if constexpr (M <= DH) return launch_form<DH, M, H, true>(m, phi, grid, s);
+    return hipErrorInvalidValue;
+  }
+  return launch_form<DH, M, H, false>(m, phi, grid, s);
 }
 
 template <int DH, int H>
@@ -467,6 +490,10 @@ bool queries_over_links_supported(int d, int h, int m) {
   return m % 32 == 0 && m >= 32 && m <= 128;
 }
 
+// One contraction X G instead of X W_Q followed by the product with K~: possible when the keys are shared, and
+// no more work or registers when there are at most as many links as head columns.
+bool fused_scores(int d, int h, int m, bool k_per_user) { return !k_per_user && m <= d / h; }
+
 size_t queries_over_links_workspace(int B, int d, int m, bool k_per_user) {
   const size_t wq = align_up(static_cast<size_t>(d) * d * 2);
   const size_t ka = align_up(static_cast<size_t>(k_per_user ? B : 1) * m * d * 2);
@@ -482,6 +509,9 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
   bf16_t* KA = reinterpret_cast<bf16_t*>(ws + align_up(static_cast<size_t>(d) * d * 2));
   bf16_t* VA = reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(KA) +
                                          align_up(static_cast<size_t>(k_per_user ? q.B : 1) * m * d * 2));
+  // The score image G costs more to build than W_Q^T and K~ do to pack (measured: the request gets slower when
+  // it is built per call), so it replaces them only where it is built once per model.
+  const bool fused = q.prepared != nullptr && fused_scores(d, h, m, k_per_user);
   PackWeight wjob{q.Wq, WqA};
   // a negative logit scale is folded into the sign of the packed keys, so the kernel sees scale >= 0
   PackProject pjobs[2] = {{q.Ksrc, q.Wk, KA, q.k_user_stride, k_per_user ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f},
@@ -505,6 +535,7 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
   a.va_user_frags = v_per_user ? static_cast<int64_t>(m) * d / 8 : 0;
   a.row_lens = q.row_lens;
   a.Wout = static_cast<bf16_t*>(q.weights_out);
+  a.fused = fused;
   a.B = q.B, a.rows = q.rows, a.tiles_per_user = (q.rows + 31) / 32;
   a.total_tiles = a.tiles_per_user * q.B;  // the caller has checked that this fits an int
   a.scale = fabsf(q.scale), a.inv_norm = 1.f / static_cast<float>(m);

@@ -20,6 +20,9 @@ struct PackArgs {
   int p_layout[kMaxJobs];
   float p_sign[kMaxJobs];
   int p_first_block[kMaxJobs + 1];  // block ranges of the projection jobs, after the weight jobs
+  const bf16_t *s_wq, *s_k, *s_wk;  // the score job (at most one), after the projection jobs
+  bf16_t* s_img;
+  float s_sign;
   int n_weights, blocks_per_weight;
   int d, dh, m;
 };
@@ -37,10 +40,77 @@ __device__ __forceinline__ int64_t values_slot(int u, int row, int col, int d, i
   return (frag * 64 + 32 * g + out_rho(c % 32)) * 8 + t;
 }
 
+// One wavefront of a score job: the 32 x 32 block (links 32lb.., rows j = 32jb..) of head a's
+//   G_a^T[l][j] = sum_c K~[l][a dh + c] Wq[j][a dh + c],   K~ = Ksrc Wk,
+// computed on the matrix cores as Ksrc (Wk_a Wq_a^T): in that order both products read their operands row-major
+// with the summed index contiguous, so no transposed copy of a weight is needed.  For each block of 32 rows k of
+// Wk the wave forms M = Wk_a[k-block] Wq_a[j-block]^T (summed over the head's columns) and feeds it straight back
+// as the B operand of Ksrc[l-block][k-block] . M (chained order, see mfma.hpp).
+template <int DH, int M, int NKB>
+__device__ void score_wave(const PackArgs& p, int combo) {
+  constexpr int D = 32 * NKB, H = D / DH, LB = M / 32, KC = DH / 16, K1 = D / 16;
+  const int lane = threadIdx.x & 63, n = lane & 31, g = lane >> 5;
+  const int lb = combo % LB, jb = (combo / LB) % NKB, a = combo / (LB * NKB);
+  if (a >= H) return;  // uniform over the wave
+  // a null weight stands for the identity
+  auto rows_of = [&](const bf16_t* W, int row, int kc) {
+    const int c0 = a * DH + 16 * kc + 8 * g;
+    if (W != nullptr) return *reinterpret_cast<const bf16x8*>(W + static_cast<int64_t>(row) * D + c0);
+    bf16x8 v;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] = static_cast<__bf16>(row == c0 + t ? 1.f : 0.f);
+    return v;
+  };
+  bf16x8 wq[KC], wk[NKB][KC], lf[NKB][2];
+#pragma unroll
+  for (int kc = 0; kc < KC; ++kc) wq[kc] = rows_of(p.s_wq, 32 * jb + n, kc);
+#pragma unroll
+  for (int kb = 0; kb < NKB; ++kb) {
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) wk[kb][kc] = rows_of(p.s_wk, 32 * kb + n, kc);
+#pragma unroll
+    for (int f = 0; f < 2; ++f) {
+      // slot t stands for k = 32kb + 16f + chain_k(g, t): columns 4g..4g+3 and 8+4g..8+4g+3 of the 16
+      const bf16_t* src = p.s_k + static_cast<int64_t>(32 * lb + n) * D + 32 * kb + 16 * f + 4 * g;
+      const bf16x4 lo = *reinterpret_cast<const bf16x4*>(src), hi = *reinterpret_cast<const bf16x4*>(src + 8);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) lf[kb][f][t] = lo[t], lf[kb][f][4 + t] = hi[t];
+    }
+  }
+  f32x16 acc;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+  for (int kb = 0; kb < NKB; ++kb) {
+    f32x16 mk;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) mk[i] = 0.f;
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) mk = mfma32(wk[kb][kc], wq[kc], mk);
+#pragma unroll
+    for (int f = 0; f < 2; ++f) acc = mfma32(lf[kb][f], pack_half(mk, f), acc);
+  }
+  // register 4jj + r is link 32lb + 8jj + 4g + r, the lane's column is row j = 32jb + n of G_a
+  const int j = 32 * jb + n;
+  const int64_t frag = (static_cast<int64_t>(a) * K1 + j / 16) * LB + lb;
+  bf16_t* dst = p.s_img + (frag * 64 + 32 * ((j % 16) / 8)) * 8 + j % 8;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) store_as(dst + (8 * (i / 4) + 4 * g + i % 4) * 8, acc[i] * p.s_sign);
+}
+
+// SDH, SM, SNKB: shape of the score job (d/h, m, d/32) this instance can run after its other jobs; 0 = none.
+template <int SDH, int SM, int SNKB>
 __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
   extern __shared__ float smem[];
   const int d = p.d, dh = p.dh, m = p.m, tid = threadIdx.x;
   int blk = blockIdx.x;
+  if constexpr (SDH != 0) {
+    if (blk >= p.n_weights * p.blocks_per_weight + p.p_first_block[kMaxJobs]) {  // uniform
+      blk -= p.n_weights * p.blocks_per_weight + p.p_first_block[kMaxJobs];
+      score_wave<SDH, SM, SNKB>(p, blk * 4 + tid / 64);
+      return;
+    }
+  }
   if (blk < p.n_weights * p.blocks_per_weight) {
     // one thread per (8 consecutive k, column): a 16-byte slot of the weight image
     const int job = blk / p.blocks_per_weight;
@@ -134,7 +204,7 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
 }  // namespace
 
 hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackProject* projections, int n_projections,
-                         int d, int h, int m, hipStream_t s) {
+                         int d, int h, int m, hipStream_t s, const PackScore* score) {
   if (n_weights > kMaxJobs || n_projections > kMaxJobs) return hipErrorInvalidValue;
   PackArgs p{};
   p.d = d, p.dh = d / h, p.m = m;
@@ -162,11 +232,28 @@ hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackPro
   for (int i = n_projections; i < kMaxJobs; ++i)
     if (i > 0) p.p_first_block[i] = 0x7fffffff;
   constexpr int nkc = 256 / (kPackCols / 8);
-  const size_t lds = (static_cast<size_t>(kPackRows) * d + static_cast<size_t>(1 + nkc) * kPackRows * kPackCols) * sizeof(float);
-  const int grid = n_weights * p.blocks_per_weight + blocks;
-  if (grid == 0) return hipSuccess;
-  hipLaunchKernelGGL(pack_kernel, dim3(grid), dim3(256), lds, s, p);
-  return hipGetLastError();
+  size_t lds = (static_cast<size_t>(kPackRows) * d + static_cast<size_t>(1 + nkc) * kPackRows * kPackCols) * sizeof(float);
+  int grid = n_weights * p.blocks_per_weight + blocks;
+  if (score == nullptr) {
+    if (grid == 0) return hipSuccess;
+    hipLaunchKernelGGL((pack_kernel<0, 0, 0>), dim3(grid), dim3(256), lds, s, p);
+    return hipGetLastError();
+  }
+  p.s_wq = static_cast<const bf16_t*>(score->Wq), p.s_k = static_cast<const bf16_t*>(score->Ksrc);
+  p.s_wk = static_cast<const bf16_t*>(score->Wk), p.s_img = static_cast<bf16_t*>(score->image);
+  p.s_sign = score->sign;
+  const int dh = d / h, nkb = d / 32;
+  grid += (h * nkb * (m / 32) + 3) / 4;  // four wavefronts per block, one 32 x 32 block of the image each
+#define LIME_SCORE_CASE(DH_, M_, NKB_)                                                              \
+  if (dh == DH_ && m == M_ && nkb == NKB_) {                                                        \
+    hipLaunchKernelGGL((pack_kernel<DH_, M_, NKB_>), dim3(grid), dim3(256), lds, s, p);             \
+    return hipGetLastError();                                                                       \
+  }
+  LIME_SCORE_CASE(64, 64, 8) LIME_SCORE_CASE(64, 64, 4) LIME_SCORE_CASE(64, 64, 2)
+  LIME_SCORE_CASE(64, 32, 8) LIME_SCORE_CASE(64, 32, 4) LIME_SCORE_CASE(64, 32, 2)
+  LIME_SCORE_CASE(32, 32, 8) LIME_SCORE_CASE(32, 32, 4) LIME_SCORE_CASE(32, 32, 2) LIME_SCORE_CASE(32, 32, 1)
+#undef LIME_SCORE_CASE
+  return hipErrorInvalidValue;
 }
 
 PreparedLayout prepared_layout(int d, int m) {
@@ -179,9 +266,15 @@ PreparedLayout prepared_layout(int d, int m) {
 hipError_t prepare_operands(const PrepareOperands& p, void* prepared, hipStream_t s) {
   const PreparedLayout l = prepared_layout(p.d, p.m);
   char* base = static_cast<char*>(prepared);
+  const float sign_cand = p.scale_cand < 0.f ? -1.f : 1.f;
   PackWeight wjobs[3] = {{p.Wk_hist, base + l.wk}, {p.Wv_hist, base + l.wv}, {p.Wq_cand, base + l.wq}};
   PackProject pjobs[2] = {{p.LC, p.Wq_hist, base + l.qb, 0, 1, kPackKeys, p.scale_hist < 0.f ? -1.f : 1.f},
-                          {p.L, p.Wk_cand, base + l.ka, 0, 1, kPackKeys, p.scale_cand < 0.f ? -1.f : 1.f}};
+                          {p.L, p.Wk_cand, base + l.ka, 0, 1, kPackKeys, sign_cand}};
+  if (fused_scores(p.d, p.h, p.m, false)) {
+    // the candidate stage then wants G = W_Q (L W_K)^T per head in place of W_Q^T and K~
+    PackScore sjob{p.Wq_cand, p.L, p.Wk_cand, base + l.wq, sign_cand};
+    return pack_operands(wjobs, 2, pjobs, 1, p.d, p.h, p.m, s, &sjob);
+  }
   return pack_operands(wjobs, 3, pjobs, 2, p.d, p.h, p.m, s);
 }
 
