@@ -407,7 +407,64 @@ def extras(binding, synth, torch, dev, timed, pct):
     torch.cuda.synchronize()
     res["prepared_operands"] = {"request_p50_ms": pct(lat, 0.5),
                                 "one_request_in_flight_ms_per_step": (time.perf_counter() - t0) * 1e3 / 400}
-    del Tc, Oc
+    # ... and with four such requests in flight, launched like the headline loop (arguments marshalled once)
+    lib = binding.lib()
+    ptr = lambda x: ctypes.c_void_p(x.data_ptr())  # noqa: E731
+    S = 4
+    pslots = [(torch.empty_like(LP), torch.empty(ws_bytes, dtype=torch.uint8, device=dev)) for _ in range(S)]
+    h_args = [(ptr(E), None, ptr(prepared), ptr(lp), w.B, w.N, w.d, w.h, w.m, w.softmax_scale, 0, binding.LIME_BF16,
+               ptr(ws_), ws_bytes) for lp, ws_ in pslots]
+    c_args = [[(ptr(Tc[j]), ptr(lp), ptr(Wv), ptr(prepared), ptr(Oc[j]), w.B, C, w.d, w.h, w.m, w.softmax_scale,
+                binding.LIME_BF16, ptr(ws_), ws_bytes) for j in range(n)] for lp, ws_ in pslots]
+
+    def prepared_direct(i, streams):
+        k = i % S
+        if lib.lime_link_history_prepared(*h_args[k], streams[k]) or \
+                lib.lime_score_candidates_prepared(*c_args[k][i % n], streams[k]):
+            raise RuntimeError(binding.last_error())
+
+    pool = [hip.stream() for _ in range(2 * S)]
+    best = None
+    for half in (pool[:S], pool[S:]):  # the halves of the pool map to the hardware queues differently (see main)
+        for i in range(100):
+            prepared_direct(i, half)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(400):
+            prepared_direct(i, half)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / 400
+        best = ms if best is None else min(best, ms)
+    res["prepared_operands"]["four_requests_in_flight_ms_per_step"] = best
+    res["prepared_operands"]["four_requests_in_flight_candidates_per_s"] = w.B * C / (best * 1e-3)
+    del Tc, Oc, c_args
+    # several users per call (the headline is one): the start-up of every kernel is shared by the batch
+    batched = {}
+    for users in (2, 4, 8):
+        cb = dict(c3)
+        cb["B"] = users
+        wb = synth.make_workload(3, **cb)
+        Eb, Tb = t(wb.E), t(wb.T)
+        pairs = max(2, -(-544 * (1 << 20) // (2 * Tb.numel() * 2)))
+        Tbs = [Tb] + [Tb.clone() for _ in range(pairs - 1)]
+        Obs = [torch.empty_like(Tb) for _ in range(pairs)]
+        LPb = torch.empty((users, wb.m, wb.d), dtype=torch.bfloat16, device=dev)
+
+        def call(i):
+            binding.lime_link_history(Eb, None, L, Wq, Wk, Wv, wb.h, wb.softmax_scale, LP=LPb)
+            binding.lime_score_candidates(Tbs[i % pairs], L, LPb, Wq, Wk, Wv, wb.h, wb.softmax_scale, O=Obs[i % pairs])
+
+        for i in range(20):
+            call(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(100):
+            call(i)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / 100
+        batched[users] = {"ms_per_call": ms, "ms_per_user": ms / users, "candidates_per_s": users * C / (ms * 1e-3)}
+        del Tbs, Obs, Eb, Tb
+    res["users_per_call_one_call_in_flight"] = batched
     # the QK-cache path of Section 3.3 at the headline shape: weights in, weighted sum out, cold buffers
     Wc = binding.lime_build_qk_cache(T, L, Wq, Wk, w.h, w.softmax_scale)
     Ws = [Wc] + [Wc.clone() for _ in range(n - 1)]
