@@ -58,7 +58,8 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   // With d = 256 the W_Q^T slice alone is a quarter of the register file; with many links (whose
   // logits and weights need registers too) the second half of its k-steps lives in LDS instead and is
   // read once per tile, which keeps the kernel free of register spills.
-  constexpr int KL = (D >= 256 && M >= 128) ? K1 / 2 : 0;  // k-steps of W_Q^T kept in LDS
+  // (eight heads: eight waves share the register file two to a SIMD, so with many links three quarters go there)
+  constexpr int KL = D < 256 ? 0 : H == 8 ? (M >= 96 ? 3 * K1 / 4 : 0) : (M >= 128 ? K1 / 2 : 0);  // k-steps of W_Q^T kept in LDS
   static_assert(!FUSED || (KL == 0 && M <= DH), "the fused form is for few links");
   constexpr int KR = K1 - KL;                // k-steps kept in registers
   constexpr int CPR = D / 8;            // 16-byte chunks per row of X

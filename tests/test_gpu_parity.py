@@ -49,6 +49,7 @@ SHAPES = [
     (2, 257, 130, 256, 4, 128, "bf16"),
     (2, 190, 77, 64, 2, 32, "bf16"),
     (1, 100, 65, 256, 8, 96, "bf16"),
+    (2, 70, 45, 256, 8, 128, "bf16"),  # eight heads, most links: three quarters of W_Q^T go through LDS
     (2, 150, 90, 96, 3, 20, "bf16"),   # m not a multiple of 32: general kernels
     (2, 75, 33, 40, 5, 7, "bf16"),     # d/h = 8: general kernels
     (2, 333, 200, 128, 4, 64, "fp32"),
