@@ -317,8 +317,8 @@ class HipRuntime:
 
 # HBM bytes per launch of the dominant kernel at the default workload, from the rocprofv3 --pmc FETCH_SIZE
 # and WRITE_SIZE passes summarised in profiles/queries_over_links_kernel_config3_C32768_hbm_traffic.md
-# (counters scaled by what they read for a plain 16 MiB device copy): 18 130 KiB fetched + 16 384 KiB written.
-TRAFFIC_BYTES_PER_LAUNCH = (18130 + 16384) * 1024
+# (counters scaled by what they read for a plain 16 MiB device copy): 18 133 KiB fetched + 16 384 KiB written.
+TRAFFIC_BYTES_PER_LAUNCH = (18133 + 16384) * 1024
 
 
 def cpu_baseline(w, scale):

@@ -398,15 +398,16 @@ def test_prepared_operands_give_the_same_bits(B, N, C, d, h, m, ragged):
     assert_close(host(O_p), orc.lime_score_candidates(w.T, w.L, host(LP), w.Wq, w.Wk, w.Wv, h, s_c), "bf16", "prepared O")
 
 
-@pytest.mark.parametrize("d,h,m", [(256, 4, 64), (256, 4, 32), (128, 2, 64), (128, 2, 32), (64, 1, 64), (64, 1, 32),
-                                   (256, 8, 32), (128, 4, 32), (64, 2, 32), (32, 1, 32)])
-@pytest.mark.parametrize("identity", ["none", "Wq", "Wk"])
+FOLDED = [(256, 4, 64), (256, 4, 32), (128, 2, 64), (128, 2, 32), (64, 1, 64), (64, 1, 32), (256, 8, 32), (128, 4, 32),
+          (64, 2, 32), (32, 1, 32)]
+
+
+@pytest.mark.parametrize("d,h,m,identity", [s + ("none",) for s in FOLDED] +
+                         [s + (i,) for s in [(256, 4, 64), (128, 4, 32), (64, 1, 32)] for i in ("Wq", "Wk")])
 def test_prepared_candidate_stage_with_folded_scores(d, h, m, identity):
     """Every shape for which lime_prepare folds the candidate-side query weights and link keys into one operand
-    (m <= d/h), with either weight absent (identity) as well: the prepared candidate stage against the oracle,
-    on several users with ragged candidate counts that do not fill the last tile."""
-    if identity != "none" and (d, h, m) not in [(256, 4, 64), (128, 4, 32), (64, 1, 32)]:
-        pytest.skip("identity weights are covered on three shapes")
+    (m <= d/h), and three of them with either weight absent (identity): the prepared candidate stage against the
+    oracle, on several users with a candidate count that does not fill the last tile."""
     B, C = 3, 205
     w = _sharp(workload=300 + d + m, B=B, N=64, C=C, d=d, h=h, m=m, dtype="bf16")
     g = DeviceWorkload(w)
