@@ -28,10 +28,20 @@ Readings of points the paper leaves open (each is repeated where it is used):
     exclusive-or of "query is source" and "key is source" (Algorithm 1), which
     is also what Eq. 7 and Appendix H.1 state.
 
+  * stacked XOR layers (Eq. 8): GatedMLP(A; eta)(X) = (A * SiLU(X Wu)) Wo,
+    eta = (Wu, Wo), the pointwise gating of the block Eq. 5 summarises without
+    its normalisation; the layers form a residual stream X_{j+1} = X_j + Y_j;
+    one theta for all layers, eta_j per layer.  The paper defines neither the
+    block nor the stacking beyond Eq. 8 and the notation table: this is an
+    assumption, and what is pinned below is the arithmetic of this reading.
+
 Pinned by tests/test_oracle_*.py (closed forms, brute force, a library routine,
-invariants, hand-derived fixtures).  The only unpinned statement is the
-paper's claim that LIME approximates full target attention (Appendix D): that
-needs trained links and is not tested ("parity unpinned").
+invariants, hand-derived fixtures).  Unpinned: the paper's claim that LIME
+approximates full target attention (Appendix D), which needs trained links and
+is not tested ("parity unpinned"); and whether the reading of GatedMLP and of
+"stacking" above is the authors' (lime_xor_layers: "parity unpinned" as to the
+reading; its arithmetic is pinned by scalar loops, the quadratic expansion and
+the invariants Eq. 8 fixes).
 """
 
 from __future__ import annotations
@@ -48,6 +58,9 @@ __all__ = [
     "lime_link_history",
     "lime_xor_history",
     "xora_quadratic",
+    "gated_mlp",
+    "lime_xor_layers",
+    "xor_layers_quadratic",
     "lime_score_candidates",
     "mha_target_attention",
     "qk_cache",
@@ -232,6 +245,70 @@ def xora_quadratic(Eb, Lb, Wq, Wk, Wv, h, scale=1.0):
             M[i, j], denom[i] = xor_mask_and_denominator(i, j, n_s, n_t)
     O = mha(X, X, X, M, Wq, Wk, Wv, h, scale, "silu", denom=denom)
     return O[:n_s], O[n_s:]
+
+
+def gated_mlp(A, X, Wu, Wo):
+    """GatedMLP(A; eta) of an interaction layer (Eq. 5, Eq. 8; the notation table calls it an MLP block that learns
+    a gated element-wise product).  The paper gives no formula; the reading taken here is the pointwise gating of
+    the block Eq. 5 summarises (HSTU): the attention output A is multiplied element-wise by a gate computed from
+    the layer's own input rows, U = SiLU(X Wu), and mapped by a linear output layer:  Y = (A * U) Wo,
+    eta = (Wu, Wo), without that block's normalisation (no LayerNorm on this path).
+
+    A, X [rows, d]; Wu, Wo [d, d].  Returns [rows, d].
+    """
+    A, X = _f64(A), _f64(X)
+    return project(A * silu(project(X, Wu)), Wo)
+
+
+def lime_xor_layers(E, lens, LC, Wq, Wk, Wv, Wu, Wo, h, scale=1.0):
+    """L^P of LIME-XOR with n stacked XOR layers (Eq. 8):  L^P = sum_j GatedMLP(XORA(X_j); eta_j) restricted to
+    the link rows, X_1 = E (+) L^C.
+
+    Per layer j: A = XORA(X_j, X_j, X_j; theta) in its block form (Eq. 7: the links attend over the valid history
+    rows, the history rows over the links, SiLU with Algorithm 1's normalisers), Y_j = GatedMLP(A; eta_j) row by
+    row, and - the reading taken for "stacking" - the next layer's input is the residual stream
+    X_{j+1} = X_j + Y_j, as in the block of Eq. 5.  One theta for all layers, as Eq. 8 writes it; eta_j per layer.
+    The history rows of the last layer feed nothing and are not computed.  A user without history gets zeros.
+
+    E [B, N, d]; LC [m, d] or [B, m, d]; Wu, Wo [n, d, d].  Returns [B, m, d].
+    """
+    E = _f64(E)
+    B, N, d = E.shape
+    lens = _lens(lens, B, N)
+    Wu, Wo = _f64(Wu), _f64(Wo)
+    n_layers = Wu.shape[0]
+    m = _links_of_user(LC, 0).shape[0]
+    LP = np.zeros((B, m, d))
+    for b in range(B):
+        n_s, n_t = int(lens[b]), m
+        if n_s == 0:
+            continue
+        Xs, Xt = E[b, :n_s], _f64(_links_of_user(LC, b))
+        for j in range(n_layers):
+            OT = mha(Xt, Xs, Xs, None, Wq, Wk, Wv, h, scale, "silu", denom=np.full(n_t, n_s))
+            Yt = gated_mlp(OT, Xt, Wu[j], Wo[j])
+            LP[b] += Yt
+            if j + 1 < n_layers:
+                OS = mha(Xs, Xt, Xt, None, Wq, Wk, Wv, h, scale, "silu", denom=np.full(n_s, n_t))
+                Xs = Xs + gated_mlp(OS, Xs, Wu[j], Wo[j])
+                Xt = Xt + Yt
+    return LP
+
+
+def xor_layers_quadratic(Eb, Lb, Wq, Wk, Wv, Wu, Wo, h, scale=1.0):
+    """Eq. 8 for one user on the concatenated sequence: every layer runs the full masked (n_s + n_t)^2 attention of
+    Eq. 6 (xora_quadratic), the gate and the output layer act on all rows, the stream is X + Y.  Returns the sum
+    over the layers of the link rows of Y [n_t, d]."""
+    Xs, Xt = _f64(Eb), _f64(Lb)
+    n_s = Xs.shape[0]
+    Wu, Wo = _f64(Wu), _f64(Wo)
+    total = np.zeros_like(Xt)
+    for j in range(Wu.shape[0]):
+        OS, OT = xora_quadratic(Xs, Xt, Wq, Wk, Wv, h, scale)
+        Y = gated_mlp(np.concatenate([OS, OT], axis=0), np.concatenate([Xs, Xt], axis=0), Wu[j], Wo[j])
+        total += Y[n_s:]
+        Xs, Xt = Xs + Y[:n_s], Xt + Y[n_s:]
+    return total
 
 
 def lime_score_candidates(T, L, LP, Wq, Wk, Wv, h, scale, return_weights=False):

@@ -440,7 +440,82 @@ def check_gathered_cache():
     np.testing.assert_array_equal(out[mask], got[mask])
 
 
+def _layer_problem(seed, B=2, N=6, d=8, m=3, n=3):
+    p = _problem(seed, B=B, N=N, d=d, m=m)
+    r = np.random.default_rng(seed + 1)
+    p["Wu"], p["Wo"] = r.standard_normal((n, d, d)) / 2, r.standard_normal((n, d, d)) / 2
+    return p
+
+
+def check_xor_layers_one_layer_from_scalars():
+    """n = 1: L^P = (O[T] * SiLU(L^C Wu)) Wo with O[T] from the scalar brute force and the gate and the output
+    layer written with math.exp and Python loops."""
+    p = _layer_problem(51, n=1)
+    lens, h, d = [6, 3], 2, 8
+    LP = orc.lime_xor_layers(p["E"], lens, p["L"], p["Wq"], p["Wk"], p["Wv"], p["Wu"], p["Wo"], h, 0.7)
+    W = (p["Wq"].tolist(), p["Wk"].tolist(), p["Wv"].tolist())
+    Lb, Wu, Wo = p["L"].tolist(), p["Wu"][0].tolist(), p["Wo"][0].tolist()
+    for b in range(2):
+        Eb = p["E"][b, : lens[b]].tolist()
+        OT = _brute_attention(Lb, Eb, Eb, *W, h, 0.7, "silu", denom=lens[b])
+        for i in range(3):
+            pre = [sum(Lb[i][k] * Wu[k][c] for k in range(d)) for c in range(d)]
+            gated = [OT[i][c] * pre[c] / (1.0 + math.exp(-pre[c])) for c in range(d)]
+            want = [sum(gated[k] * Wo[k][c] for k in range(d)) for c in range(d)]
+            np.testing.assert_allclose(LP[b, i], want, atol=1e-12)
+
+
+def check_xor_layers_block_equals_quadratic():
+    """Three stacked layers in block form = the same three layers on the concatenated sequence with the full
+    (n_s + n_t)^2 masked attention of Eq. 6 (the history rows of the last layer, which the block form skips,
+    change nothing)."""
+    p = _layer_problem(52)
+    lens, h = [6, 4], 2
+    LP = orc.lime_xor_layers(p["E"], lens, p["L"], p["Wq"], p["Wk"], p["Wv"], p["Wu"], p["Wo"], h, 0.9)
+    for b in range(2):
+        want = orc.xor_layers_quadratic(p["E"][b, : lens[b]], p["L"], p["Wq"], p["Wk"], p["Wv"], p["Wu"], p["Wo"], h, 0.9)
+        np.testing.assert_allclose(LP[b], want, atol=1e-12)
+
+
+def check_xor_layers_structure():
+    """What Eq. 8 fixes whatever the gate is: the layers' link outputs are summed (scaling the last layer's output
+    map scales exactly that layer's term); a zero gate projection gives SiLU(0) = 0 and no output; the first
+    layer's term is the one-layer result; history rows enter only through sums over the history (permutation
+    invariance); rows at or past lens[b] are never read; an empty history gives zeros."""
+    p = _layer_problem(53)
+    args = (p["Wq"], p["Wk"], p["Wv"])
+    lens, h = [5, 6], 2
+    f = lambda E, ln, Wu, Wo: orc.lime_xor_layers(E, ln, p["L"], *args, Wu, Wo, h, 0.8)  # noqa: E731
+    base = f(p["E"], lens, p["Wu"], p["Wo"])
+    Wo2, Wo0 = p["Wo"].copy(), p["Wo"].copy()
+    Wo2[2] *= 2.0
+    Wo0[2] *= 0.0
+    np.testing.assert_allclose(f(p["E"], lens, p["Wu"], Wo2) - base, base - f(p["E"], lens, p["Wu"], Wo0), atol=1e-12)
+    assert np.abs(base - f(p["E"], lens, p["Wu"], Wo0)).max() > 1e-3  # the third layer does contribute
+    assert not f(p["E"], lens, np.zeros_like(p["Wu"]), p["Wo"]).any()
+    # with the later layers' output maps at zero only the first layer's term is left
+    Wo1 = p["Wo"].copy()
+    Wo1[1:] = 0.0
+    np.testing.assert_allclose(f(p["E"], lens, p["Wu"], Wo1), f(p["E"], lens, p["Wu"][:1], p["Wo"][:1]), atol=1e-12)
+    # ... but the second layer does see the first one's output: its term differs from a one-layer run
+    two = f(p["E"], lens, p["Wu"][:2], p["Wo"][:2]) - f(p["E"], lens, p["Wu"][:1], p["Wo"][:1])
+    alone = f(p["E"], lens, p["Wu"][1:2], p["Wo"][1:2])
+    assert np.abs(two - alone).max() > 1e-3
+    perm = np.random.default_rng(3).permutation(5)
+    Ep = p["E"].copy()
+    Ep[0, :5] = p["E"][0, perm]
+    np.testing.assert_allclose(f(Ep, lens, p["Wu"], p["Wo"])[0], base[0], atol=1e-12)
+    Ebad = p["E"].copy()
+    Ebad[0, 5:] = np.nan
+    np.testing.assert_array_equal(f(Ebad, lens, p["Wu"], p["Wo"]), base)
+    np.testing.assert_array_equal(f(p["E"][:, :5], [5, 5], p["Wu"], p["Wo"])[0], base[0])
+    assert not f(p["E"], [0, 6], p["Wu"], p["Wo"])[0].any()
+
+
 PINS = [
+    check_xor_layers_one_layer_from_scalars,
+    check_xor_layers_block_equals_quadratic,
+    check_xor_layers_structure,
     check_gathered_cache,
     check_golden_eq3,
     check_golden_eq4,
@@ -541,7 +616,22 @@ def _make_mha_mutant(kind):
     return mutant
 
 
+def _mut_gate_without_silu(A, X, Wu, Wo):
+    return orc.project(orc._f64(A) * orc.project(orc._f64(X), Wu), Wo)
+
+
+def _mut_gate_from_attention(A, X, Wu, Wo):
+    return orc.project(orc._f64(A) * orc.silu(orc.project(orc._f64(A), Wu)), Wo)
+
+
+def _mut_gate_after_output(A, X, Wu, Wo):
+    return orc.project(orc._f64(A), Wo) * orc.silu(orc.project(orc._f64(X), Wu))
+
+
 MUTATIONS = [
+    ("gated_mlp", _mut_gate_without_silu),
+    ("gated_mlp", _mut_gate_from_attention),
+    ("gated_mlp", _mut_gate_after_output),
     ("project", _mut_project_transposed),
     ("silu", _mut_silu_wrong_sign),
     ("phi_softmax", _mut_softmax_ignores_mask),
