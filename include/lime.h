@@ -51,7 +51,7 @@ extern "C" {
 enum { LIME_OK = 0, LIME_INVALID_ARG = 1, LIME_UNSUPPORTED = 2, LIME_WORKSPACE_TOO_SMALL = 3, LIME_LAUNCH_FAILED = 4 };
 enum { LIME_F32 = 0, LIME_BF16 = 1 };
 enum { LIME_OP_LINK_HISTORY = 0, LIME_OP_XOR_HISTORY = 1, LIME_OP_SCORE_CANDIDATES = 2, LIME_OP_MHA_TARGET = 3,
-       LIME_OP_BUILD_QK_CACHE = 4, LIME_OP_SCORE_CACHED = 5 };
+       LIME_OP_BUILD_QK_CACHE = 4, LIME_OP_SCORE_CACHED = 5, LIME_OP_XOR_LAYERS = 6 };
 
 /*
  * User-side link personalisation, Section 3.1 Eq. 3:
@@ -78,6 +78,23 @@ int32_t lime_xor_history(const void* E, const int32_t* lens, const void* LC, int
                          const void* Wq, const void* Wk, const void* Wv, void* LP, void* OS,
                          int32_t B, int32_t N, int32_t d, int32_t h, int32_t m,
                          float scale, int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * LIME-XOR's user side with n stacked XOR layers, Section 3.2 Eq. 8:
+ *   LP[b] = sum_j GatedMLP(XORA(X_j, X_j, X_j; theta); eta_j) on the link rows,   X_1 = E[b] (+) LC_b.
+ * XORA is the layer lime_xor_history computes (Eq. 6-7, one theta = Wq, Wk, Wv for all layers).  The paper names
+ * GatedMLP ("an MLP block that learns a gated element-wise product") and the stacking without defining them; this
+ * library takes GatedMLP(A; eta)(X) = (A * SiLU(X Wu)) Wo with eta_j = (Wu[j], Wo[j]), each [d][d], applied row by
+ * row to history and link rows alike, and a residual stream X_{j+1} = X_j + GatedMLP(...) between the layers.
+ * In: E, lens, LC, lc_user_stride, Wq, Wk, Wv as for lime_xor_history; Wu[n_layers][d][d], Wo[n_layers][d][d].
+ * Out: LP[B][m][d] (zeros for a user without history).  Intermediate tensors live in the workspace
+ * (LIME_OP_XOR_LAYERS) in the storage type; the link outputs are summed in fp32.
+ * bf16 matrix-core shapes only (see Limits); anything else returns LIME_UNSUPPORTED.
+ */
+int32_t lime_xor_layers(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride,
+                        const void* Wq, const void* Wk, const void* Wv, const void* Wu, const void* Wo, int32_t n_layers,
+                        void* LP, int32_t B, int32_t N, int32_t d, int32_t h, int32_t m,
+                        float scale, int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
 
 /*
  * Candidate-side decoupled attention, Section 3.1 Eq. 4 and Section 3.3:

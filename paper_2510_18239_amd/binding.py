@@ -18,7 +18,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblime_hip.so")
 
 LIME_F32, LIME_BF16 = 0, 1
-OP_LINK_HISTORY, OP_XOR_HISTORY, OP_SCORE_CANDIDATES, OP_MHA_TARGET, OP_BUILD_QK_CACHE, OP_SCORE_CACHED = range(6)
+(OP_LINK_HISTORY, OP_XOR_HISTORY, OP_SCORE_CANDIDATES, OP_MHA_TARGET, OP_BUILD_QK_CACHE, OP_SCORE_CACHED,
+ OP_XOR_LAYERS) = range(7)
 STATUS_NAMES = {0: "LIME_OK", 1: "LIME_INVALID_ARG", 2: "LIME_UNSUPPORTED", 3: "LIME_WORKSPACE_TOO_SMALL",
                 4: "LIME_LAUNCH_FAILED"}
 
@@ -30,6 +31,8 @@ SIGNATURES = {
                                  _vp, _sz, _vp]),
     "lime_xor_history": (_i32, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32,
                                 _i32, _vp, _sz, _vp]),
+    "lime_xor_layers": (_i32, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32, _i32, _i32,
+                               _f32, _i32, _vp, _sz, _vp]),
     "lime_score_candidates": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32, _i32,
                                      _vp, _sz, _vp]),
     "mha_target_attention": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32, _i32,
@@ -193,6 +196,32 @@ def lime_xor_history(E, lens, LC, Wq, Wk, Wv, h, scale=1.0, want_os=False, LP=No
     """One XORA layer (Eq. 6-7): returns (O[T] = link states [B, m, d], O[S] [B, N, d] or None)."""
     return _history("lime_xor_history", OP_XOR_HISTORY, E, lens, LC, Wq, Wk, Wv, h, scale, LP, OS, workspace, stream,
                     want_os or OS is not None)
+
+
+def lime_xor_layers(E, lens, LC, Wq, Wk, Wv, Wu, Wo, h, scale=1.0, LP=None, workspace=None, stream=None):
+    """LP[B, m, d] of LIME-XOR with Wu.shape[0] stacked XOR layers (Eq. 8); Wu, Wo [n, d, d] are the gated blocks' weights."""
+    first = _check(E, LC, Wq, Wk, Wv, Wu, Wo, LP)
+    B, N, d = E.shape
+    if LC.dim() == 2:
+        m, stride = LC.shape[0], 0
+    else:
+        if LC.shape[0] != B:
+            raise ValueError("per-user links must be [B, m, d]")
+        m, stride = LC.shape[1], LC.shape[1] * LC.shape[2]
+    if Wu.dim() != 3 or Wu.shape != Wo.shape or tuple(Wu.shape[1:]) != (d, d):
+        raise ValueError("Wu and Wo must both be [n_layers, d, d]")
+    lens = _lens_arg(lens, B, E.device)
+    code = _dtype_code(first)
+    if LP is None:
+        LP = torch.empty((B, m, d), dtype=E.dtype, device=E.device)
+    need = workspace_bytes(OP_XOR_LAYERS, B=B, N=N, d=d, h=h, m=m, dtype=code)
+    ws = workspace if workspace is not None else get_workspace(need, E.device)
+    with torch.cuda.device(E.device):
+        st = lib().lime_xor_layers(_ptr(E), _ptr(lens), _ptr(LC), stride, _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(Wu), _ptr(Wo),
+                                   int(Wu.shape[0]), _ptr(LP), B, N, d, h, m, float(scale), code, _ptr(ws), ws.numel(),
+                                   _stream(stream))
+    _raise(st)
+    return LP
 
 
 def lime_score_candidates(T, L, LP, Wq, Wk, Wv, h, scale, O=None, workspace=None, stream=None):

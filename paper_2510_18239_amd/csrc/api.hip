@@ -81,6 +81,32 @@ HistoryPlan plan_history(void* ws, int64_t B, int64_t N, int64_t d, int64_t m, b
   return p;
 }
 
+// Workspace of lime_xor_layers: one XORA layer's own workspace, the two weight images of the current layer, and
+// the tensors that travel between the steps of a layer (bf16) plus the running sum of the link outputs (fp32).
+struct XorLayersPlan {
+  void* hist_ws;
+  size_t hist_bytes;
+  void *Wu_image, *Wo_image;
+  void *Xs[2], *OS, *Zs;   // history rows [B][N][d]: the residual stream (two copies, alternating), O[S], the gated rows
+  void *Xt[2], *OT, *Zt;   // link rows [B][m][d]: the same four
+  float* sum;              // [B][m][d]
+  size_t bytes;
+};
+
+XorLayersPlan plan_xor_layers(void* ws, int64_t B, int64_t N, int64_t d, int64_t h, int64_t m) {
+  Arena a(ws);
+  XorLayersPlan p{};
+  p.hist_bytes = lime::links_over_history_workspace(B, N, d, h, m, true) + lime::queries_over_links_workspace(B, d, m, true);
+  p.hist_ws = a.take<char>(p.hist_bytes);
+  p.Wu_image = a.take<uint16_t>(d * d);
+  p.Wo_image = a.take<uint16_t>(d * d);
+  for (void** t : {&p.Xs[0], &p.Xs[1], &p.OS, &p.Zs}) *t = a.take<uint16_t>(B * N * d);
+  for (void** t : {&p.Xt[0], &p.Xt[1], &p.OT, &p.Zt}) *t = a.take<uint16_t>(B * m * d);
+  p.sum = a.take<float>(B * m * d);
+  p.bytes = a.used;
+  return p;
+}
+
 int32_t history_impl(const char* fn, int phi, const void* E, const int32_t* lens, const void* LC,
                      int64_t lc_user_stride, const void* Wq, const void* Wk, const void* Wv, void* LP, void* OS,
                      int32_t B, int32_t N, int32_t d, int32_t h, int32_t m, float scale, int32_t dtype,
@@ -401,6 +427,64 @@ int32_t lime_score_candidates_prepared(const void* T, const void* LP, const void
   return LIME_OK;
 }
 
+int32_t lime_xor_layers(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride, const void* Wq,
+                        const void* Wk, const void* Wv, const void* Wu, const void* Wo, int32_t n_layers, void* LP,
+                        int32_t B, int32_t N, int32_t d, int32_t h, int32_t m, float scale, int32_t dtype,
+                        void* workspace, size_t ws_bytes, void* stream) {
+  const char* fn = "lime_xor_layers";
+  if (int32_t st = check_common(fn, B, d, h, dtype)) return st;
+  if (N <= 0 || m <= 0 || n_layers <= 0)
+    return fail(LIME_INVALID_ARG, "%s: N, m and n_layers must be positive (N=%d m=%d n_layers=%d)", fn, N, m, n_layers);
+  if (!E || !LC || !Wq || !Wk || !Wv || !Wu || !Wo || !LP) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  if (lc_user_stride != 0 && lc_user_stride != static_cast<int64_t>(m) * d)
+    return fail(LIME_INVALID_ARG, "%s: lc_user_stride must be 0 or m*d (got %lld)", fn, static_cast<long long>(lc_user_stride));
+  if (dtype != LIME_BF16 || !lime::links_over_history_supported(d, h, m) || !fits_tiles(B, N) ||
+      !all_aligned16(E, LC, Wq, Wk, Wv, Wu, Wo, LP, workspace))
+    return fail(LIME_UNSUPPORTED, "%s: bf16 matrix-core shapes and 16-byte aligned pointers only", fn);
+  const XorLayersPlan need = plan_xor_layers(nullptr, B, N, d, h, m);
+  if (!workspace || ws_bytes < need.bytes)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need.bytes, workspace ? ws_bytes : 0);
+  const XorLayersPlan p = plan_xor_layers(workspace, B, N, d, h, m);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int64_t hist_stride = static_cast<int64_t>(N) * d, link_stride = static_cast<int64_t>(m) * d;
+  const lime::bf16_t *Wu_all = static_cast<const lime::bf16_t*>(Wu), *Wo_all = static_cast<const lime::bf16_t*>(Wo);
+  for (int j = 0; j < n_layers; ++j) {
+    const bool first = j == 0, last = j + 1 == n_layers;
+    // the layer's inputs: the caller's tensors for the first layer, the residual stream afterwards
+    const void* Ej = first ? E : p.Xs[j & 1];
+    const void* Lj = first ? LC : p.Xt[j & 1];
+    const int64_t lj_stride = first ? lc_user_stride : link_stride;
+    // A = XORA(X_j) in block form (Eq. 7): O[T] for the link rows, O[S] for the history rows (not needed after the last layer)
+    if (int32_t st = history_impl(fn, lime::kPhiSilu, Ej, lens, Lj, lj_stride, Wq, Wk, Wv, p.OT, last ? nullptr : p.OS, B, N,
+                                  d, h, m, scale, dtype, p.hist_ws, p.hist_bytes, stream))
+      return st;
+    lime::PackWeight images[2] = {{Wu_all + static_cast<int64_t>(j) * d * d, p.Wu_image}, {Wo_all + static_cast<int64_t>(j) * d * d, p.Wo_image}};
+    LIME_HIP(lime::pack_operands(images, 2, nullptr, 0, d, h, 32, s));
+    // link rows: Y = (O[T] * SiLU(X Wu)) Wo joins the running sum (= L^P after the last layer) and the stream
+    lime::RowsProjection gate{};
+    gate.X = Lj, gate.x_user_stride = lj_stride, gate.W_image = p.Wu_image, gate.Y = p.Zt, gate.B = B, gate.rows = m;
+    gate.d = d, gate.h = h, gate.epilogue = lime::kRowsGate, gate.aux = p.OT, gate.aux_user_stride = link_stride;
+    LIME_HIP(lime::project_rows(gate, s));
+    lime::RowsProjection out{};
+    out.X = p.Zt, out.x_user_stride = link_stride, out.W_image = p.Wo_image, out.B = B, out.rows = m, out.d = d, out.h = h;
+    out.epilogue = lime::kRowsResidual, out.aux = Lj, out.aux_user_stride = lj_stride;
+    out.Y = last ? nullptr : p.Xt[(j + 1) & 1];
+    out.sum_in = first ? nullptr : p.sum, out.sum_out = last ? nullptr : p.sum, out.sum_rounded = last ? LP : nullptr;
+    LIME_HIP(lime::project_rows(out, s));
+    if (last) break;
+    // history rows: the same block with O[S]; rows at or past lens[b] stay zero
+    gate.X = Ej, gate.x_user_stride = hist_stride, gate.lens = lens, gate.Y = p.Zs, gate.rows = N, gate.aux = p.OS;
+    gate.aux_user_stride = hist_stride;
+    LIME_HIP(lime::project_rows(gate, s));
+    out = lime::RowsProjection{};
+    out.X = p.Zs, out.x_user_stride = hist_stride, out.lens = lens, out.W_image = p.Wo_image, out.B = B, out.rows = N;
+    out.d = d, out.h = h, out.epilogue = lime::kRowsResidual, out.aux = Ej, out.aux_user_stride = hist_stride;
+    out.Y = p.Xs[(j + 1) & 1];
+    LIME_HIP(lime::project_rows(out, s));
+  }
+  return LIME_OK;
+}
+
 size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t d, int32_t h, int32_t m,
                             int32_t dtype, int32_t flags) {
   if (B <= 0 || d <= 0 || h <= 0 || d % h != 0 || d / h > kMaxHeadDim || B > kMaxUsers) return 0;
@@ -418,6 +502,9 @@ size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t
                                   (os ? lime::queries_over_links_workspace(B, d, m, true) : size_t{0}));
       return need;
     }
+    case LIME_OP_XOR_LAYERS:
+      if (N <= 0 || m <= 0 || dtype != LIME_BF16 || !lime::links_over_history_supported(d, h, m)) return 0;
+      return plan_xor_layers(nullptr, B, N, d, h, m).bytes;
     case LIME_OP_SCORE_CANDIDATES:
       if (C <= 0 || m <= 0) return 0;
       return std::max(plan_queries(nullptr, static_cast<int64_t>(B) * C, m, static_cast<int64_t>(B) * m, d).bytes,

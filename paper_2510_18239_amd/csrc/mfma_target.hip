@@ -16,6 +16,7 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kOutRows = 0, kOutKeyImage = 1, kOutValueImage = 2;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 struct ProjArgs {
   const bf16_t* X;        // [B][rows][d]
@@ -23,6 +24,15 @@ struct ProjArgs {
   const bf16x8* Wimg;     // weight image
   bf16_t* Y;              // kOutRows: [B][rows][d];  images: [B][tiles][h][...]
   int B, rows, tiles_per_user, total_tiles;
+  // kOutRows only: what is done with P = X W before it is stored (the gated block of an XOR layer, Eq. 8)
+  int epilogue;           // kRowsPlain: Y = P;  kRowsGate: Y = aux * SiLU(P);  kRowsResidual: Y = aux + P
+  const bf16_t* aux;      // [B][rows][d]
+  // kRowsResidual: P is also added into a running fp32 sum (the layers' link outputs): sum_in nullable = zero;
+  // the new sum goes to sum_out (fp32) or, rounded, to sum_rounded (the last layer); Y nullable = not wanted
+  const float* sum_in;
+  float* sum_out;
+  bf16_t* sum_rounded;
+  int64_t x_user_stride, aux_user_stride;  // elements between users in X and aux (0 = one block for all users)
 };
 
 // Fragment images per (user, tile of 32 rows, head):
@@ -43,7 +53,7 @@ __global__ __launch_bounds__(64 * H) void project_rows_kernel(ProjArgs a) {
     const int b = tile / a.tiles_per_user;
     const int row = (tile - b * a.tiles_per_user) * 32 + n;
     const int len = a.lens ? min(a.lens[b], a.rows) : a.rows;
-    const bf16_t* xrow = a.X + (static_cast<int64_t>(b) * a.rows + min(row, a.rows - 1)) * D + 8 * g;
+    const bf16_t* xrow = a.X + b * a.x_user_stride + static_cast<int64_t>(min(row, a.rows - 1)) * D + 8 * g;
 #pragma unroll
     for (int kk = 0; kk < K1; ++kk) {
       bf16x8 v;
@@ -91,9 +101,37 @@ __global__ __launch_bounds__(64 * H) void project_rows_kernel(ProjArgs a) {
           for (int r = 0; r < 4; ++r) v[r] = static_cast<__bf16>(acc[mb][4 * j + r]);
           if (OUT == kOutRows) {
             const int row = ti * 32 + n;
-            if (row < a.rows)
-              *reinterpret_cast<bf16x4*>(a.Y + (static_cast<int64_t>(b) * a.rows + row) * D + head * DH + 32 * mb +
-                                         8 * j + 4 * g) = v;
+            if (row < a.rows) {
+              const int64_t at = (static_cast<int64_t>(b) * a.rows + row) * D + head * DH + 32 * mb + 8 * j + 4 * g;
+              if (a.epilogue != kRowsPlain) {  // uniform
+                const bool valid = row < (a.lens ? min(a.lens[b], a.rows) : a.rows);
+                const bf16x4 x = *reinterpret_cast<const bf16x4*>(a.aux + b * a.aux_user_stride + static_cast<int64_t>(row) * D +
+                                                                   head * DH + 32 * mb + 8 * j + 4 * g);
+                float p[4], y[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                  p[r] = acc[mb][4 * j + r];
+                  const float xr = static_cast<float>(x[r]);
+                  y[r] = a.epilogue == kRowsGate ? xr * p[r] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-p[r] * kLog2e))
+                                                 : xr + p[r];
+                  v[r] = static_cast<__bf16>(valid ? y[r] : 0.f);
+                }
+                if (a.epilogue == kRowsResidual && (a.sum_out != nullptr || a.sum_rounded != nullptr)) {
+                  f32x4 t = {0.f, 0.f, 0.f, 0.f};
+                  if (a.sum_in != nullptr) t = *reinterpret_cast<const f32x4*>(a.sum_in + at);
+#pragma unroll
+                  for (int r = 0; r < 4; ++r) t[r] += p[r];
+                  if (a.sum_out != nullptr) *reinterpret_cast<f32x4*>(a.sum_out + at) = t;
+                  if (a.sum_rounded != nullptr) {
+                    bf16x4 tr;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) tr[r] = static_cast<__bf16>(t[r]);
+                    *reinterpret_cast<bf16x4*>(a.sum_rounded + at) = tr;
+                  }
+                }
+              }
+              if (a.Y != nullptr) *reinterpret_cast<bf16x4*>(a.Y + at) = v;
+            }
           } else {
             // head column c = 32 mb + 8 j + 4 g + r belongs to k-step c / 16, lane half (c % 16) / 8, slot c % 8
             const int kk = 2 * mb + (j >> 1);
@@ -269,9 +307,11 @@ hipError_t run(const TargetAttention& q, void* workspace, hipStream_t s) {
   profile_begin(kKernelProjection, s);
   {
     ProjArgs p{static_cast<const bf16_t*>(q.T), nullptr, static_cast<const bf16x8*>(Wq), Qt, q.B, q.C, ctiles, ctiles * q.B};
+    p.x_user_stride = static_cast<int64_t>(q.C) * D;
     hipLaunchKernelGGL((project_rows_kernel<DH, H, kOutRows>), dim3(p.total_tiles < resident ? p.total_tiles : resident),
                        dim3(64 * H), 0, s, p);
     ProjArgs k{static_cast<const bf16_t*>(q.E), q.lens, static_cast<const bf16x8*>(Wk), Kimg, q.B, q.N, tiles, tiles * q.B};
+    k.x_user_stride = static_cast<int64_t>(q.N) * D;
     hipLaunchKernelGGL((project_rows_kernel<DH, H, kOutKeyImage>), dim3(k.total_tiles < resident ? k.total_tiles : resident),
                        dim3(64 * H), 0, s, k);
     k.Wimg = static_cast<const bf16x8*>(Wv), k.Y = Vimg;
@@ -291,7 +331,39 @@ hipError_t run(const TargetAttention& q, void* workspace, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int DH, int H>
+hipError_t launch_rows(const ProjArgs& p, hipStream_t s) {
+  const int resident = 2 * compute_units();
+  hipLaunchKernelGGL((project_rows_kernel<DH, H, kOutRows>), dim3(p.total_tiles < resident ? p.total_tiles : resident),
+                     dim3(64 * H), 0, s, p);
+  return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t project_rows(const RowsProjection& q, hipStream_t s) {
+  if (q.B <= 0 || q.rows <= 0) return hipSuccess;
+  const int tiles = (q.rows + 31) / 32;
+  ProjArgs p{static_cast<const bf16_t*>(q.X), q.lens, static_cast<const bf16x8*>(q.W_image), static_cast<bf16_t*>(q.Y),
+             q.B, q.rows, tiles, tiles * q.B, q.epilogue, static_cast<const bf16_t*>(q.aux), q.sum_in, q.sum_out,
+             static_cast<bf16_t*>(q.sum_rounded), q.x_user_stride, q.aux_user_stride};
+  const int dh = q.d / q.h;
+  if (dh == 32) {
+    switch (q.h) {
+      case 1: return launch_rows<32, 1>(p, s);
+      case 2: return launch_rows<32, 2>(p, s);
+      case 4: return launch_rows<32, 4>(p, s);
+      case 8: return launch_rows<32, 8>(p, s);
+    }
+  } else if (dh == 64) {
+    switch (q.h) {
+      case 1: return launch_rows<64, 1>(p, s);
+      case 2: return launch_rows<64, 2>(p, s);
+      case 4: return launch_rows<64, 4>(p, s);
+    }
+  }
+  return hipErrorInvalidValue;
+}
 
 bool target_attention_supported(int d, int h) {
   const int dh = d / h;

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     assert {"lime_link_history", "lime_xor_history", "lime_score_candidates", "mha_target_attention",
             "lime_profile_enable", "lime_profile_collect", "lime_build_qk_cache", "lime_score_candidates_cached",
             "lime_score_candidates_gathered", "lime_prepared_bytes", "lime_prepare", "lime_link_history_prepared",
-            "lime_score_candidates_prepared",
+            "lime_score_candidates_prepared", "lime_xor_layers",
             "lime_workspace_bytes", "lime_last_error", "lime_version"} <= set(names)
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
@@ -160,3 +160,28 @@ def test_prepared_operand_argument_checks():
     assert cand() == 3
     assert cand(T=None) == 1 and cand(LP=None) == 1 and cand(prepared=None) == 1 and cand(O=None) == 1 and cand(C=0) == 1
     assert cand(dtype=0) == 2 and cand(d=128, h=4, m=20) == 2
+
+
+def test_xor_layers_argument_checks():
+    lib = binding.lib()
+
+    def call(**kw):
+        a = dict(E=FAKE, lens=None, LC=FAKE, stride=0, Wq=FAKE, Wk=FAKE, Wv=FAKE, Wu=FAKE, Wo=FAKE, n=3, LP=FAKE, B=2,
+                 N=64, d=128, h=4, m=64, scale=1.0, dtype=1, ws=FAKE, ws_bytes=0, stream=None)
+        a.update(kw)
+        return lib.lime_xor_layers(a["E"], a["lens"], a["LC"], a["stride"], a["Wq"], a["Wk"], a["Wv"], a["Wu"], a["Wo"],
+                                   a["n"], a["LP"], a["B"], a["N"], a["d"], a["h"], a["m"], a["scale"], a["dtype"],
+                                   a["ws"], a["ws_bytes"], a["stream"])
+
+    need = binding.workspace_bytes(binding.OP_XOR_LAYERS, B=2, N=64, d=128, h=4, m=64)
+    assert need > 4 * 2 * 64 * 128 * 2  # at least the four history-sized tensors
+    assert call() == 3 and str(need) in binding.last_error()          # workspace too small, size named
+    assert call(ws_bytes=need - 1) == 3
+    assert call(Wu=None) == 1 and call(Wo=None) == 1 and call(LP=None) == 1 and call(E=None) == 1
+    assert call(n=0) == 1 and call(N=0) == 1 and call(m=0) == 1
+    assert call(stride=5) == 1
+    assert call(dtype=0) == 2 and "bf16" in binding.last_error()      # fp32 storage: no path
+    assert call(d=120, h=3) == 2                                        # d/h = 40: outside the matrix-core set
+    assert call(E=FAKE + 2) == 2                                        # misaligned pointer
+    assert binding.workspace_bytes(binding.OP_XOR_LAYERS, B=2, N=64, d=128, h=4, m=64, dtype=0) == 0
+    assert binding.workspace_bytes(binding.OP_XOR_LAYERS, B=2, N=64, d=120, h=3, m=64) == 0

@@ -439,3 +439,49 @@ def test_cooperative_history_kernels_on_edge_lengths(d, h, m, B, N):
     OT, _ = binding.lime_xor_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, h, s)
     OT_ref, _ = orc.lime_xor_history(w.E, w.lens, w.L, w.Wq, w.Wk, w.Wv, h, s, want_os=False)
     assert_close(host(OT), OT_ref, "bf16", "O[T]")
+
+
+# ----------------------------------------------------------------------------- stacked XOR layers (Eq. 8)
+
+def _layer_weights(seed, n, d, gain=1.0):
+    """eta_j = (Wu[j], Wo[j]) ~ N(0, 1/d) like every other weight, rounded to bf16; `gain` sharpens the gate."""
+    r = np.random.default_rng(seed)
+    Wu = (r.standard_normal((n, d, d)) * d ** -0.5 * gain).astype(np.float32)
+    Wo = (r.standard_normal((n, d, d)) * d ** -0.5).astype(np.float32)
+    rnd = lambda x: torch.from_numpy(x).to(torch.bfloat16).float().numpy()  # noqa: E731
+    return rnd(Wu), rnd(Wo)
+
+
+@pytest.mark.parametrize("B,N,d,h,m,n_layers,per_user", [
+    (3, 333, 128, 4, 64, 3, False),      # configuration-4 shape, several tiles and a ragged tail
+    (2, 257, 256, 4, 128, 3, False),
+    (2, 190, 64, 2, 32, 2, True),        # per-user contextualised links from the start
+    (1, 100, 256, 8, 96, 1, False),      # one layer: the gated block on top of lime_xor_history
+    (40, 1024, 128, 4, 64, 3, False),    # enough rows for the cooperative history kernel
+])
+def test_xor_layers(B, N, d, h, m, n_layers, per_user):
+    """lime_xor_layers against the oracle's Eq. 8 on sharp inputs (gate pre-activations and XORA logits of order
+    one, so that SiLU is far from linear), ragged lengths with an empty user, NaN in the padding rows.  The
+    intermediate tensors are bf16, so the bar is the chained one (twice the single-call bar)."""
+    w = _sharp(workload=400 + d + m + n_layers, B=B, N=N, C=8, d=d, h=h, m=m, dtype="bf16",
+               len_range=(max(1, N // 3), N), pad_value=np.nan)
+    w.lens[B - 1] = 0 if B > 1 else w.lens[0]
+    w.E[B - 1, w.lens[B - 1]:] = np.nan
+    Wu, Wo = _layer_weights(77 + d, n_layers, d, gain=2.0)
+    LC = w.L
+    if per_user:
+        LC = np.stack([np.roll(w.L, b + 1, axis=0) for b in range(B)])
+    g = DeviceWorkload(w)
+    xs = _xor_scale(w)
+    LP = binding.lime_xor_layers(g.E, g.lens, dev(LC, "bf16"), g.Wq, g.Wk, g.Wv, dev(Wu, "bf16"), dev(Wo, "bf16"), h, xs)
+    ref = orc.lime_xor_layers(w.E, w.lens, LC, w.Wq, w.Wk, w.Wv, Wu, Wo, h, xs)
+    err = assert_close(host(LP), ref, "bf16", "LP of stacked XOR layers", factor=2.0)
+    print(f"max|ref| = {np.abs(ref).max():.3e}, max-abs error {err:.3e}", flush=True)
+    if B > 1:
+        assert not host(LP)[B - 1].any()
+    if n_layers == 1:
+        # one layer is the gated block applied to the link states of lime_xor_history
+        OT, _ = binding.lime_xor_history(g.E, g.lens, dev(LC, "bf16"), g.Wq, g.Wk, g.Wv, h, xs)
+        Lb = LC if LC.ndim == 3 else np.broadcast_to(LC, (B,) + LC.shape)
+        want = np.stack([orc.gated_mlp(host(OT)[b], Lb[b], Wu[0], Wo[0]) for b in range(B)])
+        assert_close(host(LP), want, "bf16", "one layer on the GPU's own O[T]")
