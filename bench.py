@@ -491,6 +491,23 @@ def extras(binding, synth, torch, dev, timed, pct):
         lat = timed(lambda i: binding.lime_xor_history(E4, None, L4, q4, k4, v4, w4.h, 1.0), 50)
         xs[N] = pct(lat, 0.5)
     res["lime_xor_history_p50_ms_vs_N"] = xs
+    # LIME-XOR's user side with three stacked XOR layers (Eq. 8, n = 3 as in Section 4.1) at the same shapes:
+    # per layer one XORA pass with both outputs, then the gated block on link and history rows (two d x d products per row)
+    layers = {}
+    r4 = torch.Generator(device="cpu").manual_seed(20251018 + 4000 + 77)
+    Wu4 = (torch.randn((3, w4.d, w4.d), generator=r4) * w4.d ** -0.5).to(torch.bfloat16).to(dev)
+    Wo4 = (torch.randn((3, w4.d, w4.d), generator=r4) * w4.d ** -0.5).to(torch.bfloat16).to(dev)
+    for N in (2048, 4096, 8192, 16384):
+        c4["N"] = N
+        w4 = synth.make_workload(4, **c4)
+        E4, L4, q4, k4, v4 = t(w4.E), t(w4.L), t(w4.Wq), t(w4.Wk), t(w4.Wv)
+        lat = timed(lambda i: binding.lime_xor_layers(E4, None, L4, q4, k4, v4, Wu4, Wo4, w4.h, 1.0), 50)
+        # 2 layers x (O[T] + O[S] + the gated block on all rows) + the last layer's O[T] and link-row block
+        rows = w4.B * N
+        flops = 2 * (2 * (4 * w4.d * w4.d + 4 * w4.m * w4.d) * rows + 2 * 2 * w4.d * w4.d * rows) + \
+            (4 * w4.d * w4.d + 4 * w4.m * w4.d) * rows
+        layers[N] = {"p50_ms": pct(lat, 0.5), "TFLOPs": flops / (pct(lat, 0.5) * 1e-3) / 1e12}
+    res["lime_xor_layers_n3_vs_N"] = layers
     # LIME vs full target attention on identical inputs (configs[4])
     c5 = dict(synth.CONFIGS[5])
     c5["pad_value"] = 0.0
