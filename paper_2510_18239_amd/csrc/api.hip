@@ -87,8 +87,8 @@ struct XorLayersPlan {
   void* hist_ws;
   size_t hist_bytes;
   void *Wu_image, *Wo_image;
-  void *Xs[2], *OS, *Zs;   // history rows [B][N][d]: the residual stream (two copies, alternating), O[S], the gated rows
-  void *Xt[2], *OT, *Zt;   // link rows [B][m][d]: the same four
+  void *Xs[2], *OS;        // history rows [B][N][d]: the residual stream (two copies, alternating) and O[S]
+  void *Xt[2], *OT;        // link rows [B][m][d]: the same three
   float* sum;              // [B][m][d]
   size_t bytes;
 };
@@ -100,8 +100,8 @@ XorLayersPlan plan_xor_layers(void* ws, int64_t B, int64_t N, int64_t d, int64_t
   p.hist_ws = a.take<char>(p.hist_bytes);
   p.Wu_image = a.take<uint16_t>(d * d);
   p.Wo_image = a.take<uint16_t>(d * d);
-  for (void** t : {&p.Xs[0], &p.Xs[1], &p.OS, &p.Zs}) *t = a.take<uint16_t>(B * N * d);
-  for (void** t : {&p.Xt[0], &p.Xt[1], &p.OT, &p.Zt}) *t = a.take<uint16_t>(B * m * d);
+  for (void** t : {&p.Xs[0], &p.Xs[1], &p.OS}) *t = a.take<uint16_t>(B * N * d);
+  for (void** t : {&p.Xt[0], &p.Xt[1], &p.OT}) *t = a.take<uint16_t>(B * m * d);
   p.sum = a.take<float>(B * m * d);
   p.bytes = a.used;
   return p;
@@ -461,26 +461,18 @@ int32_t lime_xor_layers(const void* E, const int32_t* lens, const void* LC, int6
     lime::PackWeight images[2] = {{Wu_all + static_cast<int64_t>(j) * d * d, p.Wu_image}, {Wo_all + static_cast<int64_t>(j) * d * d, p.Wo_image}};
     LIME_HIP(lime::pack_operands(images, 2, nullptr, 0, d, h, 32, s));
     // link rows: Y = (O[T] * SiLU(X Wu)) Wo joins the running sum (= L^P after the last layer) and the stream
-    lime::RowsProjection gate{};
-    gate.X = Lj, gate.x_user_stride = lj_stride, gate.W_image = p.Wu_image, gate.Y = p.Zt, gate.B = B, gate.rows = m;
-    gate.d = d, gate.h = h, gate.epilogue = lime::kRowsGate, gate.aux = p.OT, gate.aux_user_stride = link_stride;
-    LIME_HIP(lime::project_rows(gate, s));
-    lime::RowsProjection out{};
-    out.X = p.Zt, out.x_user_stride = link_stride, out.W_image = p.Wo_image, out.B = B, out.rows = m, out.d = d, out.h = h;
-    out.epilogue = lime::kRowsResidual, out.aux = Lj, out.aux_user_stride = lj_stride;
-    out.Y = last ? nullptr : p.Xt[(j + 1) & 1];
-    out.sum_in = first ? nullptr : p.sum, out.sum_out = last ? nullptr : p.sum, out.sum_rounded = last ? LP : nullptr;
-    LIME_HIP(lime::project_rows(out, s));
+    lime::GatedBlock links{};
+    links.X = Lj, links.x_user_stride = lj_stride, links.Wu_image = p.Wu_image, links.Wo_image = p.Wo_image, links.A = p.OT;
+    links.B = B, links.rows = m, links.d = d, links.h = h;
+    links.Y = last ? nullptr : p.Xt[(j + 1) & 1];
+    links.sum_in = first ? nullptr : p.sum, links.sum_out = last ? nullptr : p.sum, links.sum_rounded = last ? LP : nullptr;
+    LIME_HIP(lime::gated_block(links, s));
     if (last) break;
     // history rows: the same block with O[S]; rows at or past lens[b] stay zero
-    gate.X = Ej, gate.x_user_stride = hist_stride, gate.lens = lens, gate.Y = p.Zs, gate.rows = N, gate.aux = p.OS;
-    gate.aux_user_stride = hist_stride;
-    LIME_HIP(lime::project_rows(gate, s));
-    out = lime::RowsProjection{};
-    out.X = p.Zs, out.x_user_stride = hist_stride, out.lens = lens, out.W_image = p.Wo_image, out.B = B, out.rows = N;
-    out.d = d, out.h = h, out.epilogue = lime::kRowsResidual, out.aux = Ej, out.aux_user_stride = hist_stride;
-    out.Y = p.Xs[(j + 1) & 1];
-    LIME_HIP(lime::project_rows(out, s));
+    lime::GatedBlock rows{};
+    rows.X = Ej, rows.x_user_stride = hist_stride, rows.lens = lens, rows.Wu_image = p.Wu_image, rows.Wo_image = p.Wo_image;
+    rows.A = p.OS, rows.Y = p.Xs[(j + 1) & 1], rows.B = B, rows.rows = N, rows.d = d, rows.h = h;
+    LIME_HIP(lime::gated_block(rows, s));
   }
   return LIME_OK;
 }

@@ -167,24 +167,22 @@ bool target_attention_supported(int d, int h);
 size_t target_attention_workspace(int B, int C, int N, int d);
 hipError_t target_attention(const TargetAttention& a, void* workspace, hipStream_t s);
 
-// ----------------------------------------------------------------------------- row projections with an epilogue
-// Y = epilogue(X W) on the matrix cores, rows streamed, the weight image (PackWeight) stationary: the two linear maps
-// of the gated block of an XOR layer (Eq. 8).  bf16, d/h in {32, 64}, h in {1, 2, 4, 8}, d <= 256.
-constexpr int kRowsPlain = 0, kRowsGate = 1, kRowsResidual = 2;
-struct RowsProjection {
-  const void* X;         // [B][rows][d] bf16
-  const int32_t* lens;   // nullable; rows >= lens[b] count as zeros and are written as zeros
-  const void* W_image;   // weight image written by pack_operands
-  void* Y;               // [B][rows][d] bf16; nullable with kRowsResidual
+// ----------------------------------------------------------------------------- gated block of an XOR layer (mfma_target.hip)
+// The gated block of an XOR layer in one kernel: Y = X + (A * SiLU(X Wu)) Wo per row (rows >= lens[b] are zeros), and
+// optionally sum_out / sum_rounded = sum_in + (A * SiLU(X Wu)) Wo (the running sum of the layers' link outputs).
+struct GatedBlock {
+  const void* X;          // [.][rows][d] bf16
+  int64_t x_user_stride;  // elements between users; 0 = one [rows][d] block for all users
+  const int32_t* lens;    // nullable
+  const void *Wu_image, *Wo_image;  // weight images written by pack_operands
+  const void* A;          // [B][rows][d] bf16
+  void* Y;                // [B][rows][d] bf16, nullable
+  const float* sum_in;    // nullable = zero
+  float* sum_out;         // nullable
+  void* sum_rounded;      // bf16, nullable
   int B, rows, d, h;
-  int epilogue;          // kRowsPlain: Y = XW;  kRowsGate: Y = aux * SiLU(XW);  kRowsResidual: Y = aux + XW
-  const void* aux;       // [B][rows][d] bf16
-  const float* sum_in;   // kRowsResidual: XW is also added to this running sum (nullable = zero) ...
-  float* sum_out;        // ... which goes here in fp32 (nullable) ...
-  void* sum_rounded;     // ... and / or here rounded to bf16 (nullable)
-  int64_t x_user_stride, aux_user_stride;  // elements between users in X and aux; 0 = one [rows][d] block for all users
 };
-hipError_t project_rows(const RowsProjection& q, hipStream_t s);
+hipError_t gated_block(const GatedBlock& q, hipStream_t s);
 
 // ----------------------------------------------------------------------------- history-side kernel family
 // Fused "few queries x many keys" attention: the m links attend over one user's N history rows;

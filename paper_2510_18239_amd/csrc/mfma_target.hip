@@ -9,6 +9,9 @@
 // every operand with one coalesced 16-byte load per lane:
 //   S^T (32 items x 32 q) = K~_tile . Q~^T        O^T (d/h x 32 q) += V~_tile^T . P^T
 // History rows at or beyond lens[b] are written as zeros by (1) and masked out of the softmax by (2).
+//
+// Also here, because it is the same "rows streamed past stationary weight slices" shape as (1): the gated block
+// of the stacked XOR layers (gated_block_kernel, Eq. 8).
 #include "mfma.hpp"
 
 namespace lime {
@@ -24,15 +27,6 @@ struct ProjArgs {
   const bf16x8* Wimg;     // weight image
   bf16_t* Y;              // kOutRows: [B][rows][d];  images: [B][tiles][h][...]
   int B, rows, tiles_per_user, total_tiles;
-  // kOutRows only: what is done with P = X W before it is stored (the gated block of an XOR layer, Eq. 8)
-  int epilogue;           // kRowsPlain: Y = P;  kRowsGate: Y = aux * SiLU(P);  kRowsResidual: Y = aux + P
-  const bf16_t* aux;      // [B][rows][d]
-  // kRowsResidual: P is also added into a running fp32 sum (the layers' link outputs): sum_in nullable = zero;
-  // the new sum goes to sum_out (fp32) or, rounded, to sum_rounded (the last layer); Y nullable = not wanted
-  const float* sum_in;
-  float* sum_out;
-  bf16_t* sum_rounded;
-  int64_t x_user_stride, aux_user_stride;  // elements between users in X and aux (0 = one block for all users)
 };
 
 // Fragment images per (user, tile of 32 rows, head):
@@ -53,7 +47,7 @@ __global__ __launch_bounds__(64 * H) void project_rows_kernel(ProjArgs a) {
     const int b = tile / a.tiles_per_user;
     const int row = (tile - b * a.tiles_per_user) * 32 + n;
     const int len = a.lens ? min(a.lens[b], a.rows) : a.rows;
-    const bf16_t* xrow = a.X + b * a.x_user_stride + static_cast<int64_t>(min(row, a.rows - 1)) * D + 8 * g;
+    const bf16_t* xrow = a.X + (static_cast<int64_t>(b) * a.rows + min(row, a.rows - 1)) * D + 8 * g;
 #pragma unroll
     for (int kk = 0; kk < K1; ++kk) {
       bf16x8 v;
@@ -101,42 +95,134 @@ __global__ __launch_bounds__(64 * H) void project_rows_kernel(ProjArgs a) {
           for (int r = 0; r < 4; ++r) v[r] = static_cast<__bf16>(acc[mb][4 * j + r]);
           if (OUT == kOutRows) {
             const int row = ti * 32 + n;
-            if (row < a.rows) {
-              const int64_t at = (static_cast<int64_t>(b) * a.rows + row) * D + head * DH + 32 * mb + 8 * j + 4 * g;
-              if (a.epilogue != kRowsPlain) {  // uniform
-                const bool valid = row < (a.lens ? min(a.lens[b], a.rows) : a.rows);
-                const bf16x4 x = *reinterpret_cast<const bf16x4*>(a.aux + b * a.aux_user_stride + static_cast<int64_t>(row) * D +
-                                                                   head * DH + 32 * mb + 8 * j + 4 * g);
-                float p[4], y[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                  p[r] = acc[mb][4 * j + r];
-                  const float xr = static_cast<float>(x[r]);
-                  y[r] = a.epilogue == kRowsGate ? xr * p[r] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-p[r] * kLog2e))
-                                                 : xr + p[r];
-                  v[r] = static_cast<__bf16>(valid ? y[r] : 0.f);
-                }
-                if (a.epilogue == kRowsResidual && (a.sum_out != nullptr || a.sum_rounded != nullptr)) {
-                  f32x4 t = {0.f, 0.f, 0.f, 0.f};
-                  if (a.sum_in != nullptr) t = *reinterpret_cast<const f32x4*>(a.sum_in + at);
-#pragma unroll
-                  for (int r = 0; r < 4; ++r) t[r] += p[r];
-                  if (a.sum_out != nullptr) *reinterpret_cast<f32x4*>(a.sum_out + at) = t;
-                  if (a.sum_rounded != nullptr) {
-                    bf16x4 tr;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) tr[r] = static_cast<__bf16>(t[r]);
-                    *reinterpret_cast<bf16x4*>(a.sum_rounded + at) = tr;
-                  }
-                }
-              }
-              if (a.Y != nullptr) *reinterpret_cast<bf16x4*>(a.Y + at) = v;
-            }
+            if (row < a.rows)
+              *reinterpret_cast<bf16x4*>(a.Y + (static_cast<int64_t>(b) * a.rows + row) * D + head * DH + 32 * mb +
+                                         8 * j + 4 * g) = v;
           } else {
             // head column c = 32 mb + 8 j + 4 g + r belongs to k-step c / 16, lane half (c % 16) / 8, slot c % 8
             const int kk = 2 * mb + (j >> 1);
             bf16_t* frag = a.Y + ((static_cast<int64_t>(tile) * H + head) * K2 + kk) * 64 * 8;
             *reinterpret_cast<bf16x4*>(frag + (32 * (j & 1) + n) * 8 + 4 * g) = v;
+          }
+        }
+    }
+  }
+}
+
+// The gated block of an XOR layer (Eq. 8) in one pass over the rows:  Y = X + (A * SiLU(X W_U)) W_O.
+// One wave per head-sized slice of the d output columns, both weight slices stationary (A operands).  Per tile of
+// 32 rows: P^T = W_U^T X^T from the rows' fragments, the gate on the accumulators (a lane owns one row), the gated
+// rows Z through LDS (every wave needs all d columns of Z as the B operand of the second product), Y^T = W_O^T Z^T,
+// then the residual and, for link rows, the running fp32 sum of the layers' outputs.
+struct GatedArgs {
+  const bf16_t* X;        // [.][rows][d] the layer's input rows (gate input and residual)
+  int64_t x_user_stride;  // elements between users (0 = shared rows)
+  const int32_t* lens;    // nullable; rows >= lens[b] count as zeros and are written as zeros
+  const bf16x8 *Wu, *Wo;  // weight images
+  const bf16_t* A;        // [B][rows][d] attention output of the layer
+  bf16_t* Y;              // [B][rows][d] next layer's input; nullable
+  const float* sum_in;    // nullable = zero
+  float* sum_out;         // nullable
+  bf16_t* sum_rounded;    // nullable
+  int B, rows, tiles_per_user, total_tiles;
+};
+
+template <int DH, int H>
+__global__ __launch_bounds__(64 * H) void gated_block_kernel(GatedArgs a) {
+  constexpr int D = DH * H, K1 = D / 16, MB = DH / 32;
+  constexpr int PITCH = 2 * D + 16;  // bytes; the padding keeps the fragment reads free of bank conflicts
+  __shared__ __attribute__((aligned(16))) unsigned char zs[32 * PITCH];
+  const int lane = threadIdx.x & 63, head = threadIdx.x >> 6;
+  const int n = lane & 31, g = lane >> 5;
+  bf16x8 wu[K1][MB], wo[K1][MB];
+#pragma unroll
+  for (int kk = 0; kk < K1; ++kk)
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      wu[kk][mb] = a.Wu[((head * K1 + kk) * MB + mb) * 64 + lane];
+      wo[kk][mb] = a.Wo[((head * K1 + kk) * MB + mb) * 64 + lane];
+    }
+  for (int tile = blockIdx.x; tile < a.total_tiles; tile += gridDim.x) {
+    const int b = tile / a.tiles_per_user, ti = tile - b * a.tiles_per_user;
+    const int row = ti * 32 + n;
+    const int len = a.lens ? min(a.lens[b], a.rows) : a.rows;
+    const bool valid = row < len;
+    const bf16_t* xrow = a.X + b * a.x_user_stride + static_cast<int64_t>(min(row, a.rows - 1)) * D;
+    bf16x8 x[K1];
+#pragma unroll
+    for (int kk = 0; kk < K1; ++kk) {
+      bf16x8 v;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = static_cast<__bf16>(0.f);
+      if (valid) v = *reinterpret_cast<const bf16x8*>(xrow + 16 * kk + 8 * g);
+      x[kk] = v;
+    }
+    // lane (row n, g), register 4j + r of block mb = column head DH + 32 mb + 8 j + 4 g + r, in both products
+    const int64_t out_row = (static_cast<int64_t>(b) * a.rows + min(row, a.rows - 1)) * D;
+    f32x16 acc[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[mb][i] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < K1; ++kk) acc[mb] = mfma32(wu[kk][mb], x[kk], acc[mb]);
+    }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int col = head * DH + 32 * mb + 8 * j + 4 * g;
+        bf16x4 att;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) att[r] = static_cast<__bf16>(0.f);
+        if (valid) att = *reinterpret_cast<const bf16x4*>(a.A + out_row + col);
+        bf16x4 z;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float p = acc[mb][4 * j + r];
+          z[r] = static_cast<__bf16>(static_cast<float>(att[r]) * p * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-p * kLog2e)));
+        }
+        *reinterpret_cast<bf16x4*>(zs + n * PITCH + col * 2) = z;
+      }
+    __syncthreads();
+    f32x16 acc2[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc2[mb][i] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < K1; ++kk)
+        acc2[mb] = mfma32(wo[kk][mb], *reinterpret_cast<const bf16x8*>(zs + n * PITCH + (16 * kk + 8 * g) * 2), acc2[mb]);
+    }
+    __syncthreads();  // the next tile's gated rows overwrite zs
+    if (row < a.rows) {
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int col = head * DH + 32 * mb + 8 * j + 4 * g;
+          const int64_t at = (static_cast<int64_t>(b) * a.rows + row) * D + col;
+          if (a.Y != nullptr) {
+            bf16x4 xr, y;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) xr[r] = static_cast<__bf16>(0.f);
+            if (valid) xr = *reinterpret_cast<const bf16x4*>(xrow + col);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) y[r] = static_cast<__bf16>(valid ? static_cast<float>(xr[r]) + acc2[mb][4 * j + r] : 0.f);
+            *reinterpret_cast<bf16x4*>(a.Y + at) = y;
+          }
+          if (a.sum_out != nullptr || a.sum_rounded != nullptr) {
+            f32x4 t = {0.f, 0.f, 0.f, 0.f};
+            if (a.sum_in != nullptr) t = *reinterpret_cast<const f32x4*>(a.sum_in + at);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) t[r] += acc2[mb][4 * j + r];
+            if (a.sum_out != nullptr) *reinterpret_cast<f32x4*>(a.sum_out + at) = t;
+            if (a.sum_rounded != nullptr) {
+              bf16x4 tr;
+#pragma unroll
+              for (int r = 0; r < 4; ++r) tr[r] = static_cast<__bf16>(t[r]);
+              *reinterpret_cast<bf16x4*>(a.sum_rounded + at) = tr;
+            }
           }
         }
     }
@@ -307,11 +393,9 @@ hipError_t run(const TargetAttention& q, void* workspace, hipStream_t s) {
   profile_begin(kKernelProjection, s);
   {
     ProjArgs p{static_cast<const bf16_t*>(q.T), nullptr, static_cast<const bf16x8*>(Wq), Qt, q.B, q.C, ctiles, ctiles * q.B};
-    p.x_user_stride = static_cast<int64_t>(q.C) * D;
     hipLaunchKernelGGL((project_rows_kernel<DH, H, kOutRows>), dim3(p.total_tiles < resident ? p.total_tiles : resident),
                        dim3(64 * H), 0, s, p);
     ProjArgs k{static_cast<const bf16_t*>(q.E), q.lens, static_cast<const bf16x8*>(Wk), Kimg, q.B, q.N, tiles, tiles * q.B};
-    k.x_user_stride = static_cast<int64_t>(q.N) * D;
     hipLaunchKernelGGL((project_rows_kernel<DH, H, kOutKeyImage>), dim3(k.total_tiles < resident ? k.total_tiles : resident),
                        dim3(64 * H), 0, s, k);
     k.Wimg = static_cast<const bf16x8*>(Wv), k.Y = Vimg;
@@ -332,34 +416,33 @@ hipError_t run(const TargetAttention& q, void* workspace, hipStream_t s) {
 }
 
 template <int DH, int H>
-hipError_t launch_rows(const ProjArgs& p, hipStream_t s) {
-  const int resident = 2 * compute_units();
-  hipLaunchKernelGGL((project_rows_kernel<DH, H, kOutRows>), dim3(p.total_tiles < resident ? p.total_tiles : resident),
-                     dim3(64 * H), 0, s, p);
+hipError_t launch_gated(const GatedArgs& p, hipStream_t s) {
+  const int resident = (DH * H <= 128 ? 2 : 1) * compute_units();
+  hipLaunchKernelGGL((gated_block_kernel<DH, H>), dim3(p.total_tiles < resident ? p.total_tiles : resident), dim3(64 * H), 0, s, p);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t project_rows(const RowsProjection& q, hipStream_t s) {
+hipError_t gated_block(const GatedBlock& q, hipStream_t s) {
   if (q.B <= 0 || q.rows <= 0) return hipSuccess;
   const int tiles = (q.rows + 31) / 32;
-  ProjArgs p{static_cast<const bf16_t*>(q.X), q.lens, static_cast<const bf16x8*>(q.W_image), static_cast<bf16_t*>(q.Y),
-             q.B, q.rows, tiles, tiles * q.B, q.epilogue, static_cast<const bf16_t*>(q.aux), q.sum_in, q.sum_out,
-             static_cast<bf16_t*>(q.sum_rounded), q.x_user_stride, q.aux_user_stride};
+  GatedArgs p{static_cast<const bf16_t*>(q.X), q.x_user_stride, q.lens, static_cast<const bf16x8*>(q.Wu_image),
+              static_cast<const bf16x8*>(q.Wo_image), static_cast<const bf16_t*>(q.A), static_cast<bf16_t*>(q.Y), q.sum_in,
+              q.sum_out, static_cast<bf16_t*>(q.sum_rounded), q.B, q.rows, tiles, tiles * q.B};
   const int dh = q.d / q.h;
   if (dh == 32) {
     switch (q.h) {
-      case 1: return launch_rows<32, 1>(p, s);
-      case 2: return launch_rows<32, 2>(p, s);
-      case 4: return launch_rows<32, 4>(p, s);
-      case 8: return launch_rows<32, 8>(p, s);
+      case 1: return launch_gated<32, 1>(p, s);
+      case 2: return launch_gated<32, 2>(p, s);
+      case 4: return launch_gated<32, 4>(p, s);
+      case 8: return launch_gated<32, 8>(p, s);
     }
   } else if (dh == 64) {
     switch (q.h) {
-      case 1: return launch_rows<64, 1>(p, s);
-      case 2: return launch_rows<64, 2>(p, s);
-      case 4: return launch_rows<64, 4>(p, s);
+      case 1: return launch_gated<64, 1>(p, s);
+      case 2: return launch_gated<64, 2>(p, s);
+      case 4: return launch_gated<64, 4>(p, s);
     }
   }
   return hipErrorInvalidValue;
