@@ -83,6 +83,25 @@ def test_config4_long_history_xora(N, gain):
                  "O")
 
 
+@pytest.mark.parametrize("N", [2048, 16384])
+@pytest.mark.parametrize("gain", ["bench", "sharp"])
+def test_config4_stacked_xor_layers(N, gain):
+    """8 users, d=128, h=4, m=64: three stacked XOR layers (Eq. 8) at the sizes bench.py --extras times; the gated
+    blocks' weights ~N(0, 1/d) like every other weight (the gate projection twice as large on sharp inputs)."""
+    w = _workload(4, gain, N=N)
+    g = DeviceWorkload(w)
+    scale = 1.0 if gain == "bench" else w.softmax_scale
+    r = np.random.default_rng(4077)
+    rnd = lambda x: torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).float().numpy()  # noqa: E731
+    Wu = rnd(r.standard_normal((3, w.d, w.d)) * w.d ** -0.5 * (2.0 if gain == "sharp" else 1.0))
+    Wo = rnd(r.standard_normal((3, w.d, w.d)) * w.d ** -0.5)
+    to_dev = lambda x: torch.from_numpy(x).to(torch.bfloat16).cuda()  # noqa: E731
+    LP = binding.lime_xor_layers(g.E, None, g.L, g.Wq, g.Wk, g.Wv, to_dev(Wu), to_dev(Wo), w.h, scale)
+    ref = orc.lime_xor_layers(w.E, None, w.L, w.Wq, w.Wk, w.Wv, Wu, Wo, w.h, scale)
+    err = assert_close(host(LP), ref, "bf16", "LP of three XOR layers", factor=2.0)
+    print(f"N={N} {gain}: max|ref| {np.abs(ref).max():.3e}, max-abs error {err:.3e}", flush=True)
+
+
 @pytest.mark.parametrize("gain", ["bench", "sharp"])
 def test_config5_lime_side(gain):
     """16 users, N=4096 ragged, C=8192, m=128, d=256: the LIME half of the speed-up comparison."""
