@@ -131,7 +131,13 @@ template <int DH, int H>
 __global__ __launch_bounds__(64 * H) void gated_block_kernel(GatedArgs a) {
   constexpr int D = DH * H, K1 = D / 16, MB = DH / 32;
   constexpr int PITCH = 2 * D + 16;  // bytes; the padding keeps the fragment reads free of bank conflicts
-  __shared__ __attribute__((aligned(16))) unsigned char zs[32 * PITCH];
+  constexpr int CPR = D / 8;         // 16-byte chunks per row
+  constexpr int LW = DH / 16;        // 1 KiB loads per wave and tile: the H waves copy a tile of 32 rows together
+  // Three tiles of 32 rows in LDS: the input rows X (fragments of the first product, then the residual), the
+  // attention rows A (the gate's other factor; later the staged output rows), the gated rows Z.  Rows travel
+  // between memory and LDS in whole 16-byte chunks, row-major and fully coalesced; the accumulator layout (a lane
+  // owns a row, four adjacent columns per register quad) only ever touches LDS.
+  __shared__ __attribute__((aligned(16))) unsigned char xs[32 * PITCH], as[32 * PITCH], zs[32 * PITCH];
   const int lane = threadIdx.x & 63, head = threadIdx.x >> 6;
   const int n = lane & 31, g = lane >> 5;
   bf16x8 wu[K1][MB], wo[K1][MB];
@@ -142,49 +148,65 @@ __global__ __launch_bounds__(64 * H) void gated_block_kernel(GatedArgs a) {
       wu[kk][mb] = a.Wu[((head * K1 + kk) * MB + mb) * 64 + lane];
       wo[kk][mb] = a.Wo[((head * K1 + kk) * MB + mb) * 64 + lane];
     }
-  for (int tile = blockIdx.x; tile < a.total_tiles; tile += gridDim.x) {
-    const int b = tile / a.tiles_per_user, ti = tile - b * a.tiles_per_user;
-    const int row = ti * 32 + n;
+  // this lane's chunks of a tile: (row, chunk) of piece j
+  int crow[LW], cchunk[LW];
+#pragma unroll
+  for (int j = 0; j < LW; ++j) {
+    const int q = (head * LW + j) * 64 + lane;
+    crow[j] = q / CPR, cchunk[j] = q % CPR;
+  }
+  bf16x8 rx[LW], ra[LW];
+  auto request = [&](int tile) {  // rows at or past the user's length arrive as zeros
+    const int b = tile / a.tiles_per_user, r0 = (tile - b * a.tiles_per_user) * 32;
     const int len = a.lens ? min(a.lens[b], a.rows) : a.rows;
-    const bool valid = row < len;
-    const bf16_t* xrow = a.X + b * a.x_user_stride + static_cast<int64_t>(min(row, a.rows - 1)) * D;
-    bf16x8 x[K1];
 #pragma unroll
-    for (int kk = 0; kk < K1; ++kk) {
-      bf16x8 v;
+    for (int j = 0; j < LW; ++j) {
+      bf16x8 vx, va;
 #pragma unroll
-      for (int t = 0; t < 8; ++t) v[t] = static_cast<__bf16>(0.f);
-      if (valid) v = *reinterpret_cast<const bf16x8*>(xrow + 16 * kk + 8 * g);
-      x[kk] = v;
+      for (int t = 0; t < 8; ++t) vx[t] = va[t] = static_cast<__bf16>(0.f);
+      const int row = r0 + crow[j];
+      if (row < len) {
+        vx = *reinterpret_cast<const bf16x8*>(a.X + b * a.x_user_stride + static_cast<int64_t>(row) * D + 8 * cchunk[j]);
+        va = *reinterpret_cast<const bf16x8*>(a.A + (static_cast<int64_t>(b) * a.rows + row) * D + 8 * cchunk[j]);
+      }
+      rx[j] = vx, ra[j] = va;
     }
-    // lane (row n, g), register 4j + r of block mb = column head DH + 32 mb + 8 j + 4 g + r, in both products
-    const int64_t out_row = (static_cast<int64_t>(b) * a.rows + min(row, a.rows - 1)) * D;
+  };
+  if (static_cast<int>(blockIdx.x) < a.total_tiles) request(blockIdx.x);
+  for (int tile = blockIdx.x; tile < a.total_tiles; tile += gridDim.x) {
+    const int b = tile / a.tiles_per_user, r0 = (tile - b * a.tiles_per_user) * 32;
+#pragma unroll
+    for (int j = 0; j < LW; ++j) {
+      *reinterpret_cast<bf16x8*>(xs + crow[j] * PITCH + cchunk[j] * 16) = rx[j];
+      *reinterpret_cast<bf16x8*>(as + crow[j] * PITCH + cchunk[j] * 16) = ra[j];
+    }
+    __syncthreads();
+    if (tile + static_cast<int>(gridDim.x) < a.total_tiles) request(tile + gridDim.x);  // in flight during this tile
+    // P^T = Wu^T X^T: lane (row n, g), register 4j + r of block mb = column head DH + 32 mb + 8 j + 4 g + r
     f32x16 acc[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mb][i] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < K1; ++kk) acc[mb] = mfma32(wu[kk][mb], x[kk], acc[mb]);
+      for (int kk = 0; kk < K1; ++kk)
+        acc[mb] = mfma32(wu[kk][mb], *reinterpret_cast<const bf16x8*>(xs + n * PITCH + (16 * kk + 8 * g) * 2), acc[mb]);
     }
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int col = head * DH + 32 * mb + 8 * j + 4 * g;
-        bf16x4 att;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) att[r] = static_cast<__bf16>(0.f);
-        if (valid) att = *reinterpret_cast<const bf16x4*>(a.A + out_row + col);
+        const int at = n * PITCH + (head * DH + 32 * mb + 8 * j + 4 * g) * 2;
+        const bf16x4 att = *reinterpret_cast<const bf16x4*>(as + at);
         bf16x4 z;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const float p = acc[mb][4 * j + r];
           z[r] = static_cast<__bf16>(static_cast<float>(att[r]) * p * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-p * kLog2e)));
         }
-        *reinterpret_cast<bf16x4*>(zs + n * PITCH + col * 2) = z;
+        *reinterpret_cast<bf16x4*>(zs + at) = z;
       }
-    __syncthreads();
+    __syncthreads();  // Z complete; nobody reads the attention rows any more
     f32x16 acc2[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
@@ -194,37 +216,43 @@ __global__ __launch_bounds__(64 * H) void gated_block_kernel(GatedArgs a) {
       for (int kk = 0; kk < K1; ++kk)
         acc2[mb] = mfma32(wo[kk][mb], *reinterpret_cast<const bf16x8*>(zs + n * PITCH + (16 * kk + 8 * g) * 2), acc2[mb]);
     }
-    __syncthreads();  // the next tile's gated rows overwrite zs
-    if (row < a.rows) {
+    const int row = r0 + n;
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int col = head * DH + 32 * mb + 8 * j + 4 * g;
+      for (int j = 0; j < 4; ++j) {
+        const int col = head * DH + 32 * mb + 8 * j + 4 * g;
+        if (a.Y != nullptr) {  // uniform: the output rows X + Y are staged where the attention rows were
+          const bf16x4 xr = *reinterpret_cast<const bf16x4*>(xs + n * PITCH + col * 2);
+          bf16x4 y;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) y[r] = static_cast<__bf16>(static_cast<float>(xr[r]) + acc2[mb][4 * j + r]);
+          *reinterpret_cast<bf16x4*>(as + n * PITCH + col * 2) = y;
+        }
+        if ((a.sum_out != nullptr || a.sum_rounded != nullptr) && row < a.rows) {
           const int64_t at = (static_cast<int64_t>(b) * a.rows + row) * D + col;
-          if (a.Y != nullptr) {
-            bf16x4 xr, y;
+          f32x4 t = {0.f, 0.f, 0.f, 0.f};
+          if (a.sum_in != nullptr) t = *reinterpret_cast<const f32x4*>(a.sum_in + at);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) xr[r] = static_cast<__bf16>(0.f);
-            if (valid) xr = *reinterpret_cast<const bf16x4*>(xrow + col);
+          for (int r = 0; r < 4; ++r) t[r] += acc2[mb][4 * j + r];
+          if (a.sum_out != nullptr) *reinterpret_cast<f32x4*>(a.sum_out + at) = t;
+          if (a.sum_rounded != nullptr) {
+            bf16x4 tr;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) y[r] = static_cast<__bf16>(valid ? static_cast<float>(xr[r]) + acc2[mb][4 * j + r] : 0.f);
-            *reinterpret_cast<bf16x4*>(a.Y + at) = y;
-          }
-          if (a.sum_out != nullptr || a.sum_rounded != nullptr) {
-            f32x4 t = {0.f, 0.f, 0.f, 0.f};
-            if (a.sum_in != nullptr) t = *reinterpret_cast<const f32x4*>(a.sum_in + at);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) t[r] += acc2[mb][4 * j + r];
-            if (a.sum_out != nullptr) *reinterpret_cast<f32x4*>(a.sum_out + at) = t;
-            if (a.sum_rounded != nullptr) {
-              bf16x4 tr;
-#pragma unroll
-              for (int r = 0; r < 4; ++r) tr[r] = static_cast<__bf16>(t[r]);
-              *reinterpret_cast<bf16x4*>(a.sum_rounded + at) = tr;
-            }
+            for (int r = 0; r < 4; ++r) tr[r] = static_cast<__bf16>(t[r]);
+            *reinterpret_cast<bf16x4*>(a.sum_rounded + at) = tr;
           }
         }
+      }
+    __syncthreads();  // output rows staged; X and Z no longer needed
+    if (a.Y != nullptr) {
+      // (a row at or past the user's length arrived as zeros and has a zero attention row: its output is zero)
+#pragma unroll
+      for (int j = 0; j < LW; ++j)
+        if (r0 + crow[j] < a.rows)
+          *reinterpret_cast<bf16x8*>(a.Y + (static_cast<int64_t>(b) * a.rows + r0 + crow[j]) * D + 8 * cchunk[j]) =
+              *reinterpret_cast<const bf16x8*>(as + crow[j] * PITCH + cchunk[j] * 16);
+      __syncthreads();  // before the next tile's rows are parked over the staged ones
     }
   }
 }
