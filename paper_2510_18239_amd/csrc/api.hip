@@ -107,10 +107,23 @@ XorLayersPlan plan_xor_layers(void* ws, int64_t B, int64_t N, int64_t d, int64_t
   return p;
 }
 
+// O[S] of XORA on the candidate-side kernel: every history row attends over the m links, SiLU / m.
+lime::QueriesOverLinks os_query(const void* E, const int32_t* lens, const void* LC, int64_t link_stride, const void* Wq,
+                                const void* Wk, const void* Wv, void* OS, int32_t B, int32_t N, int32_t d, int32_t h,
+                                int32_t m, float scale) {
+  lime::QueriesOverLinks q{};
+  q.X = E, q.O = OS, q.Wq = Wq, q.Ksrc = LC, q.Wk = Wk, q.Vsrc = LC, q.Wv = Wv;
+  q.k_user_stride = q.v_user_stride = link_stride, q.row_lens = lens;
+  q.B = B, q.rows = N, q.d = d, q.h = h, q.m = m, q.scale = scale, q.phi = lime::kPhiSilu;
+  return q;
+}
+
+// `extra`: weight images that the call's pack launch writes as well (matrix-core path only).
 int32_t history_impl(const char* fn, int phi, const void* E, const int32_t* lens, const void* LC,
                      int64_t lc_user_stride, const void* Wq, const void* Wk, const void* Wv, void* LP, void* OS,
                      int32_t B, int32_t N, int32_t d, int32_t h, int32_t m, float scale, int32_t dtype,
-                     void* workspace, size_t ws_bytes, void* stream) {
+                     void* workspace, size_t ws_bytes, void* stream, const lime::PackWeight* extra = nullptr,
+                     int n_extra = 0) {
   if (int32_t st = check_common(fn, B, d, h, dtype)) return st;
   if (N <= 0 || m <= 0) return fail(LIME_INVALID_ARG, "%s: N and m must be positive (N=%d m=%d)", fn, N, m);
   if (!E || !LC || !Wq || !Wk || !Wv || !LP) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
@@ -138,6 +151,14 @@ int32_t history_impl(const char* fn, int phi, const void* E, const int32_t* lens
     lime::LinksOverHistory q{};
     q.E = E, q.lens = lens, q.LC = LC, q.lc_user_stride = link_stride, q.Wq = Wq, q.Wk = Wk, q.Wv = Wv, q.LP = LP;
     q.B = B, q.N = N, q.d = d, q.h = h, q.m = m, q.scale = scale, q.phi = phi;
+    // one pack launch for everything this call needs on the matrix cores: the operands of both kernels and `extra`
+    lime::PackJobs jobs;
+    lime::links_over_history_jobs(q, workspace, jobs);
+    if (os_on_mfma) lime::queries_over_links_jobs(os_query(E, lens, LC, link_stride, Wq, Wk, Wv, OS, B, N, d, h, m, scale),
+                                                   static_cast<char*>(workspace) + p.bytes, jobs);
+    for (int i = 0; i < n_extra; ++i) jobs.weights[jobs.n_weights++] = extra[i];
+    LIME_HIP(lime::pack_operands(jobs.weights, jobs.n_weights, jobs.projections, jobs.n_projections, d, h, m, s));
+    q.packed = true;
     LIME_HIP(lime::links_over_history(q, workspace, s));
   } else {
     p = plan_history(nullptr, B, N, d, m, per_user, want_os && !os_on_mfma);
@@ -157,10 +178,8 @@ int32_t history_impl(const char* fn, int phi, const void* E, const int32_t* lens
     LIME_HIP(lime::generic_attention(t, s));
   }
   if (os_on_mfma) {
-    lime::QueriesOverLinks q{};
-    q.X = E, q.O = OS, q.Wq = Wq, q.Ksrc = LC, q.Wk = Wk, q.Vsrc = LC, q.Wv = Wv;
-    q.k_user_stride = q.v_user_stride = link_stride, q.row_lens = lens;
-    q.B = B, q.rows = N, q.d = d, q.h = h, q.m = m, q.scale = scale, q.phi = lime::kPhiSilu;
+    lime::QueriesOverLinks q = os_query(E, lens, LC, link_stride, Wq, Wk, Wv, OS, B, N, d, h, m, scale);
+    q.packed = true;
     LIME_HIP(lime::queries_over_links(q, static_cast<char*>(workspace) + p.bytes, s));
   } else if (want_os) {
     LIME_HIP(lime::generic_project(E, Wq, p.Qs, hist_rows, d, dtype, s));
@@ -455,11 +474,11 @@ int32_t lime_xor_layers(const void* E, const int32_t* lens, const void* LC, int6
     const void* Lj = first ? LC : p.Xt[j & 1];
     const int64_t lj_stride = first ? lc_user_stride : link_stride;
     // A = XORA(X_j) in block form (Eq. 7): O[T] for the link rows, O[S] for the history rows (not needed after the last layer)
-    if (int32_t st = history_impl(fn, lime::kPhiSilu, Ej, lens, Lj, lj_stride, Wq, Wk, Wv, p.OT, last ? nullptr : p.OS, B, N,
-                                  d, h, m, scale, dtype, p.hist_ws, p.hist_bytes, stream))
-      return st;
+    // (the layer's pack launch also writes the images of the gated block's two weights)
     lime::PackWeight images[2] = {{Wu_all + static_cast<int64_t>(j) * d * d, p.Wu_image}, {Wo_all + static_cast<int64_t>(j) * d * d, p.Wo_image}};
-    LIME_HIP(lime::pack_operands(images, 2, nullptr, 0, d, h, 32, s));
+    if (int32_t st = history_impl(fn, lime::kPhiSilu, Ej, lens, Lj, lj_stride, Wq, Wk, Wv, p.OT, last ? nullptr : p.OS, B, N,
+                                  d, h, m, scale, dtype, p.hist_ws, p.hist_bytes, stream, images, 2))
+      return st;
     // link rows: Y = (O[T] * SiLU(X Wu)) Wo joins the running sum (= L^P after the last layer) and the stream
     lime::GatedBlock links{};
     links.X = Lj, links.x_user_stride = lj_stride, links.Wu_image = p.Wu_image, links.Wo_image = p.Wo_image, links.A = p.OT;

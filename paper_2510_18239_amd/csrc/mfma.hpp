@@ -94,8 +94,16 @@ struct PackScore {
   void* image;
   float sign;        // +1 or -1
 };
+constexpr int kMaxPackWeights = 8, kMaxPackProjections = 3;  // jobs one launch takes
 hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackProject* projections, int n_projections,
                          int d, int h, int m, hipStream_t s, const PackScore* score = nullptr);
+// Jobs collected from several users of the pack kernel (same d, h, m), to be written by one launch.
+struct PackJobs {
+  PackWeight weights[kMaxPackWeights];
+  int n_weights = 0;
+  PackProject projections[kMaxPackProjections];
+  int n_projections = 0;
+};
 
 // ----------------------------------------------------------------------------- operands prepared once per model
 // What the two stages need of the model alone -- weights and shared links, not the user -- packed once into a
@@ -134,7 +142,10 @@ struct QueriesOverLinks {
   int phi;              // kPhiSoftmax, or kPhiSilu with normaliser m
   void* weights_out;    // when set: write the attention weights [B][rows][h][m] instead of O (Vsrc, Wv unused)
   const void* prepared; // when set: W_Q^T and K~ come from this prepared buffer (Wq, Ksrc, Wk unused; shared keys)
+  bool packed;          // when set: the operands have been packed into the workspace already (queries_over_links_jobs)
 };
+// The pack jobs of a call, appended to `jobs` instead of being launched by queries_over_links (not with `prepared`).
+void queries_over_links_jobs(const QueriesOverLinks& a, void* workspace, PackJobs& jobs);
 bool queries_over_links_supported(int d, int h, int m);
 bool fused_scores(int d, int h, int m, bool k_per_user);  // whether the kernel takes the score image G
 size_t queries_over_links_workspace(int B, int d, int m, bool k_per_user);
@@ -198,7 +209,9 @@ struct LinksOverHistory {
   float scale;
   int phi;              // kPhiSoftmax, or kPhiSilu with normaliser lens[b]
   const void* prepared; // when set: W_K^T, W_V and Q~ come from this prepared buffer (LC, Wq, Wk, Wv unused)
+  bool packed;          // when set: the operands have been packed into the workspace already (links_over_history_jobs)
 };
+void links_over_history_jobs(const LinksOverHistory& a, void* workspace, PackJobs& jobs);
 bool links_over_history_supported(int d, int h, int m);
 size_t links_over_history_workspace(int B, int N, int d, int h, int m, bool q_per_user);
 hipError_t links_over_history(const LinksOverHistory& a, void* workspace, hipStream_t s);

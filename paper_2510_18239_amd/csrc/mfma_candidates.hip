@@ -502,6 +502,20 @@ size_t queries_over_links_workspace(int B, int d, int m, bool k_per_user) {
   return wq + ka + va;
 }
 
+void queries_over_links_jobs(const QueriesOverLinks& q, void* workspace, PackJobs& jobs) {
+  const int d = q.d, m = q.m;
+  const bool k_per_user = q.k_user_stride != 0, v_per_user = q.v_user_stride != 0;
+  char* ws = static_cast<char*>(workspace);
+  char* KA = ws + align_up(static_cast<size_t>(d) * d * 2);
+  char* VA = KA + align_up(static_cast<size_t>(k_per_user ? q.B : 1) * m * d * 2);
+  jobs.weights[jobs.n_weights++] = PackWeight{q.Wq, ws};
+  // a negative logit scale is folded into the sign of the packed keys, so the kernel sees scale >= 0
+  jobs.projections[jobs.n_projections++] =
+      PackProject{q.Ksrc, q.Wk, KA, q.k_user_stride, k_per_user ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f};
+  if (!q.weights_out)
+    jobs.projections[jobs.n_projections++] = PackProject{q.Vsrc, q.Wv, VA, q.v_user_stride, v_per_user ? q.B : 1, kPackValues, 1.f};
+}
+
 hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStream_t s) {
   const int d = q.d, h = q.h, m = q.m, dh = d / h;
   const bool k_per_user = q.k_user_stride != 0, v_per_user = q.v_user_stride != 0;
@@ -513,18 +527,17 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
   // The score image G costs more to build than W_Q^T and K~ do to pack (measured: the request gets slower when
   // it is built per call), so it replaces them only where it is built once per model.
   const bool fused = q.prepared != nullptr && fused_scores(d, h, m, k_per_user);
-  PackWeight wjob{q.Wq, WqA};
-  // a negative logit scale is folded into the sign of the packed keys, so the kernel sees scale >= 0
-  PackProject pjobs[2] = {{q.Ksrc, q.Wk, KA, q.k_user_stride, k_per_user ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f},
-                          {q.Vsrc, q.Wv, VA, q.v_user_stride, v_per_user ? q.B : 1, kPackValues, 1.f}};
-  hipError_t e;
+  hipError_t e = hipSuccess;
   if (q.prepared != nullptr) {  // only the user's values are left to pack
     const PreparedLayout l = prepared_layout(d, m);
     WqA = reinterpret_cast<bf16_t*>(const_cast<char*>(static_cast<const char*>(q.prepared)) + l.wq);
     KA = reinterpret_cast<bf16_t*>(const_cast<char*>(static_cast<const char*>(q.prepared)) + l.ka);
-    e = pack_operands(nullptr, 0, pjobs + 1, 1, d, h, m, s);
-  } else {
-    e = pack_operands(&wjob, 1, pjobs, q.weights_out ? 1 : 2, d, h, m, s);
+    PackProject vjob{q.Vsrc, q.Wv, VA, q.v_user_stride, v_per_user ? q.B : 1, kPackValues, 1.f};
+    e = pack_operands(nullptr, 0, &vjob, q.weights_out ? 0 : 1, d, h, m, s);
+  } else if (!q.packed) {
+    PackJobs jobs;
+    queries_over_links_jobs(q, workspace, jobs);
+    e = pack_operands(jobs.weights, jobs.n_weights, jobs.projections, jobs.n_projections, d, h, m, s);
   }
   if (e != hipSuccess) return e;
 

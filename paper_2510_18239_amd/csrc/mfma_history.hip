@@ -470,6 +470,16 @@ size_t links_over_history_workspace(int B, int N, int d, int h, int m, bool q_pe
   return plan(B, N, d, h, m, q_per_user).total;
 }
 
+void links_over_history_jobs(const LinksOverHistory& q, void* workspace, PackJobs& jobs) {
+  const Layout l = plan(q.B, q.N, q.d, q.h, q.m, q.lc_user_stride != 0);
+  char* ws = static_cast<char*>(workspace);
+  jobs.weights[jobs.n_weights++] = PackWeight{q.Wk, ws};
+  jobs.weights[jobs.n_weights++] = PackWeight{q.Wv, ws + l.wk};
+  // a negative logit scale is folded into the sign of the packed queries, so the kernels see scale >= 0
+  jobs.projections[jobs.n_projections++] = PackProject{q.LC, q.Wq, ws + l.wk + l.wv, q.lc_user_stride,
+                                                       q.lc_user_stride != 0 ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f};
+}
+
 hipError_t links_over_history(const LinksOverHistory& q, void* workspace, hipStream_t s) {
   const int d = q.d, h = q.h, m = q.m, dh = d / h;
   const bool per_user = q.lc_user_stride != 0;
@@ -486,11 +496,10 @@ hipError_t links_over_history(const LinksOverHistory& q, void* workspace, hipStr
     const PreparedLayout pl = prepared_layout(d, m);
     char* base = const_cast<char*>(static_cast<const char*>(q.prepared));
     WkA = base + pl.wk, WvB = base + pl.wv, QB = base + pl.qb;
-  } else {
-    PackWeight wjobs[2] = {{q.Wk, WkA}, {q.Wv, WvB}};
-    // a negative logit scale is folded into the sign of the packed queries, so the kernels see scale >= 0
-    PackProject pjob{q.LC, q.Wq, QB, q.lc_user_stride, per_user ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f};
-    e = pack_operands(wjobs, 2, &pjob, 1, d, h, m, s);
+  } else if (!q.packed) {
+    PackJobs jobs;
+    links_over_history_jobs(q, workspace, jobs);
+    e = pack_operands(jobs.weights, jobs.n_weights, jobs.projections, jobs.n_projections, d, h, m, s);
     if (e != hipSuccess) return e;
   }
 

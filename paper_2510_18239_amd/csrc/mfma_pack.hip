@@ -7,12 +7,12 @@ namespace {
 
 constexpr int kPackRows = 4;   // rows of X per block of a projection job
 constexpr int kPackCols = 32;  // columns of W per block
-constexpr int kMaxJobs = 3;
+constexpr int kMaxJobs = kMaxPackProjections, kMaxWeights = kMaxPackWeights;
 
 struct PackArgs {
-  const bf16_t* w_src[kMaxJobs];
-  bf16x8* w_img[kMaxJobs];
-  float w_sign[kMaxJobs];
+  const bf16_t* w_src[kMaxWeights];
+  bf16x8* w_img[kMaxWeights];
+  float w_sign[kMaxWeights];
   const bf16_t* p_x[kMaxJobs];
   const bf16_t* p_w[kMaxJobs];
   bf16_t* p_img[kMaxJobs];
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
 
 hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackProject* projections, int n_projections,
                          int d, int h, int m, hipStream_t s, const PackScore* score) {
-  if (n_weights > kMaxJobs || n_projections > kMaxJobs) return hipErrorInvalidValue;
+  if (n_weights > kMaxWeights || n_projections > kMaxJobs) return hipErrorInvalidValue;
   PackArgs p{};
   p.d = d, p.dh = d / h, p.m = m;
   p.n_weights = n_weights;
