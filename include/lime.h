@@ -89,7 +89,6 @@ int32_t lime_xor_history(const void* E, const int32_t* lens, const void* LC, int
  * In: E, lens, LC, lc_user_stride, Wq, Wk, Wv as for lime_xor_history; Wu[n_layers][d][d], Wo[n_layers][d][d].
  * Out: LP[B][m][d] (zeros for a user without history).  Intermediate tensors live in the workspace
  * (LIME_OP_XOR_LAYERS) in the storage type; the link outputs are summed in fp32.
- * bf16 matrix-core shapes only (see Limits); anything else returns LIME_UNSUPPORTED.
  */
 int32_t lime_xor_layers(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride,
                         const void* Wq, const void* Wk, const void* Wv, const void* Wu, const void* Wo, int32_t n_layers,

@@ -81,8 +81,9 @@ HistoryPlan plan_history(void* ws, int64_t B, int64_t N, int64_t d, int64_t m, b
   return p;
 }
 
-// Workspace of lime_xor_layers: one XORA layer's own workspace, the two weight images of the current layer, and
-// the tensors that travel between the steps of a layer (bf16) plus the running sum of the link outputs (fp32).
+// Workspace of lime_xor_layers: one XORA layer's own workspace, the tensors that travel between the steps of a layer
+// (storage type) and the running sum of the link outputs (fp32); on the matrix cores also the two weight images of
+// the current layer, on the general kernels the scratch of the gated block.
 struct XorLayersPlan {
   void* hist_ws;
   size_t hist_bytes;
@@ -90,21 +91,42 @@ struct XorLayersPlan {
   void *Xs[2], *OS;        // history rows [B][N][d]: the residual stream (two copies, alternating) and O[S]
   void *Xt[2], *OT;        // link rows [B][m][d]: the same three
   float* sum;              // [B][m][d]
+  float* P;                // general kernels: [B][max(N, m)][d] fp32 ...
+  void* Z;                 // ... and the same in the storage type
   size_t bytes;
 };
 
-XorLayersPlan plan_xor_layers(void* ws, int64_t B, int64_t N, int64_t d, int64_t h, int64_t m) {
+XorLayersPlan plan_xor_layers(void* ws, int64_t B, int64_t N, int64_t d, int64_t h, int64_t m, int32_t dtype, bool on_mfma) {
   Arena a(ws);
   XorLayersPlan p{};
-  p.hist_bytes = lime::links_over_history_workspace(B, N, d, h, m, true) + lime::queries_over_links_workspace(B, d, m, true);
+  const size_t es = dtype == LIME_BF16 ? 2 : 4;
+  // (sized for whichever kernels the XORA step picks: with misaligned caller tensors the first layer runs on the
+  // general kernels and the later ones, whose inputs live in this workspace, on the matrix cores)
+  p.hist_bytes = plan_history(nullptr, B, N, d, m, true, true).bytes;
+  if (dtype == LIME_BF16 && lime::links_over_history_supported(d, h, m))
+    p.hist_bytes = std::max(p.hist_bytes, lime::links_over_history_workspace(B, N, d, h, m, true) +
+                                              lime::queries_over_links_workspace(B, d, m, true));
   p.hist_ws = a.take<char>(p.hist_bytes);
-  p.Wu_image = a.take<uint16_t>(d * d);
-  p.Wo_image = a.take<uint16_t>(d * d);
-  for (void** t : {&p.Xs[0], &p.Xs[1], &p.OS}) *t = a.take<uint16_t>(B * N * d);
-  for (void** t : {&p.Xt[0], &p.Xt[1], &p.OT}) *t = a.take<uint16_t>(B * m * d);
+  if (on_mfma) {
+    p.Wu_image = a.take<uint16_t>(d * d);
+    p.Wo_image = a.take<uint16_t>(d * d);
+  } else {
+    p.P = a.take<float>(B * std::max(N, m) * d);
+    p.Z = a.take<char>(B * std::max(N, m) * d * es);
+  }
+  for (void** t : {&p.Xs[0], &p.Xs[1], &p.OS}) *t = a.take<char>(B * N * d * es);
+  for (void** t : {&p.Xt[0], &p.Xt[1], &p.OT}) *t = a.take<char>(B * m * d * es);
   p.sum = a.take<float>(B * m * d);
   p.bytes = a.used;
   return p;
+}
+
+// large enough for either path (a bf16 call whose pointers are not 16-byte aligned runs on the general kernels)
+size_t xor_layers_workspace(int64_t B, int64_t N, int64_t d, int64_t h, int64_t m, int32_t dtype) {
+  size_t need = plan_xor_layers(nullptr, B, N, d, h, m, dtype, false).bytes;
+  if (dtype == LIME_BF16 && lime::links_over_history_supported(d, h, m))
+    need = std::max(need, plan_xor_layers(nullptr, B, N, d, h, m, dtype, true).bytes);
+  return need;
 }
 
 // O[S] of XORA on the candidate-side kernel: every history row attends over the m links, SiLU / m.
@@ -457,16 +479,19 @@ int32_t lime_xor_layers(const void* E, const int32_t* lens, const void* LC, int6
   if (!E || !LC || !Wq || !Wk || !Wv || !Wu || !Wo || !LP) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
   if (lc_user_stride != 0 && lc_user_stride != static_cast<int64_t>(m) * d)
     return fail(LIME_INVALID_ARG, "%s: lc_user_stride must be 0 or m*d (got %lld)", fn, static_cast<long long>(lc_user_stride));
-  if (dtype != LIME_BF16 || !lime::links_over_history_supported(d, h, m) || !fits_tiles(B, N) ||
-      !all_aligned16(E, LC, Wq, Wk, Wv, Wu, Wo, LP, workspace))
-    return fail(LIME_UNSUPPORTED, "%s: bf16 matrix-core shapes and 16-byte aligned pointers only", fn);
-  const XorLayersPlan need = plan_xor_layers(nullptr, B, N, d, h, m);
-  if (!workspace || ws_bytes < need.bytes)
-    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need.bytes, workspace ? ws_bytes : 0);
-  const XorLayersPlan p = plan_xor_layers(workspace, B, N, d, h, m);
+  // the same condition under which history_impl runs both XORA kernels on the matrix cores (the workspace pieces
+  // handed to it below are 256-byte aligned)
+  const bool on_mfma = dtype == LIME_BF16 && lime::links_over_history_supported(d, h, m) && fits_tiles(B, N) &&
+                       all_aligned16(E, LC, Wq, Wk, Wv, Wu, Wo, LP, workspace);
+  const size_t need = xor_layers_workspace(B, N, d, h, m, dtype);
+  if (!workspace || ws_bytes < need)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? ws_bytes : 0);
+  const XorLayersPlan p = plan_xor_layers(workspace, B, N, d, h, m, dtype, on_mfma);
+  const size_t es = dtype == LIME_BF16 ? 2 : 4;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int64_t hist_stride = static_cast<int64_t>(N) * d, link_stride = static_cast<int64_t>(m) * d;
-  const lime::bf16_t *Wu_all = static_cast<const lime::bf16_t*>(Wu), *Wo_all = static_cast<const lime::bf16_t*>(Wo);
+  const char *Wu_all = static_cast<const char*>(Wu), *Wo_all = static_cast<const char*>(Wo);
+  const size_t weight_bytes = static_cast<size_t>(d) * d * es;
   for (int j = 0; j < n_layers; ++j) {
     const bool first = j == 0, last = j + 1 == n_layers;
     // the layer's inputs: the caller's tensors for the first layer, the residual stream afterwards
@@ -475,10 +500,25 @@ int32_t lime_xor_layers(const void* E, const int32_t* lens, const void* LC, int6
     const int64_t lj_stride = first ? lc_user_stride : link_stride;
     // A = XORA(X_j) in block form (Eq. 7): O[T] for the link rows, O[S] for the history rows (not needed after the last layer)
     // (the layer's pack launch also writes the images of the gated block's two weights)
-    lime::PackWeight images[2] = {{Wu_all + static_cast<int64_t>(j) * d * d, p.Wu_image}, {Wo_all + static_cast<int64_t>(j) * d * d, p.Wo_image}};
+    const void *Wu_j = Wu_all + j * weight_bytes, *Wo_j = Wo_all + j * weight_bytes;
+    lime::PackWeight images[2] = {{Wu_j, p.Wu_image}, {Wo_j, p.Wo_image}};
     if (int32_t st = history_impl(fn, lime::kPhiSilu, Ej, lens, Lj, lj_stride, Wq, Wk, Wv, p.OT, last ? nullptr : p.OS, B, N,
-                                  d, h, m, scale, dtype, p.hist_ws, p.hist_bytes, stream, images, 2))
+                                  d, h, m, scale, dtype, p.hist_ws, p.hist_bytes, stream, images, on_mfma ? 2 : 0))
       return st;
+    if (!on_mfma) {
+      lime::GenericGatedBlock links{};
+      links.X = Lj, links.x_user_stride = lj_stride, links.Wu = Wu_j, links.Wo = Wo_j, links.A = p.OT;
+      links.Y = last ? nullptr : p.Xt[(j + 1) & 1];
+      links.sum_in = first ? nullptr : p.sum, links.sum_out = last ? nullptr : p.sum, links.sum_rounded = last ? LP : nullptr;
+      links.P = p.P, links.Z = p.Z, links.B = B, links.rows = m, links.d = d, links.dtype = dtype;
+      LIME_HIP(lime::generic_gated_block(links, s));
+      if (last) break;
+      lime::GenericGatedBlock rows{};
+      rows.X = Ej, rows.x_user_stride = hist_stride, rows.lens = lens, rows.Wu = Wu_j, rows.Wo = Wo_j, rows.A = p.OS;
+      rows.Y = p.Xs[(j + 1) & 1], rows.P = p.P, rows.Z = p.Z, rows.B = B, rows.rows = N, rows.d = d, rows.dtype = dtype;
+      LIME_HIP(lime::generic_gated_block(rows, s));
+      continue;
+    }
     // link rows: Y = (O[T] * SiLU(X Wu)) Wo joins the running sum (= L^P after the last layer) and the stream
     lime::GatedBlock links{};
     links.X = Lj, links.x_user_stride = lj_stride, links.Wu_image = p.Wu_image, links.Wo_image = p.Wo_image, links.A = p.OT;
@@ -514,8 +554,8 @@ size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t
       return need;
     }
     case LIME_OP_XOR_LAYERS:
-      if (N <= 0 || m <= 0 || dtype != LIME_BF16 || !lime::links_over_history_supported(d, h, m)) return 0;
-      return plan_xor_layers(nullptr, B, N, d, h, m).bytes;
+      if (N <= 0 || m <= 0) return 0;
+      return xor_layers_workspace(B, N, d, h, m, dtype);
     case LIME_OP_SCORE_CANDIDATES:
       if (C <= 0 || m <= 0) return 0;
       return std::max(plan_queries(nullptr, static_cast<int64_t>(B) * C, m, static_cast<int64_t>(B) * m, d).bytes,

@@ -64,4 +64,23 @@ hipError_t generic_qk_weights(const float* Q, const float* K, void* W, int64_t r
 hipError_t generic_cached_sum(const void* W, const int32_t* ids, int n_items, const float* V, void* O, int B, int C,
                               int d, int h, int m, int dtype, hipStream_t s);
 
+// The gated block of an XOR layer (Eq. 8) for any shape and storage type, as two projections with an element-wise
+// step after each: Z = A * SiLU(X Wu); Y = X + Z Wo (rows >= lens[b] are zeros); the running sum of the layers'
+// outputs as in the matrix-core version.  P (fp32) and Z (storage type) are scratch of B * rows * d elements.
+struct GenericGatedBlock {
+  const void* X;          // [.][rows][d]
+  int64_t x_user_stride;  // elements between users; 0 = one block for all users
+  const int32_t* lens;    // nullable
+  const void *Wu, *Wo;    // [d][d]
+  const void* A;          // [B][rows][d]
+  void* Y;                // [B][rows][d], nullable
+  const float* sum_in;    // nullable = zero
+  float* sum_out;         // nullable
+  void* sum_rounded;      // storage type, nullable
+  float* P;
+  void* Z;
+  int B, rows, d, dtype;
+};
+hipError_t generic_gated_block(const GenericGatedBlock& g, hipStream_t s);
+
 }  // namespace lime

@@ -309,6 +309,69 @@ hipError_t generic_project(const void* X, const void* W, float* Y, int64_t rows,
   return hipGetLastError();
 }
 
+namespace {
+
+// Z = A * SiLU(P), P = X Wu in fp32 (one block of rows for all users when p_user_stride == 0)
+template <typename T>
+__global__ __launch_bounds__(256) void gate_kernel(const float* __restrict__ P, int64_t p_user_stride, const T* __restrict__ A,
+                                                   const int32_t* __restrict__ lens, T* __restrict__ Z, int rows, int d,
+                                                   int64_t total) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int64_t per_user = static_cast<int64_t>(rows) * d;
+  const int b = static_cast<int>(i / per_user);
+  const int64_t rem = i - b * per_user;
+  const int row = static_cast<int>(rem / d);
+  const bool valid = row < (lens ? min(lens[b], rows) : rows);
+  const float p = P[b * p_user_stride + rem];
+  store_as(Z + i, valid ? to_float(A[i]) * p / (1.f + expf(-p)) : 0.f);
+}
+
+// Y = X + P, P = Z Wo in fp32; the running sum of P over the layers
+template <typename T>
+__global__ __launch_bounds__(256) void residual_kernel(const float* __restrict__ P, const T* __restrict__ X, int64_t x_user_stride,
+                                                       const int32_t* __restrict__ lens, T* __restrict__ Y,
+                                                       const float* __restrict__ sum_in, float* __restrict__ sum_out,
+                                                       T* __restrict__ sum_rounded, int rows, int d, int64_t total) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int64_t per_user = static_cast<int64_t>(rows) * d;
+  const int b = static_cast<int>(i / per_user);
+  const int64_t rem = i - b * per_user;
+  const int row = static_cast<int>(rem / d);
+  const bool valid = row < (lens ? min(lens[b], rows) : rows);
+  const float p = P[i];
+  if (Y != nullptr) store_as(Y + i, valid ? to_float(X[b * x_user_stride + rem]) + p : 0.f);
+  if (sum_out != nullptr || sum_rounded != nullptr) {
+    const float t = (sum_in != nullptr ? sum_in[i] : 0.f) + p;
+    if (sum_out != nullptr) sum_out[i] = t;
+    if (sum_rounded != nullptr) store_as(sum_rounded + i, t);
+  }
+}
+
+template <typename T>
+hipError_t gated_block_typed(const GenericGatedBlock& g, hipStream_t s) {
+  const int64_t total = static_cast<int64_t>(g.B) * g.rows * g.d;
+  const dim3 grid(static_cast<unsigned>((total + 255) / 256));
+  const bool shared = g.x_user_stride == 0;
+  hipError_t e = generic_project(g.X, g.Wu, g.P, shared ? g.rows : static_cast<int64_t>(g.B) * g.rows, g.d, g.dtype, s);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(gate_kernel<T>, grid, dim3(256), 0, s, g.P, shared ? int64_t{0} : static_cast<int64_t>(g.rows) * g.d,
+                     static_cast<const T*>(g.A), g.lens, static_cast<T*>(g.Z), g.rows, g.d, total);
+  e = generic_project(g.Z, g.Wo, g.P, static_cast<int64_t>(g.B) * g.rows, g.d, g.dtype, s);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(residual_kernel<T>, grid, dim3(256), 0, s, g.P, static_cast<const T*>(g.X), g.x_user_stride, g.lens,
+                     static_cast<T*>(g.Y), g.sum_in, g.sum_out, static_cast<T*>(g.sum_rounded), g.rows, g.d, total);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t generic_gated_block(const GenericGatedBlock& g, hipStream_t s) {
+  if (g.B <= 0 || g.rows <= 0) return hipSuccess;
+  return g.dtype == 0 ? gated_block_typed<float>(g, s) : gated_block_typed<bf16_t>(g, s);
+}
+
 hipError_t generic_attention(const GenericAttention& a, hipStream_t s) {
   if (a.B <= 0 || a.q_rows <= 0) return hipSuccess;
   AttnDev dev{a.Q, a.K, a.V, a.q_user_stride, a.k_user_stride, a.v_user_stride, a.O, a.q_lens, a.k_lens,

@@ -180,8 +180,9 @@ def test_xor_layers_argument_checks():
     assert call(Wu=None) == 1 and call(Wo=None) == 1 and call(LP=None) == 1 and call(E=None) == 1
     assert call(n=0) == 1 and call(N=0) == 1 and call(m=0) == 1
     assert call(stride=5) == 1
-    assert call(dtype=0) == 2 and "bf16" in binding.last_error()      # fp32 storage: no path
-    assert call(d=120, h=3) == 2                                        # d/h = 40: outside the matrix-core set
-    assert call(E=FAKE + 2) == 2                                        # misaligned pointer
-    assert binding.workspace_bytes(binding.OP_XOR_LAYERS, B=2, N=64, d=128, h=4, m=64, dtype=0) == 0
-    assert binding.workspace_bytes(binding.OP_XOR_LAYERS, B=2, N=64, d=120, h=3, m=64) == 0
+    assert call(dtype=7) == 1 and call(d=120, h=7) == 1
+    assert call(d=1024, h=2) == 2                                      # d/h = 512 exceeds the largest head
+    # fp32 storage and shapes outside the matrix-core set run on the general kernels: they have a workspace size too
+    assert binding.workspace_bytes(binding.OP_XOR_LAYERS, B=2, N=64, d=128, h=4, m=64, dtype=0) > need
+    assert binding.workspace_bytes(binding.OP_XOR_LAYERS, B=2, N=64, d=120, h=3, m=20) > 0
+    assert call(dtype=0, ws_bytes=need) == 3

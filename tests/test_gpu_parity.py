@@ -452,6 +452,30 @@ def _layer_weights(seed, n, d, gain=1.0):
     return rnd(Wu), rnd(Wo)
 
 
+@pytest.mark.parametrize("dtype,B,N,d,h,m,n_layers,per_user", [
+    ("fp32", 2, 150, 64, 2, 24, 3, False),   # fp32 storage: the 1e-4 bar (chained: 2e-4)
+    ("fp32", 3, 70, 128, 4, 64, 2, True),
+    ("bf16", 2, 90, 96, 3, 20, 3, False),    # bf16 outside the matrix-core set: general kernels
+])
+def test_xor_layers_on_general_kernels(dtype, B, N, d, h, m, n_layers, per_user):
+    w = _sharp(workload=450 + d + m, B=B, N=N, C=8, d=d, h=h, m=m, dtype=dtype, len_range=(1, N), pad_value=np.nan)
+    w.lens[B - 1] = 0
+    w.E[B - 1] = np.nan
+    Wu, Wo = _layer_weights(99 + d, n_layers, d, gain=1.0)
+    if dtype == "fp32":  # fp32 storage takes the weights unrounded as well
+        r = np.random.default_rng(99 + d)
+        Wu = (r.standard_normal((n_layers, d, d)) * d ** -0.5).astype(np.float32)
+        Wo = (r.standard_normal((n_layers, d, d)) * d ** -0.5 * 0.5).astype(np.float32)
+    LC = np.stack([np.roll(w.L, b + 1, axis=0) for b in range(B)]) if per_user else w.L
+    g = DeviceWorkload(w)
+    xs = _xor_scale(w)
+    LP = binding.lime_xor_layers(g.E, g.lens, dev(LC, dtype), g.Wq, g.Wk, g.Wv, dev(Wu, dtype), dev(Wo, dtype), h, xs)
+    ref = orc.lime_xor_layers(w.E, w.lens, LC, w.Wq, w.Wk, w.Wv, Wu, Wo, h, xs)
+    err = assert_close(host(LP), ref, dtype, "LP of stacked XOR layers", factor=2.0)
+    print(f"{dtype}: max|ref| = {np.abs(ref).max():.3e}, max-abs error {err:.3e}", flush=True)
+    assert not host(LP)[B - 1].any()
+
+
 @pytest.mark.parametrize("B,N,d,h,m,n_layers,per_user", [
     (3, 333, 128, 4, 64, 3, False),      # configuration-4 shape, several tiles and a ragged tail
     (2, 257, 256, 4, 128, 3, False),
