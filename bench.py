@@ -44,6 +44,9 @@ def parse_args():
     p.add_argument("--graphs", action="store_true", help="replay one captured HIP graph per request instead of launching its five kernels from the host")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--extras", action="store_true", help="also time the XORA history pass, the C sweep and the MHA baseline")
+    p.add_argument("--xor-layers", type=int, default=0, metavar="N",
+                   help="only run lime_xor_layers (three layers, configuration 4) at history length N, --steps times: "
+                        "the command behind the kernel-trace summary of that call")
     return p.parse_args()
 
 
@@ -61,6 +64,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+
+    if args.xor_layers > 0:
+        xor_layers_only(args, binding, synth, torch, dev)
+        return
 
     cfg = dict(synth.CONFIGS[3])
     cfg["C"], cfg["N"] = args.candidates, args.history
@@ -339,6 +346,30 @@ def cpu_baseline(w, scale):
         best = min(best, time.perf_counter() - t0)
     return {"value": w.B * w.C / best, "unit": "candidates/s", "cores": int(threads), "kind": "oracle",
             "sample": f"the full request (history N={w.N} + all C={w.C} candidates), numpy fp64, best of 3, {best:.3f} s"}
+
+
+def xor_layers_only(args, binding, synth, torch, dev):
+    """lime_xor_layers alone (configuration 4: B = 8, d = 128, h = 4, m = 64; three layers, Eq. 8), for profiling."""
+    c4 = dict(synth.CONFIGS[4])
+    c4["N"] = args.xor_layers
+    w = synth.make_workload(4, **c4)
+    t = lambda x: torch.from_numpy(x).to(torch.bfloat16).to(dev)  # noqa: E731
+    E, L, Wq, Wk, Wv = t(w.E), t(w.L), t(w.Wq), t(w.Wk), t(w.Wv)
+    g = torch.Generator(device="cpu").manual_seed(20251018 + 4000 + 77)
+    Wu = (torch.randn((3, w.d, w.d), generator=g) * w.d ** -0.5).to(torch.bfloat16).to(dev)
+    Wo = (torch.randn((3, w.d, w.d), generator=g) * w.d ** -0.5).to(torch.bfloat16).to(dev)
+    for _ in range(args.warmup):
+        binding.lime_xor_layers(E, None, L, Wq, Wk, Wv, Wu, Wo, w.h, 1.0)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for a, b in evs:
+        a.record()
+        binding.lime_xor_layers(E, None, L, Wq, Wk, Wv, Wu, Wo, w.h, 1.0)
+        b.record()
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in evs)
+    print(json.dumps({"call": "lime_xor_layers", "layers": 3, "B": w.B, "N": w.N, "d": w.d, "h": w.h, "m": w.m,
+                      "steps": args.steps, "p50_ms": ms[len(ms) // 2], "p10_ms": ms[len(ms) // 10]}))
 
 
 def extras(binding, synth, torch, dev, timed, pct):
