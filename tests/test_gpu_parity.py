@@ -209,29 +209,33 @@ def test_hip_graph_replay_matches_eager():
     LP = torch.empty((2, 64, 256), dtype=torch.bfloat16, device="cuda")
     O = torch.empty_like(g.T)
     XT = torch.empty_like(LP)
+    XL = torch.empty_like(LP)
+    Wu, Wo = (dev(x, "bf16") for x in _layer_weights(5, 2, 256))
     ws = torch.empty(max(binding.workspace_bytes(binding.OP_XOR_HISTORY, B=2, N=300, d=256, h=4, m=64),
-                         binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=2, C=400, d=256, h=4, m=64)),
+                         binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=2, C=400, d=256, h=4, m=64),
+                         binding.workspace_bytes(binding.OP_XOR_LAYERS, B=2, N=300, d=256, h=4, m=64)),
                      dtype=torch.uint8, device="cuda")
 
     def request():
         binding.lime_link_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, 4, s, LP=LP, workspace=ws)
         binding.lime_score_candidates(g.T, g.L, LP, g.Wq, g.Wk, g.Wv, 4, s, O=O, workspace=ws)
         binding.lime_xor_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, 4, s, LP=XT, workspace=ws)
+        binding.lime_xor_layers(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, Wu, Wo, 4, s, LP=XL, workspace=ws)
 
     request()
     torch.cuda.synchronize()
-    want = [t.clone() for t in (LP, O, XT)]
+    want = [t.clone() for t in (LP, O, XT, XL)]
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         request()
     for _ in range(4):
-        for t in (LP, O, XT):
+        for t in (LP, O, XT, XL):
             t.fill_(7.0)
         ws.random_(0, 255)  # the workspace carries nothing from one call to the next
         (torch.randn(1000, device="cuda") * 2).sum().item()  # unrelated eager work and a synchronisation
         graph.replay()
         torch.cuda.synchronize()
-        for got, ref in zip((LP, O, XT), want):
+        for got, ref in zip((LP, O, XT, XL), want):
             assert torch.equal(got, ref)
 
 
