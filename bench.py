@@ -555,6 +555,28 @@ def extras(binding, synth, torch, dev, timed, pct):
     lat_mha = timed(lambda i: binding.mha_target_attention(T5, E5, lens5, q5, k5, v5, w5.h, s5), 5)
     res["config5_ms"] = {"lime_request_p50": pct(lat_lime, 0.5), "mha_target_attention_p50": pct(lat_mha, 0.5),
                          "speedup": pct(lat_mha, 0.5) / pct(lat_lime, 0.5)}
+    del E5, T5
+    # The three models of the paper's latency figure (Fig. 1, Appendix F) at the headline shape, one user, 32 768
+    # candidates, one request at a time: LIME-MHA (Eq. 3 + Eq. 4), LIME-XOR (three XOR layers, Eq. 8, + Eq. 4) and
+    # full target attention (Eq. 1).  The paper's own figures are from unstated hardware: context, not a target.
+    g3 = torch.Generator(device="cpu").manual_seed(20251018 + 3000 + 77)
+    Wu3 = (torch.randn((3, w.d, w.d), generator=g3) * w.d ** -0.5).to(torch.bfloat16).to(dev)
+    Wo3 = (torch.randn((3, w.d, w.d), generator=g3) * w.d ** -0.5).to(torch.bfloat16).to(dev)
+    O3 = torch.empty_like(T)
+
+    def lime_mha(i):
+        lp = binding.lime_link_history(E, None, L, Wq, Wk, Wv, w.h, w.softmax_scale)
+        binding.lime_score_candidates(T, L, lp, Wq, Wk, Wv, w.h, w.softmax_scale, O=O3)
+
+    def lime_xor(i):
+        lp = binding.lime_xor_layers(E, None, L, Wq, Wk, Wv, Wu3, Wo3, w.h, 1.0)
+        binding.lime_score_candidates(T, L, lp, Wq, Wk, Wv, w.h, w.softmax_scale, O=O3)
+
+    res["one_user_32768_candidates_p50_ms"] = {
+        "lime_mha": pct(timed(lime_mha, 100), 0.5), "lime_xor_3_layers": pct(timed(lime_xor, 100), 0.5),
+        "mha_target_attention": pct(timed(lambda i: binding.mha_target_attention(T, E, None, Wq, Wk, Wv, w.h, w.softmax_scale,
+                                                                                 O=O3), 20), 0.5),
+        "paper_fig1_ms_unstated_hardware": {"lime_mha": 1.16, "lime_xor": 2.15, "mha": 9.53}}
     return res
 
 
