@@ -556,6 +556,20 @@ def extras(binding, synth, torch, dev, timed, pct):
     res["config5_ms"] = {"lime_request_p50": pct(lat_lime, 0.5), "mha_target_attention_p50": pct(lat_mha, 0.5),
                          "speedup": pct(lat_mha, 0.5) / pct(lat_lime, 0.5)}
     del E5, T5
+    # the batched block of configs[1]: 32 users, ragged histories of 512..1024 items, d = 128, 1024 candidates each
+    c2 = dict(synth.CONFIGS[2])
+    c2["pad_value"] = 0.0
+    w2 = synth.make_workload(2, **c2)
+    E2, L2, q2, k2, v2, T2 = t(w2.E), t(w2.L), t(w2.Wq), t(w2.Wk), t(w2.Wv), t(w2.T)
+    lens2 = torch.from_numpy(w2.lens).to(dev)
+
+    def batched(i):
+        lp = binding.lime_link_history(E2, lens2, L2, q2, k2, v2, w2.h, w2.softmax_scale)
+        binding.lime_score_candidates(T2, L2, lp, q2, k2, v2, w2.h, w2.softmax_scale)
+
+    lat2 = pct(timed(batched, 100), 0.5)
+    res["config2_batched_request"] = {"p50_ms": lat2, "candidates_per_s": w2.B * w2.C / (lat2 * 1e-3)}
+    del E2, T2
     # The three models of the paper's latency figure (Fig. 1, Appendix F) at the headline shape, one user, 32 768
     # candidates, one request at a time: LIME-MHA (Eq. 3 + Eq. 4), LIME-XOR (three XOR layers, Eq. 8, + Eq. 4) and
     # full target attention (Eq. 1).  The paper's own figures are from unstated hardware: context, not a target.
