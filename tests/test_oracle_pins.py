@@ -628,7 +628,42 @@ def _mut_gate_after_output(A, X, Wu, Wo):
     return orc.project(orc._f64(A), Wo) * orc.silu(orc.project(orc._f64(X), Wu))
 
 
+def _make_layers_mutant(kind):
+    def mutant(E, lens, LC, Wq, Wk, Wv, Wu, Wo, h, scale=1.0):
+        E = orc._f64(E)
+        B, N, d = E.shape
+        lens_ = orc._lens(lens, B, N)
+        m = orc._links_of_user(LC, 0).shape[0]
+        LP = np.zeros((B, m, d))
+        for b in range(B):
+            n_s = int(lens_[b])
+            if n_s == 0:
+                continue
+            Xs, Xt = E[b, :n_s], orc._f64(orc._links_of_user(LC, b))
+            for j in range(len(Wu)):
+                OT = orc.mha(Xt, Xs, Xs, None, Wq, Wk, Wv, h, scale, "silu", denom=np.full(m, n_s))
+                OS = orc.mha(Xs, Xt, Xt, None, Wq, Wk, Wv, h, scale, "silu", denom=np.full(n_s, m))
+                Yt, Ys = orc.gated_mlp(OT, Xt, Wu[j], Wo[j]), orc.gated_mlp(OS, Xs, Wu[j], Wo[j])
+                if kind == "last_layer_only":
+                    LP[b] = Yt
+                else:
+                    LP[b] += Yt
+                if kind == "no_residual":
+                    Xs, Xt = Ys, Yt
+                elif kind == "links_not_updated":
+                    Xs = Xs + Ys
+                else:
+                    Xs, Xt = Xs + Ys, Xt + Yt
+        return LP
+
+    mutant.__name__ = f"layers_{kind}"
+    return mutant
+
+
 MUTATIONS = [
+    ("lime_xor_layers", _make_layers_mutant("no_residual")),
+    ("lime_xor_layers", _make_layers_mutant("last_layer_only")),
+    ("lime_xor_layers", _make_layers_mutant("links_not_updated")),
     ("gated_mlp", _mut_gate_without_silu),
     ("gated_mlp", _mut_gate_from_attention),
     ("gated_mlp", _mut_gate_after_output),
