@@ -178,7 +178,7 @@ bool target_attention_supported(int d, int h);
 size_t target_attention_workspace(int B, int C, int N, int d);
 hipError_t target_attention(const TargetAttention& a, void* workspace, hipStream_t s);
 
-// ----------------------------------------------------------------------------- gated block of an XOR layer (mfma_target.hip)
+// ----------------------------------------------------------------------------- gated block of an XOR layer (mfma_layers.hip)
 // The gated block of an XOR layer in one kernel: Y = X + (A * SiLU(X Wu)) Wo per row (rows >= lens[b] are zeros), and
 // optionally sum_out / sum_rounded = sum_in + (A * SiLU(X Wu)) Wo (the running sum of the layers' link outputs).
 struct GatedBlock {
