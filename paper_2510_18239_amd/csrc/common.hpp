@@ -31,6 +31,9 @@ constexpr int kPhiSilu = 1;
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+// Compute units of the current device (256 when the query fails): what the launchers size their grids by.
+int compute_units();
+
 // ----------------------------------------------------------------------------- per-kernel timing (profile.hip)
 enum ProfiledKernel { kKernelQueriesOverLinks = 0, kKernelLinksOverHistory = 1, kKernelTargetAttention = 2,
                       kKernelProjection = 3, kKernelCachedCandidates = 4 };

@@ -95,17 +95,6 @@ __global__ __launch_bounds__(64 * H) void cached_candidates_kernel(CachedArgs a)
   }
 }
 
-int compute_units() {
-  static const int n = [] {
-    int dev = 0, cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0)
-      cu = 256;
-    return cu;
-  }();
-  return n;
-}
-
 template <int DH, int M, int H>
 void launch(const CachedArgs& a, int grid, hipStream_t s) {
   if (a.ids != nullptr)

@@ -428,17 +428,6 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   }
 }
 
-int compute_units() {
-  static const int n = [] {
-    int dev = 0, cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0)
-      cu = 256;
-    return cu;
-  }();
-  return n;
-}
-
 template <int DH, int M, int H, bool FUSED>
 hipError_t launch_form(const MainArgs& m, int phi, int grid, hipStream_t s) {
   if (m.Wout != nullptr)

@@ -366,17 +366,6 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
   store_as(a.LP + (static_cast<int64_t>(b) * a.m + link) * d + col, out);
 }
 
-int compute_units() {
-  static const int n = [] {
-    int dev = 0, cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0)
-      cu = 256;
-    return cu;
-  }();
-  return n;
-}
-
 template <int DH, int M, int H, int PHI>
 hipError_t launch_phi(const HistArgs& a, int users, bool coop, hipStream_t s) {
   constexpr bool kWkLds = DH * H >= 256;

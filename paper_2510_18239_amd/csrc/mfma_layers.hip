@@ -156,17 +156,6 @@ __global__ __launch_bounds__(64 * H) void gated_block_kernel(GatedArgs a) {
   }
 }
 
-int compute_units() {
-  static const int n = [] {
-    int dev = 0, cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0)
-      cu = 256;
-    return cu;
-  }();
-  return n;
-}
-
 template <int DH, int H>
 hipError_t launch_gated(const GatedArgs& p, hipStream_t s) {
   const int resident = (DH * H <= 128 ? 2 : 1) * compute_units();

@@ -234,17 +234,6 @@ __global__ __launch_bounds__(256) void target_attention_kernel(AttnArgs a) {
   }
 }
 
-int compute_units() {
-  static const int n = [] {
-    int dev = 0, cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0)
-      cu = 256;
-    return cu;
-  }();
-  return n;
-}
-
 template <int DH, int H>
 hipError_t run(const TargetAttention& q, void* workspace, hipStream_t s) {
   constexpr int D = DH * H;
