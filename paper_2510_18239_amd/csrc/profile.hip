@@ -4,6 +4,7 @@
 #include "../../include/lime.h"
 #include "common.hpp"
 
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -14,7 +15,7 @@ struct Span {
   hipEvent_t start, stop;
 };
 std::mutex g_mu;
-bool g_on = false;
+std::atomic<bool> g_on{false};  // read without the lock on every launch
 std::vector<Span> g_spans;
 std::vector<hipEvent_t> g_pool;
 
@@ -31,8 +32,8 @@ hipEvent_t take_event() {
 }  // namespace
 
 void profile_begin(int kernel, hipStream_t s) {
+  if (!g_on.load(std::memory_order_relaxed)) return;
   std::lock_guard<std::mutex> lock(g_mu);
-  if (!g_on) return;
   Span sp{kernel, take_event(), take_event()};
   if (!sp.start || !sp.stop) return;
   (void)hipEventRecord(sp.start, s);
@@ -40,8 +41,9 @@ void profile_begin(int kernel, hipStream_t s) {
 }
 
 void profile_end(int kernel, hipStream_t s) {
+  if (!g_on.load(std::memory_order_relaxed)) return;
   std::lock_guard<std::mutex> lock(g_mu);
-  if (!g_on || g_spans.empty() || g_spans.back().kernel != kernel) return;
+  if (g_spans.empty() || g_spans.back().kernel != kernel) return;
   (void)hipEventRecord(g_spans.back().stop, s);
 }
 }  // namespace lime
