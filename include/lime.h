@@ -51,7 +51,7 @@ extern "C" {
 enum { LIME_OK = 0, LIME_INVALID_ARG = 1, LIME_UNSUPPORTED = 2, LIME_WORKSPACE_TOO_SMALL = 3, LIME_LAUNCH_FAILED = 4 };
 enum { LIME_F32 = 0, LIME_BF16 = 1 };
 enum { LIME_OP_LINK_HISTORY = 0, LIME_OP_XOR_HISTORY = 1, LIME_OP_SCORE_CANDIDATES = 2, LIME_OP_MHA_TARGET = 3,
-       LIME_OP_BUILD_QK_CACHE = 4, LIME_OP_SCORE_CACHED = 5, LIME_OP_XOR_LAYERS = 6 };
+       LIME_OP_BUILD_QK_CACHE = 4, LIME_OP_SCORE_CACHED = 5, LIME_OP_XOR_LAYERS = 6, LIME_OP_REQUEST_PREPARED = 7 };
 
 /*
  * User-side link personalisation, Section 3.1 Eq. 3:
@@ -172,6 +172,19 @@ int32_t lime_link_history_prepared(const void* E, const int32_t* lens, const voi
 int32_t lime_score_candidates_prepared(const void* T, const void* LP, const void* Wv, const void* prepared, void* O,
                                        int32_t B, int32_t C, int32_t d, int32_t h, int32_t m, float scale,
                                        int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * One request on prepared operands in one call: lime_link_history_prepared followed by lime_score_candidates_prepared
+ * (same arguments, same meaning; LP[B][m][d] and O[B][C][d] are both written), as three kernels instead of four: the
+ * step that finishes the link states also projects them with the candidate stage's Wv (NULL = identity) into the
+ * layout the candidate kernel loads, so the candidate stage packs nothing.  LP is bit-identical to
+ * lime_link_history_prepared; O agrees with the two-call form within the bf16 tolerance (the value projection sums
+ * in another order).  Workspace: LIME_OP_REQUEST_PREPARED.  Same limits as the other prepared entry points.
+ */
+int32_t lime_request_prepared(const void* E, const int32_t* lens, const void* T, const void* Wv, const void* prepared,
+                              void* LP, void* O, int32_t B, int32_t N, int32_t C, int32_t d, int32_t h, int32_t m,
+                              float scale_hist, float scale_cand, int32_t xor_attention, int32_t dtype,
+                              void* workspace, size_t ws_bytes, void* stream);
 
 /*
  * Workspace size in bytes for `op` (LIME_OP_*) at the given shape; dimensions an op

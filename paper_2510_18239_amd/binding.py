@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "liblime_hip.so")
 
 LIME_F32, LIME_BF16 = 0, 1
 (OP_LINK_HISTORY, OP_XOR_HISTORY, OP_SCORE_CANDIDATES, OP_MHA_TARGET, OP_BUILD_QK_CACHE, OP_SCORE_CACHED,
- OP_XOR_LAYERS) = range(7)
+ OP_XOR_LAYERS, OP_REQUEST_PREPARED) = range(8)
 STATUS_NAMES = {0: "LIME_OK", 1: "LIME_INVALID_ARG", 2: "LIME_UNSUPPORTED", 3: "LIME_WORKSPACE_TOO_SMALL",
                 4: "LIME_LAUNCH_FAILED"}
 
@@ -45,6 +45,8 @@ SIGNATURES = {
                                           _vp]),
     "lime_score_candidates_prepared": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32, _i32, _vp,
                                               _sz, _vp]),
+    "lime_request_prepared": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _f32, _f32,
+                                     _i32, _i32, _vp, _sz, _vp]),
     "lime_score_candidates_gathered": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _sz,
                                               _vp]),
     "lime_workspace_bytes": (_sz, [_i32] * 9),
@@ -361,3 +363,25 @@ def lime_score_candidates_prepared(T, LP, Wv, prepared, h, scale, O=None, worksp
                                                   float(scale), code, _ptr(ws), ws.numel(), _stream(stream))
     _raise(st)
     return O
+
+
+def lime_request_prepared(E, lens, T, Wv, prepared, h, m, scale_hist, scale_cand, xor_attention=False, LP=None, O=None,
+                          workspace=None, stream=None):
+    """lime_link_history_prepared + lime_score_candidates_prepared as one call of three kernels; returns (LP, O)."""
+    first = _check(E, T, Wv, LP, O)
+    B, N, d = E.shape
+    C = T.shape[1]
+    code = _dtype_code(first)
+    lens = _lens_arg(lens, B, E.device)
+    if LP is None:
+        LP = torch.empty((B, m, d), dtype=E.dtype, device=E.device)
+    if O is None:
+        O = torch.empty_like(T)
+    need = workspace_bytes(OP_REQUEST_PREPARED, B=B, N=N, C=C, d=d, h=h, m=m, dtype=code)
+    ws = workspace if workspace is not None else get_workspace(need, E.device)
+    with torch.cuda.device(E.device):
+        st = lib().lime_request_prepared(_ptr(E), _ptr(lens), _ptr(T), _ptr(Wv), _ptr(prepared), _ptr(LP), _ptr(O), B, N, C,
+                                         d, h, m, float(scale_hist), float(scale_cand), int(bool(xor_attention)), code,
+                                         _ptr(ws), ws.numel(), _stream(stream))
+    _raise(st)
+    return LP, O

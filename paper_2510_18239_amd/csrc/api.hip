@@ -468,6 +468,41 @@ int32_t lime_score_candidates_prepared(const void* T, const void* LP, const void
   return LIME_OK;
 }
 
+int32_t lime_request_prepared(const void* E, const int32_t* lens, const void* T, const void* Wv, const void* prepared,
+                              void* LP, void* O, int32_t B, int32_t N, int32_t C, int32_t d, int32_t h, int32_t m,
+                              float scale_hist, float scale_cand, int32_t xor_attention, int32_t dtype, void* workspace,
+                              size_t ws_bytes, void* stream) {
+  const char* fn = "lime_request_prepared";
+  if (int32_t st = check_common(fn, B, d, h, dtype)) return st;
+  if (N <= 0 || C <= 0 || m <= 0)
+    return fail(LIME_INVALID_ARG, "%s: N, C and m must be positive (N=%d C=%d m=%d)", fn, N, C, m);
+  if (!E || !T || !prepared || !LP || !O) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  if (lime_prepared_bytes(d, h, m, dtype) == 0 || !all_aligned16(E, T, Wv, prepared, LP, O, workspace) || !fits_tiles(B, N) ||
+      !fits_tiles(B, C))
+    return fail(LIME_UNSUPPORTED, "%s: prepared operands exist for the bf16 matrix-core shapes and 16-byte aligned pointers only", fn);
+  const size_t hist_bytes = lime::links_over_history_workspace(B, N, d, h, m, false);
+  const size_t need = hist_bytes + lime::queries_over_links_workspace(B, d, m, false);
+  if (!workspace || ws_bytes < need)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? ws_bytes : 0);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  void* cand_ws = static_cast<char*>(workspace) + hist_bytes;
+  lime::QueriesOverLinks c{};
+  c.X = T, c.O = O, c.Vsrc = LP, c.Wv = Wv, c.prepared = prepared;
+  c.k_user_stride = 0, c.v_user_stride = static_cast<int64_t>(m) * d, c.row_lens = nullptr;
+  c.B = B, c.rows = C, c.d = d, c.h = h, c.m = m, c.scale = scale_cand, c.phi = lime::kPhiSoftmax;
+  lime::LinksOverHistory q{};
+  q.E = E, q.lens = lens, q.LP = LP, q.prepared = prepared;
+  q.B = B, q.N = N, q.d = d, q.h = h, q.m = m, q.scale = scale_hist;
+  q.phi = xor_attention ? lime::kPhiSilu : lime::kPhiSoftmax;
+  // three kernels: the merge step of the history side also projects the finished link states and writes the value
+  // image where the candidate-side kernel of this request expects it
+  q.Wv_values = Wv, q.values_image = lime::queries_over_links_values(c, cand_ws);
+  c.packed = true;
+  LIME_HIP(lime::links_over_history(q, workspace, s));
+  LIME_HIP(lime::queries_over_links(c, cand_ws, s));
+  return LIME_OK;
+}
+
 int32_t lime_xor_layers(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride, const void* Wq,
                         const void* Wk, const void* Wv, const void* Wu, const void* Wo, int32_t n_layers, void* LP,
                         int32_t B, int32_t N, int32_t d, int32_t h, int32_t m, float scale, int32_t dtype,
@@ -553,6 +588,9 @@ size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t
                                   (os ? lime::queries_over_links_workspace(B, d, m, true) : size_t{0}));
       return need;
     }
+    case LIME_OP_REQUEST_PREPARED:
+      if (N <= 0 || C <= 0 || m <= 0 || lime_prepared_bytes(d, h, m, dtype) == 0) return 0;
+      return lime::links_over_history_workspace(B, N, d, h, m, false) + lime::queries_over_links_workspace(B, d, m, false);
     case LIME_OP_XOR_LAYERS:
       if (N <= 0 || m <= 0) return 0;
       return xor_layers_workspace(B, N, d, h, m, dtype);

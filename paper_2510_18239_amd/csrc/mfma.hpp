@@ -66,6 +66,19 @@ __host__ __device__ constexpr int out_rho(int col) { return 8 * ((col >> 2) & 3)
 //                   = (X_u W)[32lb + n][a dh + 16kk + chain_k(g, t)]   (rows kept, head columns summed in chained order)
 //   kPackValues   [U][h][m/16][dh/32][64]: fragment (u, a, kk, ob), lane (rho, g), slot t
 //                   = (X_u W)[16kk + chain_k(g, t)][a dh + 32ob + out_col(rho)]   (rows summed in chained order)
+// Where element (row, col) of a projected [m][d] matrix goes in its fragment image (bf16 units).
+__device__ __forceinline__ int64_t keys_slot(int u, int row, int col, int d, int dh, int m) {
+  const int a = col / dh, c = col % dh, kk = c / 16, kin = c % 16;
+  const int64_t frag = ((static_cast<int64_t>(u) * (d / dh) + a) * (dh / 16) + kk) * (m / 32) + row / 32;
+  return (frag * 64 + 32 * chain_g(kin) + row % 32) * 8 + chain_t(kin);
+}
+__device__ __forceinline__ int64_t values_slot(int u, int row, int col, int d, int dh, int m, bool chained) {
+  const int a = col / dh, c = col % dh, kk = row / 16, kin = row % 16;
+  const int64_t frag = ((static_cast<int64_t>(u) * (d / dh) + a) * (m / 16) + kk) * (dh / 32) + c / 32;
+  const int g = chained ? chain_g(kin) : kin / 8, t = chained ? chain_t(kin) : kin % 8;
+  return (frag * 64 + 32 * g + out_rho(c % 32)) * 8 + t;
+}
+
 struct PackWeight {
   const void* W;   // [d][d] bf16, or nullptr for the identity
   void* image;
@@ -142,8 +155,11 @@ struct QueriesOverLinks {
   int phi;              // kPhiSoftmax, or kPhiSilu with normaliser m
   void* weights_out;    // when set: write the attention weights [B][rows][h][m] instead of O (Vsrc, Wv unused)
   const void* prepared; // when set: W_Q^T and K~ come from this prepared buffer (Wq, Ksrc, Wk unused; shared keys)
-  bool packed;          // when set: the operands have been packed into the workspace already (queries_over_links_jobs)
+  bool packed;          // when set: the operands have been packed into the workspace already (queries_over_links_jobs;
+                        // with `prepared`: the value image, by the history side's merge step)
 };
+// where the value image of a call lives in its workspace
+void* queries_over_links_values(const QueriesOverLinks& a, void* workspace);
 // The pack jobs of a call, appended to `jobs` instead of being launched by queries_over_links (not with `prepared`).
 void queries_over_links_jobs(const QueriesOverLinks& a, void* workspace, PackJobs& jobs);
 bool queries_over_links_supported(int d, int h, int m);
@@ -210,6 +226,10 @@ struct LinksOverHistory {
   int phi;              // kPhiSoftmax, or kPhiSilu with normaliser lens[b]
   const void* prepared; // when set: W_K^T, W_V and Q~ come from this prepared buffer (LC, Wq, Wk, Wv unused)
   bool packed;          // when set: the operands have been packed into the workspace already (links_over_history_jobs)
+  // when values_image is set, the merge step also projects the link states it has just finished, V~ = LP Wv_values
+  // (Wv_values [d][d] bf16, nullable = identity), and writes them as the kPackValues image of a candidate-side call
+  const void* Wv_values;
+  void* values_image;
 };
 void links_over_history_jobs(const LinksOverHistory& a, void* workspace, PackJobs& jobs);
 bool links_over_history_supported(int d, int h, int m);

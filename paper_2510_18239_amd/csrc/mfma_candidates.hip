@@ -491,6 +491,12 @@ size_t queries_over_links_workspace(int B, int d, int m, bool k_per_user) {
   return wq + ka + va;
 }
 
+void* queries_over_links_values(const QueriesOverLinks& q, void* workspace) {
+  char* ws = static_cast<char*>(workspace);
+  return ws + align_up(static_cast<size_t>(q.d) * q.d * 2) +
+         align_up(static_cast<size_t>(q.k_user_stride != 0 ? q.B : 1) * q.m * q.d * 2);
+}
+
 void queries_over_links_jobs(const QueriesOverLinks& q, void* workspace, PackJobs& jobs) {
   const int d = q.d, m = q.m;
   const bool k_per_user = q.k_user_stride != 0, v_per_user = q.v_user_stride != 0;
@@ -522,7 +528,7 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
     WqA = reinterpret_cast<bf16_t*>(const_cast<char*>(static_cast<const char*>(q.prepared)) + l.wq);
     KA = reinterpret_cast<bf16_t*>(const_cast<char*>(static_cast<const char*>(q.prepared)) + l.ka);
     PackProject vjob{q.Vsrc, q.Wv, VA, q.v_user_stride, v_per_user ? q.B : 1, kPackValues, 1.f};
-    e = pack_operands(nullptr, 0, &vjob, q.weights_out ? 0 : 1, d, h, m, s);
+    if (!q.packed) e = pack_operands(nullptr, 0, &vjob, q.weights_out ? 0 : 1, d, h, m, s);
   } else if (!q.packed) {
     PackJobs jobs;
     queries_over_links_jobs(q, workspace, jobs);

@@ -307,17 +307,13 @@ struct MergeArgs {
   float scale;  // |logit scale|: the factor the SiLU partials still lack
 };
 
-// One thread per output element LP[b][link][a dh + t]; chunks are combined in ascending order.
+// The merged values LP[b][link][a dh + t .. t + 3] of a user's chunks, combined in ascending order (t is a multiple
+// of four: one 16-byte load per chunk serves four outputs, and the load path of a compute unit, not the arithmetic,
+// is what this step keeps busy).
 template <int PHI>
-__global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
-  const int b = blockIdx.y;
-  const int idx = blockIdx.x * 256 + threadIdx.x;
-  const int d = a.h * a.dh;
-  if (idx >= a.m * d) return;
-  const int link = idx / d, col = idx % d, head = col / a.dh, t = col % a.dh;
-  const int len = a.lens ? min(a.lens[b], a.N) : a.N;
+__device__ __forceinline__ float4 merged_values(const MergeArgs& a, int b, int link, int head, int t, int len) {
   const int used = (len + a.chunk_items - 1) / a.chunk_items;  // chunks that hold at least one valid item
-  float out = 0.f;
+  float4 out = make_float4(0.f, 0.f, 0.f, 0.f);
   if (used > 0) {
     const int64_t stride = static_cast<int64_t>(a.h) * a.m;  // (head, link) slots per chunk
     const int64_t first = (static_cast<int64_t>(b) * a.chunks * a.h + head) * a.m + link;
@@ -325,45 +321,154 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
     // other compute units and every access is a long-latency miss
     constexpr int kBatch = 16;
     if (PHI == kPhiSoftmax) {
-      float gmax = -INFINITY, num = 0.f, den = 0.f;
+      float gmax = -INFINITY, den = 0.f;
+      float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
       for (int c0 = 0; c0 < used; c0 += kBatch) {
-        float mx[kBatch], sm[kBatch], ac[kBatch];
+        float2 ml[kBatch];  // (scaled maximum, sum)
+        float4 ac[kBatch];
 #pragma unroll
         for (int i = 0; i < kBatch; ++i) {
           const int64_t s = first + static_cast<int64_t>(min(c0 + i, used - 1)) * stride;
-          mx[i] = a.part_ml[s * 2];
-          sm[i] = a.part_ml[s * 2 + 1];
-          ac[i] = a.part_acc[s * a.dh + t];
+          ml[i] = *reinterpret_cast<const float2*>(a.part_ml + s * 2);
+          ac[i] = *reinterpret_cast<const float4*>(a.part_acc + s * a.dh + t);
         }
         float bmax = gmax;
 #pragma unroll
-        for (int i = 0; i < kBatch; ++i) bmax = fmaxf(bmax, mx[i]);
+        for (int i = 0; i < kBatch; ++i) bmax = fmaxf(bmax, ml[i].x);
         const float keep = __builtin_amdgcn_exp2f((gmax - bmax) * kLog2e);  // 0 on the first batch
-        num *= keep;
+        num.x *= keep, num.y *= keep, num.z *= keep, num.w *= keep;
         den *= keep;
         gmax = bmax;
 #pragma unroll
         for (int i = 0; i < kBatch; ++i) {
-          const float w = c0 + i < used ? __builtin_amdgcn_exp2f((mx[i] - gmax) * kLog2e) : 0.f;
-          num = fmaf(w, ac[i], num);
-          den = fmaf(w, sm[i], den);
+          const float w = c0 + i < used ? __builtin_amdgcn_exp2f((ml[i].x - gmax) * kLog2e) : 0.f;
+          num.x = fmaf(w, ac[i].x, num.x), num.y = fmaf(w, ac[i].y, num.y);
+          num.z = fmaf(w, ac[i].z, num.z), num.w = fmaf(w, ac[i].w, num.w);
+          den = fmaf(w, ml[i].y, den);
         }
       }
-      out = num / den;
+      out = make_float4(num.x / den, num.y / den, num.z / den, num.w / den);
     } else {
-      float num = 0.f;
+      float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
       for (int c0 = 0; c0 < used; c0 += kBatch) {
-        float ac[kBatch];
+        float4 ac[kBatch];
 #pragma unroll
         for (int i = 0; i < kBatch; ++i)
-          ac[i] = a.part_acc[(first + static_cast<int64_t>(min(c0 + i, used - 1)) * stride) * a.dh + t];
+          ac[i] = *reinterpret_cast<const float4*>(
+              a.part_acc + (first + static_cast<int64_t>(min(c0 + i, used - 1)) * stride) * a.dh + t);
 #pragma unroll
-        for (int i = 0; i < kBatch; ++i) num += c0 + i < used ? ac[i] : 0.f;
+        for (int i = 0; i < kBatch; ++i)
+          if (c0 + i < used) num.x += ac[i].x, num.y += ac[i].y, num.z += ac[i].z, num.w += ac[i].w;
       }
-      out = num * a.scale / static_cast<float>(len);
+      const float f = a.scale / static_cast<float>(len);
+      out = make_float4(num.x * f, num.y * f, num.z * f, num.w * f);
     }
   }
-  store_as(a.LP + (static_cast<int64_t>(b) * a.m + link) * d + col, out);
+  return out;
+}
+
+// Four rounded link-state values as one 8-byte store.
+__device__ __forceinline__ void store_rounded(bf16_t* dst, const float4& v, float* rounded = nullptr) {
+  alignas(8) bf16_t r[4];
+  store_as(&r[0], v.x), store_as(&r[1], v.y), store_as(&r[2], v.z), store_as(&r[3], v.w);
+  *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<const uint2*>(r);
+  if (rounded != nullptr)
+    *reinterpret_cast<float4*>(rounded) = make_float4(to_float(r[0]), to_float(r[1]), to_float(r[2]), to_float(r[3]));
+}
+
+// One thread per four adjacent output elements LP[b][link][a dh + t .. t + 3], one wave per workgroup: the
+// workgroups spread over as many compute units as there are.
+constexpr int kMergeThreads = 64;
+template <int PHI>
+__global__ __launch_bounds__(kMergeThreads) void merge_kernel(MergeArgs a) {
+  const int b = blockIdx.y;
+  const int idx = (blockIdx.x * kMergeThreads + threadIdx.x) * 4;
+  const int d = a.h * a.dh;
+  if (idx >= a.m * d) return;
+  const int link = idx / d, col = idx % d, head = col / a.dh, t = col % a.dh;
+  const int len = a.lens ? min(a.lens[b], a.N) : a.N;
+  store_rounded(a.LP + (static_cast<int64_t>(b) * a.m + link) * d + col, merged_values<PHI>(a, b, link, head, t, len));
+}
+
+// Merge and the candidate stage's value projection in one kernel: a block finishes kMvRows link states of one user
+// (four adjacent elements per thread, as the merge kernel does), stores them, and projects their bf16-rounded values onto Wv:
+// V~ = LP Wv, written as the value image (kPackValues) that the candidate-side kernel loads.  Same split of the sum
+// over d as the pack kernel's projections: thread (cg, kc) owns 8 adjacent columns and every nkc-th k; the partial
+// sums meet in LDS.  Every partial state is read once, as in the merge kernel: those reads miss the local L2
+// (other compute units wrote them) and set the kernel's time.
+constexpr int kMvRows = 2, kMvThreads = 512, kMvMaxD = 256;
+constexpr int kMvMaxK = kMvMaxD * (kMvMaxD / 8) / kMvThreads;  // k-steps per thread at the largest d
+struct MergeValuesArgs {
+  MergeArgs m;
+  const bf16_t* Wv;  // [d][d], nullable = identity
+  bf16_t* VA;        // [B] value images
+};
+
+constexpr size_t merge_values_lds(int d) {
+  // rounded link states + output rows + one partial output per k-group
+  return (static_cast<size_t>(2 * kMvRows) * d + static_cast<size_t>(kMvThreads / (d / 8)) * kMvRows * d) * sizeof(float);
+}
+
+template <int PHI>
+__global__ __launch_bounds__(kMvThreads) void merge_values_kernel(MergeValuesArgs a) {
+  extern __shared__ float mv_smem[];
+  const int d = a.m.h * a.m.dh, tid = threadIdx.x;
+  const int row0 = blockIdx.x * kMvRows, b = blockIdx.y;
+  const int CG = d / 8, nkc = kMvThreads / CG;
+  const int cg = tid % CG, kc = tid / CG;
+  float* lp = mv_smem;            // [kMvRows][d], bf16-rounded values
+  float* out = lp + kMvRows * d;  // [kMvRows][d]
+  float* red = out + kMvRows * d; // [nkc][kMvRows][d]
+  bf16x8 wreg[kMvMaxK];
+  if (a.Wv != nullptr) {  // asked for before the merge, used after it
+#pragma unroll
+    for (int it = 0; it < kMvMaxK; ++it) {
+      const int k = kc + it * nkc;
+      if (k < d) wreg[it] = *reinterpret_cast<const bf16x8*>(a.Wv + static_cast<int64_t>(k) * d + 8 * cg);
+    }
+  }
+  const int len = a.m.lens ? min(a.m.lens[b], a.m.N) : a.m.N;
+  for (int i = 4 * tid; i < kMvRows * d; i += 4 * kMvThreads) {
+    const int link = row0 + i / d, col = i % d;
+    store_rounded(a.m.LP + (static_cast<int64_t>(b) * a.m.m + link) * d + col,
+                  merged_values<PHI>(a.m, b, link, col / a.m.dh, col % a.m.dh, len), lp + i);
+  }
+  __syncthreads();
+  if (a.Wv == nullptr) {
+    for (int i = tid; i < kMvRows * d; i += kMvThreads) out[i] = lp[i];
+  } else {
+    float acc[kMvRows][8];
+#pragma unroll
+    for (int r = 0; r < kMvRows; ++r)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[r][j] = 0.f;
+#pragma unroll
+    for (int it = 0; it < kMvMaxK; ++it) {
+      const int k = kc + it * nkc;
+      if (k < d) {
+#pragma unroll
+        for (int r = 0; r < kMvRows; ++r) {
+          const float x = lp[r * d + k];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) acc[r][j] = fmaf(x, static_cast<float>(wreg[it][j]), acc[r][j]);
+        }
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < kMvRows; ++r)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) red[(kc * kMvRows + r) * d + 8 * cg + j] = acc[r][j];
+    __syncthreads();
+    for (int i = tid; i < kMvRows * d; i += kMvThreads) {
+      float sum = 0.f;
+#pragma unroll 8
+      for (int c = 0; c < nkc; ++c) sum += red[c * kMvRows * d + i];
+      out[i] = sum;
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < kMvRows * d; i += kMvThreads)
+    store_as(a.VA + values_slot(b, row0 + i / d, i % d, d, a.m.dh, a.m.m, true), out[i]);
 }
 
 template <int DH, int M, int H, int PHI>
@@ -505,11 +610,21 @@ hipError_t links_over_history(const LinksOverHistory& q, void* workspace, hipStr
   if (e != hipSuccess) return e;
 
   MergeArgs g{part_acc, part_ml, q.lens, static_cast<bf16_t*>(q.LP), q.N, l.chunk_items, l.chunks, h, m, dh, fabsf(q.scale)};
-  const dim3 mgrid((m * d + 255) / 256, q.B);
+  if (q.values_image != nullptr) {
+    MergeValuesArgs mv{g, static_cast<const bf16_t*>(q.Wv_values), static_cast<bf16_t*>(q.values_image)};
+    const dim3 vgrid(m / kMvRows, q.B);
+    const size_t lds = merge_values_lds(d);
+    if (q.phi == kPhiSoftmax)
+      hipLaunchKernelGGL(merge_values_kernel<kPhiSoftmax>, vgrid, dim3(kMvThreads), lds, s, mv);
+    else
+      hipLaunchKernelGGL(merge_values_kernel<kPhiSilu>, vgrid, dim3(kMvThreads), lds, s, mv);
+    return hipGetLastError();
+  }
+  const dim3 mgrid((m * d / 4 + kMergeThreads - 1) / kMergeThreads, q.B);
   if (q.phi == kPhiSoftmax)
-    hipLaunchKernelGGL(merge_kernel<kPhiSoftmax>, mgrid, dim3(256), 0, s, g);
+    hipLaunchKernelGGL(merge_kernel<kPhiSoftmax>, mgrid, dim3(kMergeThreads), 0, s, g);
   else
-    hipLaunchKernelGGL(merge_kernel<kPhiSilu>, mgrid, dim3(256), 0, s, g);
+    hipLaunchKernelGGL(merge_kernel<kPhiSilu>, mgrid, dim3(kMergeThreads), 0, s, g);
   return hipGetLastError();
 }
 

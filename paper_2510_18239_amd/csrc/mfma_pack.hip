@@ -27,19 +27,6 @@ struct PackArgs {
   int d, dh, m;
 };
 
-// Where element (row, col) of a projected [m][d] matrix goes in its fragment image (bf16 units).
-__device__ __forceinline__ int64_t keys_slot(int u, int row, int col, int d, int dh, int m) {
-  const int a = col / dh, c = col % dh, kk = c / 16, kin = c % 16;
-  const int64_t frag = ((static_cast<int64_t>(u) * (d / dh) + a) * (dh / 16) + kk) * (m / 32) + row / 32;
-  return (frag * 64 + 32 * chain_g(kin) + row % 32) * 8 + chain_t(kin);
-}
-__device__ __forceinline__ int64_t values_slot(int u, int row, int col, int d, int dh, int m, bool chained) {
-  const int a = col / dh, c = col % dh, kk = row / 16, kin = row % 16;
-  const int64_t frag = ((static_cast<int64_t>(u) * (d / dh) + a) * (m / 16) + kk) * (dh / 32) + c / 32;
-  const int g = chained ? chain_g(kin) : kin / 8, t = chained ? chain_t(kin) : kin % 8;
-  return (frag * 64 + 32 * g + out_rho(c % 32)) * 8 + t;
-}
-
 // One wavefront of a score job: the 32 x 32 block (links 32lb.., rows j = 32jb..) of head a's
 //   G_a^T[l][j] = sum_c K~[l][a dh + c] Wq[j][a dh + c],   K~ = Ksrc Wk,
 // computed on the matrix cores as Ksrc (Wk_a Wq_a^T): in that order both products read their operands row-major

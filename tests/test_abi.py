@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     assert {"lime_link_history", "lime_xor_history", "lime_score_candidates", "mha_target_attention",
             "lime_profile_enable", "lime_profile_collect", "lime_build_qk_cache", "lime_score_candidates_cached",
             "lime_score_candidates_gathered", "lime_prepared_bytes", "lime_prepare", "lime_link_history_prepared",
-            "lime_score_candidates_prepared", "lime_xor_layers",
+            "lime_score_candidates_prepared", "lime_xor_layers", "lime_request_prepared",
             "lime_workspace_bytes", "lime_last_error", "lime_version"} <= set(names)
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
@@ -186,3 +186,25 @@ def test_xor_layers_argument_checks():
     assert binding.workspace_bytes(binding.OP_XOR_LAYERS, B=2, N=64, d=128, h=4, m=64, dtype=0) > need
     assert binding.workspace_bytes(binding.OP_XOR_LAYERS, B=2, N=64, d=120, h=3, m=20) > 0
     assert call(dtype=0, ws_bytes=need) == 3
+
+
+def test_request_prepared_argument_checks():
+    lib = binding.lib()
+
+    def call(**kw):
+        a = dict(E=FAKE, lens=None, T=FAKE, Wv=FAKE, prepared=FAKE, LP=FAKE, O=FAKE, B=1, N=64, C=64, d=256, h=4, m=64,
+                 sh=1.0, sc=1.0, xor=0, dtype=1, ws=FAKE, ws_bytes=0, stream=None)
+        a.update(kw)
+        return lib.lime_request_prepared(a["E"], a["lens"], a["T"], a["Wv"], a["prepared"], a["LP"], a["O"], a["B"], a["N"],
+                                         a["C"], a["d"], a["h"], a["m"], a["sh"], a["sc"], a["xor"], a["dtype"], a["ws"],
+                                         a["ws_bytes"], a["stream"])
+
+    need = binding.workspace_bytes(binding.OP_REQUEST_PREPARED, B=1, N=64, C=64, d=256, h=4, m=64)
+    assert need == (binding.workspace_bytes(binding.OP_LINK_HISTORY, B=1, N=64, d=256, h=4, m=64) +
+                    binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=1, C=64, d=256, h=4, m=64)) or need > 0
+    assert call() == 3 and str(need) in binding.last_error()
+    assert call(prepared=None) == 1 and call(LP=None) == 1 and call(O=None) == 1 and call(T=None) == 1
+    assert call(C=0) == 1 and call(N=0) == 1
+    assert call(dtype=0) == 2 and call(d=120, h=3) == 2 and call(T=FAKE + 4) == 2
+    assert call(Wv=None) == 3  # identity values are allowed: only the workspace is wrong here
+    assert binding.workspace_bytes(binding.OP_REQUEST_PREPARED, B=1, N=64, C=64, d=256, h=4, m=64, dtype=0) == 0

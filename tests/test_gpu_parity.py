@@ -402,6 +402,32 @@ def test_prepared_operands_give_the_same_bits(B, N, C, d, h, m, ragged):
     assert_close(host(O_p), orc.lime_score_candidates(w.T, w.L, host(LP), w.Wq, w.Wk, w.Wv, h, s_c), "bf16", "prepared O")
 
 
+@pytest.mark.parametrize("B,N,C,d,h,m,xor", [(1, 2048, 4096, 256, 4, 64, False), (3, 777, 500, 256, 4, 128, False),
+                                             (5, 300, 333, 128, 4, 64, True), (40, 1024, 64, 128, 4, 32, False),
+                                             (2, 100, 70, 64, 2, 32, False), (2, 90, 33, 32, 1, 32, False)])
+def test_request_on_prepared_operands_in_one_call(B, N, C, d, h, m, xor):
+    """lime_request_prepared (three kernels: the merge step also writes the candidate stage's value image) against
+    the two prepared calls - the link states bit for bit, the outputs within the bf16 bar - and against the oracle;
+    ragged lengths with an empty user, NaN padding, a negative candidate scale, and once without Wv (identity).
+    d = 32 has no fused merge and runs the two stages as they are."""
+    w = _sharp(workload=170 + B + m, B=B, N=N, C=C, d=d, h=h, m=m, dtype="bf16", len_range=(1, N), pad_value=np.nan)
+    if B > 1:
+        w.lens[B - 1] = 0
+        w.E[B - 1] = np.nan
+    g = DeviceWorkload(w)
+    s_h, s_c = (_xor_scale(w) if xor else w.softmax_scale), -0.7 * w.softmax_scale
+    Wv_d, Wv_h = (None, None) if m == 128 else (g.Wv, w.Wv)
+    prepared = binding.lime_prepare(g.L, g.L, g.Wq, g.Wk, g.Wv, g.Wq, g.Wk, h, s_h, s_c)
+    LP2 = binding.lime_link_history_prepared(g.E, g.lens, prepared, h, m, s_h, xor_attention=xor)
+    O2 = binding.lime_score_candidates_prepared(g.T, LP2, Wv_d, prepared, h, s_c)
+    LP1, O1 = binding.lime_request_prepared(g.E, g.lens, g.T, Wv_d, prepared, h, m, s_h, s_c, xor_attention=xor)
+    assert torch.equal(LP1, LP2)
+    assert_close(host(O1), host(O2), "bf16", "one call against two calls")
+    assert_close(host(O1), orc.lime_score_candidates(w.T, w.L, host(LP1), w.Wq, w.Wk, Wv_h, h, s_c), "bf16", "O against the oracle")
+    if B > 1:
+        assert not host(LP1)[B - 1].any()
+
+
 FOLDED = [(256, 4, 64), (256, 4, 32), (128, 2, 64), (128, 2, 32), (64, 1, 64), (64, 1, 32), (256, 8, 32), (128, 4, 32),
           (64, 2, 32), (32, 1, 32)]
 
