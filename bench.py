@@ -42,6 +42,8 @@ def parse_args():
     p.add_argument("--rotate-mib", type=int, default=544, help="candidate+output bytes to rotate through (0 = reuse one pair)")
     p.add_argument("--streams", type=int, default=4, help="requests kept in flight (one stream, link-state buffer and workspace each)")
     p.add_argument("--graphs", action="store_true", help="replay one captured HIP graph per request instead of launching its five kernels from the host")
+    p.add_argument("--calls", choices=("one", "two"), default="one",
+                   help="a request as one C-ABI call (lime_request) or as lime_link_history + lime_score_candidates")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--extras", action="store_true", help="also time the XORA history pass, the C sweep and the MHA baseline")
     p.add_argument("--xor-layers", type=int, default=0, metavar="N",
@@ -85,7 +87,9 @@ def main():
     Ts = [T0] + [T0.clone() for _ in range(n_pairs - 1)]
     Os = [torch.empty_like(T0) for _ in range(n_pairs)]
     ws_bytes = max(binding.workspace_bytes(binding.OP_LINK_HISTORY, B=B, N=N, d=d, h=h, m=m),
-                   binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=B, C=C, d=d, h=h, m=m))
+                   binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=B, C=C, d=d, h=h, m=m),
+                   binding.workspace_bytes(binding.OP_REQUEST, B=B, N=N, C=C, d=d, h=h, m=m))
+    one_call = args.calls == "one"
     n_streams = max(1, args.streams)
     # one slot per request in flight: link states and workspace are private to a request
     slots = [(torch.empty((B, m, d), dtype=torch.bfloat16, device=dev),
@@ -94,6 +98,10 @@ def main():
 
     def step(i, slot=0, stream=None):
         lp, wsp = slots[slot]
+        if one_call:
+            binding.lime_request(E, None, L, Wq, Wk, Wv, Ts[i % n_pairs], L, Wq, Wk, Wv, h, scale, scale, LP=lp,
+                                 O=Os[i % n_pairs], workspace=wsp, stream=stream)
+            return
         binding.lime_link_history(E, None, L, Wq, Wk, Wv, h, scale, LP=lp, workspace=wsp, stream=stream)
         binding.lime_score_candidates(Ts[i % n_pairs], L, lp, Wq, Wk, Wv, h, scale, O=Os[i % n_pairs], workspace=wsp,
                                       stream=stream)
@@ -129,7 +137,15 @@ def main():
         cand_args = [[(ptr(Ts[j]), ptr(L), ptr(lp), ptr(Wq), ptr(Wk), ptr(Wv), ptr(Os[j]), B, C, d, h, m, scale,
                        binding.LIME_BF16, ptr(wsp), ws_bytes) for j in range(n_pairs)] for lp, wsp in slots]
 
+        req_args = [[(ptr(E), None, ptr(L), 0, ptr(Wq), ptr(Wk), ptr(Wv), ptr(Ts[j]), ptr(L), ptr(Wq), ptr(Wk), ptr(Wv), ptr(lp),
+                      ptr(Os[j]), B, N, C, d, h, m, scale, scale, 0, binding.LIME_BF16, ptr(wsp), ws_bytes)
+                     for j in range(n_pairs)] for lp, wsp in slots] if one_call else None
+
         def request(i, slot, stream):
+            if one_call:
+                if lib.lime_request(*req_args[slot][i % n_pairs], stream):
+                    raise RuntimeError(binding.last_error())
+                return
             if lib.lime_link_history(*hist_args[slot], stream) or lib.lime_score_candidates(*cand_args[slot][i % n_pairs], stream):
                 raise RuntimeError(binding.last_error())
 
@@ -232,8 +248,11 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"configs[2] candidate sweep point: B={B} user, N={N}, C={C}, d={d}, h={h}, m={m}, "
-                               "bf16, embeddings and weights ~N(0,1/d); step = lime_link_history + lime_score_candidates",
-                   "launch": ("one HIP graph per request" if args.graphs else "the two calls of a request launched from the host")
+                               "bf16, embeddings and weights ~N(0,1/d); step = "
+                               + ("lime_request (link states, then candidate scores, packing everything per call)" if one_call
+                                  else "lime_link_history + lime_score_candidates"),
+                   "launch": ("one HIP graph per request" if args.graphs else
+                              ("the call" if one_call else "the two calls") + " of a request launched from the host")
                              + f", {n_streams} requests in flight on {n_streams} streams",
                    "stream_probe_ms": probe_ms,
                    "rotating_buffer_pairs": n_pairs, "rotating_mib": n_pairs * pair_bytes / 2 ** 20},

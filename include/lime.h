@@ -51,7 +51,8 @@ extern "C" {
 enum { LIME_OK = 0, LIME_INVALID_ARG = 1, LIME_UNSUPPORTED = 2, LIME_WORKSPACE_TOO_SMALL = 3, LIME_LAUNCH_FAILED = 4 };
 enum { LIME_F32 = 0, LIME_BF16 = 1 };
 enum { LIME_OP_LINK_HISTORY = 0, LIME_OP_XOR_HISTORY = 1, LIME_OP_SCORE_CANDIDATES = 2, LIME_OP_MHA_TARGET = 3,
-       LIME_OP_BUILD_QK_CACHE = 4, LIME_OP_SCORE_CACHED = 5, LIME_OP_XOR_LAYERS = 6, LIME_OP_REQUEST_PREPARED = 7 };
+       LIME_OP_BUILD_QK_CACHE = 4, LIME_OP_SCORE_CACHED = 5, LIME_OP_XOR_LAYERS = 6, LIME_OP_REQUEST_PREPARED = 7,
+       LIME_OP_REQUEST = 8 };
 
 /*
  * User-side link personalisation, Section 3.1 Eq. 3:
@@ -185,6 +186,24 @@ int32_t lime_request_prepared(const void* E, const int32_t* lens, const void* T,
                               void* LP, void* O, int32_t B, int32_t N, int32_t C, int32_t d, int32_t h, int32_t m,
                               float scale_hist, float scale_cand, int32_t xor_attention, int32_t dtype,
                               void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * One request in one call (Eq. 3 then Eq. 4, or Eq. 7 then Eq. 4): lime_link_history (xor_attention = 0) or the LP
+ * output of lime_xor_history (xor_attention != 0) with the *_hist weights and scale_hist, followed by
+ * lime_score_candidates on that LP with the *_cand weights and scale_cand.  Arguments, layouts, nullable pointers
+ * (Wq_cand, Wk_cand, Wv_cand: NULL = identity) and errors as for those two entry points; LP[B][m][d] and
+ * O[B][C][d] are both written, nothing is kept between calls.  On the bf16 matrix-core shapes with 16-byte aligned
+ * pointers this is four kernels instead of six: one launch packs the operands of both stages, and the step that
+ * finishes the link states also projects them with Wv_cand into the layout the candidate kernel loads.  LP is then
+ * bit-identical to lime_link_history / lime_xor_history; O agrees with lime_score_candidates within the bf16
+ * tolerance (the value projection sums in another order).  Otherwise the two stages run one after the other as
+ * they are.  Workspace: LIME_OP_REQUEST.
+ */
+int32_t lime_request(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride, const void* Wq_hist,
+                     const void* Wk_hist, const void* Wv_hist, const void* T, const void* L, const void* Wq_cand,
+                     const void* Wk_cand, const void* Wv_cand, void* LP, void* O, int32_t B, int32_t N, int32_t C,
+                     int32_t d, int32_t h, int32_t m, float scale_hist, float scale_cand, int32_t xor_attention,
+                     int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
 
 /*
  * Workspace size in bytes for `op` (LIME_OP_*) at the given shape; dimensions an op

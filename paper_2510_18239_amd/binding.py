@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "liblime_hip.so")
 
 LIME_F32, LIME_BF16 = 0, 1
 (OP_LINK_HISTORY, OP_XOR_HISTORY, OP_SCORE_CANDIDATES, OP_MHA_TARGET, OP_BUILD_QK_CACHE, OP_SCORE_CACHED,
- OP_XOR_LAYERS, OP_REQUEST_PREPARED) = range(8)
+ OP_XOR_LAYERS, OP_REQUEST_PREPARED, OP_REQUEST) = range(9)
 STATUS_NAMES = {0: "LIME_OK", 1: "LIME_INVALID_ARG", 2: "LIME_UNSUPPORTED", 3: "LIME_WORKSPACE_TOO_SMALL",
                 4: "LIME_LAUNCH_FAILED"}
 
@@ -47,6 +47,8 @@ SIGNATURES = {
                                               _sz, _vp]),
     "lime_request_prepared": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _f32, _f32,
                                      _i32, _i32, _vp, _sz, _vp]),
+    "lime_request": (_i32, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
+                            _i32, _i32, _f32, _f32, _i32, _i32, _vp, _sz, _vp]),
     "lime_score_candidates_gathered": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _sz,
                                               _vp]),
     "lime_workspace_bytes": (_sz, [_i32] * 9),
@@ -363,6 +365,35 @@ def lime_score_candidates_prepared(T, LP, Wv, prepared, h, scale, O=None, worksp
                                                   float(scale), code, _ptr(ws), ws.numel(), _stream(stream))
     _raise(st)
     return O
+
+
+def lime_request(E, lens, LC, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand, Wv_cand, h, scale_hist, scale_cand,
+                 xor_attention=False, LP=None, O=None, workspace=None, stream=None):
+    """lime_link_history (or the link states of lime_xor_history) followed by lime_score_candidates, as one call; returns (LP, O)."""
+    first = _check(E, LC, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand, Wv_cand, LP, O)
+    B, N, d = E.shape
+    C = T.shape[1]
+    if LC.dim() == 2:
+        m, stride = LC.shape[0], 0
+    else:
+        if LC.shape[0] != B:
+            raise ValueError("per-user links must be [B, m, d]")
+        m, stride = LC.shape[1], LC.shape[1] * LC.shape[2]
+    code = _dtype_code(first)
+    lens = _lens_arg(lens, B, E.device)
+    if LP is None:
+        LP = torch.empty((B, m, d), dtype=E.dtype, device=E.device)
+    if O is None:
+        O = torch.empty_like(T)
+    need = workspace_bytes(OP_REQUEST, B=B, N=N, C=C, d=d, h=h, m=m, dtype=code)
+    ws = workspace if workspace is not None else get_workspace(need, E.device)
+    with torch.cuda.device(E.device):
+        st = lib().lime_request(_ptr(E), _ptr(lens), _ptr(LC), stride, _ptr(Wq_hist), _ptr(Wk_hist), _ptr(Wv_hist), _ptr(T),
+                                _ptr(L), _ptr(Wq_cand), _ptr(Wk_cand), _ptr(Wv_cand), _ptr(LP), _ptr(O), B, N, C, d, h, m,
+                                float(scale_hist), float(scale_cand), int(bool(xor_attention)), code, _ptr(ws), ws.numel(),
+                                _stream(stream))
+    _raise(st)
+    return LP, O
 
 
 def lime_request_prepared(E, lens, T, Wv, prepared, h, m, scale_hist, scale_cand, xor_attention=False, LP=None, O=None,

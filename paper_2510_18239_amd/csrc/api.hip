@@ -503,6 +503,59 @@ int32_t lime_request_prepared(const void* E, const int32_t* lens, const void* T,
   return LIME_OK;
 }
 
+int32_t lime_request(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride, const void* Wq_hist,
+                     const void* Wk_hist, const void* Wv_hist, const void* T, const void* L, const void* Wq_cand,
+                     const void* Wk_cand, const void* Wv_cand, void* LP, void* O, int32_t B, int32_t N, int32_t C,
+                     int32_t d, int32_t h, int32_t m, float scale_hist, float scale_cand, int32_t xor_attention,
+                     int32_t dtype, void* workspace, size_t ws_bytes, void* stream) {
+  const char* fn = "lime_request";
+  if (int32_t st = check_common(fn, B, d, h, dtype)) return st;
+  if (N <= 0 || C <= 0 || m <= 0)
+    return fail(LIME_INVALID_ARG, "%s: N, C and m must be positive (N=%d C=%d m=%d)", fn, N, C, m);
+  if (!E || !LC || !Wq_hist || !Wk_hist || !Wv_hist || !T || !L || !LP || !O)
+    return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  if (lc_user_stride != 0 && lc_user_stride != static_cast<int64_t>(m) * d)
+    return fail(LIME_INVALID_ARG, "%s: lc_user_stride must be 0 or m*d (got %lld)", fn, static_cast<long long>(lc_user_stride));
+  const int phi = xor_attention ? lime::kPhiSilu : lime::kPhiSoftmax;
+  const bool per_user = lc_user_stride != 0;
+  // each stage has a part of the workspace of its own, sized as for the stage's own entry point
+  const size_t hist_any = lime_workspace_bytes(LIME_OP_LINK_HISTORY, B, N, C, d, h, m, dtype, 0);
+  const size_t need = hist_any + lime_workspace_bytes(LIME_OP_SCORE_CANDIDATES, B, N, C, d, h, m, dtype, 0);
+  if (!workspace || ws_bytes < need)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? ws_bytes : 0);
+  void* cand_ws = static_cast<char*>(workspace) + hist_any;
+  const bool on_mfma = dtype == LIME_BF16 && lime::links_over_history_supported(d, h, m) &&
+                       all_aligned16(E, LC, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand, Wv_cand, LP, O, workspace) &&
+                       fits_tiles(B, N) && fits_tiles(B, C);
+  if (!on_mfma) {  // the two stages as they are (general kernels, or the matrix-core ones where each applies)
+    if (int32_t st = history_impl(fn, phi, E, lens, LC, lc_user_stride, Wq_hist, Wk_hist, Wv_hist, LP, nullptr, B, N, d, h, m,
+                                  scale_hist, dtype, workspace, hist_any, stream))
+      return st;
+    return lime_score_candidates(T, L, LP, Wq_cand, Wk_cand, Wv_cand, O, B, C, d, h, m, scale_cand, dtype, cand_ws,
+                                 ws_bytes - hist_any, stream);
+  }
+  // Four kernels: one pack launch for the operands of both stages, the history kernel, the merge step that also writes
+  // the candidate stage's value image, the candidate kernel.
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  lime::LinksOverHistory q{};
+  q.E = E, q.lens = lens, q.LC = LC, q.lc_user_stride = per_user ? static_cast<int64_t>(m) * d : 0;
+  q.Wq = Wq_hist, q.Wk = Wk_hist, q.Wv = Wv_hist, q.LP = LP;
+  q.B = B, q.N = N, q.d = d, q.h = h, q.m = m, q.scale = scale_hist, q.phi = phi;
+  lime::QueriesOverLinks c{};
+  c.X = T, c.O = O, c.Wq = Wq_cand, c.Ksrc = L, c.Wk = Wk_cand, c.Vsrc = LP, c.Wv = Wv_cand;
+  c.k_user_stride = 0, c.v_user_stride = static_cast<int64_t>(m) * d, c.row_lens = nullptr;
+  c.B = B, c.rows = C, c.d = d, c.h = h, c.m = m, c.scale = scale_cand, c.phi = lime::kPhiSoftmax;
+  lime::PackJobs jobs;
+  lime::links_over_history_jobs(q, workspace, jobs);
+  lime::queries_over_links_jobs(c, cand_ws, jobs, /*values=*/false);
+  LIME_HIP(lime::pack_operands(jobs.weights, jobs.n_weights, jobs.projections, jobs.n_projections, d, h, m, s));
+  q.packed = c.packed = true;
+  q.Wv_values = Wv_cand, q.values_image = lime::queries_over_links_values(c, cand_ws);
+  LIME_HIP(lime::links_over_history(q, workspace, s));
+  LIME_HIP(lime::queries_over_links(c, cand_ws, s));
+  return LIME_OK;
+}
+
 int32_t lime_xor_layers(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride, const void* Wq,
                         const void* Wk, const void* Wv, const void* Wu, const void* Wo, int32_t n_layers, void* LP,
                         int32_t B, int32_t N, int32_t d, int32_t h, int32_t m, float scale, int32_t dtype,
@@ -588,6 +641,10 @@ size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t
                                   (os ? lime::queries_over_links_workspace(B, d, m, true) : size_t{0}));
       return need;
     }
+    case LIME_OP_REQUEST:
+      if (N <= 0 || C <= 0 || m <= 0) return 0;
+      return lime_workspace_bytes(LIME_OP_LINK_HISTORY, B, N, C, d, h, m, dtype, 0) +
+             lime_workspace_bytes(LIME_OP_SCORE_CANDIDATES, B, N, C, d, h, m, dtype, 0);
     case LIME_OP_REQUEST_PREPARED:
       if (N <= 0 || C <= 0 || m <= 0 || lime_prepared_bytes(d, h, m, dtype) == 0) return 0;
       return lime::links_over_history_workspace(B, N, d, h, m, false) + lime::queries_over_links_workspace(B, d, m, false);

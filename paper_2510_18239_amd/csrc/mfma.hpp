@@ -160,8 +160,9 @@ struct QueriesOverLinks {
 };
 // where the value image of a call lives in its workspace
 void* queries_over_links_values(const QueriesOverLinks& a, void* workspace);
-// The pack jobs of a call, appended to `jobs` instead of being launched by queries_over_links (not with `prepared`).
-void queries_over_links_jobs(const QueriesOverLinks& a, void* workspace, PackJobs& jobs);
+// The pack jobs of a call, appended to `jobs` instead of being launched by queries_over_links (not with `prepared`);
+// without `values` when someone else writes the value image (the history side's merge step).
+void queries_over_links_jobs(const QueriesOverLinks& a, void* workspace, PackJobs& jobs, bool values = true);
 bool queries_over_links_supported(int d, int h, int m);
 bool fused_scores(int d, int h, int m, bool k_per_user);  // whether the kernel takes the score image G
 size_t queries_over_links_workspace(int B, int d, int m, bool k_per_user);

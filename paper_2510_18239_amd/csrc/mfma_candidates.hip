@@ -497,7 +497,7 @@ void* queries_over_links_values(const QueriesOverLinks& q, void* workspace) {
          align_up(static_cast<size_t>(q.k_user_stride != 0 ? q.B : 1) * q.m * q.d * 2);
 }
 
-void queries_over_links_jobs(const QueriesOverLinks& q, void* workspace, PackJobs& jobs) {
+void queries_over_links_jobs(const QueriesOverLinks& q, void* workspace, PackJobs& jobs, bool values) {
   const int d = q.d, m = q.m;
   const bool k_per_user = q.k_user_stride != 0, v_per_user = q.v_user_stride != 0;
   char* ws = static_cast<char*>(workspace);
@@ -507,7 +507,7 @@ void queries_over_links_jobs(const QueriesOverLinks& q, void* workspace, PackJob
   // a negative logit scale is folded into the sign of the packed keys, so the kernel sees scale >= 0
   jobs.projections[jobs.n_projections++] =
       PackProject{q.Ksrc, q.Wk, KA, q.k_user_stride, k_per_user ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f};
-  if (!q.weights_out)
+  if (!q.weights_out && values)
     jobs.projections[jobs.n_projections++] = PackProject{q.Vsrc, q.Wv, VA, q.v_user_stride, v_per_user ? q.B : 1, kPackValues, 1.f};
 }
 

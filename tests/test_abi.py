@@ -208,3 +208,28 @@ def test_request_prepared_argument_checks():
     assert call(dtype=0) == 2 and call(d=120, h=3) == 2 and call(T=FAKE + 4) == 2
     assert call(Wv=None) == 3  # identity values are allowed: only the workspace is wrong here
     assert binding.workspace_bytes(binding.OP_REQUEST_PREPARED, B=1, N=64, C=64, d=256, h=4, m=64, dtype=0) == 0
+
+
+def test_request_argument_checks():
+    lib = binding.lib()
+
+    def call(**kw):
+        a = dict(E=FAKE, lens=None, LC=FAKE, stride=0, Wqh=FAKE, Wkh=FAKE, Wvh=FAKE, T=FAKE, L=FAKE, Wqc=FAKE, Wkc=FAKE,
+                 Wvc=FAKE, LP=FAKE, O=FAKE, B=1, N=64, C=64, d=256, h=4, m=64, sh=1.0, sc=1.0, xor=0, dtype=1, ws=FAKE,
+                 ws_bytes=0, stream=None)
+        a.update(kw)
+        return lib.lime_request(a["E"], a["lens"], a["LC"], a["stride"], a["Wqh"], a["Wkh"], a["Wvh"], a["T"], a["L"],
+                                a["Wqc"], a["Wkc"], a["Wvc"], a["LP"], a["O"], a["B"], a["N"], a["C"], a["d"], a["h"], a["m"],
+                                a["sh"], a["sc"], a["xor"], a["dtype"], a["ws"], a["ws_bytes"], a["stream"])
+
+    for dtype in (0, 1):  # both storage types are served (fp32 on the general kernels)
+        need = binding.workspace_bytes(binding.OP_REQUEST, B=1, N=64, C=64, d=256, h=4, m=64, dtype=dtype)
+        assert need == (binding.workspace_bytes(binding.OP_LINK_HISTORY, B=1, N=64, d=256, h=4, m=64, dtype=dtype) +
+                        binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=1, C=64, d=256, h=4, m=64, dtype=dtype))
+        assert call(dtype=dtype) == 3 and str(need) in binding.last_error()
+    assert call(E=None) == 1 and call(LC=None) == 1 and call(Wqh=None) == 1 and call(T=None) == 1 and call(L=None) == 1
+    assert call(LP=None) == 1 and call(O=None) == 1
+    assert call(C=0) == 1 and call(N=0) == 1 and call(m=0) == 1 and call(stride=7) == 1
+    assert call(Wqc=None, Wkc=None, Wvc=None) == 3  # identity on the candidate side is allowed: only the workspace is wrong
+    assert call(dtype=5) == 1 or call(dtype=5) == 2
+    assert binding.workspace_bytes(binding.OP_REQUEST, B=1, N=64, C=0, d=256, h=4, m=64) == 0

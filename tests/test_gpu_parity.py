@@ -408,8 +408,7 @@ def test_prepared_operands_give_the_same_bits(B, N, C, d, h, m, ragged):
 def test_request_on_prepared_operands_in_one_call(B, N, C, d, h, m, xor):
     """lime_request_prepared (three kernels: the merge step also writes the candidate stage's value image) against
     the two prepared calls - the link states bit for bit, the outputs within the bf16 bar - and against the oracle;
-    ragged lengths with an empty user, NaN padding, a negative candidate scale, and once without Wv (identity).
-    d = 32 has no fused merge and runs the two stages as they are."""
+    ragged lengths with an empty user, NaN padding, a negative candidate scale, and once without Wv (identity)."""
     w = _sharp(workload=170 + B + m, B=B, N=N, C=C, d=d, h=h, m=m, dtype="bf16", len_range=(1, N), pad_value=np.nan)
     if B > 1:
         w.lens[B - 1] = 0
@@ -424,6 +423,48 @@ def test_request_on_prepared_operands_in_one_call(B, N, C, d, h, m, xor):
     assert torch.equal(LP1, LP2)
     assert_close(host(O1), host(O2), "bf16", "one call against two calls")
     assert_close(host(O1), orc.lime_score_candidates(w.T, w.L, host(LP1), w.Wq, w.Wk, Wv_h, h, s_c), "bf16", "O against the oracle")
+    if B > 1:
+        assert not host(LP1)[B - 1].any()
+
+
+@pytest.mark.parametrize("B,N,C,d,h,m,dtype,xor,per_user", [
+    (1, 2048, 4096, 256, 4, 64, "bf16", False, False), (3, 777, 500, 256, 4, 128, "bf16", False, True),
+    (5, 300, 333, 128, 4, 64, "bf16", True, False), (40, 1024, 64, 128, 4, 32, "bf16", False, False),
+    (2, 90, 33, 32, 1, 32, "bf16", False, True), (2, 333, 200, 128, 4, 64, "fp32", False, False),
+    (2, 100, 70, 48, 2, 5, "bf16", True, True), (1, 65, 40, 24, 1, 5, "fp32", True, False)])
+def test_request_in_one_call(B, N, C, d, h, m, dtype, xor, per_user):
+    """lime_request (per-call packing; on the matrix-core shapes four kernels, elsewhere the two stages in turn) against
+    lime_link_history / lime_xor_history followed by lime_score_candidates - the link states bit for bit, the outputs
+    within the bar - and against the oracle; ragged lengths with an empty user, NaN padding, shared and per-user
+    links, different weights and scales for the two stages, once with the candidate side's weights absent."""
+    w = _sharp(workload=190 + B + m, B=B, N=N, C=C, d=d, h=h, m=m, dtype=dtype, len_range=(1, N), pad_value=np.nan)
+    if B > 1:
+        w.lens[B - 1] = 0
+        w.E[B - 1] = np.nan
+    g = DeviceWorkload(w)
+    s_h, s_c = (_xor_scale(w) if xor else w.softmax_scale), -0.7 * w.softmax_scale
+    if per_user:
+        rng = np.random.default_rng(7)
+        LC_h = np.stack([w.L[rng.permutation(m)] for _ in range(B)])
+        LC_d = dev(LC_h, w.dtype)
+    else:
+        LC_h, LC_d = w.L, g.L
+    # the candidate stage gets the history stage's weights in another role, or none at all
+    cand_d, cand_h = ((None, None, None), (None, None, None)) if m == 128 else ((g.Wk, g.Wv, g.Wq), (w.Wk, w.Wv, w.Wq))
+    if xor:
+        LP2 = binding.lime_xor_history(g.E, g.lens, LC_d, g.Wq, g.Wk, g.Wv, h, s_h)[0]
+    else:
+        LP2 = binding.lime_link_history(g.E, g.lens, LC_d, g.Wq, g.Wk, g.Wv, h, s_h)
+    O2 = binding.lime_score_candidates(g.T, g.L, LP2, *cand_d, h, s_c)
+    LP1, O1 = binding.lime_request(g.E, g.lens, LC_d, g.Wq, g.Wk, g.Wv, g.T, g.L, *cand_d, h, s_h, s_c, xor_attention=xor)
+    assert torch.equal(LP1, LP2)
+    assert_close(host(O1), host(O2), dtype, "one call against two calls")
+    if xor:
+        ref_LP = orc.lime_xor_history(w.E, w.lens, LC_h, w.Wq, w.Wk, w.Wv, h, s_h)[0]
+    else:
+        ref_LP = orc.lime_link_history(w.E, w.lens, LC_h, w.Wq, w.Wk, w.Wv, h, s_h)
+    assert_close(host(LP1), ref_LP, dtype, "LP against the oracle")
+    assert_close(host(O1), orc.lime_score_candidates(w.T, w.L, host(LP1), *cand_h, h, s_c), dtype, "O against the oracle")
     if B > 1:
         assert not host(LP1)[B - 1].any()
 
