@@ -53,6 +53,24 @@ def test_config3_headline_request(gain):
     assert_close(host(LP), LP_ref, "bf16", "LP")
     assert_close(host(O), orc.lime_score_candidates(w.T, w.L, host(LP), w.Wq, w.Wk, w.Wv, w.h, s), "bf16", "O")
     assert_close(host(O), orc.lime_score_candidates(w.T, w.L, LP_ref, w.Wq, w.Wk, w.Wv, w.h, s), "bf16", "chain", 2.0)
+    # the same request as the one call bench.py's step makes
+    LP1, O1 = binding.lime_request(g.E, None, g.L, g.Wq, g.Wk, g.Wv, g.T, g.L, g.Wq, g.Wk, g.Wv, w.h, s, s)
+    assert torch.equal(LP1, LP)
+    assert_close(host(O1), orc.lime_score_candidates(w.T, w.L, host(LP1), w.Wq, w.Wk, w.Wv, w.h, s), "bf16", "O in one call")
+    assert_close(host(O1), orc.lime_score_candidates(w.T, w.L, LP_ref, w.Wq, w.Wk, w.Wv, w.h, s), "bf16", "chain in one call", 2.0)
+
+
+@pytest.mark.parametrize("gain", ["bench", "sharp"])
+def test_config2_and_config5_requests_in_one_call(gain):
+    """lime_request at the two batched full sizes (ragged lengths; m = 64 and m = 128), every element checked."""
+    for idx in (2, 5):
+        w = _workload(idx, gain)
+        g = DeviceWorkload(w)
+        s = w.softmax_scale
+        print(f"config {idx} {gain}: lens {w.lens.min()}..{w.lens.max()}", flush=True)
+        LP, O = binding.lime_request(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, g.T, g.L, g.Wq, g.Wk, g.Wv, w.h, s, s)
+        assert_close(host(LP), orc.lime_link_history(w.E, w.lens, w.L, w.Wq, w.Wk, w.Wv, w.h, s), "bf16", "LP")
+        assert_close(host(O), orc.lime_score_candidates(w.T, w.L, host(LP), w.Wq, w.Wk, w.Wv, w.h, s), "bf16", "O")
 
 
 @pytest.mark.parametrize("C", [16, 48, 1000, 4096])
