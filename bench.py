@@ -523,7 +523,7 @@ def extras(binding, synth, torch, dev, timed, pct):
     del Tc, Oc, c_args
     # several users per call (the headline is one): the start-up of every kernel is shared by the batch
     batched = {}
-    for users in (2, 4, 8):
+    for users in (2, 4, 8, 16):
         cb = dict(c3)
         cb["B"] = users
         wb = synth.make_workload(3, **cb)
@@ -534,8 +534,8 @@ def extras(binding, synth, torch, dev, timed, pct):
         LPb = torch.empty((users, wb.m, wb.d), dtype=torch.bfloat16, device=dev)
 
         def call(i):
-            binding.lime_link_history(Eb, None, L, Wq, Wk, Wv, wb.h, wb.softmax_scale, LP=LPb)
-            binding.lime_score_candidates(Tbs[i % pairs], L, LPb, Wq, Wk, Wv, wb.h, wb.softmax_scale, O=Obs[i % pairs])
+            binding.lime_request(Eb, None, L, Wq, Wk, Wv, Tbs[i % pairs], L, Wq, Wk, Wv, wb.h, wb.softmax_scale,
+                                 wb.softmax_scale, LP=LPb, O=Obs[i % pairs])
 
         for i in range(20):
             call(i)
@@ -600,8 +600,7 @@ def extras(binding, synth, torch, dev, timed, pct):
     s5 = w5.softmax_scale
 
     def lime(i):
-        LP5 = binding.lime_link_history(E5, lens5, L5, q5, k5, v5, w5.h, s5)
-        binding.lime_score_candidates(T5, L5, LP5, q5, k5, v5, w5.h, s5)
+        binding.lime_request(E5, lens5, L5, q5, k5, v5, T5, L5, q5, k5, v5, w5.h, s5, s5)
 
     lat_lime = timed(lime, 20)
     lat_mha = timed(lambda i: binding.mha_target_attention(T5, E5, lens5, q5, k5, v5, w5.h, s5), 5)
@@ -616,8 +615,7 @@ def extras(binding, synth, torch, dev, timed, pct):
     lens2 = torch.from_numpy(w2.lens).to(dev)
 
     def batched(i):
-        lp = binding.lime_link_history(E2, lens2, L2, q2, k2, v2, w2.h, w2.softmax_scale)
-        binding.lime_score_candidates(T2, L2, lp, q2, k2, v2, w2.h, w2.softmax_scale)
+        binding.lime_request(E2, lens2, L2, q2, k2, v2, T2, L2, q2, k2, v2, w2.h, w2.softmax_scale, w2.softmax_scale)
 
     lat2 = pct(timed(batched, 100), 0.5)
     res["config2_batched_request"] = {"p50_ms": lat2, "candidates_per_s": w2.B * w2.C / (lat2 * 1e-3)}
@@ -631,8 +629,7 @@ def extras(binding, synth, torch, dev, timed, pct):
     O3 = torch.empty_like(T)
 
     def lime_mha(i):
-        lp = binding.lime_link_history(E, None, L, Wq, Wk, Wv, w.h, w.softmax_scale)
-        binding.lime_score_candidates(T, L, lp, Wq, Wk, Wv, w.h, w.softmax_scale, O=O3)
+        binding.lime_request(E, None, L, Wq, Wk, Wv, T, L, Wq, Wk, Wv, w.h, w.softmax_scale, w.softmax_scale, O=O3)
 
     def lime_xor(i):
         lp = binding.lime_xor_layers(E, None, L, Wq, Wk, Wv, Wu3, Wo3, w.h, 1.0)

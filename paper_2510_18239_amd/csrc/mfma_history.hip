@@ -396,29 +396,26 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(MergeArgs a) {
 // over d as the pack kernel's projections: thread (cg, kc) owns 8 adjacent columns and every nkc-th k; the partial
 // sums meet in LDS.  Every partial state is read once, as in the merge kernel: those reads miss the local L2
 // (other compute units wrote them) and set the kernel's time.
-constexpr int kMvRows = 2, kMvThreads = 512, kMvMaxD = 256;
-constexpr int kMvMaxK = kMvMaxD * (kMvMaxD / 8) / kMvThreads;  // k-steps per thread at the largest d
+// The workgroup has 2 d threads: d / 8 column groups x 16 k-groups (d / 16 k-steps per thread), of which d / 2
+// threads do the merge.
+constexpr int kMvRows = 2, kMvKGroups = 16;
 struct MergeValuesArgs {
   MergeArgs m;
   const bf16_t* Wv;  // [d][d], nullable = identity
   bf16_t* VA;        // [B] value images
 };
 
-constexpr size_t merge_values_lds(int d) {
-  // rounded link states + output rows + one partial output per k-group
-  return (static_cast<size_t>(2 * kMvRows) * d + static_cast<size_t>(kMvThreads / (d / 8)) * kMvRows * d) * sizeof(float);
-}
-
-template <int PHI>
-__global__ __launch_bounds__(kMvThreads) void merge_values_kernel(MergeValuesArgs a) {
-  extern __shared__ float mv_smem[];
-  const int d = a.m.h * a.m.dh, tid = threadIdx.x;
+template <int PHI, int D>
+__global__ __launch_bounds__(2 * D) void merge_values_kernel(MergeValuesArgs a) {
+  constexpr int d = D, kMvThreads = 2 * D, CG = D / 8, nkc = kMvKGroups, kMvMaxK = D / kMvKGroups;
+  static_assert(CG * nkc == kMvThreads, "one thread per (column group, k-group)");
+  // rounded link states + output rows + one partial output per k-group (36 KiB at d = 256)
+  __shared__ float lp[kMvRows * D];         // bf16-rounded values
+  __shared__ float out[kMvRows * D];
+  __shared__ float red[nkc * kMvRows * D];
+  const int tid = threadIdx.x;
   const int row0 = blockIdx.x * kMvRows, b = blockIdx.y;
-  const int CG = d / 8, nkc = kMvThreads / CG;
   const int cg = tid % CG, kc = tid / CG;
-  float* lp = mv_smem;            // [kMvRows][d], bf16-rounded values
-  float* out = lp + kMvRows * d;  // [kMvRows][d]
-  float* red = out + kMvRows * d; // [nkc][kMvRows][d]
   bf16x8 wreg[kMvMaxK];
   if (a.Wv != nullptr) {  // asked for before the merge, used after it
 #pragma unroll
@@ -613,11 +610,23 @@ hipError_t links_over_history(const LinksOverHistory& q, void* workspace, hipStr
   if (q.values_image != nullptr) {
     MergeValuesArgs mv{g, static_cast<const bf16_t*>(q.Wv_values), static_cast<bf16_t*>(q.values_image)};
     const dim3 vgrid(m / kMvRows, q.B);
-    const size_t lds = merge_values_lds(d);
-    if (q.phi == kPhiSoftmax)
-      hipLaunchKernelGGL(merge_values_kernel<kPhiSoftmax>, vgrid, dim3(kMvThreads), lds, s, mv);
-    else
-      hipLaunchKernelGGL(merge_values_kernel<kPhiSilu>, vgrid, dim3(kMvThreads), lds, s, mv);
+    const bool softmax = q.phi == kPhiSoftmax;
+#define LIME_MV_CASE(D)                                                                                      \
+  case D:                                                                                                    \
+    if (softmax)                                                                                             \
+      hipLaunchKernelGGL((merge_values_kernel<kPhiSoftmax, D>), vgrid, dim3(2 * D), 0, s, mv);               \
+    else                                                                                                     \
+      hipLaunchKernelGGL((merge_values_kernel<kPhiSilu, D>), vgrid, dim3(2 * D), 0, s, mv);                  \
+    break;
+    switch (d) {  // every d the matrix-core kernels take
+      LIME_MV_CASE(32)
+      LIME_MV_CASE(64)
+      LIME_MV_CASE(128)
+      LIME_MV_CASE(256)
+      default:
+        return hipErrorInvalidValue;
+    }
+#undef LIME_MV_CASE
     return hipGetLastError();
   }
   const dim3 mgrid((m * d / 4 + kMergeThreads - 1) / kMergeThreads, q.B);
