@@ -403,6 +403,7 @@ struct MergeValuesArgs {
   MergeArgs m;
   const bf16_t* Wv;  // [d][d], nullable = identity
   bf16_t* VA;        // [B] value images
+  int passes;        // row pairs a workgroup handles one after the other with the same W_V registers
 };
 
 template <int PHI, int D>
@@ -413,59 +414,59 @@ __global__ __launch_bounds__(2 * D) void merge_values_kernel(MergeValuesArgs a) 
   __shared__ float lp[kMvRows * D];         // bf16-rounded values
   __shared__ float out[kMvRows * D];
   __shared__ float red[nkc * kMvRows * D];
-  const int tid = threadIdx.x;
-  const int row0 = blockIdx.x * kMvRows, b = blockIdx.y;
+  const int tid = threadIdx.x, b = blockIdx.y;
   const int cg = tid % CG, kc = tid / CG;
   bf16x8 wreg[kMvMaxK];
   if (a.Wv != nullptr) {  // asked for before the merge, used after it
 #pragma unroll
-    for (int it = 0; it < kMvMaxK; ++it) {
-      const int k = kc + it * nkc;
-      if (k < d) wreg[it] = *reinterpret_cast<const bf16x8*>(a.Wv + static_cast<int64_t>(k) * d + 8 * cg);
-    }
+    for (int it = 0; it < kMvMaxK; ++it)
+      wreg[it] = *reinterpret_cast<const bf16x8*>(a.Wv + static_cast<int64_t>(kc + it * nkc) * d + 8 * cg);
   }
   const int len = a.m.lens ? min(a.m.lens[b], a.m.N) : a.m.N;
-  for (int i = 4 * tid; i < kMvRows * d; i += 4 * kMvThreads) {
-    const int link = row0 + i / d, col = i % d;
-    store_rounded(a.m.LP + (static_cast<int64_t>(b) * a.m.m + link) * d + col,
-                  merged_values<PHI>(a.m, b, link, col / a.m.dh, col % a.m.dh, len), lp + i);
-  }
-  __syncthreads();
-  if (a.Wv == nullptr) {
-    for (int i = tid; i < kMvRows * d; i += kMvThreads) out[i] = lp[i];
-  } else {
-    float acc[kMvRows][8];
+  // (no barrier is needed between two passes: whoever writes lp, red or out again has passed two barriers since
+  // the last read of it)
+  const int passes = D >= 256 ? a.passes : 1;  // (a compile-time 1 keeps the small shapes' register count low)
+  for (int pass = 0; pass < passes; ++pass) {
+    const int row0 = (blockIdx.x * passes + pass) * kMvRows;
+    for (int i = 4 * tid; i < kMvRows * d; i += 4 * kMvThreads) {
+      const int link = row0 + i / d, col = i % d;
+      store_rounded(a.m.LP + (static_cast<int64_t>(b) * a.m.m + link) * d + col,
+                    merged_values<PHI>(a.m, b, link, col / a.m.dh, col % a.m.dh, len), lp + i);
+    }
+    __syncthreads();
+    if (a.Wv == nullptr) {
+      for (int i = tid; i < kMvRows * d; i += kMvThreads) out[i] = lp[i];
+    } else {
+      float acc[kMvRows][8];
 #pragma unroll
-    for (int r = 0; r < kMvRows; ++r)
+      for (int r = 0; r < kMvRows; ++r)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) acc[r][j] = 0.f;
+        for (int j = 0; j < 8; ++j) acc[r][j] = 0.f;
 #pragma unroll
-    for (int it = 0; it < kMvMaxK; ++it) {
-      const int k = kc + it * nkc;
-      if (k < d) {
+      for (int it = 0; it < kMvMaxK; ++it) {
 #pragma unroll
         for (int r = 0; r < kMvRows; ++r) {
-          const float x = lp[r * d + k];
+          const float x = lp[r * d + kc + it * nkc];
 #pragma unroll
           for (int j = 0; j < 8; ++j) acc[r][j] = fmaf(x, static_cast<float>(wreg[it][j]), acc[r][j]);
         }
       }
-    }
 #pragma unroll
-    for (int r = 0; r < kMvRows; ++r)
+      for (int r = 0; r < kMvRows; ++r)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) red[(kc * kMvRows + r) * d + 8 * cg + j] = acc[r][j];
-    __syncthreads();
-    for (int i = tid; i < kMvRows * d; i += kMvThreads) {
-      float sum = 0.f;
+        for (int j = 0; j < 8; ++j) red[(kc * kMvRows + r) * d + 8 * cg + j] = acc[r][j];
+      __syncthreads();
+      for (int i = tid; i < kMvRows * d; i += kMvThreads) {
+        float sum = 0.f;
 #pragma unroll 8
-      for (int c = 0; c < nkc; ++c) sum += red[c * kMvRows * d + i];
-      out[i] = sum;
+        for (int c = 0; c < nkc; ++c) sum += red[c * kMvRows * d + i];
+        out[i] = sum;
+      }
     }
+    __syncthreads();
+    for (int i = tid; i < kMvRows * d; i += kMvThreads)
+      store_as(a.VA + values_slot(b, row0 + i / d, i % d, d, a.m.dh, a.m.m, true), out[i]);
   }
-  __syncthreads();
-  for (int i = tid; i < kMvRows * d; i += kMvThreads)
-    store_as(a.VA + values_slot(b, row0 + i / d, i % d, d, a.m.dh, a.m.m, true), out[i]);
 }
 
 template <int DH, int M, int H, int PHI>
@@ -608,8 +609,14 @@ hipError_t links_over_history(const LinksOverHistory& q, void* workspace, hipStr
 
   MergeArgs g{part_acc, part_ml, q.lens, static_cast<bf16_t*>(q.LP), q.N, l.chunk_items, l.chunks, h, m, dh, fabsf(q.scale)};
   if (q.values_image != nullptr) {
-    MergeValuesArgs mv{g, static_cast<const bf16_t*>(q.Wv_values), static_cast<bf16_t*>(q.values_image)};
-    const dim3 vgrid(m / kMvRows, q.B);
+    // With many users and the largest W_V a workgroup takes several row pairs in turn, as long as every compute
+    // unit still has a workgroup: each workgroup reads all of W_V (128 KiB at d = 256; at d = 128 the shorter
+    // chain per workgroup is worth more than the 32 KiB: measured).
+    int passes = 1;
+    while (d >= 256 && passes < 16 && static_cast<int64_t>(q.B) * (m / kMvRows) / (2 * passes) >= compute_units())
+      passes *= 2;
+    MergeValuesArgs mv{g, static_cast<const bf16_t*>(q.Wv_values), static_cast<bf16_t*>(q.values_image), passes};
+    const dim3 vgrid(m / (kMvRows * passes), q.B);  // (m / 2 is a multiple of 16)
     const bool softmax = q.phi == kPhiSoftmax;
 #define LIME_MV_CASE(D)                                                                                      \
   case D:                                                                                                    \
