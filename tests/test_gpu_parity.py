@@ -210,10 +210,14 @@ def test_hip_graph_replay_matches_eager():
     O = torch.empty_like(g.T)
     XT = torch.empty_like(LP)
     XL = torch.empty_like(LP)
+    LP1, O1, LP3, O3 = torch.empty_like(LP), torch.empty_like(O), torch.empty_like(LP), torch.empty_like(O)
     Wu, Wo = (dev(x, "bf16") for x in _layer_weights(5, 2, 256))
+    prepared = binding.lime_prepare(g.L, g.L, g.Wq, g.Wk, g.Wv, g.Wq, g.Wk, 4, s, s)
     ws = torch.empty(max(binding.workspace_bytes(binding.OP_XOR_HISTORY, B=2, N=300, d=256, h=4, m=64),
                          binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=2, C=400, d=256, h=4, m=64),
-                         binding.workspace_bytes(binding.OP_XOR_LAYERS, B=2, N=300, d=256, h=4, m=64)),
+                         binding.workspace_bytes(binding.OP_XOR_LAYERS, B=2, N=300, d=256, h=4, m=64),
+                         binding.workspace_bytes(binding.OP_REQUEST, B=2, N=300, C=400, d=256, h=4, m=64),
+                         binding.workspace_bytes(binding.OP_REQUEST_PREPARED, B=2, N=300, C=400, d=256, h=4, m=64)),
                      dtype=torch.uint8, device="cuda")
 
     def request():
@@ -221,21 +225,25 @@ def test_hip_graph_replay_matches_eager():
         binding.lime_score_candidates(g.T, g.L, LP, g.Wq, g.Wk, g.Wv, 4, s, O=O, workspace=ws)
         binding.lime_xor_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, 4, s, LP=XT, workspace=ws)
         binding.lime_xor_layers(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, Wu, Wo, 4, s, LP=XL, workspace=ws)
+        binding.lime_request(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, g.T, g.L, g.Wq, g.Wk, g.Wv, 4, s, s, LP=LP1, O=O1,
+                             workspace=ws)
+        binding.lime_request_prepared(g.E, g.lens, g.T, g.Wv, prepared, 4, 64, s, s, LP=LP3, O=O3, workspace=ws)
 
+    outs = (LP, O, XT, XL, LP1, O1, LP3, O3)
     request()
     torch.cuda.synchronize()
-    want = [t.clone() for t in (LP, O, XT, XL)]
+    want = [t.clone() for t in outs]
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         request()
     for _ in range(4):
-        for t in (LP, O, XT, XL):
+        for t in outs:
             t.fill_(7.0)
         ws.random_(0, 255)  # the workspace carries nothing from one call to the next
         (torch.randn(1000, device="cuda") * 2).sum().item()  # unrelated eager work and a synchronisation
         graph.replay()
         torch.cuda.synchronize()
-        for got, ref in zip((LP, O, XT, XL), want):
+        for got, ref in zip(outs, want):
             assert torch.equal(got, ref)
 
 
@@ -250,19 +258,27 @@ def test_concurrent_requests_on_separate_streams():
         g = DeviceWorkload(w)
         LP = binding.lime_link_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, 4, w.softmax_scale)
         O = binding.lime_score_candidates(g.T, g.L, LP, g.Wq, g.Wk, g.Wv, 4, w.softmax_scale)
+        LP1, O1 = binding.lime_request(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, g.T, g.L, g.Wq, g.Wk, g.Wv, 4, w.softmax_scale,
+                                       w.softmax_scale)
         torch.cuda.synchronize()
-        want.append((LP.clone(), O.clone()))
+        assert torch.equal(LP1, LP)
+        want.append((LP.clone(), O.clone(), O1.clone()))
         inputs.append((w, g))
-        ws_list.append(torch.empty(max(binding.workspace_bytes(binding.OP_LINK_HISTORY, B=1, N=w.N, d=256, h=4, m=64),
-                                       binding.workspace_bytes(binding.OP_SCORE_CANDIDATES, B=1, C=w.C, d=256, h=4, m=64)),
+        ws_list.append(torch.empty(binding.workspace_bytes(binding.OP_REQUEST, B=1, N=w.N, C=w.C, d=256, h=4, m=64),
                                    dtype=torch.uint8, device="cuda"))
     streams = [torch.cuda.Stream() for _ in range(n)]
-    got = [(torch.empty_like(lp), torch.empty_like(o)) for lp, o in want]
+    got = [(torch.empty_like(lp), torch.empty_like(o)) for lp, o, _ in want]
+    reps = 3
     torch.cuda.synchronize()
-    for rep in range(3):
+    for rep in range(reps):
         for k in range(n):
             w, g = inputs[k]
             LP, O = got[k]
+            if (k + rep) % 2:  # the request as one call (how bench.py issues it): the same link states, and its own
+                # output bits (the value projection sums in another order)
+                binding.lime_request(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, g.T, g.L, g.Wq, g.Wk, g.Wv, 4, w.softmax_scale,
+                                     w.softmax_scale, LP=LP, O=O, workspace=ws_list[k], stream=streams[k])
+                continue
             binding.lime_link_history(g.E, g.lens, g.L, g.Wq, g.Wk, g.Wv, 4, w.softmax_scale, LP=LP,
                                       workspace=ws_list[k], stream=streams[k])
             binding.lime_score_candidates(g.T, g.L, LP, g.Wq, g.Wk, g.Wv, 4, w.softmax_scale, O=O,
@@ -270,7 +286,7 @@ def test_concurrent_requests_on_separate_streams():
     torch.cuda.synchronize()
     for k in range(n):
         assert torch.equal(got[k][0], want[k][0]), f"link states of request {k}"
-        assert torch.equal(got[k][1], want[k][1]), f"candidate outputs of request {k}"
+        assert torch.equal(got[k][1], want[k][2 if (k + reps - 1) % 2 else 1]), f"candidate outputs of request {k}"
 
 
 @pytest.mark.parametrize("scale", [-0.2, 0.0])
