@@ -35,6 +35,11 @@ Readings of points the paper leaves open (each is repeated where it is used):
     block nor the stacking beyond Eq. 8 and the notation table: this is an
     assumption, and what is pinned below is the arithmetic of this reading.
 
+  * XORA backward (Appendix H.2): the gradients of O = phi(Q K^T) V with the
+    factor phi'(Q K^T) applied element-wise (the appendix prints it like a
+    matrix factor) and SiLU' written out as the derivative of x sigmoid(x)
+    (the expression in the listing of Algorithm 3 is not that derivative).
+
 Pinned by tests/test_oracle_*.py (closed forms, brute force, a library routine,
 invariants, hand-derived fixtures).  Unpinned: the paper's claim that LIME
 approximates full target attention (Appendix D), which needs trained links and
@@ -58,6 +63,8 @@ __all__ = [
     "lime_link_history",
     "lime_xor_history",
     "xora_quadratic",
+    "silu_derivative",
+    "xor_attention_backward",
     "gated_mlp",
     "lime_xor_layers",
     "xor_layers_quadratic",
@@ -245,6 +252,68 @@ def xora_quadratic(Eb, Lb, Wq, Wk, Wv, h, scale=1.0):
             M[i, j], denom[i] = xor_mask_and_denominator(i, j, n_s, n_t)
     O = mha(X, X, X, M, Wq, Wk, Wv, h, scale, "silu", denom=denom)
     return O[:n_s], O[n_s:]
+
+
+def silu_derivative(x):
+    """d/dx [x sigmoid(x)] = sigmoid(x) (1 + x (1 - sigmoid(x))).
+
+    (The expression printed in the listing of the backward kernel, Algorithm 3, is not this derivative; the
+    derivation of Appendix H.2 only needs phi', which is what is written here.)
+    """
+    x = _f64(x)
+    s = 1.0 / (1.0 + np.exp(-x))
+    return s * (1.0 + x * (1.0 - s))
+
+
+def xor_attention_backward(QS, KS, VS, QT, KT, VT, dOT, dOS, lens, h, scale=1.0):
+    """Gradients of one XORA layer with respect to its projected inputs (Appendix H.2).
+
+    Forward (Appendix H.1), per user and head, S = source (history rows, n_s = lens[b] valid), T = target
+    (links, n_t = m), phi = SiLU(scale .) / n:
+      O[T] = phi(Q[T] K[S]^T) V[S]   (normaliser n_s),      O[S] = phi(Q[S] K[T]^T) V[T]   (normaliser n_t).
+    O[T] does not depend on Q[S], K[T], V[T] and O[S] not on Q[T], K[S], V[S], so each direction contributes to three
+    gradients.  Written for O = phi(Q K^T) V with upstream gradient G = dL/dO and Z = scale Q K^T:
+      dL/dV = phi(Z)^T G,     D = (G V^T) * phi'(Z)  (element-wise),     dL/dQ = scale D K,     dL/dK = scale D^T Q,
+    phi'(Z) = SiLU'(Z) / n.  (Appendix H.2 prints these with phi' as if it were a matrix factor; the products of its
+    total differentials are element-wise in phi', which is the reading taken.)
+
+    QS, KS, VS [B, N, d]; QT, KT, VT [B, m, d]; dOT [B, m, d]; dOS [B, N, d] or None (O[S] unused downstream);
+    rows >= lens[b] of the source tensors take no part and get zero gradients.
+    Returns dQS, dKS, dVS [B, N, d], dQT, dKT, dVT [B, m, d].
+    """
+    QS, KS, VS, QT, KT, VT, dOT = (_f64(x) for x in (QS, KS, VS, QT, KT, VT, dOT))
+    dOS = None if dOS is None else _f64(dOS)
+    B, N, d = QS.shape
+    m = QT.shape[1]
+    dh = d // h
+    lens = _lens(lens, B, N)
+    dQS, dKS, dVS = np.zeros((B, N, d)), np.zeros((B, N, d)), np.zeros((B, N, d))
+    dQT, dKT, dVT = np.zeros((B, m, d)), np.zeros((B, m, d)), np.zeros((B, m, d))
+    for b in range(B):
+        n_s, n_t = int(lens[b]), m
+        if n_s == 0:
+            continue
+        for a in range(h):
+            c = slice(a * dh, (a + 1) * dh)
+            qs, ks, vs = QS[b, :n_s, c], KS[b, :n_s, c], VS[b, :n_s, c]
+            qt, kt, vt = QT[b, :, c], KT[b, :, c], VT[b, :, c]
+            # O[T]: the links attend over the history
+            G = dOT[b, :, c]
+            Z = scale * (qt @ ks.T)
+            D = (G @ vs.T) * silu_derivative(Z) / n_s
+            dVS[b, :n_s, c] = (silu(Z) / n_s).T @ G
+            dQT[b, :, c] = scale * (D @ ks)
+            dKS[b, :n_s, c] = scale * (D.T @ qt)
+            if dOS is None:
+                continue
+            # O[S]: the history attends back to the links
+            G = dOS[b, :n_s, c]
+            Z = scale * (qs @ kt.T)
+            D = (G @ vt.T) * silu_derivative(Z) / n_t
+            dVT[b, :, c] = (silu(Z) / n_t).T @ G
+            dQS[b, :n_s, c] = scale * (D @ kt)
+            dKT[b, :, c] = scale * (D.T @ qs)
+    return dQS, dKS, dVS, dQT, dKT, dVT
 
 
 def gated_mlp(A, X, Wu, Wo):

@@ -512,7 +512,92 @@ def check_xor_layers_structure():
     assert not f(p["E"], [0, 6], p["Wu"], p["Wo"])[0].any()
 
 
+def _backward_problem(seed=11, B=2, N=5, m=4, d=6, lens=(5, 3)):
+    rng = np.random.default_rng(seed)
+    t = {k: rng.standard_normal((B, N, d)) for k in ("QS", "KS", "VS", "dOS")}
+    t.update({k: rng.standard_normal((B, m, d)) for k in ("QT", "KT", "VT", "dOT")})
+    t["lens"] = np.array(lens, dtype=np.int32)
+    return t
+
+
+def _xora_loss(t, h, scale):
+    """sum(O[T] * dOT) + sum(O[S] * dOS) with the forward of Appendix H.1 from the oracle's own MHA (weights absent)."""
+    loss = 0.0
+    m = t["QT"].shape[1]
+    for b, n_s in enumerate(t["lens"]):
+        if n_s == 0:
+            continue
+        OT = orc.mha(t["QT"][b], t["KS"][b, :n_s], t["VS"][b, :n_s], None, None, None, None, h, scale, "silu",
+                     denom=np.full(m, n_s))
+        OS = orc.mha(t["QS"][b, :n_s], t["KT"][b], t["VT"][b], None, None, None, None, h, scale, "silu",
+                     denom=np.full(n_s, m))
+        loss += (OT * t["dOT"][b]).sum() + (OS * t["dOS"][b, :n_s]).sum()
+    return loss
+
+
+def check_xor_backward_against_finite_differences():
+    """Appendix H.2: every entry of the six gradients equals the central difference of the scalar
+    sum(O[T] dOT) + sum(O[S] dOS) through the (separately pinned) forward; padded rows get exactly zero."""
+    h, scale = 2, 0.7
+    t = _backward_problem()
+    grads = dict(zip(("QS", "KS", "VS", "QT", "KT", "VT"),
+                     orc.xor_attention_backward(t["QS"], t["KS"], t["VS"], t["QT"], t["KT"], t["VT"], t["dOT"], t["dOS"],
+                                                t["lens"], h, scale)))
+    eps = 1e-5
+    for name, g in grads.items():
+        for idx in np.ndindex(*g.shape):
+            if name.endswith("S") and idx[1] >= t["lens"][idx[0]]:
+                assert g[idx] == 0.0, (name, idx)
+                continue
+            keep = t[name][idx]
+            t[name][idx] = keep + eps
+            up = _xora_loss(t, h, scale)
+            t[name][idx] = keep - eps
+            down = _xora_loss(t, h, scale)
+            t[name][idx] = keep
+            np.testing.assert_allclose(g[idx], (up - down) / (2 * eps), rtol=2e-6, atol=2e-8, err_msg=f"d{name}{idx}")
+
+
+def check_xor_backward_closed_forms_and_structure():
+    """Zero queries: Z = 0, SiLU(0) = 0 and SiLU'(0) = 1/2, so dV = 0, dK = 0 and dQ = scale ((G V^T) / (2 n)) K.
+    Without dOS the three gradients that only O[S] feeds are zero; the gradients are linear in the upstream ones;
+    padded rows may hold anything."""
+    h, scale = 3, 1.3
+    t = _backward_problem(seed=5, d=6, lens=(4, 5))
+    z = np.zeros_like
+    dQS, dKS, dVS, dQT, dKT, dVT = orc.xor_attention_backward(z(t["QS"]), t["KS"], t["VS"], z(t["QT"]), t["KT"], t["VT"],
+                                                              t["dOT"], t["dOS"], t["lens"], h, scale)
+    for g in (dVS, dVT, dKS, dKT):
+        assert not g.any()
+    dh = 2
+    for b, n_s in enumerate(t["lens"]):
+        for a in range(h):
+            c = slice(a * dh, (a + 1) * dh)
+            want_t = scale * ((t["dOT"][b, :, c] @ t["VS"][b, :n_s, c].T) / (2 * n_s)) @ t["KS"][b, :n_s, c]
+            want_s = scale * ((t["dOS"][b, :n_s, c] @ t["VT"][b, :, c].T) / (2 * 4)) @ t["KT"][b, :, c]
+            np.testing.assert_allclose(dQT[b, :, c], want_t, atol=1e-12)
+            np.testing.assert_allclose(dQS[b, :n_s, c], want_s, atol=1e-12)
+    args = (t["QS"], t["KS"], t["VS"], t["QT"], t["KT"], t["VT"])
+    full = orc.xor_attention_backward(*args, t["dOT"], t["dOS"], t["lens"], h, scale)
+    only_t = orc.xor_attention_backward(*args, t["dOT"], None, t["lens"], h, scale)
+    assert not only_t[0].any() and not only_t[4].any() and not only_t[5].any()
+    only_s = orc.xor_attention_backward(*args, z(t["dOT"]), t["dOS"], t["lens"], h, scale)
+    for f, a_, b_ in zip(full, only_t, only_s):
+        np.testing.assert_allclose(f, a_ + b_, atol=1e-12)
+    doubled = orc.xor_attention_backward(*args, 2 * t["dOT"], 2 * t["dOS"], t["lens"], h, scale)
+    for f, g in zip(full, doubled):
+        np.testing.assert_allclose(g, 2 * f, atol=1e-12)
+    bad = [x.copy() for x in args] + [t["dOT"], t["dOS"].copy()]
+    for x in (bad[0], bad[1], bad[2], bad[7]):
+        x[0, 4:] = np.nan
+    for f, g in zip(full, orc.xor_attention_backward(*bad, t["lens"], h, scale)):
+        np.testing.assert_array_equal(f, g)
+    assert not any(g[1].any() for g in orc.xor_attention_backward(*args, t["dOT"], t["dOS"], [4, 0], h, scale))
+
+
 PINS = [
+    check_xor_backward_against_finite_differences,
+    check_xor_backward_closed_forms_and_structure,
     check_xor_layers_one_layer_from_scalars,
     check_xor_layers_block_equals_quadratic,
     check_xor_layers_structure,
@@ -660,7 +745,41 @@ def _make_layers_mutant(kind):
     return mutant
 
 
+def _mut_sigmoid_derivative(x):
+    x = np.asarray(x, dtype=np.float64)
+    s = 1.0 / (1.0 + np.exp(-x))
+    return s * (1.0 - s)
+
+
+def _mut_silu_derivative_without_sigmoid_factor(x):
+    x = np.asarray(x, dtype=np.float64)
+    s = 1.0 / (1.0 + np.exp(-x))
+    return s * (1.0 - s) * (1.0 + x)
+
+
+def _make_backward_mutant(kind):
+    real = orc.xor_attention_backward
+
+    def mutant(QS, KS, VS, QT, KT, VT, dOT, dOS, lens, h, scale=1.0):
+        dQS, dKS, dVS, dQT, dKT, dVT = real(QS, KS, VS, QT, KT, VT, dOT, dOS, lens, h, scale)
+        if kind == "queries_without_scale":
+            return dQS / scale, dKS, dVS, dQT / scale, dKT, dVT
+        if kind == "directions_swapped":  # each direction's key/value gradients land on the other side's tensors
+            return real(QT, KT, VT, QS, KS, VS, dOS, dOT, None, h, scale)[3:] + real(QT, KT, VT, QS, KS, VS, dOS, dOT, None, h, scale)[:3]
+        if kind == "padding_counted":
+            return real(QS, KS, VS, QT, KT, VT, dOT, dOS, None, h, scale)
+        raise ValueError(kind)
+
+    mutant.__name__ = f"backward_{kind}"
+    return mutant
+
+
 MUTATIONS = [
+    ("silu_derivative", _mut_sigmoid_derivative),
+    ("silu_derivative", _mut_silu_derivative_without_sigmoid_factor),
+    ("xor_attention_backward", _make_backward_mutant("queries_without_scale")),
+    ("xor_attention_backward", _make_backward_mutant("directions_swapped")),
+    ("xor_attention_backward", _make_backward_mutant("padding_counted")),
     ("lime_xor_layers", _make_layers_mutant("no_residual")),
     ("lime_xor_layers", _make_layers_mutant("last_layer_only")),
     ("lime_xor_layers", _make_layers_mutant("links_not_updated")),
