@@ -52,7 +52,7 @@ enum { LIME_OK = 0, LIME_INVALID_ARG = 1, LIME_UNSUPPORTED = 2, LIME_WORKSPACE_T
 enum { LIME_F32 = 0, LIME_BF16 = 1 };
 enum { LIME_OP_LINK_HISTORY = 0, LIME_OP_XOR_HISTORY = 1, LIME_OP_SCORE_CANDIDATES = 2, LIME_OP_MHA_TARGET = 3,
        LIME_OP_BUILD_QK_CACHE = 4, LIME_OP_SCORE_CACHED = 5, LIME_OP_XOR_LAYERS = 6, LIME_OP_REQUEST_PREPARED = 7,
-       LIME_OP_REQUEST = 8 };
+       LIME_OP_REQUEST = 8, LIME_OP_XOR_BACKWARD = 9 };
 
 /*
  * User-side link personalisation, Section 3.1 Eq. 3:
@@ -204,6 +204,25 @@ int32_t lime_request(const void* E, const int32_t* lens, const void* LC, int64_t
                      const void* Wk_cand, const void* Wv_cand, void* LP, void* O, int32_t B, int32_t N, int32_t C,
                      int32_t d, int32_t h, int32_t m, float scale_hist, float scale_cand, int32_t xor_attention,
                      int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * Backward pass of one XORA layer with respect to its projected inputs (Appendix H.2; forward: Appendix H.1, Eq. 7).
+ * Per user b and head (d cut into h contiguous blocks), with S the history rows (lens[b] valid, lens NULL = all N),
+ * T the m links and phi(x) = SiLU(scale x) / n:
+ *     O[T] = phi(Q[T] K[S]^T) V[S]  (n = lens[b]),        O[S] = phi(Q[S] K[T]^T) V[T]  (n = m).
+ * Given the upstream gradients dOT[B][m][d] and dOS[B][N][d] (dOS NULL: O[S] has no consumer, its three gradients
+ * are zero) the call writes dQS, dKS, dVS [B][N][d] and dQT, dKT, dVT [B][m][d] (links per user; for shared links
+ * the caller sums over users).  For O = phi(Q K^T) V and G = dL/dO:  dV = phi(Z)^T G,  E = (G V^T) * phi'(Z)
+ * element-wise,  dQ = scale E K,  dK = scale E^T Q,  Z = scale Q K^T,  SiLU'(x) = s (1 + x (1 - s)), s = sigmoid(x).
+ * History rows at or past lens[b] are never read and get zero gradients; a user with lens[b] = 0 gets all zeros.
+ * All pointers device memory, row-major, storage type `dtype`; fp32 arithmetic; the attention matrices are
+ * recomputed in tiles, nothing of size N x m is stored.  Deterministic (no atomics).  d/h <= 64, otherwise
+ * LIME_UNSUPPORTED.  Workspace: LIME_OP_XOR_BACKWARD (partial sums of the link-side gradients).
+ */
+int32_t lime_xor_backward(const void* QS, const void* KS, const void* VS, const void* QT, const void* KT, const void* VT,
+                          const void* dOT, const void* dOS, const int32_t* lens, void* dQS, void* dKS, void* dVS,
+                          void* dQT, void* dKT, void* dVT, int32_t B, int32_t N, int32_t m, int32_t d, int32_t h,
+                          float scale, int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
 
 /*
  * Workspace size in bytes for `op` (LIME_OP_*) at the given shape; dimensions an op

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "liblime_hip.so")
 
 LIME_F32, LIME_BF16 = 0, 1
 (OP_LINK_HISTORY, OP_XOR_HISTORY, OP_SCORE_CANDIDATES, OP_MHA_TARGET, OP_BUILD_QK_CACHE, OP_SCORE_CACHED,
- OP_XOR_LAYERS, OP_REQUEST_PREPARED, OP_REQUEST) = range(9)
+ OP_XOR_LAYERS, OP_REQUEST_PREPARED, OP_REQUEST, OP_XOR_BACKWARD) = range(10)
 STATUS_NAMES = {0: "LIME_OK", 1: "LIME_INVALID_ARG", 2: "LIME_UNSUPPORTED", 3: "LIME_WORKSPACE_TOO_SMALL",
                 4: "LIME_LAUNCH_FAILED"}
 
@@ -49,6 +49,7 @@ SIGNATURES = {
                                      _i32, _i32, _vp, _sz, _vp]),
     "lime_request": (_i32, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
                             _i32, _i32, _f32, _f32, _i32, _i32, _vp, _sz, _vp]),
+    "lime_xor_backward": (_i32, [_vp] * 15 + [_i32] * 5 + [_f32, _i32, _vp, _sz, _vp]),
     "lime_score_candidates_gathered": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _sz,
                                               _vp]),
     "lime_workspace_bytes": (_sz, [_i32] * 9),
@@ -365,6 +366,26 @@ def lime_score_candidates_prepared(T, LP, Wv, prepared, h, scale, O=None, worksp
                                                   float(scale), code, _ptr(ws), ws.numel(), _stream(stream))
     _raise(st)
     return O
+
+
+def lime_xor_backward(QS, KS, VS, QT, KT, VT, dOT, dOS, lens, h, scale=1.0, workspace=None, stream=None):
+    """Gradients of one XORA layer w.r.t. its projected inputs (Appendix H.2): returns (dQS, dKS, dVS, dQT, dKT, dVT)."""
+    first = _check(QS, KS, VS, QT, KT, VT, dOT, dOS)
+    B, N, d = QS.shape
+    m = QT.shape[1]
+    if QT.dim() != 3 or QT.shape[0] != B:
+        raise ValueError("the projected links must be per user: [B, m, d]")
+    code = _dtype_code(first)
+    lens = _lens_arg(lens, B, QS.device)
+    outs = [torch.empty_like(QS) for _ in range(3)] + [torch.empty_like(QT) for _ in range(3)]
+    need = workspace_bytes(OP_XOR_BACKWARD, B=B, N=N, d=d, h=h, m=m, dtype=code)
+    ws = workspace if workspace is not None else get_workspace(need, QS.device)
+    with torch.cuda.device(QS.device):
+        st = lib().lime_xor_backward(_ptr(QS), _ptr(KS), _ptr(VS), _ptr(QT), _ptr(KT), _ptr(VT), _ptr(dOT), _ptr(dOS),
+                                     _ptr(lens), *[_ptr(o) for o in outs], B, N, m, d, h, float(scale), code, _ptr(ws),
+                                     ws.numel(), _stream(stream))
+    _raise(st)
+    return tuple(outs)
 
 
 def lime_request(E, lens, LC, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand, Wv_cand, h, scale_hist, scale_cand,

@@ -624,6 +624,28 @@ int32_t lime_xor_layers(const void* E, const int32_t* lens, const void* LC, int6
   return LIME_OK;
 }
 
+int32_t lime_xor_backward(const void* QS, const void* KS, const void* VS, const void* QT, const void* KT, const void* VT,
+                          const void* dOT, const void* dOS, const int32_t* lens, void* dQS, void* dKS, void* dVS,
+                          void* dQT, void* dKT, void* dVT, int32_t B, int32_t N, int32_t m, int32_t d, int32_t h,
+                          float scale, int32_t dtype, void* workspace, size_t ws_bytes, void* stream) {
+  const char* fn = "lime_xor_backward";
+  if (int32_t st = check_common(fn, B, d, h, dtype)) return st;
+  if (N <= 0 || m <= 0) return fail(LIME_INVALID_ARG, "%s: N and m must be positive (N=%d m=%d)", fn, N, m);
+  if (!QS || !KS || !VS || !QT || !KT || !VT || !dOT || !dQS || !dKS || !dVS || !dQT || !dKT || !dVT)
+    return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  if (!lime::xor_backward_supported(d, h))
+    return fail(LIME_UNSUPPORTED, "%s: head width d/h = %d is beyond the %d this kernel is built for", fn, d / h, 64);
+  const size_t need = lime::xor_backward_workspace(B, N, m, d, h);
+  if (!workspace || ws_bytes < need)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? ws_bytes : 0);
+  lime::XorBackward g{};
+  g.QS = QS, g.KS = KS, g.VS = VS, g.QT = QT, g.KT = KT, g.VT = VT, g.dOT = dOT, g.dOS = dOS, g.lens = lens;
+  g.dQS = dQS, g.dKS = dKS, g.dVS = dVS, g.dQT = dQT, g.dKT = dKT, g.dVT = dVT;
+  g.B = B, g.N = N, g.m = m, g.d = d, g.h = h, g.dtype = dtype, g.scale = scale;
+  LIME_HIP(lime::xor_backward(g, workspace, static_cast<hipStream_t>(stream)));
+  return LIME_OK;
+}
+
 size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t d, int32_t h, int32_t m,
                             int32_t dtype, int32_t flags) {
   if (B <= 0 || d <= 0 || h <= 0 || d % h != 0 || d / h > kMaxHeadDim || B > kMaxUsers) return 0;
@@ -641,6 +663,9 @@ size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t
                                   (os ? lime::queries_over_links_workspace(B, d, m, true) : size_t{0}));
       return need;
     }
+    case LIME_OP_XOR_BACKWARD:
+      if (N <= 0 || m <= 0 || !lime::xor_backward_supported(d, h)) return 0;
+      return lime::xor_backward_workspace(B, N, m, d, h);
     case LIME_OP_REQUEST:
       if (N <= 0 || C <= 0 || m <= 0) return 0;
       return lime_workspace_bytes(LIME_OP_LINK_HISTORY, B, N, C, d, h, m, dtype, 0) +

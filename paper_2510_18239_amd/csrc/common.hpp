@@ -86,4 +86,20 @@ struct GenericGatedBlock {
 };
 hipError_t generic_gated_block(const GenericGatedBlock& g, hipStream_t s);
 
+// Gradients of one XORA layer with respect to its projected inputs (Appendix H.2); fp32 arithmetic, any storage type.
+struct XorBackward {
+  const void *QS, *KS, *VS;     // [B][N][d] projected history rows
+  const void *QT, *KT, *VT;     // [B][m][d] projected links, per user
+  const void* dOT;              // [B][m][d]
+  const void* dOS;              // [B][N][d], nullable: O[S] has no consumer
+  const int32_t* lens;          // nullable
+  void *dQS, *dKS, *dVS;        // [B][N][d]
+  void *dQT, *dKT, *dVT;        // [B][m][d]
+  int B, N, m, d, h, dtype;     // dtype: 0 = fp32, 1 = bf16 storage
+  float scale;
+};
+bool xor_backward_supported(int d, int h);  // d/h <= 64
+size_t xor_backward_workspace(int B, int N, int m, int d, int h);
+hipError_t xor_backward(const XorBackward& g, void* workspace, hipStream_t s);
+
 }  // namespace lime

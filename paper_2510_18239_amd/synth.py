@@ -21,7 +21,9 @@ from dataclasses import dataclass, field
 import numpy as np
 
 BASE_SEED = 20251018
-_TENSOR_INDEX = {"E": 0, "T": 1, "L": 2, "Wq": 3, "Wk": 4, "Wv": 5, "lens": 6, "LCu": 7}
+_TENSOR_INDEX = {"E": 0, "T": 1, "L": 2, "Wq": 3, "Wk": 4, "Wv": 5, "lens": 6, "LCu": 7,
+                 "bwdQS": 10, "bwdKS": 11, "bwdVS": 12, "bwddOS": 13, "bwdQT": 14, "bwdKT": 15, "bwdVT": 16, "bwddOT": 17,
+                 "bwdlens": 18}
 
 
 def _rng(workload: int, name: str) -> np.random.Generator:
@@ -108,6 +110,31 @@ def per_user_links(workload: int, B: int, m: int, d: int, dtype: str, gain: floa
     """Per-user contextualised links L^C [B, m, d] (stand-in for the output of Eq. 2)."""
     x = _rng(workload, "LCu").standard_normal((B, m, d), dtype=np.float32) * np.float32(gain * d ** -0.5)
     return round_to(x, dtype)
+
+
+def backward_inputs(workload: int, B: int, N: int, m: int, d: int, h: int, dtype: str, logit_std: float = 1.0,
+                    len_range=None, pad_value: float = 0.0) -> dict:
+    """Inputs of the XORA backward pass: projected history rows QS, KS, VS [B, N, d], projected per-user links
+    QT, KT, VT [B, m, d] and upstream gradients dOS, dOT of the same shapes, all ~N(0, std^2) and rounded to the
+    storage type.  Queries and keys have the standard deviation that gives un-scaled logits <q_head, k_head> a
+    standard deviation of ``logit_std`` (the trained layer runs with logits of order one); values and gradients have
+    unit entries.  ``lens`` as in make_workload; rows at or past lens[b] of the history tensors hold ``pad_value``."""
+    dh = d // h
+    qk_std = float((logit_std / np.sqrt(dh)) ** 0.5)
+    t = {}
+    for name, rows, std in (("QS", N, qk_std), ("KS", N, qk_std), ("VS", N, 1.0), ("dOS", N, 1.0),
+                            ("QT", m, qk_std), ("KT", m, qk_std), ("VT", m, 1.0), ("dOT", m, 1.0)):
+        x = _rng(workload, "bwd" + name).standard_normal((B, rows, d), dtype=np.float32) * np.float32(std)
+        t[name] = round_to(x, dtype)
+    if len_range is None:
+        t["lens"] = None
+    else:
+        lens = _rng(workload, "bwdlens").integers(len_range[0], len_range[1] + 1, size=B).astype(np.int32)
+        t["lens"] = lens
+        for b in range(B):
+            for name in ("QS", "KS", "VS", "dOS"):
+                t[name][b, lens[b]:] = pad_value
+    return t
 
 
 def sharp_gain(d: int, h: int, scale: float, logit_std: float = 2.0) -> float:

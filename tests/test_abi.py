@@ -233,3 +233,25 @@ def test_request_argument_checks():
     assert call(Wqc=None, Wkc=None, Wvc=None) == 3  # identity on the candidate side is allowed: only the workspace is wrong
     assert call(dtype=5) == 1 or call(dtype=5) == 2
     assert binding.workspace_bytes(binding.OP_REQUEST, B=1, N=64, C=0, d=256, h=4, m=64) == 0
+
+
+def test_xor_backward_argument_checks():
+    lib = binding.lib()
+
+    def call(**kw):
+        a = dict(ins=[FAKE] * 7, dOS=FAKE, lens=None, outs=[FAKE] * 6, B=2, N=100, m=64, d=128, h=4, scale=1.0, dtype=1,
+                 ws=FAKE, ws_bytes=0, stream=None)
+        a.update(kw)
+        return lib.lime_xor_backward(*a["ins"], a["dOS"], a["lens"], *a["outs"], a["B"], a["N"], a["m"], a["d"], a["h"],
+                                     a["scale"], a["dtype"], a["ws"], a["ws_bytes"], a["stream"])
+
+    need = binding.workspace_bytes(binding.OP_XOR_BACKWARD, B=2, N=100, d=128, h=4, m=64)
+    assert need > 0 and call() == 3 and str(need) in binding.last_error()
+    assert call(dOS=None) == 3  # the source-side gradient may be absent: only the workspace is wrong here
+    for i in range(7):
+        assert call(ins=[None if j == i else FAKE for j in range(7)]) == 1
+    for i in range(6):
+        assert call(outs=[None if j == i else FAKE for j in range(6)]) == 1
+    assert call(N=0) == 1 and call(m=0) == 1 and call(d=130, h=4) != 0
+    assert call(d=512, h=2) == 2 and "64" in binding.last_error()  # d/h = 256: beyond this kernel
+    assert binding.workspace_bytes(binding.OP_XOR_BACKWARD, B=2, N=100, d=512, h=2, m=64) == 0
