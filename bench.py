@@ -46,6 +46,8 @@ def parse_args():
                    help="a request as one C-ABI call (lime_request) or as lime_link_history + lime_score_candidates")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--extras", action="store_true", help="also time the XORA history pass, the C sweep and the MHA baseline")
+    p.add_argument("--xor-backward", type=int, default=0, metavar="N",
+                   help="only run lime_xor_backward (configuration 4's shape) at history length N, --steps times: for profiling")
     p.add_argument("--xor-layers", type=int, default=0, metavar="N",
                    help="only run lime_xor_layers (three layers, configuration 4) at history length N, --steps times: "
                         "the command behind the kernel-trace summary of that call")
@@ -69,6 +71,9 @@ def main():
 
     if args.xor_layers > 0:
         xor_layers_only(args, binding, synth, torch, dev)
+        return
+    if args.xor_backward > 0:
+        xor_backward_only(args, binding, synth, torch, dev)
         return
 
     cfg = dict(synth.CONFIGS[3])
@@ -389,6 +394,32 @@ def xor_layers_only(args, binding, synth, torch, dev):
     ms = sorted(a.elapsed_time(b) for a, b in evs)
     print(json.dumps({"call": "lime_xor_layers", "layers": 3, "B": w.B, "N": w.N, "d": w.d, "h": w.h, "m": w.m,
                       "steps": args.steps, "p50_ms": ms[len(ms) // 2], "p10_ms": ms[len(ms) // 10]}))
+
+
+def xor_backward_only(args, binding, synth, torch, dev):
+    """lime_xor_backward alone (configuration 4's shape: B = 8, d = 128, h = 4, m = 64; Appendix H.2), for profiling."""
+    c4 = synth.CONFIGS[4]
+    N = args.xor_backward
+    tb = synth.backward_inputs(4, c4["B"], N, c4["m"], c4["d"], c4["h"], "bf16")
+    g = {k: torch.from_numpy(v).to(torch.bfloat16).to(dev) for k, v in tb.items() if k != "lens"}
+
+    def call():
+        binding.lime_xor_backward(g["QS"], g["KS"], g["VS"], g["QT"], g["KT"], g["VT"], g["dOT"], g["dOS"], None, c4["h"], 1.0)
+
+    for _ in range(args.warmup):
+        call()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for a, b in evs:
+        a.record()
+        call()
+        b.record()
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in evs)
+    flops = 20.0 * N * c4["m"] * c4["d"] * c4["B"]
+    print(json.dumps({"call": "lime_xor_backward", "B": c4["B"], "N": N, "d": c4["d"], "h": c4["h"], "m": c4["m"],
+                      "steps": args.steps, "p50_ms": ms[len(ms) // 2], "p10_ms": ms[len(ms) // 10],
+                      "algorithmic_TFLOPs": flops / (ms[len(ms) // 2] * 1e-3) / 1e12}))
 
 
 def extras(binding, synth, torch, dev, timed, pct):

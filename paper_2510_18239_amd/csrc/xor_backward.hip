@@ -10,7 +10,7 @@
 //   z2 = scale <Q[X]_r, K[Y]_c>,  e2 = <G[X]_r, V[Y]_c> SiLU'(z2) / n_Y
 //       dQ[X]_r += scale e2 K[Y]_c
 // (phi' applied element-wise; SiLU'(x) = s (1 + x (1 - s)), s = sigmoid(x)).  One kernel does this for a block of
-// 32 rows of X against a range of rows of Y; it runs once with X = history rows (all links as Y, results stored
+// 32 rows of X against a range of rows of Y (32 or 16 at a time); it runs once with X = history rows (all links as Y, results stored
 // directly) and once with X = links (the history rows as Y, cut into chunks whose partial sums a second kernel adds
 // in ascending order: deterministic, no atomics).
 #include "common.hpp"
@@ -19,9 +19,7 @@ namespace lime {
 namespace {
 
 constexpr int kOwn = 32;    // rows of X per workgroup
-constexpr int kOther = 16;  // rows of Y per step
-constexpr int kMaxDh = 64;  // head width the LDS tiles are sized for
-constexpr int kColsPerThread = kMaxDh / 8;
+constexpr int kMaxDh = 64;  // widest head
 
 struct SideArgs {
   const void *qx, *kx, *vx, *gx;  // [B][rows_x][d]; gx nullable (no upstream gradient for O[X])
@@ -30,7 +28,7 @@ struct SideArgs {
   float* partial;                 // [B][chunks][3][rows_x][d]: written when chunks > 1
   const int32_t* lens;            // valid history rows per user, nullable = all
   int own_is_history;             // which side the lengths apply to
-  int rows_x, rows_y, d, dh, chunks, chunk_rows;  // chunk_rows: rows of Y per chunk, a multiple of kOther
+  int rows_x, rows_y, d, dh, chunks, chunk_rows;  // chunk_rows: rows of Y per chunk, a multiple of the step
   float scale;
 };
 
@@ -39,16 +37,27 @@ __device__ __forceinline__ float silu_derivative_f(float x) {
   const float s = 1.f / (1.f + __expf(-x));
   return s * (1.f + x * (1.f - s));
 }
+__device__ __forceinline__ float dot4(const float4& a, const float4& b, float c) {
+  return fmaf(a.w, b.w, fmaf(a.z, b.z, fmaf(a.y, b.y, fmaf(a.x, b.x, c))));
+}
 
-template <typename T>
+// DHM: the head width the LDS tiles are sized for (d/h <= DHM); OTHER: rows of Y per step (32, or 16 where the
+// wider head would not leave room).  The tiles are stored transposed, [column of the head][row], so that a thread
+// reads two adjacent rows (dot-product step) or four adjacent rows of Y (accumulation step) with one LDS access:
+// the vector ALUs, not the LDS, then set the pace.
+template <typename T, int DHM, int OTHER>
 __global__ __launch_bounds__(256) void xor_backward_side_kernel(SideArgs a) {
-  __shared__ float own[4][kOwn][kMaxDh + 1];      // q, k, v, g of the block's rows of X (head slice)
-  __shared__ float other[4][kOther][kMaxDh + 1];  // q, k, v, g of the current rows of Y
-  __shared__ float p1[kOwn][kOther + 1], e1[kOwn][kOther + 1], e2[kOwn][kOther + 1];
+  constexpr int SX = kOwn + 4, SY = OTHER + 4;  // row pitches: multiples of four words (16-byte reads), not of 32
+  constexpr int CP = OTHER / 16;                // columns of the pair tile per thread in the dot-product step
+  constexpr int J = DHM / 8;                    // output columns per thread
+  __shared__ __align__(16) float own[4][DHM][SX];    // q, k, v, g of the block's rows of X (head slice)
+  __shared__ __align__(16) float other[4][DHM][SY];  // q, k, v, g of the current rows of Y
+  __shared__ __align__(16) float p1[kOwn][SY], e1[kOwn][SY], e2[kOwn][SY];
   const int tid = threadIdx.x, dh = a.dh, d = a.d;
   const int blocks_x = (a.rows_x + kOwn - 1) / kOwn;
   const int xb = blockIdx.x % blocks_x, chunk = blockIdx.x / blocks_x, head = blockIdx.y, b = blockIdx.z;
-  const int len = a.lens ? min(max(a.lens[b], 0), a.own_is_history ? a.rows_x : a.rows_y) : (a.own_is_history ? a.rows_x : a.rows_y);
+  const int hist_rows = a.own_is_history ? a.rows_x : a.rows_y;
+  const int len = a.lens ? min(max(a.lens[b], 0), hist_rows) : hist_rows;
   const int valid_x = a.own_is_history ? len : a.rows_x, valid_y = a.own_is_history ? a.rows_y : len;
   const float inv_nx = valid_x > 0 ? 1.f / static_cast<float>(valid_x) : 0.f;
   const float inv_ny = valid_y > 0 ? 1.f / static_cast<float>(valid_y) : 0.f;
@@ -59,50 +68,92 @@ __global__ __launch_bounds__(256) void xor_backward_side_kernel(SideArgs a) {
   const T* other_src[4] = {static_cast<const T*>(a.qy), static_cast<const T*>(a.ky), static_cast<const T*>(a.vy),
                            static_cast<const T*>(a.gy)};
   // rows past the valid ones (padding, or past the end of the tensor) are never read: they count as zeros
-  for (int i = tid; i < 4 * kOwn * dh; i += 256) {
-    const int w = i / (kOwn * dh), r = (i / dh) % kOwn, t = i % dh;
-    own[w][r][t] = (own_src[w] != nullptr && r0 + r < valid_x) ? to_float(own_src[w][x_base + static_cast<int64_t>(r) * d + t]) : 0.f;
+  // (indexed by the tile's compile-time width, so that the index arithmetic is shifts; columns past d/h are skipped)
+  for (int i = tid; i < 4 * kOwn * DHM; i += 256) {
+    const int w = i / (kOwn * DHM), r = (i / DHM) % kOwn, t = i % DHM;
+    if (t < dh)
+      own[w][t][r] = (own_src[w] != nullptr && r0 + r < valid_x) ? to_float(own_src[w][x_base + static_cast<int64_t>(r) * d + t]) : 0.f;
   }
-  // thread (r, tc) owns columns tc, tc + 8, ... of row r of the three outputs
+  // accumulation step: thread (r, tc) owns columns tc, tc + 8, ... of row r of the three outputs
   const int r = tid / 8, tc = tid % 8;
-  float dq[kColsPerThread], dk[kColsPerThread], dv[kColsPerThread];
+  float dq[J], dk[J], dv[J];
 #pragma unroll
-  for (int j = 0; j < kColsPerThread; ++j) dq[j] = dk[j] = dv[j] = 0.f;
+  for (int j = 0; j < J; ++j) dq[j] = dk[j] = dv[j] = 0.f;
+  // dot-product step: thread owns rows pr0, pr0 + 1 and columns pc0 .. pc0 + CP - 1 of the kOwn x OTHER pair tile
+  const int pr0 = 2 * (tid / 16), pc0 = CP * (tid % 16);
 
   const int c_begin = chunk * a.chunk_rows, c_end = min(c_begin + a.chunk_rows, valid_y);
-  for (int c0 = c_begin; c0 < c_end; c0 += kOther) {
-    __syncthreads();  // the previous step is done with `other`, p1, e1, e2 (and `own` is complete)
+  // The rows of Y for the next step are asked for before the current step is computed and parked in LDS after it:
+  // a step's loads are in flight while the previous one keeps the vector ALUs busy.
+  constexpr int kLoads = 4 * OTHER * DHM / 256;
+  float ahead[kLoads];
+  auto ask = [&](int c0) {
     const int64_t y_base = (static_cast<int64_t>(b) * a.rows_y + c0) * d + head * dh;
-    for (int i = tid; i < 4 * kOther * dh; i += 256) {
-      const int w = i / (kOther * dh), c = (i / dh) % kOther, t = i % dh;
-      other[w][c][t] = (other_src[w] != nullptr && c0 + c < c_end) ? to_float(other_src[w][y_base + static_cast<int64_t>(c) * d + t]) : 0.f;
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      const int i = tid + 256 * k;
+      const int w = i / (OTHER * DHM), c = (i / DHM) % OTHER, t = i % DHM;
+      ahead[k] = (t < dh && other_src[w] != nullptr && c0 + c < c_end)
+                     ? to_float(other_src[w][y_base + static_cast<int64_t>(c) * d + t]) : 0.f;
+    }
+  };
+  if (c_begin < c_end) ask(c_begin);
+  for (int c0 = c_begin; c0 < c_end; c0 += OTHER) {
+    __syncthreads();  // the previous step is done with `other`, p1, e1, e2 (and `own` is complete)
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      const int i = tid + 256 * k;
+      other[i / (OTHER * DHM)][i % DHM][(i / DHM) % OTHER] = ahead[k];
     }
     __syncthreads();
-    // the kOwn x kOther pairs of this step, two per thread
-    for (int pair = tid; pair < kOwn * kOther; pair += 256) {
-      const int pr = pair / kOther, pc = pair % kOther;
-      float z1 = 0.f, w1 = 0.f, z2 = 0.f, w2 = 0.f;
-      for (int t = 0; t < dh; ++t) {
-        z1 = fmaf(other[0][pc][t], own[1][pr][t], z1);  // <Q[Y]_c, K[X]_r>
-        w1 = fmaf(other[3][pc][t], own[2][pr][t], w1);  // <G[Y]_c, V[X]_r>
-        z2 = fmaf(own[0][pr][t], other[1][pc][t], z2);  // <Q[X]_r, K[Y]_c>
-        w2 = fmaf(own[3][pr][t], other[2][pc][t], w2);  // <G[X]_r, V[Y]_c>
+    if (c0 + OTHER < c_end) ask(c0 + OTHER);
+    float z1[2][CP], w1[2][CP], z2[2][CP], w2[2][CP];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < CP; ++j) z1[i][j] = w1[i][j] = z2[i][j] = w2[i][j] = 0.f;
+    for (int t = 0; t < dh; ++t) {
+      const float2 qx = *reinterpret_cast<const float2*>(&own[0][t][pr0]);
+      const float2 kx = *reinterpret_cast<const float2*>(&own[1][t][pr0]);
+      const float2 vx = *reinterpret_cast<const float2*>(&own[2][t][pr0]);
+      const float2 gx = *reinterpret_cast<const float2*>(&own[3][t][pr0]);
+      const float xq[2] = {qx.x, qx.y}, xk[2] = {kx.x, kx.y}, xv[2] = {vx.x, vx.y}, xg[2] = {gx.x, gx.y};
+#pragma unroll
+      for (int j = 0; j < CP; ++j) {
+        const float qy = other[0][t][pc0 + j], ky = other[1][t][pc0 + j], vy = other[2][t][pc0 + j],
+                    gy = other[3][t][pc0 + j];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          z1[i][j] = fmaf(qy, xk[i], z1[i][j]);  // <Q[Y]_c, K[X]_r>
+          w1[i][j] = fmaf(gy, xv[i], w1[i][j]);  // <G[Y]_c, V[X]_r>
+          z2[i][j] = fmaf(xq[i], ky, z2[i][j]);  // <Q[X]_r, K[Y]_c>
+          w2[i][j] = fmaf(xg[i], vy, w2[i][j]);  // <G[X]_r, V[Y]_c>
+        }
       }
-      z1 *= a.scale, z2 *= a.scale;
-      const bool live = r0 + pr < valid_x && c0 + pc < c_end;
-      p1[pr][pc] = live ? silu_f(z1) * inv_nx : 0.f;
-      e1[pr][pc] = live ? w1 * silu_derivative_f(z1) * inv_nx * a.scale : 0.f;
-      e2[pr][pc] = live ? w2 * silu_derivative_f(z2) * inv_ny * a.scale : 0.f;
     }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < CP; ++j) {
+        const float s1 = z1[i][j] * a.scale, s2 = z2[i][j] * a.scale;
+        const bool live = r0 + pr0 + i < valid_x && c0 + pc0 + j < c_end;
+        p1[pr0 + i][pc0 + j] = live ? silu_f(s1) * inv_nx : 0.f;
+        e1[pr0 + i][pc0 + j] = live ? w1[i][j] * silu_derivative_f(s1) * inv_nx * a.scale : 0.f;
+        e2[pr0 + i][pc0 + j] = live ? w2[i][j] * silu_derivative_f(s2) * inv_ny * a.scale : 0.f;
+      }
     __syncthreads();
 #pragma unroll
-    for (int j = 0; j < kColsPerThread; ++j) {
-      const int t = tc + 8 * j;
-      if (t < dh) {
-        for (int c = 0; c < kOther; ++c) {
-          dv[j] = fmaf(p1[r][c], other[3][c][t], dv[j]);
-          dk[j] = fmaf(e1[r][c], other[0][c][t], dk[j]);
-          dq[j] = fmaf(e2[r][c], other[1][c][t], dq[j]);
+    for (int c = 0; c < OTHER; c += 4) {
+      const float4 p = *reinterpret_cast<const float4*>(&p1[r][c]);
+      const float4 f1 = *reinterpret_cast<const float4*>(&e1[r][c]);
+      const float4 f2 = *reinterpret_cast<const float4*>(&e2[r][c]);
+#pragma unroll
+      for (int j = 0; j < J; ++j) {
+        const int t = tc + 8 * j;
+        if (t < dh) {
+          dv[j] = dot4(p, *reinterpret_cast<const float4*>(&other[3][t][c]), dv[j]);
+          dk[j] = dot4(f1, *reinterpret_cast<const float4*>(&other[0][t][c]), dk[j]);
+          dq[j] = dot4(f2, *reinterpret_cast<const float4*>(&other[1][t][c]), dq[j]);
         }
       }
     }
@@ -110,7 +161,7 @@ __global__ __launch_bounds__(256) void xor_backward_side_kernel(SideArgs a) {
   if (r0 + r >= a.rows_x) return;
   const int64_t row = static_cast<int64_t>(b) * a.rows_x + r0 + r;
 #pragma unroll
-  for (int j = 0; j < kColsPerThread; ++j) {
+  for (int j = 0; j < J; ++j) {
     const int t = tc + 8 * j;
     if (t >= dh) continue;
     const int64_t at = row * d + head * dh + t;
@@ -140,40 +191,50 @@ __global__ __launch_bounds__(256) void xor_backward_reduce_kernel(const float* p
   store_as(out + static_cast<int64_t>(b) * plane + i, sum);
 }
 
-int chunks_for_links(int B, int N, int m, int h) {
+int step_rows(int dh) { return dh <= 32 ? 32 : 16; }
+
+int chunks_for_links(int B, int N, int m, int h, int dh) {
   // enough workgroups for two per compute unit, but no chunk shorter than one step
   const int64_t per_chunk = static_cast<int64_t>((m + kOwn - 1) / kOwn) * h * B;
   int64_t chunks = (2 * static_cast<int64_t>(compute_units()) + per_chunk - 1) / per_chunk;
-  const int64_t steps = (N + kOther - 1) / kOther;
+  const int64_t steps = (N + step_rows(dh) - 1) / step_rows(dh);
   if (chunks > steps) chunks = steps;
   if (chunks < 1) chunks = 1;
   return static_cast<int>(chunks);
 }
 
 template <typename T>
+hipError_t launch_side(const SideArgs& a, dim3 grid, hipStream_t s) {
+  if (a.dh <= 32)
+    hipLaunchKernelGGL((xor_backward_side_kernel<T, 32, 32>), grid, dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL((xor_backward_side_kernel<T, kMaxDh, 16>), grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+template <typename T>
 hipError_t xor_backward_typed(const XorBackward& g, void* workspace, hipStream_t s) {
   SideArgs a{};
   a.lens = g.lens, a.d = g.d, a.dh = g.d / g.h, a.scale = g.scale;
+  const int step = step_rows(a.dh);
   // history side: every block of 32 history rows against all links
   a.qx = g.QS, a.kx = g.KS, a.vx = g.VS, a.gx = g.dOS;
   a.qy = g.QT, a.ky = g.KT, a.vy = g.VT, a.gy = g.dOT;
   a.dq = g.dQS, a.dk = g.dKS, a.dv = g.dVS, a.partial = nullptr;
   a.own_is_history = 1, a.rows_x = g.N, a.rows_y = g.m, a.chunks = 1;
-  a.chunk_rows = (g.m + kOther - 1) / kOther * kOther;
-  hipLaunchKernelGGL(xor_backward_side_kernel<T>, dim3((g.N + kOwn - 1) / kOwn, g.h, g.B), dim3(256), 0, s, a);
-  hipError_t e = hipGetLastError();
+  a.chunk_rows = (g.m + step - 1) / step * step;
+  hipError_t e = launch_side<T>(a, dim3((g.N + kOwn - 1) / kOwn, g.h, g.B), s);
   if (e != hipSuccess) return e;
   // link side: every block of 32 links against the history rows, in chunks
-  const int chunks = chunks_for_links(g.B, g.N, g.m, g.h);
+  const int chunks = chunks_for_links(g.B, g.N, g.m, g.h, a.dh);
   a.qx = g.QT, a.kx = g.KT, a.vx = g.VT, a.gx = g.dOT;
   a.qy = g.QS, a.ky = g.KS, a.vy = g.VS, a.gy = g.dOS;
   a.dq = g.dQT, a.dk = g.dKT, a.dv = g.dVT, a.partial = static_cast<float*>(workspace);
   a.own_is_history = 0, a.rows_x = g.m, a.rows_y = g.N, a.chunks = chunks;
-  const int steps = (g.N + kOther - 1) / kOther;
-  a.chunk_rows = (steps + chunks - 1) / chunks * kOther;
+  const int steps = (g.N + step - 1) / step;
+  a.chunk_rows = (steps + chunks - 1) / chunks * step;
   const int blocks_x = (g.m + kOwn - 1) / kOwn;
-  hipLaunchKernelGGL(xor_backward_side_kernel<T>, dim3(blocks_x * chunks, g.h, g.B), dim3(256), 0, s, a);
-  e = hipGetLastError();
+  e = launch_side<T>(a, dim3(blocks_x * chunks, g.h, g.B), s);
   if (e != hipSuccess || chunks == 1) return e;
   const int64_t plane = static_cast<int64_t>(g.m) * g.d;
   hipLaunchKernelGGL(xor_backward_reduce_kernel<T>, dim3(static_cast<unsigned>((plane + 255) / 256), 3, g.B), dim3(256), 0, s,
@@ -187,7 +248,7 @@ hipError_t xor_backward_typed(const XorBackward& g, void* workspace, hipStream_t
 bool xor_backward_supported(int d, int h) { return h > 0 && d % h == 0 && d / h <= kMaxDh; }
 
 size_t xor_backward_workspace(int B, int N, int m, int d, int h) {
-  const int chunks = chunks_for_links(B, N, m, h);
+  const int chunks = chunks_for_links(B, N, m, h, d / h);
   return chunks == 1 ? 256 : align_up(static_cast<size_t>(B) * chunks * 3 * m * d * sizeof(float));
 }
 
