@@ -13,7 +13,10 @@
 // 32 rows of X against a range of rows of Y (32 or 16 at a time); it runs once with X = history rows (all links as Y, results stored
 // directly) and once with X = links (the history rows as Y, cut into chunks whose partial sums a second kernel adds
 // in ascending order: deterministic, no atomics).
+#include <algorithm>
+
 #include "common.hpp"
+#include "mfma.hpp"
 
 namespace lime {
 namespace {
@@ -178,6 +181,145 @@ __global__ __launch_bounds__(256) void xor_backward_side_kernel(SideArgs a) {
   }
 }
 
+// The same step on the matrix cores (bf16 storage, d/h = 32 or 64): every contraction is a 32 x 32 x 16 MFMA.
+// Each of the workgroup's four waves takes its own 32 rows of Y per step and runs the whole step in registers:
+//   1. the four dot-product tiles, transposed: D[c][r] = <Y-tensor_c, X-tensor_r>, A operand = rows of Y, B operand =
+//      rows of X, both read row-major with the summed head columns contiguous.  All four land in the same accumulator
+//      layout (lane = row r of X, registers = rows c of Y), so p1, e1, e2 are computed register by register;
+//   2. an accumulator block is, as it stands, the B operand of a product that sums over its rows (chained order):
+//      dV[X]^T[t][r] += sum_c G[Y]^T[t][c] p1[c][r], likewise dK with Q[Y] and e1, dQ with K[Y] and e2.  The A operand
+//      is the transposed Y tensor in the same chained order, read from a transposed copy the wave parks in its own
+//      piece of LDS (no barrier: a wave reads back only what it wrote itself);
+//   3. after the last step the four waves' sums meet in LDS in wave order and are stored.
+// Rows that are not valid are loaded as zeros, which makes every term they touch zero (SiLU(0) = 0, and e1, e2 carry
+// a dot product with the zero row).
+constexpr int kMfmaStep = 128;  // rows of Y per workgroup step: 32 per wave
+template <int DH>
+__global__ __launch_bounds__(256) void xor_backward_side_mfma_kernel(SideArgs a) {
+  constexpr int KS = DH / 16, TT = DH / 32, PITCH = 36;  // PITCH: bf16 per row of the transposed copy (8-byte reads)
+  constexpr int kWaveTile = 3 * DH * PITCH;              // bf16: transposed Q[Y], K[Y], G[Y] of one wave
+  constexpr int kRed = 3 * TT * 16 * 64;                 // floats: one wave's output accumulators
+  constexpr size_t kBytes = sizeof(float) * kRed > 2 * 4 * kWaveTile ? sizeof(float) * kRed : 2 * 4 * kWaveTile;
+  __shared__ __align__(16) unsigned char smem[kBytes];
+  const int tid = threadIdx.x, wv = tid / 64, lane = tid % 64, n = lane % 32, g = lane / 32, d = a.d;
+  const int blocks_x = (a.rows_x + kOwn - 1) / kOwn;
+  const int xb = blockIdx.x % blocks_x, chunk = blockIdx.x / blocks_x, head = blockIdx.y, b = blockIdx.z;
+  const int hist_rows = a.own_is_history ? a.rows_x : a.rows_y;
+  const int len = a.lens ? min(max(a.lens[b], 0), hist_rows) : hist_rows;
+  const int valid_x = a.own_is_history ? len : a.rows_x, valid_y = a.own_is_history ? a.rows_y : len;
+  const float inv_nx = valid_x > 0 ? 1.f / static_cast<float>(valid_x) : 0.f;
+  const float inv_ny = valid_y > 0 ? 1.f / static_cast<float>(valid_y) : 0.f;
+  const int r0 = xb * kOwn;
+  bf16x8 zero;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) zero[t] = static_cast<__bf16>(0.f);
+  // fragment ks of a row-major tensor: lane (n, g) holds columns 16ks + 8g .. + 7 of row `row` (head slice)
+  auto frag = [&](const void* base, int rows, int row, bool ok, int ks) {
+    if (base == nullptr || !ok) return zero;
+    return *reinterpret_cast<const bf16x8*>(static_cast<const bf16_t*>(base) +
+                                            (static_cast<int64_t>(b) * rows + row) * d + head * DH + 16 * ks + 8 * g);
+  };
+  // the block's rows of X as B operands (lane = row r0 + n): q, k, v, g
+  bf16x8 xq[KS], xk[KS], xv[KS], xg[KS];
+  const bool x_ok = r0 + n < valid_x;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    xq[ks] = frag(a.qx, a.rows_x, r0 + n, x_ok, ks), xk[ks] = frag(a.kx, a.rows_x, r0 + n, x_ok, ks);
+    xv[ks] = frag(a.vx, a.rows_x, r0 + n, x_ok, ks), xg[ks] = frag(a.gx, a.rows_x, r0 + n, x_ok, ks);
+  }
+  f32x16 acc[3][TT];  // dV^T, dK^T, dQ^T: lane = row r0 + n, register 4j + rr = head column 32tt + 8j + 4g + rr
+#pragma unroll
+  for (int o = 0; o < 3; ++o)
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[o][tt][i] = 0.f;
+  bf16_t* yt = reinterpret_cast<bf16_t*>(smem) + wv * kWaveTile;  // [3][DH][PITCH]: Q[Y]^T, K[Y]^T, G[Y]^T
+
+  const int c_begin = chunk * a.chunk_rows, c_end = min(c_begin + a.chunk_rows, valid_y);
+  for (int c0 = c_begin + 32 * wv; c0 < c_end; c0 += kMfmaStep) {
+    const bool y_ok = c0 + n < c_end;
+    f32x16 z1, w1, z2, w2;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) z1[i] = w1[i] = z2[i] = w2[i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const bf16x8 yq = frag(a.qy, a.rows_y, c0 + n, y_ok, ks), yk = frag(a.ky, a.rows_y, c0 + n, y_ok, ks);
+      const bf16x8 yv = frag(a.vy, a.rows_y, c0 + n, y_ok, ks), yg = frag(a.gy, a.rows_y, c0 + n, y_ok, ks);
+      z1 = mfma32(yq, xk[ks], z1);  // <Q[Y]_c, K[X]_r>
+      w1 = mfma32(yg, xv[ks], w1);  // <G[Y]_c, V[X]_r>
+      z2 = mfma32(yk, xq[ks], z2);  // <K[Y]_c, Q[X]_r>
+      w2 = mfma32(yv, xg[ks], w2);  // <V[Y]_c, G[X]_r>
+      // the transposed copy: column 16ks + 8g + t of row c0 + n goes to [column][n]
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const int col = 16 * ks + 8 * g + t;
+        store_as(yt + (0 * DH + col) * PITCH + n, static_cast<float>(yq[t]));
+        store_as(yt + (1 * DH + col) * PITCH + n, static_cast<float>(yk[t]));
+        store_as(yt + (2 * DH + col) * PITCH + n, static_cast<float>(yg[t]));
+      }
+    }
+    // phi and phi' register by register: z1 becomes p1, w1 becomes e1, w2 becomes e2
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float s1 = z1[i] * a.scale, s2 = z2[i] * a.scale;
+      z1[i] = silu_f(s1) * inv_nx;
+      w1[i] = w1[i] * silu_derivative_f(s1) * inv_nx * a.scale;
+      w2[i] = w2[i] * silu_derivative_f(s2) * inv_ny * a.scale;
+    }
+#pragma unroll
+    for (int f = 0; f < 2; ++f) {
+      const bf16x8 bp = pack_half(z1, f), be1 = pack_half(w1, f), be2 = pack_half(w2, f);
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) {
+        // slot t of lane (n, g): row c0 + 16f + chain_k(g, t) of Y, head column 32tt + n
+        auto chained = [&](int arr) {
+          const bf16_t* src = yt + (arr * DH + 32 * tt + n) * PITCH + 16 * f + 4 * g;
+          const bf16x4 lo = *reinterpret_cast<const bf16x4*>(src), hi = *reinterpret_cast<const bf16x4*>(src + 8);
+          bf16x8 v;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) v[t] = lo[t], v[4 + t] = hi[t];
+          return v;
+        };
+        acc[0][tt] = mfma32(chained(2), bp, acc[0][tt]);   // dV[X]^T += G[Y]^T p1
+        acc[1][tt] = mfma32(chained(0), be1, acc[1][tt]);  // dK[X]^T += Q[Y]^T e1
+        acc[2][tt] = mfma32(chained(1), be2, acc[2][tt]);  // dQ[X]^T += K[Y]^T e2
+      }
+    }
+  }
+  // the four waves' sums, added in wave order
+  float* red = reinterpret_cast<float*>(smem);
+  for (int turn = 0; turn < 4; ++turn) {
+    __syncthreads();  // (the first one also ends every wave's use of its transposed copy)
+    if (wv == turn) {
+#pragma unroll
+      for (int o = 0; o < 3; ++o)
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            float* at = red + ((o * TT + tt) * 16 + i) * 64 + lane;
+            *at = turn == 0 ? acc[o][tt][i] : *at + acc[o][tt][i];
+          }
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < kRed; e += 256) {
+    const int o = e / (TT * 1024), tt = (e / 1024) % TT, i = (e / 64) % 16, l = e % 64;
+    const int row = r0 + l % 32, col = 32 * tt + 8 * (i / 4) + 4 * (l / 32) + i % 4;
+    if (row >= a.rows_x) continue;
+    const int64_t at = (static_cast<int64_t>(b) * a.rows_x + row) * d + head * DH + col;
+    const int which = o == 0 ? 2 : (o == 1 ? 1 : 0);  // accumulators are (dV, dK, dQ); outputs are ordered (dQ, dK, dV)
+    if (a.chunks == 1) {
+      bf16_t* out = static_cast<bf16_t*>(which == 0 ? a.dq : (which == 1 ? a.dk : a.dv));
+      store_as(out + at, red[e]);
+    } else {
+      const int64_t plane = static_cast<int64_t>(a.rows_x) * d;
+      a.partial[((static_cast<int64_t>(b) * a.chunks + chunk) * 3 + which) * plane + static_cast<int64_t>(row) * d + head * DH + col] = red[e];
+    }
+  }
+}
+
 // out[b][which][row][col] = sum over the chunks, in ascending order
 template <typename T>
 __global__ __launch_bounds__(256) void xor_backward_reduce_kernel(const float* partial, T* dq, T* dk, T* dv, int chunks,
@@ -191,42 +333,51 @@ __global__ __launch_bounds__(256) void xor_backward_reduce_kernel(const float* p
   store_as(out + static_cast<int64_t>(b) * plane + i, sum);
 }
 
-int step_rows(int dh) { return dh <= 32 ? 32 : 16; }
+int step_rows(int dh, bool on_mfma) { return on_mfma ? kMfmaStep : (dh <= 32 ? 32 : 16); }
 
-int chunks_for_links(int B, int N, int m, int h, int dh) {
+int chunks_for_links(int B, int N, int m, int h, int step) {
   // enough workgroups for two per compute unit, but no chunk shorter than one step
   const int64_t per_chunk = static_cast<int64_t>((m + kOwn - 1) / kOwn) * h * B;
   int64_t chunks = (2 * static_cast<int64_t>(compute_units()) + per_chunk - 1) / per_chunk;
-  const int64_t steps = (N + step_rows(dh) - 1) / step_rows(dh);
+  const int64_t steps = (N + step - 1) / step;
   if (chunks > steps) chunks = steps;
   if (chunks < 1) chunks = 1;
   return static_cast<int>(chunks);
 }
 
 template <typename T>
-hipError_t launch_side(const SideArgs& a, dim3 grid, hipStream_t s) {
-  if (a.dh <= 32)
+hipError_t launch_side(const SideArgs& a, dim3 grid, bool on_mfma, hipStream_t s) {
+  if (on_mfma && a.dh == 32)
+    hipLaunchKernelGGL(xor_backward_side_mfma_kernel<32>, grid, dim3(256), 0, s, a);
+  else if (on_mfma)
+    hipLaunchKernelGGL(xor_backward_side_mfma_kernel<64>, grid, dim3(256), 0, s, a);
+  else if (a.dh <= 32)
     hipLaunchKernelGGL((xor_backward_side_kernel<T, 32, 32>), grid, dim3(256), 0, s, a);
   else
     hipLaunchKernelGGL((xor_backward_side_kernel<T, kMaxDh, 16>), grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
 template <typename T>
 hipError_t xor_backward_typed(const XorBackward& g, void* workspace, hipStream_t s) {
   SideArgs a{};
   a.lens = g.lens, a.d = g.d, a.dh = g.d / g.h, a.scale = g.scale;
-  const int step = step_rows(a.dh);
+  // the matrix-core form reads 16-byte pieces of bf16 rows
+  bool on_mfma = g.dtype == 1 && (a.dh == 32 || a.dh == 64);
+  for (const void* p : {g.QS, g.KS, g.VS, g.QT, g.KT, g.VT, g.dOT, g.dOS}) on_mfma = on_mfma && aligned16(p);
+  const int step = step_rows(a.dh, on_mfma);
   // history side: every block of 32 history rows against all links
   a.qx = g.QS, a.kx = g.KS, a.vx = g.VS, a.gx = g.dOS;
   a.qy = g.QT, a.ky = g.KT, a.vy = g.VT, a.gy = g.dOT;
   a.dq = g.dQS, a.dk = g.dKS, a.dv = g.dVS, a.partial = nullptr;
   a.own_is_history = 1, a.rows_x = g.N, a.rows_y = g.m, a.chunks = 1;
   a.chunk_rows = (g.m + step - 1) / step * step;
-  hipError_t e = launch_side<T>(a, dim3((g.N + kOwn - 1) / kOwn, g.h, g.B), s);
+  hipError_t e = launch_side<T>(a, dim3((g.N + kOwn - 1) / kOwn, g.h, g.B), on_mfma, s);
   if (e != hipSuccess) return e;
   // link side: every block of 32 links against the history rows, in chunks
-  const int chunks = chunks_for_links(g.B, g.N, g.m, g.h, a.dh);
+  const int chunks = chunks_for_links(g.B, g.N, g.m, g.h, step);
   a.qx = g.QT, a.kx = g.KT, a.vx = g.VT, a.gx = g.dOT;
   a.qy = g.QS, a.ky = g.KS, a.vy = g.VS, a.gy = g.dOS;
   a.dq = g.dQT, a.dk = g.dKT, a.dv = g.dVT, a.partial = static_cast<float*>(workspace);
@@ -234,7 +385,7 @@ hipError_t xor_backward_typed(const XorBackward& g, void* workspace, hipStream_t
   const int steps = (g.N + step - 1) / step;
   a.chunk_rows = (steps + chunks - 1) / chunks * step;
   const int blocks_x = (g.m + kOwn - 1) / kOwn;
-  e = launch_side<T>(a, dim3(blocks_x * chunks, g.h, g.B), s);
+  e = launch_side<T>(a, dim3(blocks_x * chunks, g.h, g.B), on_mfma, s);
   if (e != hipSuccess || chunks == 1) return e;
   const int64_t plane = static_cast<int64_t>(g.m) * g.d;
   hipLaunchKernelGGL(xor_backward_reduce_kernel<T>, dim3(static_cast<unsigned>((plane + 255) / 256), 3, g.B), dim3(256), 0, s,
@@ -248,7 +399,9 @@ hipError_t xor_backward_typed(const XorBackward& g, void* workspace, hipStream_t
 bool xor_backward_supported(int d, int h) { return h > 0 && d % h == 0 && d / h <= kMaxDh; }
 
 size_t xor_backward_workspace(int B, int N, int m, int d, int h) {
-  const int chunks = chunks_for_links(B, N, m, h, d / h);
+  // large enough for either kernel (a bf16 call whose pointers are not 16-byte aligned runs on the vector ALUs)
+  const int chunks = std::max(chunks_for_links(B, N, m, h, step_rows(d / h, false)),
+                              chunks_for_links(B, N, m, h, step_rows(d / h, true)));
   return chunks == 1 ? 256 : align_up(static_cast<size_t>(B) * chunks * 3 * m * d * sizeof(float));
 }
 
