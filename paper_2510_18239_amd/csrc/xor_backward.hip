@@ -35,11 +35,11 @@ struct SideArgs {
   float scale;
 };
 
-__device__ __forceinline__ float silu_f(float x) { return x / (1.f + __expf(-x)); }
-__device__ __forceinline__ float silu_derivative_f(float x) {
-  const float s = 1.f / (1.f + __expf(-x));
-  return s * (1.f + x * (1.f - s));
+// sigmoid with the hardware's exp2 and reciprocal (about one ulp each); SiLU(x) = x s, SiLU'(x) = s (1 + x (1 - s))
+__device__ __forceinline__ float sigmoid_f(float x) {
+  return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
 }
+__device__ __forceinline__ float silu_derivative_from(float x, float s) { return s * fmaf(x, 1.f - s, 1.f); }
 __device__ __forceinline__ float dot4(const float4& a, const float4& b, float c) {
   return fmaf(a.w, b.w, fmaf(a.z, b.z, fmaf(a.y, b.y, fmaf(a.x, b.x, c))));
 }
@@ -140,9 +140,10 @@ __global__ __launch_bounds__(256) void xor_backward_side_kernel(SideArgs a) {
       for (int j = 0; j < CP; ++j) {
         const float s1 = z1[i][j] * a.scale, s2 = z2[i][j] * a.scale;
         const bool live = r0 + pr0 + i < valid_x && c0 + pc0 + j < c_end;
-        p1[pr0 + i][pc0 + j] = live ? silu_f(s1) * inv_nx : 0.f;
-        e1[pr0 + i][pc0 + j] = live ? w1[i][j] * silu_derivative_f(s1) * inv_nx * a.scale : 0.f;
-        e2[pr0 + i][pc0 + j] = live ? w2[i][j] * silu_derivative_f(s2) * inv_ny * a.scale : 0.f;
+        const float g1 = sigmoid_f(s1), g2 = sigmoid_f(s2);
+        p1[pr0 + i][pc0 + j] = live ? s1 * g1 * inv_nx : 0.f;
+        e1[pr0 + i][pc0 + j] = live ? w1[i][j] * silu_derivative_from(s1, g1) * inv_nx * a.scale : 0.f;
+        e2[pr0 + i][pc0 + j] = live ? w2[i][j] * silu_derivative_from(s2, g2) * inv_ny * a.scale : 0.f;
       }
     __syncthreads();
 #pragma unroll
@@ -191,10 +192,12 @@ __global__ __launch_bounds__(256) void xor_backward_side_kernel(SideArgs a) {
 //      is the transposed Y tensor in the same chained order, read from a transposed copy the wave parks in its own
 //      piece of LDS (no barrier: a wave reads back only what it wrote itself);
 //   3. after the last step the four waves' sums meet in LDS in wave order and are stored.
+// With OWN_PER_WAVE (many rows of X, few of Y: the history side) each wave instead takes its own 32 rows of X, walks
+// all of Y itself and stores its accumulators directly: no sums to combine.
 // Rows that are not valid are loaded as zeros, which makes every term they touch zero (SiLU(0) = 0, and e1, e2 carry
 // a dot product with the zero row).
 constexpr int kMfmaStep = 128;  // rows of Y per workgroup step: 32 per wave
-template <int DH>
+template <int DH, bool OWN_PER_WAVE>
 __global__ __launch_bounds__(256) void xor_backward_side_mfma_kernel(SideArgs a) {
   constexpr int KS = DH / 16, TT = DH / 32, PITCH = 36;  // PITCH: bf16 per row of the transposed copy (8-byte reads)
   constexpr int kWaveTile = 3 * DH * PITCH;              // bf16: transposed Q[Y], K[Y], G[Y] of one wave
@@ -202,14 +205,15 @@ __global__ __launch_bounds__(256) void xor_backward_side_mfma_kernel(SideArgs a)
   constexpr size_t kBytes = sizeof(float) * kRed > 2 * 4 * kWaveTile ? sizeof(float) * kRed : 2 * 4 * kWaveTile;
   __shared__ __align__(16) unsigned char smem[kBytes];
   const int tid = threadIdx.x, wv = tid / 64, lane = tid % 64, n = lane % 32, g = lane / 32, d = a.d;
-  const int blocks_x = (a.rows_x + kOwn - 1) / kOwn;
+  const int own_rows = OWN_PER_WAVE ? 4 * kOwn : kOwn;  // rows of X per workgroup
+  const int blocks_x = (a.rows_x + own_rows - 1) / own_rows;
   const int xb = blockIdx.x % blocks_x, chunk = blockIdx.x / blocks_x, head = blockIdx.y, b = blockIdx.z;
   const int hist_rows = a.own_is_history ? a.rows_x : a.rows_y;
   const int len = a.lens ? min(max(a.lens[b], 0), hist_rows) : hist_rows;
   const int valid_x = a.own_is_history ? len : a.rows_x, valid_y = a.own_is_history ? a.rows_y : len;
   const float inv_nx = valid_x > 0 ? 1.f / static_cast<float>(valid_x) : 0.f;
   const float inv_ny = valid_y > 0 ? 1.f / static_cast<float>(valid_y) : 0.f;
-  const int r0 = xb * kOwn;
+  const int r0 = xb * own_rows + (OWN_PER_WAVE ? wv * kOwn : 0);
   bf16x8 zero;
 #pragma unroll
   for (int t = 0; t < 8; ++t) zero[t] = static_cast<__bf16>(0.f);
@@ -237,35 +241,49 @@ __global__ __launch_bounds__(256) void xor_backward_side_mfma_kernel(SideArgs a)
   bf16_t* yt = reinterpret_cast<bf16_t*>(smem) + wv * kWaveTile;  // [3][DH][PITCH]: Q[Y]^T, K[Y]^T, G[Y]^T
 
   const int c_begin = chunk * a.chunk_rows, c_end = min(c_begin + a.chunk_rows, valid_y);
-  for (int c0 = c_begin + 32 * wv; c0 < c_end; c0 += kMfmaStep) {
+  const int c_first = c_begin + (OWN_PER_WAVE ? 0 : 32 * wv), c_step = OWN_PER_WAVE ? 32 : kMfmaStep;
+  // the wave's next 32 rows of Y as A operands (lane = row c0 + n): asked for one step ahead
+  bf16x8 nq[KS], nk[KS], nv[KS], ng[KS];
+  auto ask = [&](int c0) {
     const bool y_ok = c0 + n < c_end;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      nq[ks] = frag(a.qy, a.rows_y, c0 + n, y_ok, ks), nk[ks] = frag(a.ky, a.rows_y, c0 + n, y_ok, ks);
+      nv[ks] = frag(a.vy, a.rows_y, c0 + n, y_ok, ks), ng[ks] = frag(a.gy, a.rows_y, c0 + n, y_ok, ks);
+    }
+  };
+  if (c_first < c_end) ask(c_first);
+  for (int c0 = c_first; c0 < c_end; c0 += c_step) {
+    bf16x8 yq[KS], yk[KS], yv[KS], yg[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) yq[ks] = nq[ks], yk[ks] = nk[ks], yv[ks] = nv[ks], yg[ks] = ng[ks];
+    if (c0 + c_step < c_end) ask(c0 + c_step);
     f32x16 z1, w1, z2, w2;
 #pragma unroll
     for (int i = 0; i < 16; ++i) z1[i] = w1[i] = z2[i] = w2[i] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      const bf16x8 yq = frag(a.qy, a.rows_y, c0 + n, y_ok, ks), yk = frag(a.ky, a.rows_y, c0 + n, y_ok, ks);
-      const bf16x8 yv = frag(a.vy, a.rows_y, c0 + n, y_ok, ks), yg = frag(a.gy, a.rows_y, c0 + n, y_ok, ks);
-      z1 = mfma32(yq, xk[ks], z1);  // <Q[Y]_c, K[X]_r>
-      w1 = mfma32(yg, xv[ks], w1);  // <G[Y]_c, V[X]_r>
-      z2 = mfma32(yk, xq[ks], z2);  // <K[Y]_c, Q[X]_r>
-      w2 = mfma32(yv, xg[ks], w2);  // <V[Y]_c, G[X]_r>
+      z1 = mfma32(yq[ks], xk[ks], z1);  // <Q[Y]_c, K[X]_r>
+      w1 = mfma32(yg[ks], xv[ks], w1);  // <G[Y]_c, V[X]_r>
+      z2 = mfma32(yk[ks], xq[ks], z2);  // <K[Y]_c, Q[X]_r>
+      w2 = mfma32(yv[ks], xg[ks], w2);  // <V[Y]_c, G[X]_r>
       // the transposed copy: column 16ks + 8g + t of row c0 + n goes to [column][n]
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
         const int col = 16 * ks + 8 * g + t;
-        store_as(yt + (0 * DH + col) * PITCH + n, static_cast<float>(yq[t]));
-        store_as(yt + (1 * DH + col) * PITCH + n, static_cast<float>(yk[t]));
-        store_as(yt + (2 * DH + col) * PITCH + n, static_cast<float>(yg[t]));
+        store_as(yt + (0 * DH + col) * PITCH + n, static_cast<float>(yq[ks][t]));
+        store_as(yt + (1 * DH + col) * PITCH + n, static_cast<float>(yk[ks][t]));
+        store_as(yt + (2 * DH + col) * PITCH + n, static_cast<float>(yg[ks][t]));
       }
     }
     // phi and phi' register by register: z1 becomes p1, w1 becomes e1, w2 becomes e2
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const float s1 = z1[i] * a.scale, s2 = z2[i] * a.scale;
-      z1[i] = silu_f(s1) * inv_nx;
-      w1[i] = w1[i] * silu_derivative_f(s1) * inv_nx * a.scale;
-      w2[i] = w2[i] * silu_derivative_f(s2) * inv_ny * a.scale;
+      const float g1 = sigmoid_f(s1), g2 = sigmoid_f(s2);
+      z1[i] = s1 * g1 * inv_nx;
+      w1[i] = w1[i] * silu_derivative_from(s1, g1) * (inv_nx * a.scale);
+      w2[i] = w2[i] * silu_derivative_from(s2, g2) * (inv_ny * a.scale);
     }
 #pragma unroll
     for (int f = 0; f < 2; ++f) {
@@ -286,6 +304,34 @@ __global__ __launch_bounds__(256) void xor_backward_side_mfma_kernel(SideArgs a)
         acc[2][tt] = mfma32(chained(1), be2, acc[2][tt]);  // dQ[X]^T += K[Y]^T e2
       }
     }
+  }
+  auto out_of = [&](int which) { return static_cast<bf16_t*>(which == 0 ? a.dq : (which == 1 ? a.dk : a.dv)); };
+  const int64_t plane = static_cast<int64_t>(a.rows_x) * d;
+  if constexpr (OWN_PER_WAVE) {
+    // lane (n, g) holds, for its row r0 + n, head columns 32tt + 8j + 4g .. + 3 in registers 4j .. 4j + 3
+    if (r0 + n >= a.rows_x) return;
+#pragma unroll
+    for (int o = 0; o < 3; ++o) {
+      const int which = 2 - o;  // accumulators are (dV, dK, dQ); outputs are ordered (dQ, dK, dV)
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int64_t at = (static_cast<int64_t>(b) * a.rows_x + r0 + n) * d + head * DH + 32 * tt + 8 * j + 4 * g;
+          if (a.chunks == 1) {
+            alignas(8) bf16_t r4[4];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) store_as(&r4[rr], acc[o][tt][4 * j + rr]);
+            *reinterpret_cast<uint2*>(out_of(which) + at) = *reinterpret_cast<const uint2*>(r4);
+          } else {
+            float* dst = a.partial + ((static_cast<int64_t>(b) * a.chunks + chunk) * 3 + which) * plane +
+                         static_cast<int64_t>(r0 + n) * d + head * DH + 32 * tt + 8 * j + 4 * g;
+            *reinterpret_cast<float4*>(dst) = make_float4(acc[o][tt][4 * j], acc[o][tt][4 * j + 1], acc[o][tt][4 * j + 2],
+                                                          acc[o][tt][4 * j + 3]);
+          }
+        }
+    }
+    return;
   }
   // the four waves' sums, added in wave order
   float* red = reinterpret_cast<float*>(smem);
@@ -309,14 +355,11 @@ __global__ __launch_bounds__(256) void xor_backward_side_mfma_kernel(SideArgs a)
     const int row = r0 + l % 32, col = 32 * tt + 8 * (i / 4) + 4 * (l / 32) + i % 4;
     if (row >= a.rows_x) continue;
     const int64_t at = (static_cast<int64_t>(b) * a.rows_x + row) * d + head * DH + col;
-    const int which = o == 0 ? 2 : (o == 1 ? 1 : 0);  // accumulators are (dV, dK, dQ); outputs are ordered (dQ, dK, dV)
-    if (a.chunks == 1) {
-      bf16_t* out = static_cast<bf16_t*>(which == 0 ? a.dq : (which == 1 ? a.dk : a.dv));
-      store_as(out + at, red[e]);
-    } else {
-      const int64_t plane = static_cast<int64_t>(a.rows_x) * d;
+    const int which = 2 - o;  // accumulators are (dV, dK, dQ); outputs are ordered (dQ, dK, dV)
+    if (a.chunks == 1)
+      store_as(out_of(which) + at, red[e]);
+    else
       a.partial[((static_cast<int64_t>(b) * a.chunks + chunk) * 3 + which) * plane + static_cast<int64_t>(row) * d + head * DH + col] = red[e];
-    }
   }
 }
 
@@ -346,11 +389,15 @@ int chunks_for_links(int B, int N, int m, int h, int step) {
 }
 
 template <typename T>
-hipError_t launch_side(const SideArgs& a, dim3 grid, bool on_mfma, hipStream_t s) {
-  if (on_mfma && a.dh == 32)
-    hipLaunchKernelGGL(xor_backward_side_mfma_kernel<32>, grid, dim3(256), 0, s, a);
+hipError_t launch_side(const SideArgs& a, dim3 grid, bool on_mfma, bool own_per_wave, hipStream_t s) {
+  if (on_mfma && a.dh == 32 && own_per_wave)
+    hipLaunchKernelGGL((xor_backward_side_mfma_kernel<32, true>), grid, dim3(256), 0, s, a);
+  else if (on_mfma && a.dh == 32)
+    hipLaunchKernelGGL((xor_backward_side_mfma_kernel<32, false>), grid, dim3(256), 0, s, a);
+  else if (on_mfma && own_per_wave)
+    hipLaunchKernelGGL((xor_backward_side_mfma_kernel<64, true>), grid, dim3(256), 0, s, a);
   else if (on_mfma)
-    hipLaunchKernelGGL(xor_backward_side_mfma_kernel<64>, grid, dim3(256), 0, s, a);
+    hipLaunchKernelGGL((xor_backward_side_mfma_kernel<64, false>), grid, dim3(256), 0, s, a);
   else if (a.dh <= 32)
     hipLaunchKernelGGL((xor_backward_side_kernel<T, 32, 32>), grid, dim3(256), 0, s, a);
   else
@@ -374,7 +421,9 @@ hipError_t xor_backward_typed(const XorBackward& g, void* workspace, hipStream_t
   a.dq = g.dQS, a.dk = g.dKS, a.dv = g.dVS, a.partial = nullptr;
   a.own_is_history = 1, a.rows_x = g.N, a.rows_y = g.m, a.chunks = 1;
   a.chunk_rows = (g.m + step - 1) / step * step;
-  hipError_t e = launch_side<T>(a, dim3((g.N + kOwn - 1) / kOwn, g.h, g.B), on_mfma, s);
+  // (on the matrix cores a workgroup takes 128 history rows, one wave per 32, each wave against all links)
+  const int own_rows = on_mfma ? 4 * kOwn : kOwn;
+  hipError_t e = launch_side<T>(a, dim3((g.N + own_rows - 1) / own_rows, g.h, g.B), on_mfma, true, s);
   if (e != hipSuccess) return e;
   // link side: every block of 32 links against the history rows, in chunks
   const int chunks = chunks_for_links(g.B, g.N, g.m, g.h, step);
@@ -385,7 +434,7 @@ hipError_t xor_backward_typed(const XorBackward& g, void* workspace, hipStream_t
   const int steps = (g.N + step - 1) / step;
   a.chunk_rows = (steps + chunks - 1) / chunks * step;
   const int blocks_x = (g.m + kOwn - 1) / kOwn;
-  e = launch_side<T>(a, dim3(blocks_x * chunks, g.h, g.B), on_mfma, s);
+  e = launch_side<T>(a, dim3(blocks_x * chunks, g.h, g.B), on_mfma, false, s);
   if (e != hipSuccess || chunks == 1) return e;
   const int64_t plane = static_cast<int64_t>(g.m) * g.d;
   hipLaunchKernelGGL(xor_backward_reduce_kernel<T>, dim3(static_cast<unsigned>((plane + 255) / 256), 3, g.B), dim3(256), 0, s,

@@ -24,9 +24,11 @@ def _run(t, h, scale, dtype, with_dos=True):
 
 
 @pytest.mark.parametrize("B,N,m,d,h,dtype,scale", [
-    (2, 100, 64, 128, 4, "bf16", 1.0),      # one chunk per link block? no: several chunks, ragged tail in N
+    (2, 100, 64, 128, 4, "bf16", 1.0),      # matrix-core form (bf16, d/h = 32), ragged tail in N
     (3, 700, 64, 128, 4, "bf16", 1.0),      # many chunks
     (2, 333, 128, 256, 4, "bf16", 0.7),     # d/h = 64, the widest head
+    (2, 50, 40, 128, 4, "bf16", 1.0),       # matrix-core form with m and N that fill no tile
+    (2, 200, 64, 64, 4, "bf16", 1.0),       # bf16 with d/h = 16: the fp32-arithmetic kernel on bf16 storage
     (1, 65, 5, 24, 1, "fp32", 1.0),         # m and d/h far from any tile size
     (2, 47, 37, 40, 5, "fp32", -0.5),       # d/h = 8, negative scale
     (4, 16, 32, 64, 2, "fp32", 1.3),
