@@ -215,9 +215,10 @@ int32_t lime_request(const void* E, const int32_t* lens, const void* LC, int64_t
  * the caller sums over users).  For O = phi(Q K^T) V and G = dL/dO:  dV = phi(Z)^T G,  E = (G V^T) * phi'(Z)
  * element-wise,  dQ = scale E K,  dK = scale E^T Q,  Z = scale Q K^T,  SiLU'(x) = s (1 + x (1 - s)), s = sigmoid(x).
  * History rows at or past lens[b] are never read and get zero gradients; a user with lens[b] = 0 gets all zeros.
- * All pointers device memory, row-major, storage type `dtype`; fp32 arithmetic; the attention matrices are
- * recomputed in tiles, nothing of size N x m is stored.  Deterministic (no atomics).  d/h <= 64, otherwise
- * LIME_UNSUPPORTED.  Workspace: LIME_OP_XOR_BACKWARD (partial sums of the link-side gradients).
+ * All pointers device memory, row-major, storage type `dtype`; the attention matrices are recomputed in tiles,
+ * nothing of size N x m is stored.  bf16 storage with d/h = 32 or 64 and 16-byte aligned pointers runs on the matrix
+ * cores (bf16 operands, fp32 accumulation; phi and phi' terms rounded to bf16 before the gradient products), anything
+ * else in fp32 arithmetic on the vector ALUs.  Deterministic (no atomics).  d/h <= 64, otherwise LIME_UNSUPPORTED.  Workspace: LIME_OP_XOR_BACKWARD (partial sums of the link-side gradients).
  */
 int32_t lime_xor_backward(const void* QS, const void* KS, const void* VS, const void* QT, const void* KT, const void* VT,
                           const void* dOT, const void* dOS, const int32_t* lens, void* dQS, void* dKS, void* dVS,

@@ -86,7 +86,8 @@ struct GenericGatedBlock {
 };
 hipError_t generic_gated_block(const GenericGatedBlock& g, hipStream_t s);
 
-// Gradients of one XORA layer with respect to its projected inputs (Appendix H.2); fp32 arithmetic, any storage type.
+// Gradients of one XORA layer with respect to its projected inputs (Appendix H.2): matrix cores for bf16 storage with
+// d/h = 32 or 64, fp32 arithmetic on the vector ALUs otherwise.
 struct XorBackward {
   const void *QS, *KS, *VS;     // [B][N][d] projected history rows
   const void *QT, *KT, *VT;     // [B][m][d] projected links, per user

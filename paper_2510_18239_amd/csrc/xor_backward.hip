@@ -1,5 +1,6 @@
-// Backward pass of one XORA layer with respect to its projected inputs (Appendix H.2), fp32 arithmetic on the
-// vector ALUs with the attention matrices recomputed tile by tile (nothing of size N x m is stored).
+// Backward pass of one XORA layer with respect to its projected inputs (Appendix H.2), with the attention matrices
+// recomputed tile by tile (nothing of size N x m is stored): a matrix-core form for bf16 storage and a form in fp32
+// arithmetic on the vector ALUs for everything else.
 //
 // The layer is symmetric in its two sides (Appendix H.1): with X one side and Y the other,
 //   O[Y] = phi(Q[Y] K[X]^T) V[X]   (normaliser n_X, the number of valid rows of X),
