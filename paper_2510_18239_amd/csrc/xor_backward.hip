@@ -11,7 +11,7 @@
 //   z2 = scale <Q[X]_r, K[Y]_c>,  e2 = <G[X]_r, V[Y]_c> SiLU'(z2) / n_Y
 //       dQ[X]_r += scale e2 K[Y]_c
 // (phi' applied element-wise; SiLU'(x) = s (1 + x (1 - s)), s = sigmoid(x)).  One kernel does this for a block of
-// 32 rows of X against a range of rows of Y (32 or 16 at a time); it runs once with X = history rows (all links as Y, results stored
+// 32 rows of X against a range of rows of Y; it runs once with X = history rows (all links as Y, results stored
 // directly) and once with X = links (the history rows as Y, cut into chunks whose partial sums a second kernel adds
 // in ascending order: deterministic, no atomics).
 #include <algorithm>
