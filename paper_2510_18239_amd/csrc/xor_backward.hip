@@ -197,6 +197,10 @@ __global__ __launch_bounds__(256) void xor_backward_side_kernel(SideArgs a) {
 // all of Y itself and stores its accumulators directly: no sums to combine.
 // Rows that are not valid are loaded as zeros, which makes every term they touch zero (SiLU(0) = 0, and e1, e2 carry
 // a dot product with the zero row).
+// The transposed copy is written one bf16 at a time and read back four at a time: both through types that may alias
+// anything, so that the compiler keeps the order of a wave's stores and loads.
+typedef __bf16 __attribute__((may_alias)) bf16_any;
+typedef bf16x4 __attribute__((may_alias)) bf16x4_any;
 constexpr int kMfmaStep = 128;  // rows of Y per workgroup step: 32 per wave
 template <int DH, bool OWN_PER_WAVE>
 __global__ __launch_bounds__(256) void xor_backward_side_mfma_kernel(SideArgs a) {
@@ -239,7 +243,7 @@ __global__ __launch_bounds__(256) void xor_backward_side_mfma_kernel(SideArgs a)
     for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[o][tt][i] = 0.f;
-  bf16_t* yt = reinterpret_cast<bf16_t*>(smem) + wv * kWaveTile;  // [3][DH][PITCH]: Q[Y]^T, K[Y]^T, G[Y]^T
+  bf16_any* yt = reinterpret_cast<bf16_any*>(smem) + wv * kWaveTile;  // [3][DH][PITCH]: Q[Y]^T, K[Y]^T, G[Y]^T
 
   const int c_begin = chunk * a.chunk_rows, c_end = min(c_begin + a.chunk_rows, valid_y);
   const int c_first = c_begin + (OWN_PER_WAVE ? 0 : 32 * wv), c_step = OWN_PER_WAVE ? 32 : kMfmaStep;
@@ -272,9 +276,9 @@ __global__ __launch_bounds__(256) void xor_backward_side_mfma_kernel(SideArgs a)
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
         const int col = 16 * ks + 8 * g + t;
-        store_as(yt + (0 * DH + col) * PITCH + n, static_cast<float>(yq[ks][t]));
-        store_as(yt + (1 * DH + col) * PITCH + n, static_cast<float>(yk[ks][t]));
-        store_as(yt + (2 * DH + col) * PITCH + n, static_cast<float>(yg[ks][t]));
+        yt[(0 * DH + col) * PITCH + n] = yq[ks][t];
+        yt[(1 * DH + col) * PITCH + n] = yk[ks][t];
+        yt[(2 * DH + col) * PITCH + n] = yg[ks][t];
       }
     }
     // phi and phi' register by register: z1 becomes p1, w1 becomes e1, w2 becomes e2
@@ -293,8 +297,8 @@ __global__ __launch_bounds__(256) void xor_backward_side_mfma_kernel(SideArgs a)
       for (int tt = 0; tt < TT; ++tt) {
         // slot t of lane (n, g): row c0 + 16f + chain_k(g, t) of Y, head column 32tt + n
         auto chained = [&](int arr) {
-          const bf16_t* src = yt + (arr * DH + 32 * tt + n) * PITCH + 16 * f + 4 * g;
-          const bf16x4 lo = *reinterpret_cast<const bf16x4*>(src), hi = *reinterpret_cast<const bf16x4*>(src + 8);
+          const bf16_any* src = yt + (arr * DH + 32 * tt + n) * PITCH + 16 * f + 4 * g;
+          const bf16x4 lo = *reinterpret_cast<const bf16x4_any*>(src), hi = *reinterpret_cast<const bf16x4_any*>(src + 8);
           bf16x8 v;
 #pragma unroll
           for (int t = 0; t < 4; ++t) v[t] = lo[t], v[4 + t] = hi[t];
