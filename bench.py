@@ -624,7 +624,7 @@ def extras(binding, synth, torch, dev, timed, pct):
     res["lime_xor_layers_n3_vs_N"] = layers
     # The backward pass of one XORA layer (Appendix H.2) at the same shapes: ten products of N x m x d/h per head and
     # user (two logit matrices and two G V^T matrices recomputed, six gradients), 20 N m d flops per user; the kernel
-    # recomputes the four matrices for each side, 28 N m d executed.  fp32 on the vector ALUs.
+    # recomputes the four matrices for each side, 28 N m d executed.  bf16 storage: on the matrix cores, HBM-bound.
     back = {}
     for N in (2048, 16384):
         tb = synth.backward_inputs(4, w4.B, N, w4.m, w4.d, w4.h, "bf16")
@@ -632,8 +632,10 @@ def extras(binding, synth, torch, dev, timed, pct):
         lat = timed(lambda i: binding.lime_xor_backward(gb["QS"], gb["KS"], gb["VS"], gb["QT"], gb["KT"], gb["VT"], gb["dOT"],
                                                         gb["dOS"], None, w4.h, 1.0), 30)
         flops = 20.0 * N * w4.m * w4.d * w4.B
+        # the history-side tensors are read by both side kernels (4 + 4) and their three gradients written once
+        nbytes = 11.0 * w4.B * N * w4.d * 2
         back[N] = {"p50_ms": pct(lat, 0.5), "algorithmic_TFLOPs": flops / (pct(lat, 0.5) * 1e-3) / 1e12,
-                   "frac_of_fp32_vector_peak": flops / (pct(lat, 0.5) * 1e-3) / 1e12 / 157.3}
+                   "history_side_bytes": nbytes, "frac_of_hbm_bound": nbytes / (HBM_PEAK_GBS * 1e9) / (pct(lat, 0.5) * 1e-3)}
         del gb
     res["lime_xor_backward_vs_N"] = back
     # LIME vs full target attention on identical inputs (configs[4])

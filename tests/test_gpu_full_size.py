@@ -147,3 +147,14 @@ def test_config5_target_attention_sampled(gain):
         idx = np.unique(np.concatenate([[0, w.C - 1], rng.integers(0, w.C, 94)]))
         ref = orc.mha_target_attention(w.T[b:b + 1, idx], w.E[b:b + 1], w.lens[b:b + 1], w.Wq, w.Wk, w.Wv, w.h, s)
         assert_close(host(A[b:b + 1, torch.from_numpy(idx).cuda()]), ref, "bf16", f"MHA user {b}")
+
+
+def test_config4_xor_backward_long_history():
+    """8 users, d = 128, h = 4, m = 64 at N = 16384, the larger size bench.py --extras times for lime_xor_backward:
+    all six gradients, every element, against the oracle."""
+    t = synth.backward_inputs(4, 8, 16384, 64, 128, 4, "bf16")
+    g = {k: torch.from_numpy(v).to(torch.bfloat16).cuda() for k, v in t.items() if k != "lens"}
+    got = binding.lime_xor_backward(g["QS"], g["KS"], g["VS"], g["QT"], g["KT"], g["VT"], g["dOT"], g["dOS"], None, 4, 1.0)
+    ref = orc.xor_attention_backward(t["QS"], t["KS"], t["VS"], t["QT"], t["KT"], t["VT"], t["dOT"], t["dOS"], None, 4, 1.0)
+    for name, x, r in zip(("dQS", "dKS", "dVS", "dQT", "dKT", "dVT"), got, ref):
+        assert_close(host(x), r, "bf16", name)
