@@ -37,6 +37,7 @@
  * Limits.  d/h <= 256.  The bf16 matrix-core (MFMA) kernels serve d/h in {32, 64}
  *   with h in {1, 2, 4, 8}, d <= 256 and m a multiple of 32 up to 128; every other
  *   shape, and all of fp32, runs on the general fp32-arithmetic kernels.
+ *   lime_xor_backward: d/h <= 64; its matrix-core form serves bf16 with d/h in {32, 64}, any h and m.
  */
 #ifndef LIME_H_
 #define LIME_H_
