@@ -203,7 +203,7 @@ typedef __bf16 __attribute__((may_alias)) bf16_any;
 typedef bf16x4 __attribute__((may_alias)) bf16x4_any;
 constexpr int kMfmaStep = 128;  // rows of Y per workgroup step: 32 per wave
 template <int DH, bool OWN_PER_WAVE>
-__global__ __launch_bounds__(256) void xor_backward_side_mfma_kernel(SideArgs a) {
+__global__ __launch_bounds__(256, (DH == 32 ? 2 : 1)) void xor_backward_side_mfma_kernel(SideArgs a) {
   constexpr int KS = DH / 16, TT = DH / 32, PITCH = 36;  // PITCH: bf16 per row of the transposed copy (8-byte reads)
   constexpr int kWaveTile = 3 * DH * PITCH;              // bf16: transposed Q[Y], K[Y], G[Y] of one wave
   constexpr int kRed = 3 * TT * 16 * 64;                 // floats: one wave's output accumulators
@@ -314,26 +314,46 @@ __global__ __launch_bounds__(256) void xor_backward_side_mfma_kernel(SideArgs a)
   const int64_t plane = static_cast<int64_t>(a.rows_x) * d;
   if constexpr (OWN_PER_WAVE) {
     // lane (n, g) holds, for its row r0 + n, head columns 32tt + 8j + 4g .. + 3 in registers 4j .. 4j + 3
+    if (a.chunks == 1) {
+      // Stored through the wave's piece of LDS, so that a store instruction writes whole head slices of a few rows
+      // (16 bytes per lane, four or eight lanes per row) instead of eight bytes in each of 32 rows: the memory
+      // pipeline works per cache line touched.
+      constexpr int P2 = DH + 8, CPR = DH / 8;  // bf16 per staged row; 16-byte pieces per row
+      typedef bf16x8 __attribute__((may_alias)) bf16x8_any;
+#pragma unroll
+      for (int o = 0; o < 3; ++o) {
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            bf16x4 v;
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) v[rr] = static_cast<__bf16>(acc[o][tt][4 * j + rr]);
+            *reinterpret_cast<bf16x4_any*>(yt + n * P2 + 32 * tt + 8 * j + 4 * g) = v;
+          }
+        bf16_t* out = out_of(2 - o);  // accumulators are (dV, dK, dQ); outputs are ordered (dQ, dK, dV)
+#pragma unroll
+        for (int i = 0; i < 32 * CPR / 64; ++i) {
+          const int idx = lane + 64 * i, row = idx / CPR, piece = idx % CPR;
+          const bf16x8 v = *reinterpret_cast<const bf16x8_any*>(yt + row * P2 + 8 * piece);
+          if (r0 + row < a.rows_x)
+            *reinterpret_cast<bf16x8_any*>(out + (static_cast<int64_t>(b) * a.rows_x + r0 + row) * d + head * DH + 8 * piece) = v;
+        }
+      }
+      return;
+    }
     if (r0 + n >= a.rows_x) return;
 #pragma unroll
     for (int o = 0; o < 3; ++o) {
-      const int which = 2 - o;  // accumulators are (dV, dK, dQ); outputs are ordered (dQ, dK, dV)
+      const int which = 2 - o;
 #pragma unroll
       for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const int64_t at = (static_cast<int64_t>(b) * a.rows_x + r0 + n) * d + head * DH + 32 * tt + 8 * j + 4 * g;
-          if (a.chunks == 1) {
-            alignas(8) bf16_t r4[4];
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) store_as(&r4[rr], acc[o][tt][4 * j + rr]);
-            *reinterpret_cast<uint2*>(out_of(which) + at) = *reinterpret_cast<const uint2*>(r4);
-          } else {
-            float* dst = a.partial + ((static_cast<int64_t>(b) * a.chunks + chunk) * 3 + which) * plane +
-                         static_cast<int64_t>(r0 + n) * d + head * DH + 32 * tt + 8 * j + 4 * g;
-            *reinterpret_cast<float4*>(dst) = make_float4(acc[o][tt][4 * j], acc[o][tt][4 * j + 1], acc[o][tt][4 * j + 2],
-                                                          acc[o][tt][4 * j + 3]);
-          }
+          float* dst = a.partial + ((static_cast<int64_t>(b) * a.chunks + chunk) * 3 + which) * plane +
+                       static_cast<int64_t>(r0 + n) * d + head * DH + 32 * tt + 8 * j + 4 * g;
+          *reinterpret_cast<float4*>(dst) = make_float4(acc[o][tt][4 * j], acc[o][tt][4 * j + 1], acc[o][tt][4 * j + 2],
+                                                        acc[o][tt][4 * j + 3]);
         }
     }
     return;
@@ -419,6 +439,7 @@ hipError_t xor_backward_typed(const XorBackward& g, void* workspace, hipStream_t
   // the matrix-core form reads 16-byte pieces of bf16 rows
   bool on_mfma = g.dtype == 1 && (a.dh == 32 || a.dh == 64);
   for (const void* p : {g.QS, g.KS, g.VS, g.QT, g.KT, g.VT, g.dOT, g.dOS}) on_mfma = on_mfma && aligned16(p);
+  for (const void* p : {g.dQS, g.dKS, g.dVS}) on_mfma = on_mfma && aligned16(p);  // (stored 16 bytes at a time)
   const int step = step_rows(a.dh, on_mfma);
   // history side: every block of 32 history rows against all links
   a.qx = g.QS, a.kx = g.KS, a.vx = g.VS, a.gx = g.dOS;
