@@ -222,19 +222,37 @@ __global__ __launch_bounds__(256, (DH == 32 ? 2 : 1)) void xor_backward_side_mfm
   bf16x8 zero;
 #pragma unroll
   for (int t = 0; t < 8; ++t) zero[t] = static_cast<__bf16>(0.f);
-  // fragment ks of a row-major tensor: lane (n, g) holds columns 16ks + 8g .. + 7 of row `row` (head slice)
-  auto frag = [&](const void* base, int rows, int row, bool ok, int ks) {
-    if (base == nullptr || !ok) return zero;
-    return *reinterpret_cast<const bf16x8*>(static_cast<const bf16_t*>(base) +
-                                            (static_cast<int64_t>(b) * rows + row) * d + head * DH + 16 * ks + 8 * g);
+  // A 32-row tile of a row-major tensor (head slice) is fetched row-contiguous - KS loads of 16 bytes per lane, DH/8
+  // lanes per row, so that a load touches few cache lines - and turned into operand fragments (lane (n, g) holds
+  // columns 16ks + 8g .. + 7 of row n) through the wave's piece of LDS.  Rows at or past `limit` count as zeros.
+  constexpr int P2 = DH + 8, CPR = DH / 8;  // bf16 per staged row; 16-byte pieces per row
+  typedef bf16x8 __attribute__((may_alias)) bf16x8_any;
+  auto fetch = [&](const void* base, int rows, int row0, int limit, bf16x8 (&piece)[KS]) {
+#pragma unroll
+    for (int i = 0; i < KS; ++i) {
+      const int idx = lane + 64 * i, row = row0 + idx / CPR;
+      piece[i] = (base == nullptr || row >= limit) ? zero
+                 : *reinterpret_cast<const bf16x8*>(static_cast<const bf16_t*>(base) +
+                                                    (static_cast<int64_t>(b) * rows + row) * d + head * DH + 8 * (idx % CPR));
+    }
+  };
+  bf16_any* yt = reinterpret_cast<bf16_any*>(smem) + wv * kWaveTile;  // [3][DH][PITCH]: Q[Y]^T, K[Y]^T, G[Y]^T
+  auto to_fragments = [&](const bf16x8 (&piece)[KS], bf16x8 (&fr)[KS]) {
+#pragma unroll
+    for (int i = 0; i < KS; ++i) {
+      const int idx = lane + 64 * i;
+      *reinterpret_cast<bf16x8_any*>(yt + (idx / CPR) * P2 + 8 * (idx % CPR)) = piece[i];
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) fr[ks] = *reinterpret_cast<const bf16x8_any*>(yt + n * P2 + 16 * ks + 8 * g);
   };
   // the block's rows of X as B operands (lane = row r0 + n): q, k, v, g
   bf16x8 xq[KS], xk[KS], xv[KS], xg[KS];
-  const bool x_ok = r0 + n < valid_x;
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    xq[ks] = frag(a.qx, a.rows_x, r0 + n, x_ok, ks), xk[ks] = frag(a.kx, a.rows_x, r0 + n, x_ok, ks);
-    xv[ks] = frag(a.vx, a.rows_x, r0 + n, x_ok, ks), xg[ks] = frag(a.gx, a.rows_x, r0 + n, x_ok, ks);
+  {
+    bf16x8 pq[KS], pk[KS], pv[KS], pg[KS];
+    fetch(a.qx, a.rows_x, r0, valid_x, pq), fetch(a.kx, a.rows_x, r0, valid_x, pk);
+    fetch(a.vx, a.rows_x, r0, valid_x, pv), fetch(a.gx, a.rows_x, r0, valid_x, pg);
+    to_fragments(pq, xq), to_fragments(pk, xk), to_fragments(pv, xv), to_fragments(pg, xg);
   }
   f32x16 acc[3][TT];  // dV^T, dK^T, dQ^T: lane = row r0 + n, register 4j + rr = head column 32tt + 8j + 4g + rr
 #pragma unroll
@@ -243,25 +261,19 @@ __global__ __launch_bounds__(256, (DH == 32 ? 2 : 1)) void xor_backward_side_mfm
     for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[o][tt][i] = 0.f;
-  bf16_any* yt = reinterpret_cast<bf16_any*>(smem) + wv * kWaveTile;  // [3][DH][PITCH]: Q[Y]^T, K[Y]^T, G[Y]^T
-
   const int c_begin = chunk * a.chunk_rows, c_end = min(c_begin + a.chunk_rows, valid_y);
   const int c_first = c_begin + (OWN_PER_WAVE ? 0 : 32 * wv), c_step = OWN_PER_WAVE ? 32 : kMfmaStep;
-  // the wave's next 32 rows of Y as A operands (lane = row c0 + n): asked for one step ahead
+  // the wave's next 32 rows of Y (row-contiguous pieces, made into A operands when their step starts): asked for one
+  // step ahead
   bf16x8 nq[KS], nk[KS], nv[KS], ng[KS];
   auto ask = [&](int c0) {
-    const bool y_ok = c0 + n < c_end;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      nq[ks] = frag(a.qy, a.rows_y, c0 + n, y_ok, ks), nk[ks] = frag(a.ky, a.rows_y, c0 + n, y_ok, ks);
-      nv[ks] = frag(a.vy, a.rows_y, c0 + n, y_ok, ks), ng[ks] = frag(a.gy, a.rows_y, c0 + n, y_ok, ks);
-    }
+    fetch(a.qy, a.rows_y, c0, c_end, nq), fetch(a.ky, a.rows_y, c0, c_end, nk);
+    fetch(a.vy, a.rows_y, c0, c_end, nv), fetch(a.gy, a.rows_y, c0, c_end, ng);
   };
   if (c_first < c_end) ask(c_first);
   for (int c0 = c_first; c0 < c_end; c0 += c_step) {
     bf16x8 yq[KS], yk[KS], yv[KS], yg[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) yq[ks] = nq[ks], yk[ks] = nk[ks], yv[ks] = nv[ks], yg[ks] = ng[ks];
+    to_fragments(nq, yq), to_fragments(nk, yk), to_fragments(nv, yv), to_fragments(ng, yg);
     if (c0 + c_step < c_end) ask(c0 + c_step);
     f32x16 z1, w1, z2, w2;
 #pragma unroll
@@ -318,8 +330,6 @@ __global__ __launch_bounds__(256, (DH == 32 ? 2 : 1)) void xor_backward_side_mfm
       // Stored through the wave's piece of LDS, so that a store instruction writes whole head slices of a few rows
       // (16 bytes per lane, four or eight lanes per row) instead of eight bytes in each of 32 rows: the memory
       // pipeline works per cache line touched.
-      constexpr int P2 = DH + 8, CPR = DH / 8;  // bf16 per staged row; 16-byte pieces per row
-      typedef bf16x8 __attribute__((may_alias)) bf16x8_any;
 #pragma unroll
       for (int o = 0; o < 3; ++o) {
 #pragma unroll
