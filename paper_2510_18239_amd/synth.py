@@ -5,7 +5,7 @@ holds none of the method's arithmetic, so that the tests can hand the very
 same bytes to the HIP library and to the CPU oracle.
 
 Recipe (Section 4 latency study, Appendix C hyper-parameters for the shapes):
-every tensor is iid Gaussian.  Weights W_Q, W_K, W_V always have variance 1/d.
+every tensor is iid Gaussian.  Weights W_Q, W_K, W_V have variance 1/d (W_V times ``value_gain``^2 where a test sizes its outputs).
 Embeddings E, T, L have standard deviation ``gain * d**-0.5``: ``gain = 1`` is
 the benchmark distribution; a larger gain sharpens the attention logits so that
 the softmaxes are far from uniform (used by the parity tests, since at gain 1
@@ -80,10 +80,13 @@ class Workload:
 
 def make_workload(workload: int, B: int, N: int, C: int, d: int, h: int, m: int, dtype: str = "bf16",
                   gain: float = 1.0, len_range: tuple[int, int] | None = None,
-                  pad_value: float | None = None) -> Workload:
+                  pad_value: float | None = None, value_gain: float = 1.0) -> Workload:
     """Draw one workload.  ``len_range = (lo, hi)`` draws ragged lengths uniform on
     [lo, hi]; history rows at or beyond a user's length are then overwritten with
-    ``pad_value`` (NaN in the mask tests, 0 for timing) when it is given."""
+    ``pad_value`` (NaN in the mask tests, 0 for timing) when it is given.
+    ``value_gain`` multiplies the standard deviation of W_V only: it sizes the outputs
+    without touching any logit (the parity tests keep the sharpened outputs below one,
+    where the absolute error bar applies as stated)."""
     sd = gain * d ** -0.5
 
     def normal(name, shape, std):
@@ -94,7 +97,7 @@ def make_workload(workload: int, B: int, N: int, C: int, d: int, h: int, m: int,
     L = normal("L", (m, d), sd)
     Wq = normal("Wq", (d, d), d ** -0.5)
     Wk = normal("Wk", (d, d), d ** -0.5)
-    Wv = normal("Wv", (d, d), d ** -0.5)
+    Wv = normal("Wv", (d, d), value_gain * d ** -0.5)
     lens = None
     if len_range is not None:
         lo, hi = len_range
@@ -103,7 +106,7 @@ def make_workload(workload: int, B: int, N: int, C: int, d: int, h: int, m: int,
             for b in range(B):
                 E[b, lens[b]:] = pad_value
     return Workload(B, N, C, d, h, m, dtype, E, T, L, Wq, Wk, Wv, lens,
-                    {"workload": workload, "gain": gain, "len_range": len_range})
+                    {"workload": workload, "gain": gain, "len_range": len_range, "value_gain": value_gain})
 
 
 def per_user_links(workload: int, B: int, m: int, d: int, dtype: str, gain: float = 1.0) -> np.ndarray:
@@ -113,17 +116,18 @@ def per_user_links(workload: int, B: int, m: int, d: int, dtype: str, gain: floa
 
 
 def backward_inputs(workload: int, B: int, N: int, m: int, d: int, h: int, dtype: str, logit_std: float = 1.0,
-                    len_range=None, pad_value: float = 0.0) -> dict:
+                    len_range=None, pad_value: float = 0.0, value_std: float = 1.0, grad_std: float = 1.0) -> dict:
     """Inputs of the XORA backward pass: projected history rows QS, KS, VS [B, N, d], projected per-user links
     QT, KT, VT [B, m, d] and upstream gradients dOS, dOT of the same shapes, all ~N(0, std^2) and rounded to the
     storage type.  Queries and keys have the standard deviation that gives un-scaled logits <q_head, k_head> a
-    standard deviation of ``logit_std`` (the trained layer runs with logits of order one); values and gradients have
-    unit entries.  ``lens`` as in make_workload; rows at or past lens[b] of the history tensors hold ``pad_value``."""
+    standard deviation of ``logit_std`` (the trained layer runs with logits of order one); values and upstream
+    gradients have standard deviations ``value_std`` and ``grad_std`` (one for timing; the parity tests size them so
+    that the gradients, which are linear in both, stay below one, where the absolute error bar applies as stated).  ``lens`` as in make_workload; rows at or past lens[b] of the history tensors hold ``pad_value``."""
     dh = d // h
     qk_std = float((logit_std / np.sqrt(dh)) ** 0.5)
     t = {}
-    for name, rows, std in (("QS", N, qk_std), ("KS", N, qk_std), ("VS", N, 1.0), ("dOS", N, 1.0),
-                            ("QT", m, qk_std), ("KT", m, qk_std), ("VT", m, 1.0), ("dOT", m, 1.0)):
+    for name, rows, std in (("QS", N, qk_std), ("KS", N, qk_std), ("VS", N, value_std), ("dOS", N, grad_std),
+                            ("QT", m, qk_std), ("KT", m, qk_std), ("VT", m, value_std), ("dOT", m, grad_std)):
         x = _rng(workload, "bwd" + name).standard_normal((B, rows, d), dtype=np.float32) * np.float32(std)
         t[name] = round_to(x, dtype)
     if len_range is None:
@@ -135,6 +139,12 @@ def backward_inputs(workload: int, B: int, N: int, m: int, d: int, h: int, dtype
             for name in ("QS", "KS", "VS", "dOS"):
                 t[name][b, lens[b]:] = pad_value
     return t
+
+
+# W_V gain of the sharpened parity inputs: at logit standard deviation 2 a softmax picks out single rows, so an
+# output is about as large as a projected value, gain * value_gain * d^-1/2 * sqrt(d) = 1.4 * value_gain per
+# standard deviation with the softmax scale; a quarter keeps the largest output entry below one.
+SHARP_VALUE_GAIN = 0.25
 
 
 def sharp_gain(d: int, h: int, scale: float, logit_std: float = 2.0) -> float:

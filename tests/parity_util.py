@@ -34,22 +34,24 @@ class DeviceWorkload:
             setattr(self, k, dev(getattr(w, k), w.dtype))
 
 
-def assert_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str, factor: float = 1.0):
-    """max-abs error within the stated bar.
+ERRORS = []  # (what, dtype, err, max|ref|, err / max|ref|) of every comparison of this process, in order
 
-    The bar is absolute (1e-4 fp32, 2e-2 bf16) and, because every benchmark-distribution output is far
-    smaller than 1, it is also applied relative to the largest reference entry: err <= tol * max|ref|.
-    When max|ref| exceeds 1 only the relative form is meaningful (rounding a bf16 output of magnitude x
-    alone costs x * 2^-9), so the absolute bar scales with max(1, max|ref|).
-    """
+
+def assert_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str):
+    """The stated bar, unscaled: max-abs error <= 1e-4 (fp32 storage) / 2e-2 (bf16), whatever the size of the
+    reference; and, since the benchmark distribution's outputs are far smaller than that bar, the same number
+    relative to the largest reference entry as well: err <= tol * max|ref|.  Both must hold.  Every comparison
+    prints err, max|ref| and their ratio."""
     assert got.shape == ref.shape, (what, got.shape, ref.shape)
     assert np.isfinite(got).all(), f"{what}: non-finite output"
-    tol = TOL[dtype] * factor
+    tol = TOL[dtype]
     err = float(np.abs(got - ref).max()) if got.size else 0.0
     ref_max = float(np.abs(ref).max()) if ref.size else 0.0
-    assert err <= tol * max(1.0, ref_max), f"{what}: max-abs error {err:.3e} > {tol:.1e} (max|ref| = {ref_max:.3e})"
-    if ref_max > 0:
-        assert err / ref_max <= tol, f"{what}: error relative to max|ref| {err / ref_max:.3e} > {tol:.1e}"
+    ratio = err / ref_max if ref_max > 0 else 0.0
+    ERRORS.append((what, dtype, err, ref_max, ratio))
+    print(f"parity {dtype} {what}: err {err:.3e}  max|ref| {ref_max:.3e}  err/max|ref| {ratio:.3e}", flush=True)
+    assert err <= tol, f"{what}: max-abs error {err:.3e} > {tol:.1e} (max|ref| = {ref_max:.3e})"
+    assert ratio <= tol, f"{what}: error relative to max|ref| {ratio:.3e} > {tol:.1e} (max|ref| = {ref_max:.3e})"
     return err
 
 

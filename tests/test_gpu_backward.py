@@ -11,6 +11,10 @@ from parity_util import assert_close, dev, host
 pytestmark = pytest.mark.gpu
 
 NAMES = ("dQS", "dKS", "dVS", "dQT", "dKT", "dVT")
+# The gradients are linear in the values and in the upstream gradients: sized so that every gradient entry stays
+# below one (sums over thousands of rows, divisions by history lengths of one or two), where the stated absolute
+# bar applies; the logits keep their unit standard deviation.
+SIZED = dict(value_std=0.5, grad_std=0.1)
 
 
 def _run(t, h, scale, dtype, with_dos=True):
@@ -36,7 +40,7 @@ def _run(t, h, scale, dtype, with_dos=True):
 ])
 def test_xor_backward_matches_oracle(B, N, m, d, h, dtype, scale):
     """Ragged histories with NaN padding and, from three users on, one empty user; all six gradients."""
-    t = synth.backward_inputs(500 + N + m, B, N, m, d, h, dtype, len_range=(1, N), pad_value=np.nan)
+    t = synth.backward_inputs(500 + N + m, B, N, m, d, h, dtype, len_range=(1, N), pad_value=np.nan, **SIZED)
     if B >= 3:
         t["lens"][B - 1] = 0
         for k in ("QS", "KS", "VS", "dOS"):
@@ -56,7 +60,7 @@ def test_xor_backward_matches_oracle(B, N, m, d, h, dtype, scale):
 def test_xor_backward_without_source_gradient(dtype):
     """dOS absent (O[S] has no consumer, as in a single layer): dQS, dKT and dVT are exactly zero, the other three
     are those of the full call with a zero dOS; all lengths full (lens absent)."""
-    t = synth.backward_inputs(77, 2, 130, 64, 128, 4, dtype)
+    t = synth.backward_inputs(77, 2, 130, 64, 128, 4, dtype, **SIZED)
     got, ref = _run(t, 4, 1.0, dtype, with_dos=False)
     for name, x, r in zip(NAMES, got, ref):
         assert_close(x, r, dtype, name)
@@ -70,7 +74,7 @@ def test_xor_backward_without_source_gradient(dtype):
 def test_xor_backward_at_benchmark_size_is_deterministic():
     """Configuration 4's shape (8 users, d = 128, h = 4, m = 64) at N = 2048, the size bench.py --extras times: every
     element against the oracle, and two runs give the same bits (chunk partial sums are added in a fixed order)."""
-    t = synth.backward_inputs(4, 8, 2048, 64, 128, 4, "bf16", len_range=(1024, 2048))
+    t = synth.backward_inputs(4, 8, 2048, 64, 128, 4, "bf16", len_range=(1024, 2048), **SIZED)
     got, ref = _run(t, 4, 1.0, "bf16")
     for name, x, r in zip(NAMES, got, ref):
         assert_close(x, r, "bf16", name)

@@ -1,6 +1,7 @@
 """GPU parity: the HIP library, called through the C ABI, against the CPU oracle on the
-same seeded inputs, element by element.  Bars: max-abs 1e-4 (fp32) / 2e-2 (bf16), also
-relative to the largest reference entry; masks, zero padding and determinism bit-exact."""
+same seeded inputs, element by element.  Bars: max-abs 1e-4 (fp32) / 2e-2 (bf16) as stated,
+unscaled, and the same number relative to the largest reference entry; masks, zero padding
+and determinism bit-exact."""
 
 import numpy as np
 import pytest
@@ -13,10 +14,16 @@ from parity_util import DeviceWorkload, assert_close, dev, host, run_all_paths
 pytestmark = pytest.mark.gpu
 
 
-def _sharp(d, h, dtype, **kw):
-    """Workload whose softmax logits have a standard deviation of about 2 (far from uniform)."""
+def _sharp(d, h, dtype, value_gain=synth.SHARP_VALUE_GAIN, **kw):
+    """Workload whose softmax logits have a standard deviation of about 2 (far from uniform); W_V sized so that
+    the outputs stay below one, where the stated absolute bar applies."""
     g = synth.sharp_gain(d, h, (d // h) ** -0.5, 2.0)
-    return synth.make_workload(d=d, h=h, dtype=dtype, gain=g, **kw)
+    return synth.make_workload(d=d, h=h, dtype=dtype, gain=g, value_gain=value_gain, **kw)
+
+
+# XORA divides by the history length: over one or two rows O[T] is SiLU(logit) x value, several times a value
+# (a softmax weight never exceeds one), so the tests with such users take smaller values still.
+TINY_HISTORY_VALUE_GAIN = 0.03
 
 
 def _xor_scale(w):
@@ -27,8 +34,7 @@ def _xor_scale(w):
 def _check_all(w, **kw):
     print(f"case B={w.B} N={w.N} C={w.C} d={w.d} h={w.h} m={w.m} {w.dtype} gain={w.meta['gain']:.2f}", flush=True)
     for name, (got, ref) in run_all_paths(w, xor_scale=_xor_scale(w), **kw).items():
-        # the chained result carries the storage rounding of the link states as well
-        assert_close(got, ref, w.dtype, name, factor=2.0 if name == "chain" else 1.0)
+        assert_close(got, ref, w.dtype, name)
 
 
 # ----------------------------------------------------------------------------- configuration 1 (fp32)
@@ -72,13 +78,13 @@ def test_ragged_shapes(shape, gain):
 
 @pytest.mark.parametrize("dtype,d,h,m", [("bf16", 128, 4, 64), ("fp32", 32, 2, 8), ("bf16", 256, 4, 128)])
 def test_empty_and_tiny_histories(dtype, d, h, m):
-    w = _sharp(workload=30, B=5, N=70, C=9, d=d, h=h, m=m, dtype=dtype)
+    w = _sharp(workload=30, B=5, N=70, C=9, d=d, h=h, m=m, dtype=dtype, value_gain=TINY_HISTORY_VALUE_GAIN)
     w.lens = np.array([0, 1, 2, 70, 33], dtype=np.int32)
     for b in range(5):
         w.E[b, w.lens[b]:] = np.nan
     res = run_all_paths(w, xor_scale=w.softmax_scale)
     for name, (got, ref) in res.items():
-        assert_close(got, ref, dtype, name, factor=2.0 if name == "chain" else 1.0)
+        assert_close(got, ref, dtype, name)
     assert not res["lime_link_history"][0][0].any()  # empty history -> exact zeros
     assert not res["lime_xor_history.OT"][0][0].any()
     assert not res["mha_target_attention"][0][0].any()
@@ -89,7 +95,7 @@ def test_empty_and_tiny_histories(dtype, d, h, m):
 
 @pytest.mark.parametrize("dtype,d,h,m", [("bf16", 128, 4, 64), ("fp32", 64, 1, 16), ("bf16", 256, 4, 64)])
 def test_single_row_problems(dtype, d, h, m):
-    w = _sharp(workload=31, B=1, N=1, C=1, d=d, h=h, m=m, dtype=dtype)
+    w = _sharp(workload=31, B=1, N=1, C=1, d=d, h=h, m=m, dtype=dtype, value_gain=TINY_HISTORY_VALUE_GAIN)
     _check_all(w)
 
 
@@ -149,7 +155,7 @@ def test_identity_projections_in_candidate_stage(dtype, d, h, m):
     """NULL weights give the literal phi(T L^t) L^P of Eq. 4; any subset may be NULL."""
     w = _sharp(workload=35, B=2, N=8, C=150, d=d, h=h, m=m, dtype=dtype)
     g = DeviceWorkload(w)
-    LPv = synth.per_user_links(35, 2, m, d, dtype, gain=w.meta["gain"])
+    LPv = synth.per_user_links(35, 2, m, d, dtype, gain=w.meta["gain"] * synth.SHARP_VALUE_GAIN)  # values: outputs below one
     LP = dev(LPv, dtype)
     s = w.softmax_scale / w.meta["gain"]  # raw embeddings are larger than projected ones
     for mask in [(0, 0, 0), (1, 0, 0), (0, 1, 0), (0, 0, 1), (1, 1, 0)]:
@@ -341,7 +347,7 @@ def test_qk_cache_path(dtype, d, h, m, C):
     w = _sharp(workload=42, B=2, N=8, C=C, d=d, h=h, m=m, dtype=dtype)
     g = DeviceWorkload(w)
     s = w.softmax_scale
-    LPv = synth.per_user_links(42, 2, m, d, dtype, gain=w.meta["gain"])
+    LPv = synth.per_user_links(42, 2, m, d, dtype, gain=w.meta["gain"] * synth.SHARP_VALUE_GAIN)
     LP = dev(LPv, dtype)
     W = binding.lime_build_qk_cache(g.T, g.L, g.Wq, g.Wk, h, s)
     assert W.shape == (2, C, h, m)
@@ -353,9 +359,9 @@ def test_qk_cache_path(dtype, d, h, m, C):
     O = binding.lime_score_candidates_cached(W, LP, g.Wv)
     assert_close(host(O), orc.lime_score_candidates_cached(host(W), LPv, w.Wv, h), dtype, "cached O")
     # and the chain against Eq. 4 evaluated directly
-    assert_close(host(O), orc.lime_score_candidates(w.T, w.L, LPv, w.Wq, w.Wk, w.Wv, h, s), dtype, "cached chain", 2.0)
+    assert_close(host(O), orc.lime_score_candidates(w.T, w.L, LPv, w.Wq, w.Wk, w.Wv, h, s), dtype, "cached chain")
     direct = binding.lime_score_candidates(g.T, g.L, LP, g.Wq, g.Wk, g.Wv, h, s)
-    assert_close(host(O), host(direct).astype(np.float64), dtype, "cached vs direct on the GPU", 2.0)
+    assert_close(host(O), host(direct).astype(np.float64), dtype, "cached vs direct on the GPU")
 
 
 @pytest.mark.parametrize("dtype,d,h,m,n_items,C", [("bf16", 256, 4, 64, 5000, 1000), ("bf16", 128, 4, 64, 700, 333),
@@ -369,7 +375,7 @@ def test_gathered_qk_cache(dtype, d, h, m, n_items, C):
     w = _sharp(workload=44, B=1, N=8, C=n_items, d=d, h=h, m=m, dtype=dtype)  # T[0] is the corpus
     g = DeviceWorkload(w)
     s = w.softmax_scale
-    LPv = synth.per_user_links(44, B, m, d, dtype, gain=w.meta["gain"])
+    LPv = synth.per_user_links(44, B, m, d, dtype, gain=w.meta["gain"] * synth.SHARP_VALUE_GAIN)
     LP = dev(LPv, dtype)
     table = binding.lime_build_qk_cache(g.T, g.L, g.Wq, g.Wk, h, s)[0]
     rng = np.random.default_rng(4400 + n_items)
@@ -385,7 +391,7 @@ def test_gathered_qk_cache(dtype, d, h, m, n_items, C):
     assert np.array_equal(got[0, 0], got[0, 4])
     valid = (ids >= 0) & (ids < n_items)
     chain = orc.lime_score_candidates(w.T[0][np.where(valid, ids, 0)], w.L, LPv, w.Wq, w.Wk, w.Wv, h, s)
-    assert_close(got[valid], chain[valid], dtype, "gathered chain", 2.0)
+    assert_close(got[valid], chain[valid], dtype, "gathered chain")
 
 
 @pytest.mark.parametrize("B,N,C,d,h,m,ragged", [(1, 2048, 4096, 256, 4, 64, False), (3, 777, 500, 256, 4, 64, True),
@@ -512,7 +518,8 @@ def test_cooperative_history_kernels_on_edge_lengths(d, h, m, B, N):
     """Enough users x tiles for the cooperative history kernels (at d = 256 the variant with all W_K slices in
     LDS and one tile buffer), with the lengths that stress them: empty users, one item, one short of / exactly /
     one past a tile, a chunk boundary, the full history; padding rows hold NaN."""
-    w = _sharp(workload=90 + m, B=B, N=N, C=8, d=d, h=h, m=m, dtype="bf16", len_range=(1, N), pad_value=np.nan)
+    w = _sharp(workload=90 + m, B=B, N=N, C=8, d=d, h=h, m=m, dtype="bf16", len_range=(1, N), pad_value=np.nan,
+               value_gain=TINY_HISTORY_VALUE_GAIN)
     special = [0, 1, 31, 32, 33, 255, 256, 257, N - 1, N, 0, N]
     w.lens[:len(special)] = special
     for b, n in enumerate(special):
@@ -540,7 +547,7 @@ def _layer_weights(seed, n, d, gain=1.0):
 
 
 @pytest.mark.parametrize("dtype,B,N,d,h,m,n_layers,per_user", [
-    ("fp32", 2, 150, 64, 2, 24, 3, False),   # fp32 storage: the 1e-4 bar (chained: 2e-4)
+    ("fp32", 2, 150, 64, 2, 24, 3, False),   # fp32 storage: the 1e-4 bar
     ("fp32", 3, 70, 128, 4, 64, 2, True),
     ("bf16", 2, 90, 96, 3, 20, 3, False),    # bf16 outside the matrix-core set: general kernels
 ])
@@ -558,7 +565,7 @@ def test_xor_layers_on_general_kernels(dtype, B, N, d, h, m, n_layers, per_user)
     xs = _xor_scale(w)
     LP = binding.lime_xor_layers(g.E, g.lens, dev(LC, dtype), g.Wq, g.Wk, g.Wv, dev(Wu, dtype), dev(Wo, dtype), h, xs)
     ref = orc.lime_xor_layers(w.E, w.lens, LC, w.Wq, w.Wk, w.Wv, Wu, Wo, h, xs)
-    err = assert_close(host(LP), ref, dtype, "LP of stacked XOR layers", factor=2.0)
+    err = assert_close(host(LP), ref, dtype, "LP of stacked XOR layers")
     print(f"{dtype}: max|ref| = {np.abs(ref).max():.3e}, max-abs error {err:.3e}", flush=True)
     assert not host(LP)[B - 1].any()
 
@@ -573,7 +580,7 @@ def test_xor_layers_on_general_kernels(dtype, B, N, d, h, m, n_layers, per_user)
 def test_xor_layers(B, N, d, h, m, n_layers, per_user):
     """lime_xor_layers against the oracle's Eq. 8 on sharp inputs (gate pre-activations and XORA logits of order
     one, so that SiLU is far from linear), ragged lengths with an empty user, NaN in the padding rows.  The
-    intermediate tensors are bf16, so the bar is the chained one (twice the single-call bar)."""
+    intermediate tensors are bf16; the bar is the single-call one all the same."""
     w = _sharp(workload=400 + d + m + n_layers, B=B, N=N, C=8, d=d, h=h, m=m, dtype="bf16",
                len_range=(max(1, N // 3), N), pad_value=np.nan)
     w.lens[B - 1] = 0 if B > 1 else w.lens[0]
@@ -586,7 +593,7 @@ def test_xor_layers(B, N, d, h, m, n_layers, per_user):
     xs = _xor_scale(w)
     LP = binding.lime_xor_layers(g.E, g.lens, dev(LC, "bf16"), g.Wq, g.Wk, g.Wv, dev(Wu, "bf16"), dev(Wo, "bf16"), h, xs)
     ref = orc.lime_xor_layers(w.E, w.lens, LC, w.Wq, w.Wk, w.Wv, Wu, Wo, h, xs)
-    err = assert_close(host(LP), ref, "bf16", "LP of stacked XOR layers", factor=2.0)
+    err = assert_close(host(LP), ref, "bf16", "LP of stacked XOR layers")
     print(f"max|ref| = {np.abs(ref).max():.3e}, max-abs error {err:.3e}", flush=True)
     if B > 1:
         assert not host(LP)[B - 1].any()
