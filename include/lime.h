@@ -207,6 +207,26 @@ int32_t lime_request(const void* E, const int32_t* lens, const void* LC, int64_t
                      int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
 
 /*
+ * lime_request for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels and the same bits as lime_request, without the workspace: the
+ * scratch memory is a fixed array inside the library's device code (lime_request_static_capacity() bytes, 16 MiB, on
+ * every GPU the library runs on, held until the process ends).  The call allocates and frees nothing and calls no
+ * allocating routine; its first call on a device looks the array's address up (a host-side query, best made once
+ * before any graph capture).  A shape whose kernels need more scratch than the array holds is rejected with
+ * LIME_UNSUPPORTED and a message that names both sizes (nothing is enqueued); the headline request (B = 1, N = 2048,
+ * C = 32768, d = 256, h = 4, m = 64, bf16) needs 2.7 MiB.  All calls on one GPU share that GPU's array and nothing
+ * in it needs clearing between calls (every kernel writes what it later reads), so calls on one GPU must not
+ * overlap: two of them in flight at once, on different streams or from different threads, race on the scratch.
+ * Calls in order on one stream are safe.
+ */
+int32_t lime_request_static(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride,
+                            const void* Wq_hist, const void* Wk_hist, const void* Wv_hist, const void* T, const void* L,
+                            const void* Wq_cand, const void* Wk_cand, const void* Wv_cand, void* LP, void* O, int32_t B,
+                            int32_t N, int32_t C, int32_t d, int32_t h, int32_t m, float scale_hist, float scale_cand,
+                            int32_t xor_attention, int32_t dtype, void* stream);
+size_t lime_request_static_capacity(void);
+
+/*
  * Backward pass of one XORA layer with respect to its projected inputs (Appendix H.2; forward: Appendix H.1, Eq. 7).
  * Per user b and head (d cut into h contiguous blocks), with S the history rows (lens[b] valid, lens NULL = all N),
  * T the m links and phi(x) = SiLU(scale x) / n:

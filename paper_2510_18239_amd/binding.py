@@ -49,6 +49,9 @@ SIGNATURES = {
                                      _i32, _i32, _vp, _sz, _vp]),
     "lime_request": (_i32, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
                             _i32, _i32, _f32, _f32, _i32, _i32, _vp, _sz, _vp]),
+    "lime_request_static": (_i32, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32,
+                                   _i32, _i32, _i32, _f32, _f32, _i32, _i32, _vp]),
+    "lime_request_static_capacity": (_sz, []),
     "lime_xor_backward": (_i32, [_vp] * 15 + [_i32] * 5 + [_f32, _i32, _vp, _sz, _vp]),
     "lime_score_candidates_gathered": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _sz,
                                               _vp]),
@@ -413,6 +416,34 @@ def lime_request(E, lens, LC, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand,
                                 _ptr(L), _ptr(Wq_cand), _ptr(Wk_cand), _ptr(Wv_cand), _ptr(LP), _ptr(O), B, N, C, d, h, m,
                                 float(scale_hist), float(scale_cand), int(bool(xor_attention)), code, _ptr(ws), ws.numel(),
                                 _stream(stream))
+    _raise(st)
+    return LP, O
+
+
+def lime_request_static(E, lens, LC, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand, Wv_cand, h, scale_hist, scale_cand,
+                        xor_attention=False, LP=None, O=None, stream=None):
+    """lime_request on the library's own fixed scratch array instead of a workspace; returns (LP, O).  Calls on one
+    GPU must not overlap."""
+    first = _check(E, LC, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand, Wv_cand, LP, O)
+    B, N, d = E.shape
+    C = T.shape[1]
+    if LC.dim() == 2:
+        m, stride = LC.shape[0], 0
+    else:
+        if LC.shape[0] != B:
+            raise ValueError("per-user links must be [B, m, d]")
+        m, stride = LC.shape[1], LC.shape[1] * LC.shape[2]
+    code = _dtype_code(first)
+    lens = _lens_arg(lens, B, E.device)
+    if LP is None:
+        LP = torch.empty((B, m, d), dtype=E.dtype, device=E.device)
+    if O is None:
+        O = torch.empty_like(T)
+    with torch.cuda.device(E.device):
+        st = lib().lime_request_static(_ptr(E), _ptr(lens), _ptr(LC), stride, _ptr(Wq_hist), _ptr(Wk_hist), _ptr(Wv_hist),
+                                       _ptr(T), _ptr(L), _ptr(Wq_cand), _ptr(Wk_cand), _ptr(Wv_cand), _ptr(LP), _ptr(O), B, N,
+                                       C, d, h, m, float(scale_hist), float(scale_cand), int(bool(xor_attention)), code,
+                                       _stream(stream))
     _raise(st)
     return LP, O
 

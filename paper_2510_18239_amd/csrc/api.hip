@@ -5,9 +5,15 @@
 #include <stdio.h>
 
 #include <algorithm>
+#include <mutex>
 
 #include "common.hpp"
 #include "mfma.hpp"
+
+// Scratch of lime_request_static, the entry point for callers that cannot allocate or pass a workspace: 16 MiB per
+// GPU, held from the moment the library's code is loaded on that GPU until the process ends.
+constexpr size_t kStaticScratchBytes = size_t{16} << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -503,12 +509,41 @@ int32_t lime_request_prepared(const void* E, const int32_t* lens, const void* T,
   return LIME_OK;
 }
 
-int32_t lime_request(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride, const void* Wq_hist,
-                     const void* Wk_hist, const void* Wv_hist, const void* T, const void* L, const void* Wq_cand,
-                     const void* Wk_cand, const void* Wv_cand, void* LP, void* O, int32_t B, int32_t N, int32_t C,
-                     int32_t d, int32_t h, int32_t m, float scale_hist, float scale_cand, int32_t xor_attention,
-                     int32_t dtype, void* workspace, size_t ws_bytes, void* stream) {
-  const char* fn = "lime_request";
+namespace {
+
+// A request's workspace: the history stage's part, then the candidate stage's.  `any_path`: both parts sized for
+// whichever kernels a call of this shape could take (what lime_workspace_bytes reports); otherwise for the kernels
+// this call does take.
+struct RequestPlan {
+  bool on_mfma;
+  size_t hist_bytes, total;
+};
+
+RequestPlan plan_request(bool on_mfma, bool any_path, bool per_user, int32_t B, int32_t N, int32_t C, int32_t d, int32_t h,
+                         int32_t m, int32_t dtype) {
+  RequestPlan p{on_mfma, 0, 0};
+  if (any_path) {
+    p.hist_bytes = lime_workspace_bytes(LIME_OP_LINK_HISTORY, B, N, C, d, h, m, dtype, 0);
+    p.total = p.hist_bytes + lime_workspace_bytes(LIME_OP_SCORE_CANDIDATES, B, N, C, d, h, m, dtype, 0);
+  } else if (on_mfma) {
+    p.hist_bytes = lime::links_over_history_workspace(B, N, d, h, m, per_user);
+    p.total = p.hist_bytes + lime::queries_over_links_workspace(B, d, m, false);
+  } else {
+    // the two stages in turn: each picks its kernels by itself, so each part is sized for either choice
+    p.hist_bytes = plan_history(nullptr, B, N, d, m, per_user, false).bytes;
+    size_t cand = plan_queries(nullptr, static_cast<int64_t>(B) * C, m, static_cast<int64_t>(B) * m, d).bytes;
+    if (dtype == LIME_BF16 && lime::links_over_history_supported(d, h, m)) {
+      p.hist_bytes = std::max(p.hist_bytes, lime::links_over_history_workspace(B, N, d, h, m, per_user));
+      cand = std::max(cand, lime::queries_over_links_workspace(B, d, m, false));
+    }
+    p.total = p.hist_bytes + cand;
+  }
+  return p;
+}
+
+int32_t check_request(const char* fn, const void* E, const void* LC, int64_t lc_user_stride, const void* Wq_hist,
+                      const void* Wk_hist, const void* Wv_hist, const void* T, const void* L, void* LP, void* O, int32_t B,
+                      int32_t N, int32_t C, int32_t d, int32_t h, int32_t m, int32_t dtype) {
   if (int32_t st = check_common(fn, B, d, h, dtype)) return st;
   if (N <= 0 || C <= 0 || m <= 0)
     return fail(LIME_INVALID_ARG, "%s: N, C and m must be positive (N=%d C=%d m=%d)", fn, N, C, m);
@@ -516,23 +551,24 @@ int32_t lime_request(const void* E, const int32_t* lens, const void* LC, int64_t
     return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
   if (lc_user_stride != 0 && lc_user_stride != static_cast<int64_t>(m) * d)
     return fail(LIME_INVALID_ARG, "%s: lc_user_stride must be 0 or m*d (got %lld)", fn, static_cast<long long>(lc_user_stride));
+  return LIME_OK;
+}
+
+// Arguments checked, workspace of p.total bytes at hand.
+int32_t request_impl(const char* fn, const RequestPlan& p, const void* E, const int32_t* lens, const void* LC,
+                     int64_t lc_user_stride, const void* Wq_hist, const void* Wk_hist, const void* Wv_hist, const void* T,
+                     const void* L, const void* Wq_cand, const void* Wk_cand, const void* Wv_cand, void* LP, void* O,
+                     int32_t B, int32_t N, int32_t C, int32_t d, int32_t h, int32_t m, float scale_hist, float scale_cand,
+                     int32_t xor_attention, int32_t dtype, void* workspace, void* stream) {
   const int phi = xor_attention ? lime::kPhiSilu : lime::kPhiSoftmax;
   const bool per_user = lc_user_stride != 0;
-  // each stage has a part of the workspace of its own, sized as for the stage's own entry point
-  const size_t hist_any = lime_workspace_bytes(LIME_OP_LINK_HISTORY, B, N, C, d, h, m, dtype, 0);
-  const size_t need = hist_any + lime_workspace_bytes(LIME_OP_SCORE_CANDIDATES, B, N, C, d, h, m, dtype, 0);
-  if (!workspace || ws_bytes < need)
-    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? ws_bytes : 0);
-  void* cand_ws = static_cast<char*>(workspace) + hist_any;
-  const bool on_mfma = dtype == LIME_BF16 && lime::links_over_history_supported(d, h, m) &&
-                       all_aligned16(E, LC, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand, Wv_cand, LP, O, workspace) &&
-                       fits_tiles(B, N) && fits_tiles(B, C);
-  if (!on_mfma) {  // the two stages as they are (general kernels, or the matrix-core ones where each applies)
+  void* cand_ws = static_cast<char*>(workspace) + p.hist_bytes;
+  if (!p.on_mfma) {  // the two stages as they are (general kernels, or the matrix-core ones where each applies)
     if (int32_t st = history_impl(fn, phi, E, lens, LC, lc_user_stride, Wq_hist, Wk_hist, Wv_hist, LP, nullptr, B, N, d, h, m,
-                                  scale_hist, dtype, workspace, hist_any, stream))
+                                  scale_hist, dtype, workspace, p.hist_bytes, stream))
       return st;
     return lime_score_candidates(T, L, LP, Wq_cand, Wk_cand, Wv_cand, O, B, C, d, h, m, scale_cand, dtype, cand_ws,
-                                 ws_bytes - hist_any, stream);
+                                 p.total - p.hist_bytes, stream);
   }
   // Four kernels: one pack launch for the operands of both stages, the history kernel, the merge step that also writes
   // the candidate stage's value image, the candidate kernel.
@@ -555,6 +591,75 @@ int32_t lime_request(const void* E, const int32_t* lens, const void* LC, int64_t
   LIME_HIP(lime::queries_over_links(c, cand_ws, s));
   return LIME_OK;
 }
+
+// ----------------------------------------------------------------------------- the request without a workspace argument
+// Scratch of lime_request_static: every GPU the library runs on holds its own copy of this array, at its own
+// address, until the process ends.  In host code the array's name is not a device address: the address comes from
+// hipGetSymbolAddress, once per device, and only that pointer is handed to kernels.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// The current device's copy of `scratch` (looked up on the first call on that device).
+int32_t static_scratch(const char* fn, void** out) {
+  int dev = -1;
+  LIME_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(LIME_UNSUPPORTED, "%s: device ordinal %d is beyond %d", fn, dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    LIME_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr) return fail(LIME_LAUNCH_FAILED, "%s: hipGetSymbolAddress returned no address", fn);
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return LIME_OK;
+}
+
+}  // namespace
+
+int32_t lime_request(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride, const void* Wq_hist,
+                     const void* Wk_hist, const void* Wv_hist, const void* T, const void* L, const void* Wq_cand,
+                     const void* Wk_cand, const void* Wv_cand, void* LP, void* O, int32_t B, int32_t N, int32_t C,
+                     int32_t d, int32_t h, int32_t m, float scale_hist, float scale_cand, int32_t xor_attention,
+                     int32_t dtype, void* workspace, size_t ws_bytes, void* stream) {
+  const char* fn = "lime_request";
+  if (int32_t st = check_request(fn, E, LC, lc_user_stride, Wq_hist, Wk_hist, Wv_hist, T, L, LP, O, B, N, C, d, h, m, dtype))
+    return st;
+  const bool on_mfma = dtype == LIME_BF16 && lime::links_over_history_supported(d, h, m) &&
+                       all_aligned16(E, LC, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand, Wv_cand, LP, O, workspace) &&
+                       fits_tiles(B, N) && fits_tiles(B, C);
+  // each stage has a part of the workspace of its own, sized as for the stage's own entry point
+  const RequestPlan p = plan_request(on_mfma, /*any_path=*/true, lc_user_stride != 0, B, N, C, d, h, m, dtype);
+  if (!workspace || ws_bytes < p.total)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, p.total, workspace ? ws_bytes : 0);
+  return request_impl(fn, p, E, lens, LC, lc_user_stride, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand, Wv_cand, LP, O,
+                      B, N, C, d, h, m, scale_hist, scale_cand, xor_attention, dtype, workspace, stream);
+}
+
+int32_t lime_request_static(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride,
+                            const void* Wq_hist, const void* Wk_hist, const void* Wv_hist, const void* T, const void* L,
+                            const void* Wq_cand, const void* Wk_cand, const void* Wv_cand, void* LP, void* O, int32_t B,
+                            int32_t N, int32_t C, int32_t d, int32_t h, int32_t m, float scale_hist, float scale_cand,
+                            int32_t xor_attention, int32_t dtype, void* stream) {
+  const char* fn = "lime_request_static";
+  if (int32_t st = check_request(fn, E, LC, lc_user_stride, Wq_hist, Wk_hist, Wv_hist, T, L, LP, O, B, N, C, d, h, m, dtype))
+    return st;
+  const bool on_mfma = dtype == LIME_BF16 && lime::links_over_history_supported(d, h, m) &&
+                       all_aligned16(E, LC, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand, Wv_cand, LP, O) &&
+                       fits_tiles(B, N) && fits_tiles(B, C);
+  // sized for the kernels this call takes, so that the matrix-core shapes need little
+  const RequestPlan p = plan_request(on_mfma, /*any_path=*/false, lc_user_stride != 0, B, N, C, d, h, m, dtype);
+  if (p.total > kStaticScratchBytes)
+    return fail(LIME_UNSUPPORTED, "%s: this shape needs %zu bytes of scratch, the library's own buffer holds %zu; use lime_request with a workspace",
+                fn, p.total, kStaticScratchBytes);
+  void* ws = nullptr;
+  if (int32_t st = static_scratch(fn, &ws)) return st;
+  return request_impl(fn, p, E, lens, LC, lc_user_stride, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand, Wv_cand, LP, O,
+                      B, N, C, d, h, m, scale_hist, scale_cand, xor_attention, dtype, ws, stream);
+}
+
+size_t lime_request_static_capacity(void) { return kStaticScratchBytes; }
 
 int32_t lime_xor_layers(const void* E, const int32_t* lens, const void* LC, int64_t lc_user_stride, const void* Wq,
                         const void* Wk, const void* Wv, const void* Wu, const void* Wo, int32_t n_layers, void* LP,

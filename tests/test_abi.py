@@ -235,6 +235,26 @@ def test_request_argument_checks():
     assert binding.workspace_bytes(binding.OP_REQUEST, B=1, N=64, C=0, d=256, h=4, m=64) == 0
 
 
+def test_request_static_argument_checks():
+    """The entry point without a workspace: the same host-side checks as lime_request, and a shape whose scratch does not
+    fit the library's fixed array is refused before anything touches a device."""
+    lib = binding.lib()
+
+    def call(**kw):
+        a = dict(E=FAKE, lens=None, LC=FAKE, stride=0, Wq=FAKE, Wk=FAKE, Wv=FAKE, T=FAKE, L=FAKE, LP=FAKE, O=FAKE, B=1,
+                 N=64, C=64, d=64, h=2, m=32, dtype=1)
+        a.update(kw)
+        return lib.lime_request_static(a["E"], a["lens"], a["LC"], a["stride"], a["Wq"], a["Wk"], a["Wv"], a["T"], a["L"],
+                                       a["Wq"], a["Wk"], a["Wv"], a["LP"], a["O"], a["B"], a["N"], a["C"], a["d"], a["h"],
+                                       a["m"], 1.0, 1.0, 0, a["dtype"], None)
+
+    assert lib.lime_request_static_capacity() == 16 << 20
+    assert call(E=None) == 1 and call(O=None) == 1 and call(N=0) == 1 and call(h=3) == 1 and call(dtype=5) == 1
+    assert call(stride=7) == 1
+    assert call(B=64, N=4096, d=256, h=4, m=128) == 2 and "scratch" in binding.last_error()  # needs far more than 16 MiB
+    assert call(B=1, N=1 << 20, C=16, d=64, h=2, m=20, dtype=0) == 2  # general kernels: fp32 projections of the history
+
+
 def test_xor_backward_argument_checks():
     lib = binding.lib()
 
