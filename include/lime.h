@@ -4,8 +4,10 @@
  * Conventions common to every entry point
  * ---------------------------------------
  * Pointers.  Every tensor pointer is a DEVICE pointer owned by the caller.  The
- *   library never allocates, frees, copies to the host or synchronises.  `lens`
- *   is a device pointer too.  Outputs must not alias inputs.
+ *   entry points never allocate, free, copy to the host or synchronise (the one
+ *   exception is the benchmark's timing helper at the end of this file:
+ *   lime_profile_enable makes launches create HIP events, lime_profile_collect
+ *   waits for them).  `lens` is a device pointer too.  Outputs must not alias inputs.
  * Layout.  Row-major, innermost dimension contiguous, no padding between rows:
  *   E[B][N][d], T[B][C][d], L[m][d], LP[B][m][d], W[d_in][d_out] (so that the
  *   projection of Eq. 1 is X~ = X W).
@@ -255,18 +257,32 @@ size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t
                             int32_t dtype, int32_t flags);
 
 /*
- * Per-kernel timing for benchmarks (callers that only want results never need it).
- * lime_profile_enable(1): from now on every main kernel launched by the entry points above is
- * bracketed by a pair of HIP events on its stream (kernel ids: 0 = the candidate-side kernel
- * of lime_score_candidates and of O[S]; 1 = the links-over-history kernel of lime_link_history /
- * lime_xor_history; 2 = the attention kernel of mha_target_attention; 3 = their K/V projection; 4 = the kernel of
- * lime_score_candidates_cached and lime_score_candidates_gathered).
+ * Per-kernel timing for benchmarks (callers that only want results never need it; these are the only functions of
+ * the library that create HIP events and wait on the device).
+ * lime_profile_enable(1): from now on every main kernel launched by the entry points above carries a start and a
+ * stop event of its own (hipExtLaunchKernel), which the runtime fills with the dispatch's begin and end time stamps:
+ * the kernel's own duration as a kernel trace reports it.  Kernel ids: 0 = the candidate-side kernel of
+ * lime_score_candidates and of O[S]; 1 = the links-over-history kernel of lime_link_history / lime_xor_history;
+ * 2 = the attention kernel of mha_target_attention; 3 = its three row projections (one duration each); 4 = the kernel
+ * of lime_score_candidates_cached and lime_score_candidates_gathered; 5, 6 = the two probes below.
  * lime_profile_collect(kernel, ms, capacity): waits for the recorded launches of that kernel,
  * writes up to `capacity` durations in milliseconds to the HOST array `ms` in launch order,
  * forgets them and returns how many it wrote.  Only the matrix-core kernels are instrumented.
  */
 void lime_profile_enable(int32_t on);
 int32_t lime_profile_collect(int32_t kernel, float* ms, int32_t capacity);
+
+/*
+ * Achievable-peak probes for the benchmark's roofline context (Section 4 "Inference Speed" is measured against a
+ * machine; these say what this one sustains).  lime_probe_copy: a plain streaming copy of `bytes` (a multiple of 16,
+ * both pointers 16-byte aligned device memory) on `stream`; returns a status.  lime_probe_mfma: every compute unit
+ * runs `iters` x 4 register-resident v_mfma_f32_32x32x16_bf16 per wave; `out` is device memory of
+ * lime_probe_mfma_out_bytes() bytes; returns the floating-point operations the launch executes (0 on error).
+ * Time either with lime_profile_enable / lime_profile_collect (kernel ids 5 and 6).
+ */
+int32_t lime_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+size_t lime_probe_mfma_out_bytes(void);
+double lime_probe_mfma(void* out, int32_t iters, void* stream);
 
 /* Text of the calling thread's most recent non-zero status ("" if none).  Host memory, owned by the library. */
 const char* lime_last_error(void);

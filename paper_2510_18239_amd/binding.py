@@ -56,6 +56,9 @@ SIGNATURES = {
     "lime_score_candidates_gathered": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _sz,
                                               _vp]),
     "lime_workspace_bytes": (_sz, [_i32] * 9),
+    "lime_probe_copy": (_i32, [_vp, _vp, _sz, _vp]),
+    "lime_probe_mfma_out_bytes": (_sz, []),
+    "lime_probe_mfma": (_c.c_double, [_vp, _i32, _vp]),
     "lime_profile_enable": (None, [_i32]),
     "lime_profile_collect": (_i32, [_i32, _c.POINTER(_c.c_float), _i32]),
     "lime_last_error": (_c.c_char_p, []),
@@ -103,6 +106,27 @@ def profile_collect(kernel: int, capacity: int = 65536) -> list[float]:
     buf = (_c.c_float * capacity)()
     n = lib().lime_profile_collect(kernel, buf, capacity)
     return [float(buf[i]) for i in range(n)]
+
+
+KERNEL_PROBE_COPY, KERNEL_PROBE_MFMA = 5, 6
+
+
+def probe_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
+    """A plain device copy of src into dst (same byte size, a multiple of 16) by the library's streaming-copy probe."""
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size() and src.is_contiguous() and dst.is_contiguous()
+    with torch.cuda.device(src.device):
+        _raise(lib().lime_probe_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)))
+
+
+def probe_mfma(iters: int, stream=None) -> float:
+    """Runs the register-resident matrix-instruction loop; returns the floating-point operations it executes."""
+    out = get_workspace(lib().lime_probe_mfma_out_bytes(), torch.device("cuda", torch.cuda.current_device()))
+    with torch.cuda.device(out.device):
+        flops = lib().lime_probe_mfma(_ptr(out), int(iters), _stream(stream))
+    if flops <= 0:
+        raise LimeError(4, "lime_probe_mfma failed")
+    return float(flops)
 
 
 def workspace_bytes(op: int, B=1, N=1, C=1, d=1, h=1, m=1, dtype=LIME_BF16, flags=0) -> int:

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -36,9 +37,20 @@ int compute_units();
 
 // ----------------------------------------------------------------------------- per-kernel timing (profile.hip)
 enum ProfiledKernel { kKernelQueriesOverLinks = 0, kKernelLinksOverHistory = 1, kKernelTargetAttention = 2,
-                      kKernelProjection = 3, kKernelCachedCandidates = 4 };
-void profile_begin(int kernel, hipStream_t s);
-void profile_end(int kernel, hipStream_t s);
+                      kKernelProjection = 3, kKernelCachedCandidates = 4, kKernelProbeCopy = 5, kKernelProbeMfma = 6 };
+// When profiling is on: a fresh pair of events for one launch of `kernel`, remembered for lime_profile_collect.
+bool profile_events(int kernel, hipEvent_t* start, hipEvent_t* stop);
+// Launches a main kernel; with profiling on, the launch carries a start and a stop event of its own, which the
+// runtime fills from the dispatch's begin and end time stamps (the kernel's duration as a tracer sees it, without
+// the gaps an event recorded before or after the launch would include).
+template <typename... KA, typename... A>
+inline void launch_timed(int kernel_id, void (*kernel)(KA...), dim3 grid, dim3 block, size_t lds, hipStream_t s, A... args) {
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (profile_events(kernel_id, &e0, &e1))
+    hipExtLaunchKernelGGL(kernel, grid, block, static_cast<uint32_t>(lds), s, e0, e1, 0, args...);
+  else
+    hipLaunchKernelGGL(kernel, grid, block, lds, s, args...);
+}
 
 // ----------------------------------------------------------------------------- general kernels (generic.hip)
 // Y[rows][d] (fp32) = X[rows][d] * W[d][d]; W == nullptr copies X (identity projection).

@@ -98,9 +98,9 @@ __global__ __launch_bounds__(64 * H) void cached_candidates_kernel(CachedArgs a)
 template <int DH, int M, int H>
 void launch(const CachedArgs& a, int grid, hipStream_t s) {
   if (a.ids != nullptr)
-    hipLaunchKernelGGL((cached_candidates_kernel<DH, M, H, true>), dim3(grid), dim3(64 * H), 0, s, a);
+    launch_timed(kKernelCachedCandidates, cached_candidates_kernel<DH, M, H, true>, dim3(grid), dim3(64 * H), 0, s, a);
   else
-    hipLaunchKernelGGL((cached_candidates_kernel<DH, M, H, false>), dim3(grid), dim3(64 * H), 0, s, a);
+    launch_timed(kKernelCachedCandidates, cached_candidates_kernel<DH, M, H, false>, dim3(grid), dim3(64 * H), 0, s, a);
 }
 
 template <int DH, int H>
@@ -140,9 +140,7 @@ hipError_t cached_candidates(const CachedCandidates& q, void* workspace, hipStre
   // small register footprint: several workgroups per compute unit hide the memory latency
   const int resident = compute_units() * 4;
   const int grid = a.total_tiles < resident ? a.total_tiles : resident;
-  profile_begin(kKernelCachedCandidates, s);
   e = dh == 32 ? dispatch_h<32>(a, h, m, grid, s) : dispatch_h<64>(a, h, m, grid, s);
-  profile_end(kKernelCachedCandidates, s);
   return e;
 }
 

@@ -431,11 +431,11 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
 template <int DH, int M, int H, bool FUSED>
 hipError_t launch_form(const MainArgs& m, int phi, int grid, hipStream_t s) {
   if (m.Wout != nullptr)
-    hipLaunchKernelGGL((queries_over_links_kernel<DH, M, H, kPhiSoftmax, true, FUSED>), dim3(grid), dim3(64 * H), 0, s, m);
+    launch_timed(kKernelQueriesOverLinks, queries_over_links_kernel<DH, M, H, kPhiSoftmax, true, FUSED>, dim3(grid), dim3(64 * H), 0, s, m);
   else if (phi == kPhiSoftmax)
-    hipLaunchKernelGGL((queries_over_links_kernel<DH, M, H, kPhiSoftmax, false, FUSED>), dim3(grid), dim3(64 * H), 0, s, m);
+    launch_timed(kKernelQueriesOverLinks, queries_over_links_kernel<DH, M, H, kPhiSoftmax, false, FUSED>, dim3(grid), dim3(64 * H), 0, s, m);
   else
-    hipLaunchKernelGGL((queries_over_links_kernel<DH, M, H, kPhiSilu, false, FUSED>), dim3(grid), dim3(64 * H), 0, s, m);
+    launch_timed(kKernelQueriesOverLinks, queries_over_links_kernel<DH, M, H, kPhiSilu, false, FUSED>, dim3(grid), dim3(64 * H), 0, s, m);
   return hipGetLastError();
 }
 
@@ -552,9 +552,7 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
   // two when its footprint is small (d/h = 32)
   const int resident = compute_units() * (dh == 32 && h <= 4 ? 2 : 1);
   const int grid = a.total_tiles < resident ? a.total_tiles : resident;
-  profile_begin(kKernelQueriesOverLinks, s);
   e = dh == 32 ? dispatch_h<32>(a, h, m, q.phi, grid, s) : dispatch_h<64>(a, h, m, q.phi, grid, s);
-  profile_end(kKernelQueriesOverLinks, s);
   return e;
 }
 

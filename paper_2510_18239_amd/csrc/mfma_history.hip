@@ -482,7 +482,7 @@ hipError_t launch_phi(const HistArgs& a, int users, bool coop, hipStream_t s) {
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (attr != hipSuccess) return attr;
       }
-      hipLaunchKernelGGL(kernel, dim3(a.chunks, users), dim3(64 * H), lds, s, a);
+      launch_timed(kKernelLinksOverHistory, kernel, dim3(a.chunks, users), dim3(64 * H), lds, s, a);
       return hipGetLastError();
     }
   }
@@ -492,7 +492,7 @@ hipError_t launch_phi(const HistArgs& a, int users, bool coop, hipStream_t s) {
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(slice));
     if (attr != hipSuccess) return attr;
   }
-  hipLaunchKernelGGL(kernel, dim3(a.chunks, users, H), dim3(64), slice, s, a);
+  launch_timed(kKernelLinksOverHistory, kernel, dim3(a.chunks, users, H), dim3(64), slice, s, a);
   return hipGetLastError();
 }
 
@@ -602,9 +602,7 @@ hipError_t links_over_history(const LinksOverHistory& q, void* workspace, hipStr
   a.qb_user_frags = per_user ? static_cast<int64_t>(m) * d / 8 : 0;
   a.part_acc = part_acc, a.part_ml = part_ml;
   a.N = q.N, a.chunk_items = l.chunk_items, a.chunks = l.chunks, a.scale = fabsf(q.scale);
-  profile_begin(kKernelLinksOverHistory, s);
   e = dh == 32 ? dispatch_h<32>(a, h, m, q.phi, q.B, l.coop, s) : dispatch_h<64>(a, h, m, q.phi, q.B, l.coop, s);
-  profile_end(kKernelLinksOverHistory, s);
   if (e != hipSuccess) return e;
 
   MergeArgs g{part_acc, part_ml, q.lens, static_cast<bf16_t*>(q.LP), q.N, l.chunk_items, l.chunks, h, m, dh, fabsf(q.scale)};

@@ -255,28 +255,24 @@ hipError_t run(const TargetAttention& q, void* workspace, hipStream_t s) {
   if (e != hipSuccess) return e;
 
   const int resident = compute_units();
-  profile_begin(kKernelProjection, s);
   {
     ProjArgs p{static_cast<const bf16_t*>(q.T), nullptr, static_cast<const bf16x8*>(Wq), Qt, q.B, q.C, ctiles, ctiles * q.B};
-    hipLaunchKernelGGL((project_rows_kernel<DH, H, kOutRows>), dim3(p.total_tiles < resident ? p.total_tiles : resident),
+    launch_timed(kKernelProjection, project_rows_kernel<DH, H, kOutRows>, dim3(p.total_tiles < resident ? p.total_tiles : resident),
                        dim3(64 * H), 0, s, p);
     ProjArgs k{static_cast<const bf16_t*>(q.E), q.lens, static_cast<const bf16x8*>(Wk), Kimg, q.B, q.N, tiles, tiles * q.B};
-    hipLaunchKernelGGL((project_rows_kernel<DH, H, kOutKeyImage>), dim3(k.total_tiles < resident ? k.total_tiles : resident),
+    launch_timed(kKernelProjection, project_rows_kernel<DH, H, kOutKeyImage>, dim3(k.total_tiles < resident ? k.total_tiles : resident),
                        dim3(64 * H), 0, s, k);
     k.Wimg = static_cast<const bf16x8*>(Wv), k.Y = Vimg;
-    hipLaunchKernelGGL((project_rows_kernel<DH, H, kOutValueImage>), dim3(k.total_tiles < resident ? k.total_tiles : resident),
+    launch_timed(kKernelProjection, project_rows_kernel<DH, H, kOutValueImage>, dim3(k.total_tiles < resident ? k.total_tiles : resident),
                        dim3(64 * H), 0, s, k);
   }
-  profile_end(kKernelProjection, s);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
 
   AttnArgs a{Qt, reinterpret_cast<const bf16x8*>(Kimg), reinterpret_cast<const bf16x8*>(Vimg), q.lens,
              static_cast<bf16_t*>(q.O), q.C, q.N, tiles, fabsf(q.scale)};
   const dim3 grid((q.C + 511) / 512, H, q.B);
-  profile_begin(kKernelTargetAttention, s);
-  hipLaunchKernelGGL((target_attention_kernel<DH, H>), grid, dim3(256), 0, s, a);
-  profile_end(kKernelTargetAttention, s);
+  launch_timed(kKernelTargetAttention, target_attention_kernel<DH, H>, grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -1,6 +1,7 @@
-// Optional per-kernel timing: when switched on, the launchers bracket each main kernel with a
-// pair of HIP events on the launch stream, so a caller can read that kernel's own duration
-// (without the small pack / merge kernels around it).  Off by default; costs nothing then.
+// Optional per-kernel timing: when switched on, each main kernel is launched with a start and a stop
+// event of its own (hipExtLaunchKernel), which carry the dispatch's begin and end time stamps, so a caller
+// can read that kernel's own duration (without the small pack / merge kernels around it and without the
+// gaps between launches).  Off by default; costs nothing then.  Creates events and, in collect, waits for them.
 #include "../../include/lime.h"
 #include "common.hpp"
 
@@ -31,20 +32,14 @@ hipEvent_t take_event() {
 }
 }  // namespace
 
-void profile_begin(int kernel, hipStream_t s) {
-  if (!g_on.load(std::memory_order_relaxed)) return;
+bool profile_events(int kernel, hipEvent_t* start, hipEvent_t* stop) {
+  if (!g_on.load(std::memory_order_relaxed)) return false;
   std::lock_guard<std::mutex> lock(g_mu);
   Span sp{kernel, take_event(), take_event()};
-  if (!sp.start || !sp.stop) return;
-  (void)hipEventRecord(sp.start, s);
+  if (!sp.start || !sp.stop) return false;
   g_spans.push_back(sp);
-}
-
-void profile_end(int kernel, hipStream_t s) {
-  if (!g_on.load(std::memory_order_relaxed)) return;
-  std::lock_guard<std::mutex> lock(g_mu);
-  if (g_spans.empty() || g_spans.back().kernel != kernel) return;
-  (void)hipEventRecord(g_spans.back().stop, s);
+  *start = sp.start, *stop = sp.stop;
+  return true;
 }
 }  // namespace lime
 
