@@ -24,9 +24,9 @@ def sources() -> list[str]:
     return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ_DIR, os.path.basename(src)[:-4] + ".o")
-    cmd = ["hipcc", *HIPCC_FLAGS, "-c", src, "-o", obj]
+def _compile(src: str, obj_dir: str = OBJ_DIR, defines: tuple = ()) -> str:
+    obj = os.path.join(obj_dir, os.path.basename(src)[:-4] + ".o")
+    cmd = ["hipcc", *HIPCC_FLAGS, *[f"-D{d}" for d in defines], "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
@@ -37,16 +37,18 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build_library(jobs: int = 8) -> str:
-    """Compile every csrc/*.hip for gfx950 and link the shared library.  Always recompiles."""
-    os.makedirs(OBJ_DIR, exist_ok=True)
+def build_library(jobs: int = 8, lib: str = LIB, defines: tuple = ()) -> str:
+    """Compile every csrc/*.hip for gfx950 and link the shared library.  Always recompiles.
+    ``lib`` / ``defines``: another output path and preprocessor definitions (for comparing variants of a kernel)."""
+    obj_dir = OBJ_DIR if lib == LIB else lib + ".objs"
+    os.makedirs(obj_dir, exist_ok=True)
     with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(_compile, sources()))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+        objs = list(ex.map(lambda src: _compile(src, obj_dir, defines), sources()))
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":

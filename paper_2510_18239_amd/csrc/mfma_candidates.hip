@@ -26,6 +26,15 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
+#ifdef LIME_X_STAMPS
+}  // namespace
+__device__ long long g_stamps[1024][16];
+namespace {
+#define STAMP(i) do { if (threadIdx.x == 0) g_stamps[blockIdx.x][i] = wall_clock64(); } while (0)
+#else
+#define STAMP(i) do { } while (0)
+#endif
+
 // ----------------------------------------------------------------------------- main kernel
 struct MainArgs {
   const bf16_t* X;
@@ -77,6 +86,7 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   const int first = blockIdx.x * per_wg;
   const int last = min(first + per_wg, a.total_tiles);  // one past this workgroup's final tile
   if (first >= last) return;  // uniform
+  STAMP(0);
 
   // Rows past a user's last row are read from whatever follows (the next user's rows; zeros past the
   // end of the tensor): every row is an independent column of the three products and such columns
@@ -142,14 +152,18 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   // workgroups go to different XCDs) therefore start at different k-steps.  The destination registers and the
   // order of the products stay the same: kRot copies of the load sequence, chosen by a uniform switch.
   bf16x8 wq[KR][FB];
+#ifdef LIME_X_NOROT
+  constexpr int kRot = 1;
+#else
   constexpr int kRot = KR >= 8 ? 4 : 1;
+#endif
   auto load_wq = [&](auto rot_tag) {
     constexpr int start = decltype(rot_tag)::value * (KR / kRot);
 #pragma unroll
     for (int i = 0; i < KR; ++i) {
       const int kk = (i + start) % KR;
 #pragma unroll
-      for (int mb = 0; mb < FB; ++mb) wq[kk][mb] = a.WqA[((head * K1 + kk) * FB + mb) * 64 + lane];
+      for (int mb = 0; mb < FB; ++mb) wq[kk][mb] = a.WqA[((head * K1 + kk) * FB + mb + head * kQueryImageHeadPad) * 64 + lane];
     }
   };
   switch (kRot == 1 ? 0 : (blockIdx.x / 8) % kRot) {
@@ -161,7 +175,7 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   if constexpr (KL > 0) {
     bf16x8 tmp[KL * FB];
 #pragma unroll
-    for (int i = 0; i < KL * FB; ++i) tmp[i] = a.WqA[((head * K1 + KR) * FB + i) * 64 + lane];
+    for (int i = 0; i < KL * FB; ++i) tmp[i] = a.WqA[((head * K1 + KR) * FB + i + head * kQueryImageHeadPad) * 64 + lane];
 #pragma unroll
     for (int i = 0; i < KL * FB; ++i) wq_lds[(head * KL * FB + i) * 64 + lane] = tmp[i];
     // each wave reads back only what it wrote itself: no barrier needed
@@ -280,11 +294,13 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   // first product of tile i+1, whose X rows were parked in the other LDS buffer.
   park(ring[0], xs[0]);
   __syncthreads();
+  STAMP(1);
   if (first + P < last) {
     issue(ib, ir0, ring[0]);
     advance(ib, ir0);
   }
   first_product(xs[0]);
+  STAMP(2);
   int b = b_first, r0 = r0_first;  // the tile being computed
 
   for (int base = first; base < last; base += P) {
@@ -409,7 +425,7 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
                              ((static_cast<int64_t>(b) * a.rows + r0) * D + head * DH) * 2;
       if (r0 + 32 <= min(rlen, a.rows)) {  // uniform: every row of the tile is stored as computed
 #pragma unroll
-        for (int j = 0; j < LW; ++j) *reinterpret_cast<bf16x8*>(obase + ooff[j]) = ov[j];
+        for (int j = 0; j < LW; ++j) store_through(obase, 32 * 2 * D, ooff[j], ov[j]);
       } else {
 #pragma unroll
         for (int j = 0; j < LW; ++j) {
@@ -424,9 +440,20 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
       }
       }
       advance(b, r0);
+      STAMP(3 + (tile - first < 12 ? tile - first : 12));
     }
   }
 }
+
+#ifdef LIME_X_STAMPS
+}  // namespace
+}  // namespace lime
+extern "C" __attribute__((visibility("default"))) int lime_debug_stamps(long long* host) {
+  return hipMemcpyFromSymbol(host, HIP_SYMBOL(lime::g_stamps), sizeof(long long) * 1024 * 16);
+}
+namespace lime {
+namespace {
+#endif
 
 template <int DH, int M, int H, bool FUSED>
 hipError_t launch_form(const MainArgs& m, int phi, int grid, hipStream_t s) {
@@ -485,7 +512,7 @@ bool queries_over_links_supported(int d, int h, int m) {
 bool fused_scores(int d, int h, int m, bool k_per_user) { return !k_per_user && m <= d / h; }
 
 size_t queries_over_links_workspace(int B, int d, int m, bool k_per_user) {
-  const size_t wq = align_up(static_cast<size_t>(d) * d * 2);
+  const size_t wq = align_up(static_cast<size_t>(d) * d * 2 + kQueryImagePadBytes);
   const size_t ka = align_up(static_cast<size_t>(k_per_user ? B : 1) * m * d * 2);
   const size_t va = align_up(static_cast<size_t>(B) * m * d * 2);
   return wq + ka + va;
@@ -493,7 +520,7 @@ size_t queries_over_links_workspace(int B, int d, int m, bool k_per_user) {
 
 void* queries_over_links_values(const QueriesOverLinks& q, void* workspace) {
   char* ws = static_cast<char*>(workspace);
-  return ws + align_up(static_cast<size_t>(q.d) * q.d * 2) +
+  return ws + align_up(static_cast<size_t>(q.d) * q.d * 2 + kQueryImagePadBytes) +
          align_up(static_cast<size_t>(q.k_user_stride != 0 ? q.B : 1) * q.m * q.d * 2);
 }
 
@@ -501,9 +528,9 @@ void queries_over_links_jobs(const QueriesOverLinks& q, void* workspace, PackJob
   const int d = q.d, m = q.m;
   const bool k_per_user = q.k_user_stride != 0, v_per_user = q.v_user_stride != 0;
   char* ws = static_cast<char*>(workspace);
-  char* KA = ws + align_up(static_cast<size_t>(d) * d * 2);
+  char* KA = ws + align_up(static_cast<size_t>(d) * d * 2 + kQueryImagePadBytes);
   char* VA = KA + align_up(static_cast<size_t>(k_per_user ? q.B : 1) * m * d * 2);
-  jobs.weights[jobs.n_weights++] = PackWeight{q.Wq, ws};
+  jobs.weights[jobs.n_weights++] = PackWeight{q.Wq, ws, 1.f, kQueryImageHeadPad};
   // a negative logit scale is folded into the sign of the packed keys, so the kernel sees scale >= 0
   jobs.projections[jobs.n_projections++] =
       PackProject{q.Ksrc, q.Wk, KA, q.k_user_stride, k_per_user ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f};
@@ -516,7 +543,7 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
   const bool k_per_user = q.k_user_stride != 0, v_per_user = q.v_user_stride != 0;
   char* ws = static_cast<char*>(workspace);
   bf16_t* WqA = reinterpret_cast<bf16_t*>(ws);
-  bf16_t* KA = reinterpret_cast<bf16_t*>(ws + align_up(static_cast<size_t>(d) * d * 2));
+  bf16_t* KA = reinterpret_cast<bf16_t*>(ws + align_up(static_cast<size_t>(d) * d * 2 + kQueryImagePadBytes));
   bf16_t* VA = reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(KA) +
                                          align_up(static_cast<size_t>(k_per_user ? q.B : 1) * m * d * 2));
   // The score image G costs more to build than W_Q^T and K~ do to pack (measured: the request gets slower when

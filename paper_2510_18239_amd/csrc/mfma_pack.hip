@@ -13,6 +13,7 @@ struct PackArgs {
   const bf16_t* w_src[kMaxWeights];
   bf16x8* w_img[kMaxWeights];
   float w_sign[kMaxWeights];
+  int w_pad[kMaxWeights];
   const bf16_t* p_x[kMaxJobs];
   const bf16_t* p_w[kMaxJobs];
   bf16_t* p_img[kMaxJobs];
@@ -79,7 +80,7 @@ __device__ void score_wave(const PackArgs& p, int combo) {
   }
   // register 4jj + r is link 32lb + 8jj + 4g + r, the lane's column is row j = 32jb + n of G_a
   const int j = 32 * jb + n;
-  const int64_t frag = (static_cast<int64_t>(a) * K1 + j / 16) * LB + lb;
+  const int64_t frag = (static_cast<int64_t>(a) * K1 + j / 16) * LB + lb + a * kQueryImageHeadPad;
   bf16_t* dst = p.s_img + (frag * 64 + 32 * ((j % 16) / 8)) * 8 + j % 8;
 #pragma unroll
   for (int i = 0; i < 16; ++i) store_as(dst + (8 * (i / 4) + 4 * g + i % 4) * 8, acc[i] * p.s_sign);
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
     const int a = col / dh, c = col % dh, mb = c / 32, n = c % 32;
     const int kk = k0 / 16, g = (k0 % 16) / 8;
     const int64_t frag = (static_cast<int64_t>(a) * (d / 16) + kk) * (dh / 32) + mb;
-    p.w_img[job][frag * 64 + 32 * g + n] = v;
+    p.w_img[job][(frag + a * p.w_pad[job]) * 64 + 32 * g + n] = v;
     return;
   }
   blk -= p.n_weights * p.blocks_per_weight;
@@ -201,6 +202,7 @@ hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackPro
     p.w_src[i] = static_cast<const bf16_t*>(weights[i].W);
     p.w_img[i] = static_cast<bf16x8*>(weights[i].image);
     p.w_sign[i] = weights[i].sign;
+    p.w_pad[i] = weights[i].head_pad;
   }
   int blocks = 0;
   for (int i = 0; i < kMaxJobs; ++i) {
@@ -245,7 +247,7 @@ hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackPro
 
 PreparedLayout prepared_layout(int d, int m) {
   PreparedLayout l{};
-  const size_t w = align_up(static_cast<size_t>(d) * d * 2), links = align_up(static_cast<size_t>(m) * d * 2);
+  const size_t w = align_up(static_cast<size_t>(d) * d * 2 + kQueryImagePadBytes), links = align_up(static_cast<size_t>(m) * d * 2);
   l.wk = 0, l.wv = w, l.qb = 2 * w, l.wq = 2 * w + links, l.ka = 3 * w + links, l.total = 3 * w + 2 * links;
   return l;
 }
@@ -254,7 +256,7 @@ hipError_t prepare_operands(const PrepareOperands& p, void* prepared, hipStream_
   const PreparedLayout l = prepared_layout(p.d, p.m);
   char* base = static_cast<char*>(prepared);
   const float sign_cand = p.scale_cand < 0.f ? -1.f : 1.f;
-  PackWeight wjobs[3] = {{p.Wk_hist, base + l.wk}, {p.Wv_hist, base + l.wv}, {p.Wq_cand, base + l.wq}};
+  PackWeight wjobs[3] = {{p.Wk_hist, base + l.wk}, {p.Wv_hist, base + l.wv}, {p.Wq_cand, base + l.wq, 1.f, kQueryImageHeadPad}};
   PackProject pjobs[2] = {{p.LC, p.Wq_hist, base + l.qb, 0, 1, kPackKeys, p.scale_hist < 0.f ? -1.f : 1.f},
                           {p.L, p.Wk_cand, base + l.ka, 0, 1, kPackKeys, sign_cand}};
   if (fused_scores(p.d, p.h, p.m, false)) {
