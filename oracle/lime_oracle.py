@@ -59,6 +59,7 @@ __all__ = [
     "phi_softmax",
     "phi_silu",
     "mha",
+    "xor_mask",
     "xor_mask_and_denominator",
     "lime_link_history",
     "lime_xor_history",
@@ -155,18 +156,25 @@ def mha(Q, K, V, M, Wq, Wk, Wv, h, scale, phi="softmax", denom=None, return_weig
     return (out, weights) if return_weights else out
 
 
-def xor_mask_and_denominator(i, j, n_s, n_t):
-    """Algorithm 1: the XOR mask bit and the normaliser for query i, key j.
+def xor_mask(n_s, n_t):
+    """M_xor and the per-row normaliser of XORA over X = source (+) target (Eq. 6-7).
 
-    Positions [0, n_s) are source (history), [n_s, n_s + n_t) target (links).
-    A pair attends iff exactly one of the two is a source; the normaliser is
-    the size of the partition the query does NOT belong to.
+    Eq. 7 splits the attention into the two off-diagonal blocks, source queries x target keys and target queries x
+    source keys; nothing attends within its own partition.  So with ``is_source`` marking the first n_s of the
+    n_s + n_t positions, M[i, j] is true exactly where the two positions lie in different partitions, and a row is
+    normalised by the number of keys it can see: the size of the other partition (the "d" of Appendix I).
+    Returns (M [n, n] bool, denom [n]).
     """
-    q_is_source = i < n_s
-    k_is_source = j < n_s
-    attend = q_is_source != k_is_source
-    normaliser = n_t if q_is_source else n_s
-    return bool(attend), int(normaliser)
+    is_source = np.arange(n_s + n_t) < n_s
+    M = is_source[:, None] != is_source[None, :]
+    denom = np.where(is_source, n_t, n_s).astype(np.float64)
+    return M, denom
+
+
+def xor_mask_and_denominator(i, j, n_s, n_t):
+    """Entry (i, j) of M_xor and the normaliser of row i (see xor_mask): what Algorithm 1 returns for one pair."""
+    M, denom = xor_mask(n_s, n_t)
+    return bool(M[i, j]), int(denom[i])
 
 
 def _lens(lens, B, N):
@@ -237,19 +245,14 @@ def lime_xor_history(E, lens, LC, Wq, Wk, Wv, h, scale=1.0, want_os=True):
 def xora_quadratic(Eb, Lb, Wq, Wk, Wv, h, scale=1.0):
     """XORA(X, X, X; theta) = MHA(X, X, X; M_xor; theta), X = E (+) L^C (Eq. 6).
 
-    The full (n_s + n_t)^2 score matrix is formed and Algorithm 1 is evaluated
-    for every (i, j).  One user; Eb holds that user's n_s valid rows.
+    The full (n_s + n_t)^2 score matrix is formed and masked with M_xor (xor_mask).  One user; Eb holds that user's n_s valid rows.
     Returns (O[S] [n_s, d], O[T] [n_t, d]).
     """
     Eb, Lb = _f64(Eb), _f64(Lb)
     n_s, n_t = Eb.shape[0], Lb.shape[0]
     n = n_s + n_t
     X = np.concatenate([Eb, Lb], axis=0)
-    M = np.zeros((n, n), dtype=bool)
-    denom = np.zeros(n)
-    for i in range(n):
-        for j in range(n):
-            M[i, j], denom[i] = xor_mask_and_denominator(i, j, n_s, n_t)
+    M, denom = xor_mask(n_s, n_t)
     O = mha(X, X, X, M, Wq, Wk, Wv, h, scale, "silu", denom=denom)
     return O[:n_s], O[n_s:]
 

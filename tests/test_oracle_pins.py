@@ -675,13 +675,15 @@ def _mut_free_silu(x):
     return x / (1.0 + np.exp(-x))
 
 
-def _mut_xor_mask_and(i, j, n_s, n_t):
+def _mut_xor_mask_and(n_s, n_t):
     # the formula printed beside Eq. 7 (a conjunction): both indices are sources
-    return bool(i < n_s and j < n_s), int(n_t if i < n_s else n_s)
+    src = np.arange(n_s + n_t) < n_s
+    return src[:, None] & src[None, :], np.where(src, n_t, n_s).astype(np.float64)
 
 
-def _mut_xor_same_side_denominator(i, j, n_s, n_t):
-    return bool((i < n_s) != (j < n_s)), int(n_s if i < n_s else n_t)
+def _mut_xor_same_side_denominator(n_s, n_t):
+    src = np.arange(n_s + n_t) < n_s
+    return src[:, None] != src[None, :], np.where(src, n_s, n_t).astype(np.float64)
 
 
 def _make_mha_mutant(kind):
@@ -791,8 +793,8 @@ MUTATIONS = [
     ("phi_softmax", _mut_softmax_ignores_mask),
     ("phi_softmax", _mut_softmax_mask_after),
     ("phi_silu", _mut_phi_silu_unnormalised),
-    ("xor_mask_and_denominator", _mut_xor_mask_and),
-    ("xor_mask_and_denominator", _mut_xor_same_side_denominator),
+    ("xor_mask", _mut_xor_mask_and),
+    ("xor_mask", _mut_xor_same_side_denominator),
     ("mha", "no_heads"),
     ("mha", "no_scale"),
     ("mha", "keys_from_values"),
