@@ -40,6 +40,17 @@ Readings of points the paper leaves open (each is repeated where it is used):
     matrix factor) and SiLU' written out as the derivative of x sigmoid(x)
     (the expression in the listing of Algorithm 3 is not that derivative).
 
+  * the scoring pipeline around the two attention stages (Appendix C "Model Design", Eq. 2, Section 3.3), for
+    which the paper gives names and sizes only:  layer normalisation is the standard one over the d features of a
+    row (biased variance, eps inside the square root, learnable scale gamma and shift beta), applied to every
+    tensor that enters an MHA, once per tensor and role: the query-side tensor, the key-side tensor and the
+    value-side tensor each have their own (gamma, beta), and where keys and values are the same tensor (the
+    history in Eq. 3) one normalisation serves both;  Eq. 2's MLP is two affine maps with a ReLU between them,
+    applied to each link row concatenated with the user's context vector;  the interaction network is an MLP
+    with ReLU after every hidden layer and a last affine map to one logit per candidate, fed with the LIME
+    embedding alone.  The arithmetic of these readings is pinned; whether they are the authors' is not ("parity
+    unpinned" as to the reading).
+
 Pinned by tests/test_oracle_*.py (closed forms, brute force, a library routine,
 invariants, hand-derived fixtures).  Unpinned: the paper's claim that LIME
 approximates full target attention (Appendix D), which needs trained links and
@@ -73,6 +84,11 @@ __all__ = [
     "mha_target_attention",
     "qk_cache",
     "lime_score_candidates_cached",
+    "layer_norm",
+    "relu",
+    "contextualize_links",
+    "interaction_mlp",
+    "lime_scores",
 ]
 
 
@@ -487,3 +503,80 @@ def lime_score_candidates_gathered(Wtable, ids, LP, Wv, h):
             for a in range(h):
                 O[b, c, a * dh:(a + 1) * dh] = Wtable[i, a] @ Vt[:, a * dh:(a + 1) * dh]
     return O
+
+
+# ----------------------------------------------------------------------------- the scoring pipeline around the attention stages
+
+def layer_norm(X, gamma, beta, eps=1e-5):
+    """Layer normalisation of every row of X over its last axis (Appendix C, "Model Design": applied before the
+    Q, K, V projections):  y = (x - mean(x)) / sqrt(var(x) + eps) * gamma + beta, with the biased variance.
+
+    ``gamma`` / ``beta`` [d] (None = 1 / 0).  Rows holding NaN (padding) give NaN rows, which nothing reads.
+    """
+    X = _f64(X)
+    with np.errstate(invalid="ignore"):
+        mean = X.mean(axis=-1, keepdims=True)
+        var = ((X - mean) ** 2).mean(axis=-1, keepdims=True)
+        Y = (X - mean) / np.sqrt(var + eps)
+    if gamma is not None:
+        Y = Y * _f64(gamma)
+    if beta is not None:
+        Y = Y + _f64(beta)
+    return Y
+
+
+def relu(x):
+    return np.maximum(_f64(x), 0.0)
+
+
+def contextualize_links(L, EC, W1, b1, W2, b2):
+    """Link contextualisation, Eq. 2:  L^C = MLP(L (+) E^C) per user.
+
+    L [m, d] raw links (shared by all users); EC [B, dc] one context vector per user.  Every link row is
+    concatenated with the user's context vector ([m, d + dc]) and sent through the MLP, read as
+    ReLU(X W1 + b1) W2 + b2 with W1 [d + dc, dhid], W2 [dhid, d].  Returns [B, m, d].
+    """
+    L, EC = _f64(L), _f64(EC)
+    m, d = L.shape
+    B = EC.shape[0]
+    LC = np.zeros((B, m, d))
+    for b in range(B):
+        X = np.concatenate([L, np.broadcast_to(EC[b], (m, EC.shape[1]))], axis=1)
+        LC[b] = relu(X @ _f64(W1) + _f64(b1)) @ _f64(W2) + _f64(b2)
+    return LC
+
+
+def interaction_mlp(O, weights, biases):
+    """The shallow interaction network of Section 3.3 on the LIME embeddings: hidden layers x <- ReLU(x W_i + b_i)
+    (sizes as in the hyper-parameter table of Appendix C, e.g. [512, 128, 64]) and a last affine map to one logit.
+
+    O [..., d]; weights[i] [d_in, d_out] with the last d_out = 1.  Returns the logits, shape O.shape[:-1].
+    """
+    x = _f64(O)
+    for i, (W, b) in enumerate(zip(weights, biases)):
+        x = x @ _f64(W) + _f64(b)
+        if i + 1 < len(weights):
+            x = relu(x)
+    assert x.shape[-1] == 1
+    return x[..., 0]
+
+
+def lime_scores(E, lens, L, EC, T, p, h, scale_hist, scale_cand, eps=1e-5, return_all=False):
+    """One LIME-MHA request from embeddings to scores (Section 3.1 Eq. 2-4, Section 3.3, Appendix C):
+
+      L^C = MLP(L (+) E^C)                                              Eq. 2
+      L^P = MHA(LN(L^C), LN(E), LN(E); theta_hist)                      Eq. 3, normalised inputs
+      O   = MHA(LN(T), LN(L), LN(L^P); theta_cand)                      Eq. 4, normalised inputs
+      score = InteractionMLP(O)                                         Section 3.3
+
+    ``p`` is a dict of parameters: ctx = (W1, b1, W2, b2); hist = (Wq, Wk, Wv); cand = (Wq, Wk, Wv);
+    ln_hist_q, ln_hist_kv, ln_cand_q, ln_cand_k, ln_cand_v = (gamma, beta) each; mlp = (weights, biases).
+    Returns scores [B, C] (with return_all: also LC, LP, O).
+    """
+    LC = contextualize_links(L, EC, *p["ctx"])
+    LP = lime_link_history(layer_norm(E, *p["ln_hist_kv"], eps), lens, layer_norm(LC, *p["ln_hist_q"], eps), *p["hist"], h,
+                           scale_hist)
+    O = lime_score_candidates(layer_norm(T, *p["ln_cand_q"], eps), layer_norm(L, *p["ln_cand_k"], eps),
+                              layer_norm(LP, *p["ln_cand_v"], eps), *p["cand"], h, scale_cand)
+    scores = interaction_mlp(O, *p["mlp"])
+    return (scores, LC, LP, O) if return_all else scores
