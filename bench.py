@@ -472,6 +472,19 @@ def curves(binding, synth, torch, dev, timed, pct):
         sweep[C] = {"lime_score_candidates_p50_ms": cand, "lime_request_p50_ms": req}
     res["latency_vs_candidates"] = {"workload": "BASELINE.json configs[2]: B=1, N=2048, d=256, h=4, m=64, bf16 (warm buffers)",
                                     "points": sweep}
+    # ... and the same request from embeddings to scores (lime_scores: Eq. 2, layer normalisation before the projections,
+    # Eq. 3, Eq. 4, the interaction network of Section 3.3) with Appendix C's industrial network [96] and its largest one
+    sc = {}
+    for widths in ([96, 1], [512, 128, 64, 1]):
+        ps = synth.scoring_params(3, w.B, w.m, w.d, 64, 256, widths, "bf16")
+        pair = lambda tt: tuple(t(x) for x in tt)  # noqa: E731
+        keep = (pair(ps["ctx"]), pair(ps["hist"]), pair(ps["cand"]), [pair(ps[k]) for k in ("ln_hist_q", "ln_hist_kv", "ln_cand_q",
+                "ln_cand_k", "ln_cand_v")], ([t(x) for x in ps["mlp"][0]], [t(x) for x in ps["mlp"][1]]))
+        model = binding.scoring_model(L, keep[0], keep[1], keep[2], *keep[3], keep[4], w.h, s, s)
+        EC = t(ps["EC"])
+        sc[",".join(str(x) for x in widths[:-1])] = pct(timed(lambda i: binding.lime_scores(model, E, None, EC, T), 40), 0.5)
+    res["embeddings_to_scores_p50_ms"] = {"workload": "the headline request, C = 32768, as lime_scores; keyed by the hidden widths of the "
+                                                      "interaction network", "points": sc}
     del E, T
     # (b) history length: one XORA layer (link states only, and with O[S]), N = 2048 ... 16384
     c4 = dict(synth.CONFIGS[4])

@@ -249,6 +249,66 @@ int32_t lime_xor_backward(const void* QS, const void* KS, const void* VS, const 
                           float scale, int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
 
 /*
+ * The scoring pipeline around the two attention stages.  The paper names these parts and gives their sizes without
+ * defining them; the readings taken here are stated with each.
+ *
+ * lime_layer_norm - Appendix C ("Model Design", Normalization: layer normalisation before each linear projection in
+ *   the QKV projections).  Y[r] = (X[r] - mean) / sqrt(var + eps) * gamma + beta over the d features of row r, biased
+ *   variance, statistics in fp32; gamma, beta [d] device pointers in `dtype`, NULL = 1 / 0.  X, Y [rows][d]; Y may be X.
+ * lime_contextualize_links - Section 3.1 Eq. 2, L^C = MLP(L (+) E^C): every raw link row L[i] ([m][d], shared) is
+ *   concatenated with user b's context vector EC[b] ([B][dc]) and sent through the MLP, read as
+ *   ReLU(x W1 + b1) W2 + b2 with W1 [d + dc][dhid], b1 [dhid], W2 [dhid][d], b2 [d] (b1, b2 nullable = 0).
+ *   Out: LC[B][m][d] (use it with lc_user_stride = m*d).  Workspace: B * m * dhid floats, rounded up to 256 bytes.
+ * lime_interaction_mlp - Section 3.3 (the shallow interaction network; widths as in Appendix C's hyper-parameter
+ *   table, e.g. 512, 128, 64): n_maps affine maps x <- x W[i] + b[i], ReLU after all but the last, the last to ONE
+ *   logit per row.  W, b, widths are HOST arrays of n_maps entries (device pointers W[i] [d_in][widths[i]] and b[i]
+ *   [widths[i]], nullable; widths[n_maps-1] = 1; n_maps <= 4).  In: O[rows][d].  Out: scores[rows], always fp32.
+ *   bf16 with (d; hidden widths) in {32, 64, 128, 256} x {(512,128,64), (512,256,128), (96)} (not d = 64 with the
+ *   second) runs on the matrix cores with the hidden activations kept in registers (rounded to bf16 between layers);
+ *   everything else in fp32 arithmetic.  Workspace: lime_interaction_mlp_workspace_bytes.
+ * lime_scores - one LIME-MHA request from embeddings to scores:
+ *     L^C = MLP(L (+) E^C)                                   Eq. 2
+ *     L^P = MHA(LN(L^C), LN(E), LN(E); theta_hist)           Eq. 3 on normalised inputs, softmax over valid history rows
+ *     O   = MHA(LN(T), LN(L), LN(L^P); theta_cand)           Eq. 4 on normalised inputs (keys: raw links, values: L^P)
+ *     scores = InteractionMLP(O)                             Section 3.3
+ *   Reading of Appendix C's normalisation: every tensor that enters an MHA is layer-normalised once per role - query,
+ *   key and value side each with its own (gamma, beta) - and where keys and values are the same tensor (the history
+ *   in Eq. 3) one normalisation serves both.  `model` is a HOST struct of device pointers and sizes; E[B][N][d], lens,
+ *   EC[B][dc], T[B][C][d] as elsewhere.  Out: scores[B][C] fp32; LC, LP [B][m][d] and O [B][C][d] when not NULL.
+ *   Workspace: lime_scores_workspace_bytes, 256-byte aligned (it holds the normalised copies of E and T).
+ */
+typedef struct lime_scoring_model {
+  int32_t d, h, m, dc, dhid;  /* embedding width, heads, links, width of the context vector, hidden width of Eq. 2's MLP */
+  const void* L;              /* [m][d] raw links */
+  const void *ctx_W1, *ctx_b1, *ctx_W2, *ctx_b2;
+  const void *hist_Wq, *hist_Wk, *hist_Wv;  /* theta of Eq. 3 */
+  const void *cand_Wq, *cand_Wk, *cand_Wv;  /* theta of Eq. 4 (all three required here) */
+  const void* ln_hist_q[2];   /* (gamma, beta) of the layer normalisation of L^C; each [d], NULL = 1 / 0 */
+  const void* ln_hist_kv[2];  /* of E (keys and values of Eq. 3) */
+  const void* ln_cand_q[2];   /* of T */
+  const void* ln_cand_k[2];   /* of L */
+  const void* ln_cand_v[2];   /* of L^P */
+  int32_t n_mlp;              /* affine maps of the interaction network (1..4), the last to one logit */
+  int32_t mlp_width[4];
+  const void* mlp_W[4];
+  const void* mlp_b[4];
+  float scale_hist, scale_cand, ln_eps;
+} lime_scoring_model;
+
+int32_t lime_layer_norm(const void* X, const void* gamma, const void* beta, float eps, void* Y, int64_t rows, int32_t d,
+                        int32_t dtype, void* stream);
+int32_t lime_contextualize_links(const void* L, const void* EC, const void* W1, const void* b1, const void* W2, const void* b2,
+                                 void* LC, int32_t B, int32_t m, int32_t d, int32_t dc, int32_t dhid, int32_t dtype,
+                                 void* workspace, size_t ws_bytes, void* stream);
+size_t lime_interaction_mlp_workspace_bytes(int64_t rows, int32_t d, const int32_t* widths, int32_t n_maps, int32_t dtype);
+int32_t lime_interaction_mlp(const void* O, const void* const* W, const void* const* b, const int32_t* widths, int32_t n_maps,
+                             float* scores, int64_t rows, int32_t d, int32_t dtype, void* workspace, size_t ws_bytes, void* stream);
+size_t lime_scores_workspace_bytes(const lime_scoring_model* model, int32_t B, int32_t N, int32_t C, int32_t dtype);
+int32_t lime_scores(const lime_scoring_model* model, const void* E, const int32_t* lens, const void* EC, const void* T,
+                    void* LC, void* LP, void* O, float* scores, int32_t B, int32_t N, int32_t C, int32_t dtype,
+                    void* workspace, size_t ws_bytes, void* stream);
+
+/*
  * Workspace size in bytes for `op` (LIME_OP_*) at the given shape; dimensions an op
  * does not have are ignored.  `flags` bit 0: lime_xor_history will be asked for OS.
  * Returns 0 for shapes the op would reject.

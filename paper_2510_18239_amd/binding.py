@@ -65,6 +65,28 @@ SIGNATURES = {
     "lime_version": (_c.c_char_p, []),
 }
 
+
+
+class ScoringModel(_c.Structure):
+    """lime_scoring_model of include/lime.h (a host struct of device pointers and sizes)."""
+    _fields_ = [("d", _i32), ("h", _i32), ("m", _i32), ("dc", _i32), ("dhid", _i32), ("L", _vp),
+                ("ctx_W1", _vp), ("ctx_b1", _vp), ("ctx_W2", _vp), ("ctx_b2", _vp),
+                ("hist_Wq", _vp), ("hist_Wk", _vp), ("hist_Wv", _vp), ("cand_Wq", _vp), ("cand_Wk", _vp), ("cand_Wv", _vp),
+                ("ln_hist_q", _vp * 2), ("ln_hist_kv", _vp * 2), ("ln_cand_q", _vp * 2), ("ln_cand_k", _vp * 2),
+                ("ln_cand_v", _vp * 2), ("n_mlp", _i32), ("mlp_width", _i32 * 4), ("mlp_W", _vp * 4), ("mlp_b", _vp * 4),
+                ("scale_hist", _f32), ("scale_cand", _f32), ("ln_eps", _f32)]
+
+
+SIGNATURES.update({
+    "lime_layer_norm": (_i32, [_vp, _vp, _vp, _f32, _vp, _i64, _i32, _i32, _vp]),
+    "lime_contextualize_links": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _sz, _vp]),
+    "lime_interaction_mlp_workspace_bytes": (_sz, [_i64, _i32, _c.POINTER(_i32), _i32, _i32]),
+    "lime_interaction_mlp": (_i32, [_vp, _c.POINTER(_vp), _c.POINTER(_vp), _c.POINTER(_i32), _i32, _vp, _i64, _i32, _i32, _vp, _sz,
+                                    _vp]),
+    "lime_scores_workspace_bytes": (_sz, [_c.POINTER(ScoringModel), _i32, _i32, _i32, _i32]),
+    "lime_scores": (_i32, [_c.POINTER(ScoringModel), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _sz, _vp]),
+})
+
 _lib = None
 
 
@@ -492,3 +514,108 @@ def lime_request_prepared(E, lens, T, Wv, prepared, h, m, scale_hist, scale_cand
                                          _ptr(ws), ws.numel(), _stream(stream))
     _raise(st)
     return LP, O
+
+
+def lime_layer_norm(X, gamma, beta, eps=1e-5, Y=None, stream=None):
+    """Y = LayerNorm(X; gamma, beta, eps) over the last axis (Appendix C); gamma, beta [d] or None."""
+    first = _check(X, gamma, beta, Y)
+    d = X.shape[-1]
+    if Y is None:
+        Y = torch.empty_like(X)
+    with torch.cuda.device(X.device):
+        st = lib().lime_layer_norm(_ptr(X), _ptr(gamma), _ptr(beta), float(eps), _ptr(Y), X.numel() // d, d, _dtype_code(first),
+                                   _stream(stream))
+    _raise(st)
+    return Y
+
+
+def lime_contextualize_links(L, EC, W1, b1, W2, b2, LC=None, workspace=None, stream=None):
+    """LC[B, m, d] = ReLU([L | EC_b] W1 + b1) W2 + b2 per user (Eq. 2)."""
+    first = _check(L, EC, W1, b1, W2, b2, LC)
+    m, d = L.shape
+    B, dc = EC.shape
+    dhid = W1.shape[1]
+    if W1.shape[0] != d + dc or tuple(W2.shape) != (dhid, d):
+        raise ValueError("W1 must be [d + dc, dhid] and W2 [dhid, d]")
+    if LC is None:
+        LC = torch.empty((B, m, d), dtype=L.dtype, device=L.device)
+    need = (B * m * dhid * 4 + 255) // 256 * 256
+    ws = workspace if workspace is not None else get_workspace(need, L.device)
+    with torch.cuda.device(L.device):
+        st = lib().lime_contextualize_links(_ptr(L), _ptr(EC), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), _ptr(LC), B, m, d, dc, dhid,
+                                            _dtype_code(first), _ptr(ws), ws.numel(), _stream(stream))
+    _raise(st)
+    return LC
+
+
+def _mlp_arrays(weights, biases):
+    n = len(weights)
+    W = (_vp * n)(*[_ptr(w) for w in weights])
+    b = (_vp * n)(*[_ptr(x) for x in biases])
+    widths = (_i32 * n)(*[int(w.shape[1]) for w in weights])
+    return n, W, b, widths
+
+
+def lime_interaction_mlp(O, weights, biases, scores=None, workspace=None, stream=None):
+    """scores[...] (fp32) of the interaction network (Section 3.3) on the rows of O[..., d]: weights[i] [d_in, d_out] with
+    ReLU after all but the last map, whose d_out is 1; biases[i] [d_out] or None."""
+    first = _check(O, *weights, *biases)
+    d = O.shape[-1]
+    rows = O.numel() // d
+    n, W, b, widths = _mlp_arrays(weights, biases)
+    code = _dtype_code(first)
+    if scores is None:
+        scores = torch.empty(O.shape[:-1], dtype=torch.float32, device=O.device)
+    need = int(lib().lime_interaction_mlp_workspace_bytes(rows, d, widths, n, code))
+    ws = workspace if workspace is not None else get_workspace(need, O.device)
+    with torch.cuda.device(O.device):
+        st = lib().lime_interaction_mlp(_ptr(O), W, b, widths, n, _ptr(scores), rows, d, code, _ptr(ws), ws.numel(), _stream(stream))
+    _raise(st)
+    return scores
+
+
+def scoring_model(L, ctx, hist, cand, ln_hist_q, ln_hist_kv, ln_cand_q, ln_cand_k, ln_cand_v, mlp, h, scale_hist, scale_cand,
+                  ln_eps=1e-5) -> ScoringModel:
+    """The host struct lime_scores takes: ctx = (W1, b1, W2, b2); hist, cand = (Wq, Wk, Wv); ln_* = (gamma, beta) or
+    (None, None); mlp = (weights, biases).  The tensors must stay alive while the struct is used."""
+    M = ScoringModel()
+    M.m, M.d = L.shape
+    M.h, M.dc, M.dhid = h, ctx[0].shape[0] - L.shape[1], ctx[0].shape[1]
+    M.L = _ptr(L)
+    M.ctx_W1, M.ctx_b1, M.ctx_W2, M.ctx_b2 = (_ptr(x) for x in ctx)
+    M.hist_Wq, M.hist_Wk, M.hist_Wv = (_ptr(x) for x in hist)
+    M.cand_Wq, M.cand_Wk, M.cand_Wv = (_ptr(x) for x in cand)
+    for name, gb in (("ln_hist_q", ln_hist_q), ("ln_hist_kv", ln_hist_kv), ("ln_cand_q", ln_cand_q), ("ln_cand_k", ln_cand_k),
+                     ("ln_cand_v", ln_cand_v)):
+        setattr(M, name, (_vp * 2)(_ptr(gb[0]), _ptr(gb[1])))
+    weights, biases = mlp
+    M.n_mlp = len(weights)
+    for i, (w, bias) in enumerate(zip(weights, biases)):
+        M.mlp_width[i], M.mlp_W[i], M.mlp_b[i] = int(w.shape[1]), _ptr(w), _ptr(bias)
+    M.scale_hist, M.scale_cand, M.ln_eps = float(scale_hist), float(scale_cand), float(ln_eps)
+    return M
+
+
+def lime_scores(model: ScoringModel, E, lens, EC, T, want_intermediates=False, workspace=None, stream=None):
+    """One LIME-MHA request from embeddings to scores (Eq. 2 -> LN -> Eq. 3 -> LN -> Eq. 4 -> interaction network).
+    Returns scores [B, C] (fp32), and with want_intermediates also (LC, LP, O)."""
+    first = _check(E, EC, T)
+    B, N, d = E.shape
+    C = T.shape[1]
+    code = _dtype_code(first)
+    lens = _lens_arg(lens, B, E.device)
+    scores = torch.empty((B, C), dtype=torch.float32, device=E.device)
+    LC = LP = O = None
+    if want_intermediates:
+        LC = torch.empty((B, model.m, d), dtype=E.dtype, device=E.device)
+        LP = torch.empty_like(LC)
+        O = torch.empty_like(T)
+    need = int(lib().lime_scores_workspace_bytes(_c.byref(model), B, N, C, code))
+    if need == 0:
+        raise LimeError(1, "lime_scores: the model or the sizes are not valid")
+    ws = workspace if workspace is not None else get_workspace(need, E.device)
+    with torch.cuda.device(E.device):
+        st = lib().lime_scores(_c.byref(model), _ptr(E), _ptr(lens), _ptr(EC), _ptr(T), _ptr(LC), _ptr(LP), _ptr(O), _ptr(scores), B, N,
+                               C, code, _ptr(ws), ws.numel(), _stream(stream))
+    _raise(st)
+    return (scores, LC, LP, O) if want_intermediates else scores

@@ -9,6 +9,7 @@
 
 #include "common.hpp"
 #include "mfma.hpp"
+#include "scoring.hpp"
 
 // Scratch of lime_request_static, the entry point for callers that cannot allocate or pass a workspace: 16 MiB per
 // GPU, held from the moment the library's code is loaded on that GPU until the process ends.
@@ -749,6 +750,221 @@ int32_t lime_xor_backward(const void* QS, const void* KS, const void* VS, const 
   g.B = B, g.N = N, g.m = m, g.d = d, g.h = h, g.dtype = dtype, g.scale = scale;
   LIME_HIP(lime::xor_backward(g, workspace, static_cast<hipStream_t>(stream)));
   return LIME_OK;
+}
+
+
+// ----------------------------------------------------------------------------- the scoring pipeline around the attention stages
+namespace {
+
+constexpr int kMaxMlpMaps = 4;
+
+int32_t check_mlp(const char* fn, const void* const* W, const void* const* b, const int32_t* widths, int32_t n_maps, int32_t d) {
+  if (!W || !b || !widths) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  if (n_maps < 1 || n_maps > kMaxMlpMaps)
+    return fail(LIME_INVALID_ARG, "%s: the interaction network has 1 to %d affine maps (got %d)", fn, kMaxMlpMaps, n_maps);
+  for (int i = 0; i < n_maps; ++i) {
+    if (widths[i] <= 0 || !W[i]) return fail(LIME_INVALID_ARG, "%s: map %d has no weights or a non-positive width", fn, i);
+  }
+  if (widths[n_maps - 1] != 1) return fail(LIME_INVALID_ARG, "%s: the last map must produce one logit (width %d)", fn, widths[n_maps - 1]);
+  if (d <= 0) return fail(LIME_INVALID_ARG, "%s: d must be positive", fn);
+  return LIME_OK;
+}
+
+bool mlp_on_mfma(const void* O, const void* const* W, const void* const* b, const int32_t* widths, int32_t n_maps, int32_t d,
+                 int32_t dtype, const void* workspace) {
+  if (dtype != LIME_BF16 || !lime::interaction_mlp_on_matrix_cores(d, n_maps, widths) || !all_aligned16(O, workspace)) return false;
+  for (int i = 0; i < n_maps; ++i)
+    if ((reinterpret_cast<uintptr_t>(W[i]) | reinterpret_cast<uintptr_t>(b[i])) & 1u) return false;
+  return true;
+}
+
+size_t mlp_workspace(int64_t rows, int32_t d, const int32_t* widths, int32_t n_maps, int32_t dtype) {
+  int widest = 1;
+  for (int i = 0; i < n_maps; ++i) widest = std::max(widest, widths[i]);
+  // general kernels: two fp32 buffers of rows x the widest layer, used in turn
+  size_t need = 2 * lime::align_up(static_cast<size_t>(rows) * widest * sizeof(float));
+  if (dtype == LIME_BF16 && lime::interaction_mlp_on_matrix_cores(d, n_maps, widths))
+    need = std::max(need, lime::interaction_mlp_image_bytes(d, n_maps, widths));
+  return need;
+}
+
+int32_t mlp_impl(const char* fn, const void* O, const void* const* W, const void* const* b, const int32_t* widths, int32_t n_maps,
+                 float* scores, int64_t rows, int32_t d, int32_t dtype, void* workspace, size_t ws_bytes, void* stream) {
+  const size_t need = mlp_workspace(rows, d, widths, n_maps, dtype);
+  if (!workspace || ws_bytes < need)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? ws_bytes : 0);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (mlp_on_mfma(O, W, b, widths, n_maps, d, dtype, workspace)) {
+    LIME_HIP(lime::interaction_mlp_mfma(O, rows, d, n_maps, widths, W, b, scores, workspace, s));
+    return LIME_OK;
+  }
+  int widest = 1;
+  for (int i = 0; i < n_maps; ++i) widest = std::max(widest, widths[i]);
+  float* buf[2] = {static_cast<float*>(workspace),
+                   reinterpret_cast<float*>(static_cast<char*>(workspace) + lime::align_up(static_cast<size_t>(rows) * widest * sizeof(float)))};
+  const void* x = O;
+  int din = d, x_dtype = dtype;
+  for (int i = 0; i < n_maps; ++i) {
+    const bool last = i + 1 == n_maps;
+    lime::Dense q{};
+    q.X1 = x, q.W = W[i], q.b = b[i], q.Y = last ? static_cast<void*>(scores) : static_cast<void*>(buf[i & 1]);
+    q.rows = rows, q.d1 = din, q.dout = widths[i], q.relu = !last;
+    q.x_dtype = x_dtype, q.w_dtype = dtype, q.y_dtype = LIME_F32;
+    LIME_HIP(lime::dense_rows(q, s));
+    x = buf[i & 1], din = widths[i], x_dtype = LIME_F32;
+  }
+  return LIME_OK;
+}
+
+int32_t contextualize_impl(const char* fn, const void* L, const void* EC, const void* W1, const void* b1, const void* W2,
+                           const void* b2, void* LC, int32_t B, int32_t m, int32_t d, int32_t dc, int32_t dhid, int32_t dtype,
+                           void* workspace, size_t ws_bytes, void* stream) {
+  const size_t need = lime::align_up(static_cast<size_t>(B) * m * dhid * sizeof(float));
+  if (!workspace || ws_bytes < need)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? ws_bytes : 0);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int64_t rows = static_cast<int64_t>(B) * m;
+  lime::Dense h{};  // hidden = ReLU([L | E^C_b] W1 + b1)
+  h.X1 = L, h.x1_rows = m, h.X2 = EC, h.x2_rows_per = m, h.W = W1, h.b = b1, h.Y = workspace;
+  h.rows = rows, h.d1 = d, h.d2 = dc, h.dout = dhid, h.relu = true, h.x_dtype = dtype, h.w_dtype = dtype, h.y_dtype = LIME_F32;
+  LIME_HIP(lime::dense_rows(h, s));
+  lime::Dense o{};  // L^C = hidden W2 + b2
+  o.X1 = workspace, o.W = W2, o.b = b2, o.Y = LC;
+  o.rows = rows, o.d1 = dhid, o.dout = d, o.relu = false, o.x_dtype = LIME_F32, o.w_dtype = dtype, o.y_dtype = dtype;
+  LIME_HIP(lime::dense_rows(o, s));
+  return LIME_OK;
+}
+
+struct ScoresPlan {
+  size_t LC, hid, En, LCn, Tn, Ln, LP, LPn, O, hist, cand, mlp, total;
+  size_t hist_bytes, cand_bytes, mlp_bytes, hid_bytes;
+};
+
+ScoresPlan plan_scores(const lime_scoring_model& M, int32_t B, int32_t N, int32_t C, int32_t dtype) {
+  ScoresPlan p{};
+  const size_t es = dtype == LIME_BF16 ? 2 : 4;
+  const size_t links = lime::align_up(static_cast<size_t>(B) * M.m * M.d * es);
+  size_t at = 0;
+  auto take = [&](size_t bytes) { const size_t o = at; at += lime::align_up(bytes); return o; };
+  p.LC = take(links);
+  p.hid_bytes = lime::align_up(static_cast<size_t>(B) * M.m * M.dhid * sizeof(float));
+  p.hid = take(p.hid_bytes);
+  p.En = take(static_cast<size_t>(B) * N * M.d * es);
+  p.LCn = take(links);
+  p.Tn = take(static_cast<size_t>(B) * C * M.d * es);
+  p.Ln = take(static_cast<size_t>(M.m) * M.d * es);
+  p.LP = take(links);
+  p.LPn = take(links);
+  p.O = take(static_cast<size_t>(B) * C * M.d * es);
+  p.hist_bytes = lime_workspace_bytes(LIME_OP_LINK_HISTORY, B, N, C, M.d, M.h, M.m, dtype, 0);
+  p.hist = take(p.hist_bytes);
+  p.cand_bytes = lime_workspace_bytes(LIME_OP_SCORE_CANDIDATES, B, N, C, M.d, M.h, M.m, dtype, 0);
+  p.cand = take(p.cand_bytes);
+  p.mlp_bytes = mlp_workspace(static_cast<int64_t>(B) * C, M.d, M.mlp_width, M.n_mlp, dtype);
+  p.mlp = take(p.mlp_bytes);
+  p.total = at;
+  return p;
+}
+
+int32_t check_scoring_model(const char* fn, const lime_scoring_model* M, int32_t dtype) {
+  if (!M) return fail(LIME_INVALID_ARG, "%s: model is NULL", fn);
+  if (int32_t st = check_common(fn, 1, M->d, M->h, dtype)) return st;
+  if (M->m <= 0 || M->dc <= 0 || M->dhid <= 0)
+    return fail(LIME_INVALID_ARG, "%s: m, dc and dhid must be positive (m=%d dc=%d dhid=%d)", fn, M->m, M->dc, M->dhid);
+  if (!M->L || !M->ctx_W1 || !M->ctx_W2 || !M->hist_Wq || !M->hist_Wk || !M->hist_Wv || !M->cand_Wq || !M->cand_Wk || !M->cand_Wv)
+    return fail(LIME_INVALID_ARG, "%s: a required pointer of the model is NULL", fn);
+  if (!(M->ln_eps >= 0.f)) return fail(LIME_INVALID_ARG, "%s: ln_eps must not be negative", fn);
+  return check_mlp(fn, M->mlp_W, M->mlp_b, M->mlp_width, M->n_mlp, M->d);
+}
+
+}  // namespace
+
+int32_t lime_layer_norm(const void* X, const void* gamma, const void* beta, float eps, void* Y, int64_t rows, int32_t d,
+                        int32_t dtype, void* stream) {
+  const char* fn = "lime_layer_norm";
+  if (dtype != LIME_F32 && dtype != LIME_BF16) return fail(LIME_INVALID_ARG, "%s: unknown dtype %d", fn, dtype);
+  if (rows <= 0 || d <= 0) return fail(LIME_INVALID_ARG, "%s: rows and d must be positive (rows=%lld d=%d)", fn, static_cast<long long>(rows), d);
+  if (!X || !Y) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  if (!(eps >= 0.f)) return fail(LIME_INVALID_ARG, "%s: eps must not be negative", fn);
+  LIME_HIP(lime::layer_norm_rows(X, gamma, beta, eps, Y, rows, d, nullptr, 1, dtype, static_cast<hipStream_t>(stream)));
+  return LIME_OK;
+}
+
+int32_t lime_contextualize_links(const void* L, const void* EC, const void* W1, const void* b1, const void* W2, const void* b2,
+                                 void* LC, int32_t B, int32_t m, int32_t d, int32_t dc, int32_t dhid, int32_t dtype,
+                                 void* workspace, size_t ws_bytes, void* stream) {
+  const char* fn = "lime_contextualize_links";
+  if (dtype != LIME_F32 && dtype != LIME_BF16) return fail(LIME_INVALID_ARG, "%s: unknown dtype %d", fn, dtype);
+  if (B <= 0 || m <= 0 || d <= 0 || dc <= 0 || dhid <= 0)
+    return fail(LIME_INVALID_ARG, "%s: B, m, d, dc, dhid must be positive (B=%d m=%d d=%d dc=%d dhid=%d)", fn, B, m, d, dc, dhid);
+  if (!L || !EC || !W1 || !W2 || !LC) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  return contextualize_impl(fn, L, EC, W1, b1, W2, b2, LC, B, m, d, dc, dhid, dtype, workspace, ws_bytes, stream);
+}
+
+size_t lime_interaction_mlp_workspace_bytes(int64_t rows, int32_t d, const int32_t* widths, int32_t n_maps, int32_t dtype) {
+  if (rows <= 0 || d <= 0 || !widths || n_maps < 1 || n_maps > kMaxMlpMaps || (dtype != LIME_F32 && dtype != LIME_BF16)) return 0;
+  for (int i = 0; i < n_maps; ++i)
+    if (widths[i] <= 0) return 0;
+  return mlp_workspace(rows, d, widths, n_maps, dtype);
+}
+
+int32_t lime_interaction_mlp(const void* O, const void* const* W, const void* const* b, const int32_t* widths, int32_t n_maps,
+                             float* scores, int64_t rows, int32_t d, int32_t dtype, void* workspace, size_t ws_bytes, void* stream) {
+  const char* fn = "lime_interaction_mlp";
+  if (dtype != LIME_F32 && dtype != LIME_BF16) return fail(LIME_INVALID_ARG, "%s: unknown dtype %d", fn, dtype);
+  if (rows <= 0) return fail(LIME_INVALID_ARG, "%s: rows must be positive", fn);
+  if (!O || !scores) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  if (int32_t st = check_mlp(fn, W, b, widths, n_maps, d)) return st;
+  return mlp_impl(fn, O, W, b, widths, n_maps, scores, rows, d, dtype, workspace, ws_bytes, stream);
+}
+
+size_t lime_scores_workspace_bytes(const lime_scoring_model* model, int32_t B, int32_t N, int32_t C, int32_t dtype) {
+  if (!model || B <= 0 || N <= 0 || C <= 0 || model->d <= 0 || model->h <= 0 || model->m <= 0 || model->dc <= 0 || model->dhid <= 0 ||
+      model->d % model->h != 0 || model->n_mlp < 1 || model->n_mlp > kMaxMlpMaps || (dtype != LIME_F32 && dtype != LIME_BF16))
+    return 0;
+  for (int i = 0; i < model->n_mlp; ++i)
+    if (model->mlp_width[i] <= 0) return 0;
+  return plan_scores(*model, B, N, C, dtype).total;
+}
+
+int32_t lime_scores(const lime_scoring_model* model, const void* E, const int32_t* lens, const void* EC, const void* T,
+                    void* LC, void* LP, void* O, float* scores, int32_t B, int32_t N, int32_t C, int32_t dtype,
+                    void* workspace, size_t ws_bytes, void* stream) {
+  const char* fn = "lime_scores";
+  if (int32_t st = check_scoring_model(fn, model, dtype)) return st;
+  if (int32_t st = check_common(fn, B, model->d, model->h, dtype)) return st;
+  if (N <= 0 || C <= 0) return fail(LIME_INVALID_ARG, "%s: N and C must be positive (N=%d C=%d)", fn, N, C);
+  if (!E || !EC || !T || !scores) return fail(LIME_INVALID_ARG, "%s: a required pointer is NULL", fn);
+  const lime_scoring_model& M = *model;
+  const ScoresPlan p = plan_scores(M, B, N, C, dtype);
+  if (!workspace || ws_bytes < p.total)
+    return fail(LIME_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", fn, p.total, workspace ? ws_bytes : 0);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(LIME_INVALID_ARG, "%s: the workspace must be 256-byte aligned", fn);
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int d = M.d, m = M.m;
+  void* lc = LC ? LC : ws + p.LC;
+  void* lp = LP ? LP : ws + p.LP;
+  void* o = O ? O : ws + p.O;
+  // Eq. 2
+  if (int32_t st = contextualize_impl(fn, M.L, EC, M.ctx_W1, M.ctx_b1, M.ctx_W2, M.ctx_b2, lc, B, m, d, M.dc, M.dhid, dtype,
+                                      ws + p.hid, p.hid_bytes, stream))
+    return st;
+  // Eq. 3 on normalised inputs (history rows past lens[b] are skipped: nothing reads them)
+  LIME_HIP(lime::layer_norm_rows(E, M.ln_hist_kv[0], M.ln_hist_kv[1], M.ln_eps, ws + p.En, static_cast<int64_t>(B) * N, d, lens, N, dtype, s));
+  LIME_HIP(lime::layer_norm_rows(lc, M.ln_hist_q[0], M.ln_hist_q[1], M.ln_eps, ws + p.LCn, static_cast<int64_t>(B) * m, d, nullptr, 1, dtype, s));
+  if (int32_t st = history_impl(fn, lime::kPhiSoftmax, ws + p.En, lens, ws + p.LCn, static_cast<int64_t>(m) * d, M.hist_Wq, M.hist_Wk,
+                                M.hist_Wv, lp, nullptr, B, N, d, M.h, m, M.scale_hist, dtype, ws + p.hist, p.hist_bytes, stream))
+    return st;
+  // Eq. 4 on normalised inputs: keys from the raw links, values from the personalised links
+  LIME_HIP(lime::layer_norm_rows(T, M.ln_cand_q[0], M.ln_cand_q[1], M.ln_eps, ws + p.Tn, static_cast<int64_t>(B) * C, d, nullptr, 1, dtype, s));
+  LIME_HIP(lime::layer_norm_rows(M.L, M.ln_cand_k[0], M.ln_cand_k[1], M.ln_eps, ws + p.Ln, m, d, nullptr, 1, dtype, s));
+  LIME_HIP(lime::layer_norm_rows(lp, M.ln_cand_v[0], M.ln_cand_v[1], M.ln_eps, ws + p.LPn, static_cast<int64_t>(B) * m, d, nullptr, 1, dtype, s));
+  if (int32_t st = lime_score_candidates(ws + p.Tn, ws + p.Ln, ws + p.LPn, M.cand_Wq, M.cand_Wk, M.cand_Wv, o, B, C, d, M.h, m,
+                                         M.scale_cand, dtype, ws + p.cand, p.cand_bytes, stream))
+    return st;
+  // Section 3.3: the interaction network
+  return mlp_impl(fn, o, M.mlp_W, M.mlp_b, M.mlp_width, M.n_mlp, scores, static_cast<int64_t>(B) * C, d, dtype, ws + p.mlp, p.mlp_bytes, stream);
 }
 
 size_t lime_workspace_bytes(int32_t op, int32_t B, int32_t N, int32_t C, int32_t d, int32_t h, int32_t m,

@@ -23,7 +23,7 @@ import numpy as np
 BASE_SEED = 20251018
 _TENSOR_INDEX = {"E": 0, "T": 1, "L": 2, "Wq": 3, "Wk": 4, "Wv": 5, "lens": 6, "LCu": 7,
                  "bwdQS": 10, "bwdKS": 11, "bwdVS": 12, "bwddOS": 13, "bwdQT": 14, "bwdKT": 15, "bwdVT": 16, "bwddOT": 17,
-                 "bwdlens": 18}
+                 "bwdlens": 18, "scoring": 30}
 
 
 def _rng(workload: int, name: str) -> np.random.Generator:
@@ -139,6 +139,32 @@ def backward_inputs(workload: int, B: int, N: int, m: int, d: int, h: int, dtype
             for name in ("QS", "KS", "VS", "dOS"):
                 t[name][b, lens[b]:] = pad_value
     return t
+
+
+def scoring_params(workload: int, B: int, m: int, d: int, dc: int, dhid: int, widths, dtype: str,
+                   value_gain: float = 0.25) -> dict:
+    """Parameters of the scoring pipeline around the attention stages, all seeded Gaussians rounded to the storage type:
+    user context vectors EC [B, dc] ~ N(0, 1); Eq. 2's MLP ctx = (W1 [d + dc, dhid] ~ N(0, 2/(d + dc)), b1 ~ N(0, 0.1^2),
+    W2 [dhid, d] ~ N(0, 1/dhid), b2 ~ N(0, 0.1^2)); five layer normalisations ln_* = (gamma ~ 1 + N(0, 0.2^2),
+    beta ~ N(0, 0.2^2)); two weight sets hist, cand = (Wq, Wk, Wv) ~ N(0, 1/d) with W_V times ``value_gain`` (normalised
+    rows have unit entries, so the logits of a head have standard deviation about sqrt(d/h) before the scale and the
+    outputs stay below one); the interaction network mlp = (weights, biases) with He-scaled weights ~ N(0, 2/d_in),
+    biases ~ N(0, 0.1^2), ``widths`` the hidden widths followed by 1."""
+    r = _rng(workload, "scoring")
+
+    def normal(shape, std, mean=0.0):
+        return round_to(r.standard_normal(shape, dtype=np.float32) * np.float32(std) + np.float32(mean), dtype)
+
+    p = {"EC": normal((B, dc), 1.0),
+         "ctx": (normal((d + dc, dhid), (2.0 / (d + dc)) ** 0.5), normal((dhid,), 0.1), normal((dhid, d), dhid ** -0.5), normal((d,), 0.1))}
+    for name in ("ln_hist_q", "ln_hist_kv", "ln_cand_q", "ln_cand_k", "ln_cand_v"):
+        p[name] = (normal((d,), 0.2, 1.0), normal((d,), 0.2))
+    for name in ("hist", "cand"):
+        p[name] = (normal((d, d), d ** -0.5), normal((d, d), d ** -0.5), normal((d, d), value_gain * d ** -0.5))
+    dims = [d] + list(widths)
+    p["mlp"] = ([normal((dims[i], dims[i + 1]), (2.0 / dims[i]) ** 0.5) for i in range(len(widths))],
+                [normal((dims[i + 1],), 0.1) for i in range(len(widths))])
+    return p
 
 
 # W_V gain of the sharpened parity inputs: at logit standard deviation 2 a softmax picks out single rows, so an
