@@ -186,7 +186,7 @@ int32_t history_impl(const char* fn, int phi, const void* E, const int32_t* lens
     if (os_on_mfma) lime::queries_over_links_jobs(os_query(E, lens, LC, link_stride, Wq, Wk, Wv, OS, B, N, d, h, m, scale),
                                                    static_cast<char*>(workspace) + p.bytes, jobs);
     for (int i = 0; i < n_extra; ++i) jobs.weights[jobs.n_weights++] = extra[i];
-    LIME_HIP(lime::pack_operands(jobs.weights, jobs.n_weights, jobs.projections, jobs.n_projections, d, h, m, s));
+    LIME_HIP(lime::pack_operands(jobs, d, h, m, s));
     q.packed = true;
     LIME_HIP(lime::links_over_history(q, workspace, s));
   } else {
@@ -585,7 +585,7 @@ int32_t request_impl(const char* fn, const RequestPlan& p, const void* E, const 
   lime::PackJobs jobs;
   lime::links_over_history_jobs(q, workspace, jobs);
   lime::queries_over_links_jobs(c, cand_ws, jobs, /*values=*/false);
-  LIME_HIP(lime::pack_operands(jobs.weights, jobs.n_weights, jobs.projections, jobs.n_projections, d, h, m, s));
+  LIME_HIP(lime::pack_operands(jobs, d, h, m, s));
   q.packed = c.packed = true;
   q.Wv_values = Wv_cand, q.values_image = lime::queries_over_links_values(c, cand_ws);
   LIME_HIP(lime::links_over_history(q, workspace, s));

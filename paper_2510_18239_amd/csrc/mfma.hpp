@@ -89,12 +89,10 @@ __device__ __forceinline__ int64_t values_slot(int u, int row, int col, int d, i
   return (frag * 64 + 32 * g + out_rho(c % 32)) * 8 + t;
 }
 
-#ifndef LIME_X_HEADPAD
-#define LIME_X_HEADPAD 0
-#endif
 // Fragments (1 KiB each) left free between the head slices of the candidate side's query-weight image (and of the
-// score image that replaces it), so that the heads' slices start at different cache-channel phases.
-constexpr int kQueryImageHeadPad = LIME_X_HEADPAD;
+// score image that replaces it).  Zero: starting the heads' slices at different cache-channel phases was measured
+// and changed nothing.
+constexpr int kQueryImageHeadPad = 0;
 constexpr size_t kQueryImagePadBytes = 8 * 1024 * static_cast<size_t>(kQueryImageHeadPad);  // up to eight heads
 struct PackWeight {
   const void* W;   // [d][d] bf16, or nullptr for the identity
@@ -134,7 +132,10 @@ struct PackJobs {
   int n_weights = 0;
   PackProject projections[kMaxPackProjections];
   int n_projections = 0;
+  PackScore score{};      // at most one score image per launch
+  bool has_score = false;
 };
+hipError_t pack_operands(const PackJobs& jobs, int d, int h, int m, hipStream_t s);
 
 // ----------------------------------------------------------------------------- operands prepared once per model
 // What the two stages need of the model alone -- weights and shared links, not the user -- packed once into a

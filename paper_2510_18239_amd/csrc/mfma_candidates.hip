@@ -26,15 +26,6 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-#ifdef LIME_X_STAMPS
-}  // namespace
-__device__ long long g_stamps[1024][16];
-namespace {
-#define STAMP(i) do { if (threadIdx.x == 0) g_stamps[blockIdx.x][i] = wall_clock64(); } while (0)
-#else
-#define STAMP(i) do { } while (0)
-#endif
-
 // ----------------------------------------------------------------------------- main kernel
 struct MainArgs {
   const bf16_t* X;
@@ -86,7 +77,6 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   const int first = blockIdx.x * per_wg;
   const int last = min(first + per_wg, a.total_tiles);  // one past this workgroup's final tile
   if (first >= last) return;  // uniform
-  STAMP(0);
 
   // Rows past a user's last row are read from whatever follows (the next user's rows; zeros past the
   // end of the tensor): every row is an independent column of the three products and such columns
@@ -152,11 +142,7 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   // workgroups go to different XCDs) therefore start at different k-steps.  The destination registers and the
   // order of the products stay the same: kRot copies of the load sequence, chosen by a uniform switch.
   bf16x8 wq[KR][FB];
-#ifdef LIME_X_NOROT
-  constexpr int kRot = 1;
-#else
   constexpr int kRot = KR >= 8 ? 4 : 1;
-#endif
   auto load_wq = [&](auto rot_tag) {
     constexpr int start = decltype(rot_tag)::value * (KR / kRot);
 #pragma unroll
@@ -294,13 +280,11 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
   // first product of tile i+1, whose X rows were parked in the other LDS buffer.
   park(ring[0], xs[0]);
   __syncthreads();
-  STAMP(1);
   if (first + P < last) {
     issue(ib, ir0, ring[0]);
     advance(ib, ir0);
   }
   first_product(xs[0]);
-  STAMP(2);
   int b = b_first, r0 = r0_first;  // the tile being computed
 
   for (int base = first; base < last; base += P) {
@@ -440,20 +424,10 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
       }
       }
       advance(b, r0);
-      STAMP(3 + (tile - first < 12 ? tile - first : 12));
     }
   }
 }
 
-#ifdef LIME_X_STAMPS
-}  // namespace
-}  // namespace lime
-extern "C" __attribute__((visibility("default"))) int lime_debug_stamps(long long* host) {
-  return hipMemcpyFromSymbol(host, HIP_SYMBOL(lime::g_stamps), sizeof(long long) * 1024 * 16);
-}
-namespace lime {
-namespace {
-#endif
 
 template <int DH, int M, int H, bool FUSED>
 hipError_t launch_form(const MainArgs& m, int phi, int grid, hipStream_t s) {
@@ -546,8 +520,8 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
   bf16_t* KA = reinterpret_cast<bf16_t*>(ws + align_up(static_cast<size_t>(d) * d * 2 + kQueryImagePadBytes));
   bf16_t* VA = reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(KA) +
                                          align_up(static_cast<size_t>(k_per_user ? q.B : 1) * m * d * 2));
-  // The score image G costs more to build than W_Q^T and K~ do to pack (measured: the request gets slower when
-  // it is built per call), so it replaces them only where it is built once per model.
+  // The score image G costs more to build than W_Q^T and K~ do to pack (measured twice: 0.7 us off this kernel against
+  // 3 us more for the request when it is built per call), so it replaces them only where it is built once per model.
   const bool fused = q.prepared != nullptr && fused_scores(d, h, m, k_per_user);
   hipError_t e = hipSuccess;
   if (q.prepared != nullptr) {  // only the user's values are left to pack
@@ -559,7 +533,7 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
   } else if (!q.packed) {
     PackJobs jobs;
     queries_over_links_jobs(q, workspace, jobs);
-    e = pack_operands(jobs.weights, jobs.n_weights, jobs.projections, jobs.n_projections, d, h, m, s);
+    e = pack_operands(jobs, d, h, m, s);
   }
   if (e != hipSuccess) return e;
 

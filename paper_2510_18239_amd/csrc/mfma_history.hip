@@ -591,7 +591,7 @@ hipError_t links_over_history(const LinksOverHistory& q, void* workspace, hipStr
   } else if (!q.packed) {
     PackJobs jobs;
     links_over_history_jobs(q, workspace, jobs);
-    e = pack_operands(jobs.weights, jobs.n_weights, jobs.projections, jobs.n_projections, d, h, m, s);
+    e = pack_operands(jobs, d, h, m, s);
     if (e != hipSuccess) return e;
   }
 

@@ -245,6 +245,11 @@ hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackPro
   return hipErrorInvalidValue;
 }
 
+hipError_t pack_operands(const PackJobs& jobs, int d, int h, int m, hipStream_t s) {
+  return pack_operands(jobs.weights, jobs.n_weights, jobs.projections, jobs.n_projections, d, h, m, s,
+                       jobs.has_score ? &jobs.score : nullptr);
+}
+
 PreparedLayout prepared_layout(int d, int m) {
   PreparedLayout l{};
   const size_t w = align_up(static_cast<size_t>(d) * d * 2 + kQueryImagePadBytes), links = align_up(static_cast<size_t>(m) * d * 2);
