@@ -222,11 +222,8 @@ __global__ __launch_bounds__(COOP ? 64 * H : 64) void links_over_history_kernel(
         // SiLU(scale * s) = scale * s * sigmoid(scale * s); the factor `scale` is applied by the merge
 #pragma unroll
         for (int i = 0; i < 16; ++i) sc[i] = sc[i] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-sc[i] * c));
-        if (ragged) {
-#pragma unroll
-          for (int i = 0; i < 16; ++i)
-            if (i0 + 8 * (i >> 2) + 4 * g + (i & 3) >= i_end) sc[i] = 0.f;
-        }
+        // (no mask is needed here: rows past the end of the chunk were loaded as zeros, so their projected keys are
+        // zero, their logits are zero and SiLU(0) = 0 exactly)
       }
       const bf16x8 p0 = pack_half(sc, 0), p1 = pack_half(sc, 1);
 #pragma unroll
@@ -413,7 +410,9 @@ __global__ __launch_bounds__(2 * D) void merge_values_kernel(MergeValuesArgs a) 
   // rounded link states + output rows + one partial output per k-group (36 KiB at d = 256)
   __shared__ float lp[kMvRows * D];         // bf16-rounded values
   __shared__ float out[kMvRows * D];
-  __shared__ float red[nkc * kMvRows * D];
+  // (a column c sits at c + c / 32: the writers' columns are 8 apart, which would otherwise share four banks)
+  constexpr int kRedRow = D + D / 32;
+  __shared__ float red[nkc * kMvRows * kRedRow];
   const int tid = threadIdx.x, b = blockIdx.y;
   const int cg = tid % CG, kc = tid / CG;
   bf16x8 wreg[kMvMaxK];
@@ -454,12 +453,12 @@ __global__ __launch_bounds__(2 * D) void merge_values_kernel(MergeValuesArgs a) 
 #pragma unroll
       for (int r = 0; r < kMvRows; ++r)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) red[(kc * kMvRows + r) * d + 8 * cg + j] = acc[r][j];
+        for (int j = 0; j < 8; ++j) red[(kc * kMvRows + r) * kRedRow + 8 * cg + j + (cg >> 2)] = acc[r][j];
       __syncthreads();
       for (int i = tid; i < kMvRows * d; i += kMvThreads) {
         float sum = 0.f;
 #pragma unroll 8
-        for (int c = 0; c < nkc; ++c) sum += red[c * kMvRows * d + i];
+        for (int c = 0; c < nkc; ++c) sum += red[(c * kMvRows + i / d) * kRedRow + i % d + (i % d) / 32];
         out[i] = sum;
       }
     }

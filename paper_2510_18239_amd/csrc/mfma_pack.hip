@@ -132,9 +132,10 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
 
   float* xs = smem;                          // [kPackRows][d]
   float* out = xs + kPackRows * d;           // [kPackRows][kPackCols]
-  float* red = out + kPackRows * kPackCols;  // [nkc][kPackRows][kPackCols]
+  float* red = out + kPackRows * kPackCols;  // [nkc][kPackRows * kPackCols + 1]: the odd pitch spreads the k-groups over the banks
   constexpr int CG = kPackCols / 8, nkc = 256 / CG;
   constexpr int kMaxK = 256 / nkc;  // k-steps per thread at the largest d (256)
+  constexpr int kRedPitch = kPackRows * kPackCols + 1;
   const int cg = tid % CG, kc = tid / CG;
   // every load this block needs is issued before the first wait
   bf16x8 wreg[kMaxK];
@@ -170,12 +171,12 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
 #pragma unroll
     for (int r = 0; r < kPackRows; ++r)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) red[(kc * kPackRows + r) * kPackCols + 8 * cg + j] = acc[r][j];
+      for (int j = 0; j < 8; ++j) red[kc * kRedPitch + r * kPackCols + 8 * cg + j] = acc[r][j];
     __syncthreads();
     for (int i = tid; i < kPackRows * kPackCols; i += 256) {
       float sum = 0.f;
 #pragma unroll 8
-      for (int c = 0; c < nkc; ++c) sum += red[c * kPackRows * kPackCols + i];
+      for (int c = 0; c < nkc; ++c) sum += red[c * kRedPitch + i];
       out[i] = sum;
     }
   }
@@ -221,7 +222,7 @@ hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackPro
   for (int i = n_projections; i < kMaxJobs; ++i)
     if (i > 0) p.p_first_block[i] = 0x7fffffff;
   constexpr int nkc = 256 / (kPackCols / 8);
-  size_t lds = (static_cast<size_t>(kPackRows) * d + static_cast<size_t>(1 + nkc) * kPackRows * kPackCols) * sizeof(float);
+  size_t lds = (static_cast<size_t>(kPackRows) * d + static_cast<size_t>(1 + nkc) * kPackRows * kPackCols + nkc) * sizeof(float);
   int grid = n_weights * p.blocks_per_weight + blocks;
   if (score == nullptr) {
     if (grid == 0) return hipSuccess;
