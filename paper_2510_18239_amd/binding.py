@@ -143,7 +143,7 @@ def probe_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
 
 def probe_mfma(iters: int, stream=None) -> float:
     """Runs the register-resident matrix-instruction loop; returns the floating-point operations it executes."""
-    out = get_workspace(lib().lime_probe_mfma_out_bytes(), torch.device("cuda", torch.cuda.current_device()))
+    out = get_workspace(lib().lime_probe_mfma_out_bytes(), torch.device("cuda", torch.cuda.current_device()), stream)
     with torch.cuda.device(out.device):
         flops = lib().lime_probe_mfma(_ptr(out), int(iters), _stream(stream))
     if flops <= 0:
@@ -180,21 +180,30 @@ def _check(*tensors):
 
 
 _workspaces: dict = {}
-
-
-def get_workspace(nbytes: int, device) -> torch.Tensor:
-    """A grow-only scratch buffer per device (caller-owned memory as far as the C ABI is concerned)."""
-    key = torch.device(device)
-    ws = _workspaces.get(key)
-    if ws is None or ws.numel() < nbytes:
-        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=key)
-        _workspaces[key] = ws
-    return ws
+_outgrown: list = []
 
 
 def _stream(stream):
     s = stream if stream is not None else torch.cuda.current_stream()
     return s.cuda_stream
+
+
+def get_workspace(nbytes: int, device, stream=None) -> torch.Tensor:
+    """A grow-only scratch buffer per (device, stream): caller-owned memory as far as the C ABI is concerned.
+    Calls on different streams may run at the same time, so they must not share scratch memory; calls on one
+    stream are ordered and may.  A buffer that is outgrown is replaced by one at least twice its size and kept
+    until the process ends (work already queued on the stream may still use it)."""
+    device = torch.device(device)
+    with torch.cuda.device(device):
+        key = (device, _stream(stream))
+    ws = _workspaces.get(key)
+    if ws is None or ws.numel() < nbytes:
+        if ws is not None:
+            _outgrown.append(ws)
+            nbytes = max(nbytes, 2 * ws.numel())
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        _workspaces[key] = ws
+    return ws
 
 
 def _raise(status):
@@ -226,7 +235,7 @@ def _history(fn_name, op, E, lens, LC, Wq, Wk, Wv, h, scale, LP, OS, workspace, 
     if want_os and OS is None:
         OS = torch.empty((B, N, d), dtype=E.dtype, device=E.device)
     need = workspace_bytes(op, B=B, N=N, d=d, h=h, m=m, dtype=code, flags=1 if want_os else 0)
-    ws = workspace if workspace is not None else get_workspace(need, E.device)
+    ws = workspace if workspace is not None else get_workspace(need, E.device, stream)
     fn = getattr(lib(), fn_name)
     with torch.cuda.device(E.device):
         if op == OP_LINK_HISTORY:
@@ -269,7 +278,7 @@ def lime_xor_layers(E, lens, LC, Wq, Wk, Wv, Wu, Wo, h, scale=1.0, LP=None, work
     if LP is None:
         LP = torch.empty((B, m, d), dtype=E.dtype, device=E.device)
     need = workspace_bytes(OP_XOR_LAYERS, B=B, N=N, d=d, h=h, m=m, dtype=code)
-    ws = workspace if workspace is not None else get_workspace(need, E.device)
+    ws = workspace if workspace is not None else get_workspace(need, E.device, stream)
     with torch.cuda.device(E.device):
         st = lib().lime_xor_layers(_ptr(E), _ptr(lens), _ptr(LC), stride, _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(Wu), _ptr(Wo),
                                    int(Wu.shape[0]), _ptr(LP), B, N, d, h, m, float(scale), code, _ptr(ws), ws.numel(),
@@ -287,7 +296,7 @@ def lime_score_candidates(T, L, LP, Wq, Wk, Wv, h, scale, O=None, workspace=None
     if O is None:
         O = torch.empty_like(T)
     need = workspace_bytes(OP_SCORE_CANDIDATES, B=B, C=C, d=d, h=h, m=m, dtype=code)
-    ws = workspace if workspace is not None else get_workspace(need, T.device)
+    ws = workspace if workspace is not None else get_workspace(need, T.device, stream)
     with torch.cuda.device(T.device):
         st = lib().lime_score_candidates(_ptr(T), _ptr(L), _ptr(LP), _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(O), B, C, d,
                                          h, m, float(scale), code, _ptr(ws), ws.numel(), _stream(stream))
@@ -305,7 +314,7 @@ def mha_target_attention(T, E, lens, Wq, Wk, Wv, h, scale, O=None, workspace=Non
     if O is None:
         O = torch.empty_like(T)
     need = workspace_bytes(OP_MHA_TARGET, B=B, N=N, C=C, d=d, h=h, dtype=code)
-    ws = workspace if workspace is not None else get_workspace(need, T.device)
+    ws = workspace if workspace is not None else get_workspace(need, T.device, stream)
     with torch.cuda.device(T.device):
         st = lib().mha_target_attention(_ptr(T), _ptr(E), _ptr(lens), _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(O), B, C, N,
                                         d, h, float(scale), code, _ptr(ws), ws.numel(), _stream(stream))
@@ -322,7 +331,7 @@ def lime_build_qk_cache(T, L, Wq, Wk, h, scale, W=None, workspace=None, stream=N
     if W is None:
         W = torch.empty((B, C, h, m), dtype=T.dtype, device=T.device)
     need = workspace_bytes(OP_BUILD_QK_CACHE, B=B, C=C, d=d, h=h, m=m, dtype=code)
-    ws = workspace if workspace is not None else get_workspace(need, T.device)
+    ws = workspace if workspace is not None else get_workspace(need, T.device, stream)
     with torch.cuda.device(T.device):
         st = lib().lime_build_qk_cache(_ptr(T), _ptr(L), _ptr(Wq), _ptr(Wk), _ptr(W), B, C, d, h, m, float(scale), code,
                                        _ptr(ws), ws.numel(), _stream(stream))
@@ -339,7 +348,7 @@ def lime_score_candidates_cached(W, LP, Wv, O=None, workspace=None, stream=None)
     if O is None:
         O = torch.empty((B, C, d), dtype=W.dtype, device=W.device)
     need = workspace_bytes(OP_SCORE_CACHED, B=B, C=C, d=d, h=h, m=m, dtype=code)
-    ws = workspace if workspace is not None else get_workspace(need, W.device)
+    ws = workspace if workspace is not None else get_workspace(need, W.device, stream)
     with torch.cuda.device(W.device):
         st = lib().lime_score_candidates_cached(_ptr(W), _ptr(LP), _ptr(Wv), _ptr(O), B, C, d, h, m, code, _ptr(ws),
                                                 ws.numel(), _stream(stream))
@@ -359,7 +368,7 @@ def lime_score_candidates_gathered(Wtable, ids, LP, Wv, O=None, workspace=None, 
     if O is None:
         O = torch.empty((B, C, d), dtype=Wtable.dtype, device=Wtable.device)
     need = workspace_bytes(OP_SCORE_CACHED, B=B, C=C, d=d, h=h, m=m, dtype=code)
-    ws = workspace if workspace is not None else get_workspace(need, Wtable.device)
+    ws = workspace if workspace is not None else get_workspace(need, Wtable.device, stream)
     with torch.cuda.device(Wtable.device):
         st = lib().lime_score_candidates_gathered(_ptr(Wtable), _ptr(ids), n_items, _ptr(LP), _ptr(Wv), _ptr(O), B, C, d,
                                                   h, m, code, _ptr(ws), ws.numel(), _stream(stream))
@@ -392,7 +401,7 @@ def lime_link_history_prepared(E, lens, prepared, h, m, scale, xor_attention=Fal
     if LP is None:
         LP = torch.empty((B, m, d), dtype=E.dtype, device=E.device)
     need = workspace_bytes(OP_LINK_HISTORY, B=B, N=N, d=d, h=h, m=m, dtype=code)
-    ws = workspace if workspace is not None else get_workspace(need, E.device)
+    ws = workspace if workspace is not None else get_workspace(need, E.device, stream)
     with torch.cuda.device(E.device):
         st = lib().lime_link_history_prepared(_ptr(E), _ptr(lens), _ptr(prepared), _ptr(LP), B, N, d, h, m, float(scale),
                                               int(bool(xor_attention)), code, _ptr(ws), ws.numel(), _stream(stream))
@@ -409,7 +418,7 @@ def lime_score_candidates_prepared(T, LP, Wv, prepared, h, scale, O=None, worksp
     if O is None:
         O = torch.empty_like(T)
     need = workspace_bytes(OP_SCORE_CANDIDATES, B=B, C=C, d=d, h=h, m=m, dtype=code)
-    ws = workspace if workspace is not None else get_workspace(need, T.device)
+    ws = workspace if workspace is not None else get_workspace(need, T.device, stream)
     with torch.cuda.device(T.device):
         st = lib().lime_score_candidates_prepared(_ptr(T), _ptr(LP), _ptr(Wv), _ptr(prepared), _ptr(O), B, C, d, h, m,
                                                   float(scale), code, _ptr(ws), ws.numel(), _stream(stream))
@@ -428,7 +437,7 @@ def lime_xor_backward(QS, KS, VS, QT, KT, VT, dOT, dOS, lens, h, scale=1.0, work
     lens = _lens_arg(lens, B, QS.device)
     outs = [torch.empty_like(QS) for _ in range(3)] + [torch.empty_like(QT) for _ in range(3)]
     need = workspace_bytes(OP_XOR_BACKWARD, B=B, N=N, d=d, h=h, m=m, dtype=code)
-    ws = workspace if workspace is not None else get_workspace(need, QS.device)
+    ws = workspace if workspace is not None else get_workspace(need, QS.device, stream)
     with torch.cuda.device(QS.device):
         st = lib().lime_xor_backward(_ptr(QS), _ptr(KS), _ptr(VS), _ptr(QT), _ptr(KT), _ptr(VT), _ptr(dOT), _ptr(dOS),
                                      _ptr(lens), *[_ptr(o) for o in outs], B, N, m, d, h, float(scale), code, _ptr(ws),
@@ -456,7 +465,7 @@ def lime_request(E, lens, LC, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand,
     if O is None:
         O = torch.empty_like(T)
     need = workspace_bytes(OP_REQUEST, B=B, N=N, C=C, d=d, h=h, m=m, dtype=code)
-    ws = workspace if workspace is not None else get_workspace(need, E.device)
+    ws = workspace if workspace is not None else get_workspace(need, E.device, stream)
     with torch.cuda.device(E.device):
         st = lib().lime_request(_ptr(E), _ptr(lens), _ptr(LC), stride, _ptr(Wq_hist), _ptr(Wk_hist), _ptr(Wv_hist), _ptr(T),
                                 _ptr(L), _ptr(Wq_cand), _ptr(Wk_cand), _ptr(Wv_cand), _ptr(LP), _ptr(O), B, N, C, d, h, m,
@@ -507,7 +516,7 @@ def lime_request_prepared(E, lens, T, Wv, prepared, h, m, scale_hist, scale_cand
     if O is None:
         O = torch.empty_like(T)
     need = workspace_bytes(OP_REQUEST_PREPARED, B=B, N=N, C=C, d=d, h=h, m=m, dtype=code)
-    ws = workspace if workspace is not None else get_workspace(need, E.device)
+    ws = workspace if workspace is not None else get_workspace(need, E.device, stream)
     with torch.cuda.device(E.device):
         st = lib().lime_request_prepared(_ptr(E), _ptr(lens), _ptr(T), _ptr(Wv), _ptr(prepared), _ptr(LP), _ptr(O), B, N, C,
                                          d, h, m, float(scale_hist), float(scale_cand), int(bool(xor_attention)), code,
@@ -540,7 +549,7 @@ def lime_contextualize_links(L, EC, W1, b1, W2, b2, LC=None, workspace=None, str
     if LC is None:
         LC = torch.empty((B, m, d), dtype=L.dtype, device=L.device)
     need = (B * m * dhid * 4 + 255) // 256 * 256
-    ws = workspace if workspace is not None else get_workspace(need, L.device)
+    ws = workspace if workspace is not None else get_workspace(need, L.device, stream)
     with torch.cuda.device(L.device):
         st = lib().lime_contextualize_links(_ptr(L), _ptr(EC), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), _ptr(LC), B, m, d, dc, dhid,
                                             _dtype_code(first), _ptr(ws), ws.numel(), _stream(stream))
@@ -567,7 +576,7 @@ def lime_interaction_mlp(O, weights, biases, scores=None, workspace=None, stream
     if scores is None:
         scores = torch.empty(O.shape[:-1], dtype=torch.float32, device=O.device)
     need = int(lib().lime_interaction_mlp_workspace_bytes(rows, d, widths, n, code))
-    ws = workspace if workspace is not None else get_workspace(need, O.device)
+    ws = workspace if workspace is not None else get_workspace(need, O.device, stream)
     with torch.cuda.device(O.device):
         st = lib().lime_interaction_mlp(_ptr(O), W, b, widths, n, _ptr(scores), rows, d, code, _ptr(ws), ws.numel(), _stream(stream))
     _raise(st)
@@ -613,7 +622,7 @@ def lime_scores(model: ScoringModel, E, lens, EC, T, want_intermediates=False, w
     need = int(lib().lime_scores_workspace_bytes(_c.byref(model), B, N, C, code))
     if need == 0:
         raise LimeError(1, "lime_scores: the model or the sizes are not valid")
-    ws = workspace if workspace is not None else get_workspace(need, E.device)
+    ws = workspace if workspace is not None else get_workspace(need, E.device, stream)
     with torch.cuda.device(E.device):
         st = lib().lime_scores(_c.byref(model), _ptr(E), _ptr(lens), _ptr(EC), _ptr(T), _ptr(LC), _ptr(LP), _ptr(O), _ptr(scores), B, N,
                                C, code, _ptr(ws), ws.numel(), _stream(stream))
