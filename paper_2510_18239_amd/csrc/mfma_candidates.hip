@@ -137,12 +137,24 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
       advance(ib, ir0);
     }
 
-  // Every workgroup wants the same W_Q^T fragments; asked for in the same order by all compute units at once,
-  // the requests queue up at one cache channel after another.  The workgroups of an XCD (consecutive
+  // A wave's vector memory instructions issue in program order, and the compute unit's address path takes a
+  // 16-byte-per-lane load of a wave in 16 cycles: asked for up front, the 50-odd loads of the stationary
+  // operands of four waves hold every wave for 1.5 us before it reaches the first use of the first of them.
+  // Where all of W_Q^T lives in registers (kJit) the prologue therefore asks for the first tiles and kLead
+  // k-steps of W_Q^T only, and feeds the remaining requests (W_Q^T, then K~, then V~^T: the order of their
+  // first use) between the matrix instructions of the first tile's first product.
+  constexpr bool kJit = KL == 0;
+  constexpr int kLead = KR < 4 ? KR : 4;
+  bf16x8 wq[KR][FB];
+  auto load_wq_step = [&](int kk) {
+#pragma unroll
+    for (int mb = 0; mb < FB; ++mb) wq[kk][mb] = a.WqA[((head * K1 + kk) * FB + mb + head * kQueryImageHeadPad) * 64 + lane];
+  };
+  // Otherwise: every workgroup wants the same W_Q^T fragments; asked for in the same order by all compute units
+  // at once, the requests queue up at one cache channel after another.  The workgroups of an XCD (consecutive
   // workgroups go to different XCDs) therefore start at different k-steps.  The destination registers and the
   // order of the products stay the same: kRot copies of the load sequence, chosen by a uniform switch.
-  bf16x8 wq[KR][FB];
-  constexpr int kRot = KR >= 8 ? 4 : 1;
+  constexpr int kRot = !kJit && KR >= 8 ? 4 : 1;
   auto load_wq = [&](auto rot_tag) {
     constexpr int start = decltype(rot_tag)::value * (KR / kRot);
 #pragma unroll
@@ -152,11 +164,16 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
       for (int mb = 0; mb < FB; ++mb) wq[kk][mb] = a.WqA[((head * K1 + kk) * FB + mb + head * kQueryImageHeadPad) * 64 + lane];
     }
   };
-  switch (kRot == 1 ? 0 : (blockIdx.x / 8) % kRot) {
-    case 1: load_wq(std::integral_constant<int, 1>{}); break;
-    case 2: load_wq(std::integral_constant<int, 2>{}); break;
-    case 3: load_wq(std::integral_constant<int, 3>{}); break;
-    default: load_wq(std::integral_constant<int, 0>{}); break;
+  if constexpr (kJit) {
+#pragma unroll
+    for (int kk = 0; kk < kLead && kk < KR; ++kk) load_wq_step(kk);
+  } else {
+    switch (kRot == 1 ? 0 : (blockIdx.x / 8) % kRot) {
+      case 1: load_wq(std::integral_constant<int, 1>{}); break;
+      case 2: load_wq(std::integral_constant<int, 2>{}); break;
+      case 3: load_wq(std::integral_constant<int, 3>{}); break;
+      default: load_wq(std::integral_constant<int, 0>{}); break;
+    }
   }
   if constexpr (KL > 0) {
     bf16x8 tmp[KL * FB];
@@ -272,19 +289,53 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
         for (int mb = 0; mb < MB; ++mb) va[kk][mb] = src[(kk * MB + mb) * 64 + lane];
     }
   };
+  // item t of the first user's operands, in the order of their first use (the keys, then the values)
+  constexpr int nKA = FUSED ? 0 : K2 * LB, nVA = WEIGHTS ? 0 : K3 * MB, nUser = nKA + nVA;
+  auto load_user_item = [&](int b, int t) {
+    if (t < nKA) {
+      const bf16x8* src = a.KA + b * a.ka_user_frags + static_cast<int64_t>(head) * K2 * LB * 64;
+      ka[t / LB][t % LB] = src[t * 64 + lane];
+    } else {
+      const int u = t - nKA;
+      const bf16x8* src = a.VA + b * a.va_user_frags + static_cast<int64_t>(head) * K3 * MB * 64;
+      va[u / MB][u % MB] = src[u * 64 + lane];
+    }
+  };
   int cur_user = first / a.tiles_per_user;
-  load_user(cur_user, !FUSED, !WEIGHTS);  // requested with everything else, long before their first use
+  if constexpr (!kJit) load_user(cur_user, !FUSED, !WEIGHTS);  // requested with everything else, long before their first use
   int rlen = a.row_lens ? min(a.row_lens[cur_user], a.rows) : a.rows;
 
   // Software pipeline: while the vector ALUs do phi of tile i, the matrix cores already run the
   // first product of tile i+1, whose X rows were parked in the other LDS buffer.
   park(ring[0], xs[0]);
   __syncthreads();
-  if (first + P < last) {
-    issue(ib, ir0, ring[0]);
-    advance(ib, ir0);
+  if constexpr (kJit) {
+    first_begin(xs[0]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < K1; ++kk) {
+      if (kk + kLead < KR) {
+        load_wq_step(kk + kLead);
+      } else {
+        const int slot = kk + kLead - KR;  // 0 .. kLead - 1: the k-steps that have no W_Q^T left to ask for
+#pragma unroll
+        for (int t = slot * nUser / kLead; t < (slot + 1) * nUser / kLead; ++t) load_user_item(cur_user, t);
+      }
+#pragma unroll
+      for (int mb = 0; mb < FB; ++mb) first_mfma(kk * FB + mb);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (first + P < last) {
+      issue(ib, ir0, ring[0]);
+      advance(ib, ir0);
+    }
+  } else {
+    if (first + P < last) {
+      issue(ib, ir0, ring[0]);
+      advance(ib, ir0);
+    }
+    first_product(xs[0]);
   }
-  first_product(xs[0]);
   int b = b_first, r0 = r0_first;  // the tile being computed
 
   for (int base = first; base < last; base += P) {
