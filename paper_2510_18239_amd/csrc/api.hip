@@ -555,16 +555,24 @@ int32_t check_request(const char* fn, const void* E, const void* LC, int64_t lc_
   return LIME_OK;
 }
 
+// Layer normalisations applied on the way into the request's kernels (matrix-core path only): of the link rows that
+// become the history stage's queries, and of the candidate stage's query, key and value rows.  (The history rows,
+// which are keys and values at once, are normalised by a pass of their own before the request.)
+struct RequestNorms {
+  lime::RowNorm hist_q, cand_q, cand_k, cand_v;
+};
+
 // Arguments checked, workspace of p.total bytes at hand.
 int32_t request_impl(const char* fn, const RequestPlan& p, const void* E, const int32_t* lens, const void* LC,
                      int64_t lc_user_stride, const void* Wq_hist, const void* Wk_hist, const void* Wv_hist, const void* T,
                      const void* L, const void* Wq_cand, const void* Wk_cand, const void* Wv_cand, void* LP, void* O,
                      int32_t B, int32_t N, int32_t C, int32_t d, int32_t h, int32_t m, float scale_hist, float scale_cand,
-                     int32_t xor_attention, int32_t dtype, void* workspace, void* stream) {
+                     int32_t xor_attention, int32_t dtype, void* workspace, void* stream, const RequestNorms* norms = nullptr) {
   const int phi = xor_attention ? lime::kPhiSilu : lime::kPhiSoftmax;
   const bool per_user = lc_user_stride != 0;
   void* cand_ws = static_cast<char*>(workspace) + p.hist_bytes;
   if (!p.on_mfma) {  // the two stages as they are (general kernels, or the matrix-core ones where each applies)
+    if (norms != nullptr) return fail(LIME_UNSUPPORTED, "%s: normalised operands need the matrix-core path", fn);
     if (int32_t st = history_impl(fn, phi, E, lens, LC, lc_user_stride, Wq_hist, Wk_hist, Wv_hist, LP, nullptr, B, N, d, h, m,
                                   scale_hist, dtype, workspace, p.hist_bytes, stream))
       return st;
@@ -582,6 +590,8 @@ int32_t request_impl(const char* fn, const RequestPlan& p, const void* E, const 
   c.X = T, c.O = O, c.Wq = Wq_cand, c.Ksrc = L, c.Wk = Wk_cand, c.Vsrc = LP, c.Wv = Wv_cand;
   c.k_user_stride = 0, c.v_user_stride = static_cast<int64_t>(m) * d, c.row_lens = nullptr;
   c.B = B, c.rows = C, c.d = d, c.h = h, c.m = m, c.scale = scale_cand, c.phi = lime::kPhiSoftmax;
+  if (norms != nullptr)
+    q.q_norm = norms->hist_q, q.values_norm = norms->cand_v, c.x_norm = norms->cand_q, c.k_norm = norms->cand_k;
   lime::PackJobs jobs;
   lime::links_over_history_jobs(q, workspace, jobs);
   lime::queries_over_links_jobs(c, cand_ws, jobs, /*values=*/false);
@@ -856,10 +866,11 @@ ScoresPlan plan_scores(const lime_scoring_model& M, int32_t B, int32_t N, int32_
   p.LP = take(links);
   p.LPn = take(links);
   p.O = take(static_cast<size_t>(B) * C * M.d * es);
-  p.hist_bytes = lime_workspace_bytes(LIME_OP_LINK_HISTORY, B, N, C, M.d, M.h, M.m, dtype, 0);
-  p.hist = take(p.hist_bytes);
-  p.cand_bytes = lime_workspace_bytes(LIME_OP_SCORE_CANDIDATES, B, N, C, M.d, M.h, M.m, dtype, 0);
-  p.cand = take(p.cand_bytes);
+  // the two attention stages' scratch, laid out as a request's (the history stage's part, then the candidate stage's)
+  const RequestPlan r = plan_request(false, /*any_path=*/true, true, B, N, C, M.d, M.h, M.m, dtype);
+  p.hist_bytes = r.hist_bytes, p.cand_bytes = r.total - r.hist_bytes;
+  p.hist = take(r.total);
+  p.cand = p.hist + p.hist_bytes;
   p.mlp_bytes = mlp_workspace(static_cast<int64_t>(B) * C, M.d, M.mlp_width, M.n_mlp, dtype);
   p.mlp = take(p.mlp_bytes);
   p.total = at;
@@ -952,17 +963,41 @@ int32_t lime_scores(const lime_scoring_model* model, const void* E, const int32_
     return st;
   // Eq. 3 on normalised inputs (history rows past lens[b] are skipped: nothing reads them)
   LIME_HIP(lime::layer_norm_rows(E, M.ln_hist_kv[0], M.ln_hist_kv[1], M.ln_eps, ws + p.En, static_cast<int64_t>(B) * N, d, lens, N, dtype, s));
-  LIME_HIP(lime::layer_norm_rows(lc, M.ln_hist_q[0], M.ln_hist_q[1], M.ln_eps, ws + p.LCn, static_cast<int64_t>(B) * m, d, nullptr, 1, dtype, s));
-  if (int32_t st = history_impl(fn, lime::kPhiSoftmax, ws + p.En, lens, ws + p.LCn, static_cast<int64_t>(m) * d, M.hist_Wq, M.hist_Wk,
-                                M.hist_Wv, lp, nullptr, B, N, d, M.h, m, M.scale_hist, dtype, ws + p.hist, p.hist_bytes, stream))
-    return st;
-  // Eq. 4 on normalised inputs: keys from the raw links, values from the personalised links
-  LIME_HIP(lime::layer_norm_rows(T, M.ln_cand_q[0], M.ln_cand_q[1], M.ln_eps, ws + p.Tn, static_cast<int64_t>(B) * C, d, nullptr, 1, dtype, s));
-  LIME_HIP(lime::layer_norm_rows(M.L, M.ln_cand_k[0], M.ln_cand_k[1], M.ln_eps, ws + p.Ln, m, d, nullptr, 1, dtype, s));
-  LIME_HIP(lime::layer_norm_rows(lp, M.ln_cand_v[0], M.ln_cand_v[1], M.ln_eps, ws + p.LPn, static_cast<int64_t>(B) * m, d, nullptr, 1, dtype, s));
-  if (int32_t st = lime_score_candidates(ws + p.Tn, ws + p.Ln, ws + p.LPn, M.cand_Wq, M.cand_Wk, M.cand_Wv, o, B, C, d, M.h, m,
-                                         M.scale_cand, dtype, ws + p.cand, p.cand_bytes, stream))
-    return st;
+  const int64_t link_stride = static_cast<int64_t>(m) * d;
+  const bool on_mfma = dtype == LIME_BF16 && lime::links_over_history_supported(d, M.h, m) && fits_tiles(B, N) && fits_tiles(B, C) &&
+                       all_aligned16(E, T, M.L, lc, lp, o, M.hist_Wq, M.hist_Wk, M.hist_Wv, M.cand_Wq, M.cand_Wk, M.cand_Wv) &&
+                       // (the kernels that normalise on the way in fetch scale and shift unconditionally, 16 bytes at a time)
+                       M.ln_hist_q[0] && M.ln_hist_q[1] && M.ln_cand_q[0] && M.ln_cand_q[1] && M.ln_cand_k[0] && M.ln_cand_k[1] &&
+                       M.ln_cand_v[0] && M.ln_cand_v[1] &&
+                       all_aligned16(M.ln_hist_q[0], M.ln_hist_q[1], M.ln_cand_q[0], M.ln_cand_q[1], M.ln_cand_k[0], M.ln_cand_k[1],
+                                     M.ln_cand_v[0], M.ln_cand_v[1]);
+  if (on_mfma) {
+    // The request's four kernels with the other four normalisations inside them: the link rows L^C and L as the pack
+    // step reads them, the finished link states L^P as the merge step projects them, the candidate rows as the
+    // candidate kernel parks their tiles.  Each rounds to bf16 where the separate pass would have stored its result.
+    RequestNorms norms;
+    norms.hist_q = {true, M.ln_hist_q[0], M.ln_hist_q[1], M.ln_eps};
+    norms.cand_q = {true, M.ln_cand_q[0], M.ln_cand_q[1], M.ln_eps};
+    norms.cand_k = {true, M.ln_cand_k[0], M.ln_cand_k[1], M.ln_eps};
+    norms.cand_v = {true, M.ln_cand_v[0], M.ln_cand_v[1], M.ln_eps};
+    RequestPlan r = plan_request(true, /*any_path=*/true, true, B, N, C, d, M.h, m, dtype);
+    if (int32_t st = request_impl(fn, r, ws + p.En, lens, lc, link_stride, M.hist_Wq, M.hist_Wk, M.hist_Wv, T, M.L, M.cand_Wq,
+                                  M.cand_Wk, M.cand_Wv, lp, o, B, N, C, d, M.h, m, M.scale_hist, M.scale_cand, 0, dtype,
+                                  ws + p.hist, stream, &norms))
+      return st;
+  } else {
+    LIME_HIP(lime::layer_norm_rows(lc, M.ln_hist_q[0], M.ln_hist_q[1], M.ln_eps, ws + p.LCn, static_cast<int64_t>(B) * m, d, nullptr, 1, dtype, s));
+    if (int32_t st = history_impl(fn, lime::kPhiSoftmax, ws + p.En, lens, ws + p.LCn, link_stride, M.hist_Wq, M.hist_Wk,
+                                  M.hist_Wv, lp, nullptr, B, N, d, M.h, m, M.scale_hist, dtype, ws + p.hist, p.hist_bytes, stream))
+      return st;
+    // Eq. 4 on normalised inputs: keys from the raw links, values from the personalised links
+    LIME_HIP(lime::layer_norm_rows(T, M.ln_cand_q[0], M.ln_cand_q[1], M.ln_eps, ws + p.Tn, static_cast<int64_t>(B) * C, d, nullptr, 1, dtype, s));
+    LIME_HIP(lime::layer_norm_rows(M.L, M.ln_cand_k[0], M.ln_cand_k[1], M.ln_eps, ws + p.Ln, m, d, nullptr, 1, dtype, s));
+    LIME_HIP(lime::layer_norm_rows(lp, M.ln_cand_v[0], M.ln_cand_v[1], M.ln_eps, ws + p.LPn, static_cast<int64_t>(B) * m, d, nullptr, 1, dtype, s));
+    if (int32_t st = lime_score_candidates(ws + p.Tn, ws + p.Ln, ws + p.LPn, M.cand_Wq, M.cand_Wk, M.cand_Wv, o, B, C, d, M.h, m,
+                                           M.scale_cand, dtype, ws + p.cand, p.cand_bytes, stream))
+      return st;
+  }
   // Section 3.3: the interaction network
   return mlp_impl(fn, o, M.mlp_W, M.mlp_b, M.mlp_width, M.n_mlp, scores, static_cast<int64_t>(B) * C, d, dtype, ws + p.mlp, p.mlp_bytes, stream);
 }

@@ -51,6 +51,33 @@ __device__ __forceinline__ float pair_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// Sums over groups of G neighbouring lanes (G a power of two, groups aligned), every lane of a group getting the
+// group's sum, without an LDS round trip where G is 16 or 32: four DPP rotations inside the 16-lane row, then
+// v_permlane16_swap, which with both operands x returns (x of the even row, x of the odd row) of the lane's row pair.
+template <int N>
+__device__ __forceinline__ float row_rotated(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x120 + N, 0xF, 0xF, false));  // row_ror:N
+}
+template <int G>
+__device__ __forceinline__ float group_sum(float x) {
+  if constexpr (G == 16 || G == 32) {
+    x += row_rotated<8>(x);
+    x += row_rotated<4>(x);
+    x += row_rotated<2>(x);
+    x += row_rotated<1>(x);
+    if constexpr (G == 32) {
+      const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+      x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    }
+  } else {
+#pragma unroll
+    for (int o = 1; o < G; o *= 2) x += __shfl_xor(x, o, 64);
+  }
+  return x;
+}
+
+__device__ __forceinline__ float wave_sum(float x) { return pair_sum(group_sum<32>(x)); }
+
 // A 16-byte store that writes through the L2 (agent scope, `sc1`): `base` is uniform over the wave, `offset` the
 // lane's byte offset below `span` bytes.  The XCDs' L2s are not coherent with each other, so whatever a kernel
 // leaves dirty in them is written back when the kernel ends; an output stream that nobody on the chip reads again is
@@ -100,6 +127,17 @@ struct PackWeight {
   float sign = 1.f;  // +1 or -1, multiplies every element (exact)
   int head_pad = 0;  // fragments left free between the head slices of the image
 };
+// Layer normalisation of an operand's rows on their way into a kernel (Appendix C: the tensors that enter an MHA are
+// normalised before the Q, K, V projections): y = (x - mean) / sqrt(var + eps) * gamma + beta over the d features
+// (biased variance, statistics in fp32, mean first and then the centred second moment), rounded to bf16 exactly
+// where a separate normalisation pass would have stored it.  gamma, beta [d] bf16, both required when `on` (the
+// kernels fetch them unconditionally, together with their other operands).
+struct RowNorm {
+  bool on = false;
+  const void* gamma = nullptr;
+  const void* beta = nullptr;
+  float eps = 0.f;
+};
 //   kPackValuesNatural: as kPackValues with the rows summed in natural order, 16kk + 8g + t (for a B operand
 //                   that is read row-major from memory rather than taken from accumulators)
 constexpr int kPackKeys = 0, kPackValues = 1, kPackValuesNatural = 2;
@@ -111,6 +149,7 @@ struct PackProject {
   int users;
   int layout;      // kPackKeys, kPackValues or kPackValuesNatural
   float sign;      // +1 or -1: multiplies every projected element (exact); lets kernels assume scale >= 0
+  RowNorm norm;    // applied to the rows of X before the projection
 };
 //   score image   [h][d/16][m/32][64]: fragment (a, kk, lb), lane (n, g), slot t = G_a[16kk + 8g + t][32lb + n] with
 //                   G_a = W_Q[:, head a] (L W_K)[:, head a]^T  (d x m): the logits of head a are X G_a, so when the keys
@@ -176,6 +215,8 @@ struct QueriesOverLinks {
   const void* prepared; // when set: W_Q^T and K~ come from this prepared buffer (Wq, Ksrc, Wk unused; shared keys)
   bool packed;          // when set: the operands have been packed into the workspace already (queries_over_links_jobs;
                         // with `prepared`: the value image, by the history side's merge step)
+  RowNorm x_norm;       // applied to the query rows as their tiles are loaded (softmax, O output, per-call operands)
+  RowNorm k_norm, v_norm;  // applied to the key / value rows by the pack step
 };
 // where the value image of a call lives in its workspace
 void* queries_over_links_values(const QueriesOverLinks& a, void* workspace);
@@ -250,6 +291,8 @@ struct LinksOverHistory {
   // (Wv_values [d][d] bf16, nullable = identity), and writes them as the kPackValues image of a candidate-side call
   const void* Wv_values;
   void* values_image;
+  RowNorm values_norm;  // applied to the finished link states before that projection (LP itself is stored as it is)
+  RowNorm q_norm;       // applied to the link rows LC by the pack step
 };
 void links_over_history_jobs(const LinksOverHistory& a, void* workspace, PackJobs& jobs);
 bool links_over_history_supported(int d, int h, int m);

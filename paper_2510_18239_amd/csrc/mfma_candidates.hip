@@ -37,11 +37,19 @@ struct MainArgs {
   float scale, inv_norm;
   bf16_t* Wout;  // WEIGHTS variant only
   bool fused;
+  // NORM variant only: layer normalisation of the query rows (gamma, beta nullable = 1, 0)
+  const bf16_t *ln_gamma, *ln_beta;
+  float ln_eps;
+  bool ln_on;
 };
 
 // WEIGHTS: stop after phi and write the normalised attention weights [rows][h][m] (the QK cache of
 // Section 3.3) instead of the weighted sum.
-template <int DH, int M, int H, int PHI, bool WEIGHTS, bool FUSED>
+// NORM: the query rows are layer-normalised over their d features (Appendix C) on their way from the register ring
+// into LDS: a row is 16 bytes in each of d/8 neighbouring lanes of one load, so its statistics are a few lane
+// exchanges, and every element is handled once per tile whichever waves read it afterwards.  Rounded to bf16 where
+// a normalisation pass of its own would have stored the row.
+template <int DH, int M, int H, int PHI, bool WEIGHTS, bool FUSED, bool NORM = false>
 __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) {
   constexpr int D = DH * H;
   constexpr int K1 = D / 16, MB = DH / 32;   // first product: k-steps over d, row blocks over d/h
@@ -118,11 +126,35 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
     tr0 += 32;
     if (tr0 >= a.rows) tr0 = 0, ++tb;
   };
+  // NORM: scale and shift of this lane's eight columns (the same in every tile), asked for ahead of everything else
+  bf16x8 ln_gv, ln_bv;
+  if constexpr (NORM) {
+    ln_gv = *reinterpret_cast<const bf16x8*>(a.ln_gamma + 8 * (lane % CPR));
+    ln_bv = *reinterpret_cast<const bf16x8*>(a.ln_beta + 8 * (lane % CPR));
+  }
+  auto normalised = [&](const bf16x8& v) -> bf16x8 {
+    float x[8], sum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) x[t] = static_cast<float>(v[t]), sum += x[t];
+    sum = group_sum<CPR>(sum);
+    const float mean = sum * (1.f / D);
+    float q = 0.f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) x[t] -= mean, q = fmaf(x[t], x[t], q);
+    q = group_sum<CPR>(q);
+    const float inv = __builtin_amdgcn_rsqf(q * (1.f / D) + a.ln_eps);
+    bf16x8 y;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) y[t] = static_cast<__bf16>(fmaf(x[t] * inv, static_cast<float>(ln_gv[t]), static_cast<float>(ln_bv[t])));
+    return y;
+  };
   auto park = [&](const bf16x8 (&r)[LW], unsigned char* buf) {
 #pragma unroll
     for (int j = 0; j < LW; ++j) {
       const int q = (head * LW + j) * 64 + lane;
-      *reinterpret_cast<bf16x8*>(buf + (q / CPR) * PITCH + (q % CPR) * 16) = r[j];
+      bf16x8* dst = reinterpret_cast<bf16x8*>(buf + (q / CPR) * PITCH + (q % CPR) * 16);
+      if constexpr (NORM) *dst = normalised(r[j]);
+      else *dst = r[j];
     }
   };
 
@@ -484,6 +516,11 @@ template <int DH, int M, int H, bool FUSED>
 hipError_t launch_form(const MainArgs& m, int phi, int grid, hipStream_t s) {
   if (m.Wout != nullptr)
     launch_timed(kKernelQueriesOverLinks, queries_over_links_kernel<DH, M, H, kPhiSoftmax, true, FUSED>, dim3(grid), dim3(64 * H), 0, s, m);
+  else if (phi == kPhiSoftmax && m.ln_on) {
+    if constexpr (FUSED) return hipErrorInvalidValue;
+    else launch_timed(kKernelQueriesOverLinks, queries_over_links_kernel<DH, M, H, kPhiSoftmax, false, false, true>, dim3(grid), dim3(64 * H), 0, s, m);
+  } else if (m.ln_on)
+    return hipErrorInvalidValue;
   else if (phi == kPhiSoftmax)
     launch_timed(kKernelQueriesOverLinks, queries_over_links_kernel<DH, M, H, kPhiSoftmax, false, FUSED>, dim3(grid), dim3(64 * H), 0, s, m);
   else
@@ -558,9 +595,9 @@ void queries_over_links_jobs(const QueriesOverLinks& q, void* workspace, PackJob
   jobs.weights[jobs.n_weights++] = PackWeight{q.Wq, ws, 1.f, kQueryImageHeadPad};
   // a negative logit scale is folded into the sign of the packed keys, so the kernel sees scale >= 0
   jobs.projections[jobs.n_projections++] =
-      PackProject{q.Ksrc, q.Wk, KA, q.k_user_stride, k_per_user ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f};
+      PackProject{q.Ksrc, q.Wk, KA, q.k_user_stride, k_per_user ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f, q.k_norm};
   if (!q.weights_out && values)
-    jobs.projections[jobs.n_projections++] = PackProject{q.Vsrc, q.Wv, VA, q.v_user_stride, v_per_user ? q.B : 1, kPackValues, 1.f};
+    jobs.projections[jobs.n_projections++] = PackProject{q.Vsrc, q.Wv, VA, q.v_user_stride, v_per_user ? q.B : 1, kPackValues, 1.f, q.v_norm};
 }
 
 hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStream_t s) {
@@ -597,6 +634,8 @@ hipError_t queries_over_links(const QueriesOverLinks& q, void* workspace, hipStr
   a.row_lens = q.row_lens;
   a.Wout = static_cast<bf16_t*>(q.weights_out);
   a.fused = fused;
+  a.ln_on = q.x_norm.on, a.ln_eps = q.x_norm.eps;
+  a.ln_gamma = static_cast<const bf16_t*>(q.x_norm.gamma), a.ln_beta = static_cast<const bf16_t*>(q.x_norm.beta);
   a.B = q.B, a.rows = q.rows, a.tiles_per_user = (q.rows + 31) / 32;
   a.total_tiles = a.tiles_per_user * q.B;  // the caller has checked that this fits an int
   a.scale = fabsf(q.scale), a.inv_norm = 1.f / static_cast<float>(m);

@@ -401,6 +401,10 @@ struct MergeValuesArgs {
   const bf16_t* Wv;  // [d][d], nullable = identity
   bf16_t* VA;        // [B] value images
   int passes;        // row pairs a workgroup handles one after the other with the same W_V registers
+  // layer normalisation of the finished link states before the projection (ln_on; LP is stored un-normalised)
+  const bf16_t *ln_gamma, *ln_beta;
+  float ln_eps;
+  int ln_on;
 };
 
 template <int PHI, int D>
@@ -421,6 +425,7 @@ __global__ __launch_bounds__(2 * D) void merge_values_kernel(MergeValuesArgs a) 
     for (int it = 0; it < kMvMaxK; ++it)
       wreg[it] = *reinterpret_cast<const bf16x8*>(a.Wv + static_cast<int64_t>(kc + it * nkc) * d + 8 * cg);
   }
+  constexpr int kLnWaves = kMvThreads / 64, kLnPerLane = (D + 63) / 64;
   const int len = a.m.lens ? min(a.m.lens[b], a.m.N) : a.m.N;
   // (no barrier is needed between two passes: whoever writes lp, red or out again has passed two barriers since
   // the last read of it)
@@ -433,6 +438,46 @@ __global__ __launch_bounds__(2 * D) void merge_values_kernel(MergeValuesArgs a) 
                     merged_values<PHI>(a.m, b, link, col / a.m.dh, col % a.m.dh, len), lp + i);
     }
     __syncthreads();
+    if (a.ln_on) {  // uniform
+      // a wavefront per row: mean, centred second moment, then the normalised row rounded to bf16, as a
+      // normalisation pass of its own would have stored it
+      // (the thread index through an opaque copy: what is derived from it here - addresses, the scale and the shift -
+      // is then computed and fetched here, not ahead of the merge, which has no registers to carry it and would
+      // spill; the fetches are in flight during the two reductions)
+      int t_ln = tid;
+      asm volatile("" : "+v"(t_ln));
+      for (int r = t_ln / 64; r < kMvRows; r += kLnWaves) {
+        float* xr = lp + r * d;
+        bf16_t ln_g[kLnPerLane], ln_b[kLnPerLane];
+#pragma unroll
+        for (int i = 0; i < kLnPerLane; ++i) {
+          const int k = min(t_ln % 64 + 64 * i, d - 1);
+          ln_g[i] = a.ln_gamma[k], ln_b[i] = a.ln_beta[k];
+        }
+        float x[kLnPerLane], sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < kLnPerLane; ++i) {
+          const int k = t_ln % 64 + 64 * i;
+          x[i] = k < d ? xr[k] : 0.f;
+          sum += x[i];
+        }
+        const float mean = wave_sum(sum) * (1.f / d);
+        float q = 0.f;
+#pragma unroll
+        for (int i = 0; i < kLnPerLane; ++i) {
+          const int k = t_ln % 64 + 64 * i;
+          x[i] = k < d ? x[i] - mean : 0.f;
+          q = fmaf(x[i], x[i], q);
+        }
+        const float inv = 1.f / sqrtf(wave_sum(q) * (1.f / d) + a.ln_eps);
+#pragma unroll
+        for (int i = 0; i < kLnPerLane; ++i) {
+          const int k = t_ln % 64 + 64 * i;
+          if (k < d) xr[k] = static_cast<float>(static_cast<__bf16>(fmaf(x[i] * inv, to_float(ln_g[i]), to_float(ln_b[i]))));
+        }
+      }
+      __syncthreads();
+    }
     if (a.Wv == nullptr) {
       for (int i = tid; i < kMvRows * d; i += kMvThreads) out[i] = lp[i];
     } else {
@@ -568,7 +613,7 @@ void links_over_history_jobs(const LinksOverHistory& q, void* workspace, PackJob
   jobs.weights[jobs.n_weights++] = PackWeight{q.Wv, ws + l.wk};
   // a negative logit scale is folded into the sign of the packed queries, so the kernels see scale >= 0
   jobs.projections[jobs.n_projections++] = PackProject{q.LC, q.Wq, ws + l.wk + l.wv, q.lc_user_stride,
-                                                       q.lc_user_stride != 0 ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f};
+                                                       q.lc_user_stride != 0 ? q.B : 1, kPackKeys, q.scale < 0.f ? -1.f : 1.f, q.q_norm};
 }
 
 hipError_t links_over_history(const LinksOverHistory& q, void* workspace, hipStream_t s) {
@@ -612,7 +657,9 @@ hipError_t links_over_history(const LinksOverHistory& q, void* workspace, hipStr
     int passes = 1;
     while (d >= 256 && passes < 16 && static_cast<int64_t>(q.B) * (m / kMvRows) / (2 * passes) >= compute_units())
       passes *= 2;
-    MergeValuesArgs mv{g, static_cast<const bf16_t*>(q.Wv_values), static_cast<bf16_t*>(q.values_image), passes};
+    MergeValuesArgs mv{g, static_cast<const bf16_t*>(q.Wv_values), static_cast<bf16_t*>(q.values_image), passes,
+                       static_cast<const bf16_t*>(q.values_norm.gamma), static_cast<const bf16_t*>(q.values_norm.beta),
+                       q.values_norm.eps, q.values_norm.on ? 1 : 0};
     const dim3 vgrid(m / (kMvRows * passes), q.B);  // (m / 2 is a multiple of 16)
     const bool softmax = q.phi == kPhiSoftmax;
 #define LIME_MV_CASE(D)                                                                                      \

@@ -20,6 +20,10 @@ struct PackArgs {
   int64_t p_stride[kMaxJobs];
   int p_layout[kMaxJobs];
   float p_sign[kMaxJobs];
+  const bf16_t* p_gamma[kMaxJobs];  // layer normalisation of a job's rows before its projection (p_norm set)
+  const bf16_t* p_beta[kMaxJobs];
+  float p_eps[kMaxJobs];
+  int p_norm[kMaxJobs];
   int p_first_block[kMaxJobs + 1];  // block ranges of the projection jobs, after the weight jobs
   const bf16_t *s_wq, *s_k, *s_wk;  // the score job (at most one), after the projection jobs
   bf16_t* s_img;
@@ -106,12 +110,21 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
     if (idx >= d * d / 8) return;
     const bf16_t* W = p.w_src[job];
     const int col = idx % d, k0 = (idx / d) * 8;
+    // (one uniform branch around all eight loads: a test per element would make each load wait for the one before)
+    float x[8];
+    if (W != nullptr) {
+      bf16_t raw[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) raw[t] = W[static_cast<int64_t>(k0 + t) * d + col];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) x[t] = to_float(raw[t]);
+    } else {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) x[t] = k0 + t == col ? 1.f : 0.f;
+    }
     bf16x8 v;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      const float x = W ? to_float(W[static_cast<int64_t>(k0 + t) * d + col]) : (k0 + t == col ? 1.f : 0.f);
-      v[t] = static_cast<__bf16>(x * p.w_sign[job]);
-    }
+    for (int t = 0; t < 8; ++t) v[t] = static_cast<__bf16>(x[t] * p.w_sign[job]);
     const int a = col / dh, c = col % dh, mb = c / 32, n = c % 32;
     const int kk = k0 / 16, g = (k0 % 16) / 8;
     const int64_t frag = (static_cast<int64_t>(a) * (d / 16) + kk) * (dh / 32) + mb;
@@ -146,8 +159,53 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
       if (k < d) wreg[it] = *reinterpret_cast<const bf16x8*>(W + static_cast<int64_t>(k) * d + col0 + 8 * cg);
     }
   }
+  // (scale and shift of a normalised job: asked for with everything else, used after the rows have arrived; a lane
+  // takes pairs of neighbouring columns so that they come as 32-bit loads, which nothing touches before their use)
+  constexpr int kNormPairs = 256 / 128;  // column pairs per lane at the largest d
+  uint32_t ln_g[kNormPairs], ln_b[kNormPairs];
+  if (p.p_norm[job]) {
+#pragma unroll
+    for (int i = 0; i < kNormPairs; ++i) {
+      const int k = min(2 * (tid % 64) + 128 * i, d - 2);
+      ln_g[i] = reinterpret_cast<const uint32_t*>(p.p_gamma[job])[k / 2];
+      ln_b[i] = reinterpret_cast<const uint32_t*>(p.p_beta[job])[k / 2];
+    }
+  }
   for (int i = tid; i < kPackRows * d; i += 256) xs[i] = to_float(X[i]);
   __syncthreads();
+  if (p.p_norm[job]) {
+    // one wavefront per row (kPackRows of them): mean, centred second moment, then the normalised row rounded to
+    // bf16, as a normalisation pass of its own would have stored it
+    static_assert(kPackRows * 64 == 256, "a wavefront per row");
+    float* xr = xs + (tid / 64) * d;
+    float x[2 * kNormPairs], sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < kNormPairs; ++i) {
+      const int k = 2 * (tid % 64) + 128 * i;
+      x[2 * i] = k < d ? xr[k] : 0.f, x[2 * i + 1] = k < d ? xr[k + 1] : 0.f;
+      sum += x[2 * i] + x[2 * i + 1];
+    }
+    const float mean = wave_sum(sum) / static_cast<float>(d);
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < kNormPairs; ++i) {
+      const int k = 2 * (tid % 64) + 128 * i;
+      x[2 * i] = k < d ? x[2 * i] - mean : 0.f, x[2 * i + 1] = k < d ? x[2 * i + 1] - mean : 0.f;
+      q = fmaf(x[2 * i], x[2 * i], fmaf(x[2 * i + 1], x[2 * i + 1], q));
+    }
+    const float inv = 1.f / sqrtf(wave_sum(q) / static_cast<float>(d) + p.p_eps[job]);
+#pragma unroll
+    for (int i = 0; i < kNormPairs; ++i) {
+      const int k = 2 * (tid % 64) + 128 * i;
+      if (k < d) {
+        xr[k] = static_cast<float>(static_cast<__bf16>(
+            fmaf(x[2 * i] * inv, __uint_as_float(ln_g[i] << 16), __uint_as_float(ln_b[i] << 16))));
+        xr[k + 1] = static_cast<float>(static_cast<__bf16>(
+            fmaf(x[2 * i + 1] * inv, __uint_as_float(ln_g[i] & 0xffff0000u), __uint_as_float(ln_b[i] & 0xffff0000u))));
+      }
+    }
+    __syncthreads();
+  }
   if (W == nullptr) {
     for (int i = tid; i < kPackRows * kPackCols; i += 256) out[i] = xs[(i / kPackCols) * d + col0 + i % kPackCols];
   } else {
@@ -215,6 +273,10 @@ hipError_t pack_operands(const PackWeight* weights, int n_weights, const PackPro
       p.p_stride[i] = projections[i].user_stride;
       p.p_layout[i] = projections[i].layout;
       p.p_sign[i] = projections[i].sign;
+      p.p_norm[i] = projections[i].norm.on ? 1 : 0;
+      p.p_gamma[i] = static_cast<const bf16_t*>(projections[i].norm.gamma);
+      p.p_beta[i] = static_cast<const bf16_t*>(projections[i].norm.beta);
+      p.p_eps[i] = projections[i].norm.eps;
       blocks += projections[i].users * (m / kPackRows) * (d / kPackCols);
     }
   }

@@ -12,6 +12,8 @@
 //    after bias and ReLU, are as they stand the B operand of the next layer (chained k order, see mfma.hpp) and the
 //    hidden activations never leave registers; the last affine map to one logit is a dot product over the lane's
 //    registers plus one exchange with lane ^ 32.
+#include <type_traits>
+
 #include "scoring.hpp"
 
 namespace lime {
@@ -195,8 +197,91 @@ __global__ __launch_bounds__(256) void dense_few_rows_kernel(DenseArgs a) {
   store_as(static_cast<TY*>(a.Y) + (r0 + kq) * a.dout + c0 + col, y);
 }
 
+// Few rows and bf16 weights whose rows can be read 16 bytes at a time (d_out a multiple of 8, W 16-byte aligned): a
+// thread owns 8 adjacent columns and every 32nd k.  These kernels are chains of memory latencies (Eq. 2 is two of them
+// per request), so every load is independent of every other and is issued before the first is used: the rows of X
+// through a selected address instead of a test per element (a test makes each load wait for the one before), the
+// weights in batches of 16 loads with the index clamped and the out-of-range terms zeroed on the X side.
+constexpr int kVecKGroups = 32, kVecBatch = 16;
+template <typename TX, typename TY>
+__global__ __launch_bounds__(256) void dense_few_rows_vec_kernel(DenseArgs a) {
+  __shared__ float Xs[kFewRows][kFewMaxDin];
+  __shared__ float red[kVecKGroups][kFewRows * kDenseCols + 1];  // (odd pitch: the k-groups spread over the banks)
+  const int tid = threadIdx.x, cg = tid % 8, kq = tid / 8;
+  const int64_t r0 = static_cast<int64_t>(blockIdx.x) * kFewRows;
+  const int c0 = blockIdx.y * kDenseCols + 8 * cg, din = a.d1 + a.d2;
+  const int cc = min(c0, a.dout - 8);  // columns past d_out are computed on the last valid ones and not stored
+  const bf16_t* W = static_cast<const bf16_t*>(a.W);
+  bf16x8 w[kVecBatch];
+#pragma unroll
+  for (int j = 0; j < kVecBatch; ++j)
+    w[j] = *reinterpret_cast<const bf16x8*>(W + static_cast<int64_t>(min(kq + kVecKGroups * j, din - 1)) * a.dout + cc);
+  for (int base = 0; base < kFewRows * din; base += 4 * 256) {
+    TX v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int i = min(base + j * 256 + tid, kFewRows * din - 1), k = i % din;
+      const int64_t row = min(r0 + i / din, a.rows - 1);
+      const TX* src = k < a.d1 ? static_cast<const TX*>(a.X1) + (row % a.x1_rows) * a.d1 + k
+                               : static_cast<const TX*>(a.X2) + (row / a.x2_rows_per) * a.d2 + (k - a.d1);
+      v[j] = *src;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int i = base + j * 256 + tid;
+      if (i < kFewRows * din) Xs[i / din][i % din] = r0 + i / din < a.rows ? to_float(v[j]) : 0.f;
+    }
+  }
+  __syncthreads();
+  float acc[kFewRows][8];
+#pragma unroll
+  for (int r = 0; r < kFewRows; ++r)
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[r][t] = 0.f;
+  for (int k0 = 0; k0 < din; k0 += kVecKGroups * kVecBatch) {
+    if (k0 > 0) {  // (d_in beyond 512: the next batch of weight rows)
+#pragma unroll
+      for (int j = 0; j < kVecBatch; ++j)
+        w[j] = *reinterpret_cast<const bf16x8*>(W + static_cast<int64_t>(min(k0 + kq + kVecKGroups * j, din - 1)) * a.dout + cc);
+    }
+#pragma unroll
+    for (int j = 0; j < kVecBatch; ++j) {
+      const int k = k0 + kq + kVecKGroups * j;
+      if (k0 + kVecKGroups * j >= din) break;  // uniform
+#pragma unroll
+      for (int r = 0; r < kFewRows; ++r) {
+        const float x = k < din ? Xs[r][min(k, din - 1)] : 0.f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[r][t] = fmaf(x, static_cast<float>(w[j][t]), acc[r][t]);
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < kFewRows; ++r)
+#pragma unroll
+    for (int t = 0; t < 8; ++t) red[kq][r * kDenseCols + 8 * cg + t] = acc[r][t];
+  __syncthreads();
+  // thread (r, col) finishes one output
+  const int r = tid / kDenseCols, col = blockIdx.y * kDenseCols + tid % kDenseCols;
+  if (col >= a.dout || r0 + r >= a.rows) return;
+  float y = 0.f;
+#pragma unroll 8
+  for (int g = 0; g < kVecKGroups; ++g) y += red[g][tid];
+  if (a.b != nullptr) y += to_float(static_cast<const bf16_t*>(a.b)[col]);
+  if (a.relu) y = fmaxf(y, 0.f);
+  store_as(static_cast<TY*>(a.Y) + (r0 + r) * a.dout + col, y);
+}
+
 template <typename TX, typename TW, typename TY>
 hipError_t launch_dense(const DenseArgs& a, hipStream_t s) {
+  if constexpr (std::is_same<TW, bf16_t>::value) {
+    if (a.rows <= 2048 && a.d1 + a.d2 <= kFewMaxDin && a.dout >= 8 && a.dout % 8 == 0 &&
+        (reinterpret_cast<uintptr_t>(a.W) & 15u) == 0) {
+      const dim3 few(static_cast<unsigned>((a.rows + kFewRows - 1) / kFewRows), (a.dout + kDenseCols - 1) / kDenseCols);
+      hipLaunchKernelGGL((dense_few_rows_vec_kernel<TX, TY>), few, dim3(256), 0, s, a);
+      return hipGetLastError();
+    }
+  }
   if (a.rows <= 2048 && a.d1 + a.d2 <= kFewMaxDin) {
     const dim3 few(static_cast<unsigned>((a.rows + kFewRows - 1) / kFewRows), (a.dout + kDenseCols - 1) / kDenseCols);
     hipLaunchKernelGGL((dense_few_rows_kernel<TX, TW, TY>), few, dim3(256), 0, s, a);
@@ -226,12 +311,12 @@ template <int D, int H1, int H2, int H3>
 __global__ __launch_bounds__(256) void interaction_mlp_kernel(MlpArgs a) {
   constexpr int HL = H3 > 0 ? H3 : (H2 > 0 ? H2 : H1);  // width of the last hidden layer
   constexpr int NB = H1 + H2 + H3 + HL;
-  constexpr int KMAX = H2 == 0 ? D : (H3 == 0 ? (D > H1 ? D : H1) : (D > H1 ? D : (H1 > H2 ? H1 : H2)));  // widest input
-  // A 32-column block of a layer's weight image (K/16 fragments of 1 KiB) is the A operand of all four wavefronts:
-  // the waves fetch it together, a quarter each, one block ahead, and read it back from LDS.  Two buffers while a
-  // block is at most 16 KiB, one (and a second barrier per block) for the wider layers.
-  constexpr int kStage = KMAX / 16 * 64;  // bf16x8 units of the largest block
-  __shared__ bf16x8 stage[KMAX <= 256 ? 2 * kStage : kStage];
+  // A 32-column block of a layer's weight image (K/16 fragments of 1 KiB) is the A operand of all four wavefronts.
+  // It travels in chunks of at most 16 fragments (16 KiB: a block of the widest layer is two of them): the waves fetch
+  // a chunk together, a quarter each, kAhead chunks before its products (one chunk's products are 0.2 us, a fetch
+  // from L2 several times that), park it in one of two LDS buffers and read it back from there.
+  constexpr int kChunkFrags = 16, kAhead = 3;
+  __shared__ bf16x8 stage[2 * kChunkFrags * 64];
   __shared__ __attribute__((aligned(16))) float tab[NB];  // biases of the hidden layers, then the last map's weights
   for (int i = threadIdx.x; i < NB; i += 256) {
     float v;
@@ -253,41 +338,57 @@ __global__ __launch_bounds__(256) void interaction_mlp_kernel(MlpArgs a) {
   // one layer: Y^T = W^T X^T block by block; bias and ReLU on the accumulators; the rounded result is the next B operand
   auto layer = [&](auto k_tag, auto out_tag, const bf16x8* img, const bf16x8* in, int bias_at, bf16x8* out, f32x16* keep) {
     constexpr int K = decltype(k_tag)::value, OUT = decltype(out_tag)::value;
-    constexpr int KF = K / 16, NCB = OUT / 32;    // fragments per block, blocks
-    constexpr int PER = (KF + 3) / 4;              // fragments a wave fetches per block
-    constexpr bool kTwo = KMAX <= 256;
-    bf16x8 pre[PER];
-    auto fetch = [&](int cb) {
+    constexpr int KF = K / 16, NCB = OUT / 32;                    // fragments per block, blocks
+    constexpr int CH = (KF + kChunkFrags - 1) / kChunkFrags;      // chunks per block
+    constexpr int CF = KF / CH;                                   // fragments per chunk (KF is 2, 4, 8, 16 or 32)
+    static_assert(CF * CH == KF, "a block is a whole number of equal chunks");
+    constexpr int NCH = NCB * CH;                                 // chunks of the layer: chunk c holds fragments c CF ..
+    constexpr int PER = (CF + 3) / 4;                             // fragments a wave fetches per chunk
+    bf16x8 pre[kAhead][PER];
+    auto fetch = [&](int c) {
 #pragma unroll
       for (int i = 0; i < PER; ++i)
-        if (wave + 4 * i < KF) pre[i] = img[(cb * KF + wave + 4 * i) * 64 + lane];
+        if (wave + 4 * i < CF) pre[c % kAhead][i] = img[(c * CF + wave + 4 * i) * 64 + lane];
     };
-    fetch(0);
-    __syncthreads();  // the previous layer's last block has been read by everyone (and tab is written)
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) {
-      bf16x8* buf = stage + (kTwo ? (cb & 1) * kStage : 0);
+    for (int c = 0; c < kAhead && c < NCH; ++c) fetch(c);
+    __syncthreads();  // the previous layer's last chunks have been read by everyone (and tab is written)
+    f32x16 acc;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int cb = c / CH, part = c % CH;
+      // (the buffer written here was last read two chunks ago, and every wave has passed a barrier since)
+      bf16x8* buf = stage + (c & 1) * kChunkFrags * 64;
 #pragma unroll
       for (int i = 0; i < PER; ++i)
-        if (wave + 4 * i < KF) buf[(wave + 4 * i) * 64 + lane] = pre[i];
+        if (wave + 4 * i < CF) buf[(wave + 4 * i) * 64 + lane] = pre[c % kAhead][i];
       __syncthreads();
-      if (cb + 1 < NCB) fetch(cb + 1);
-      f32x16 acc;
+      if (c + kAhead < NCH) fetch(c + kAhead);
+      if (part == 0) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {  // registers 4j .. 4j+3 are columns 32cb + 8j + 4g + 0..3
-        const float4 b4 = *reinterpret_cast<const float4*>(&tab[bias_at + 32 * cb + 8 * j + 4 * g]);
-        acc[4 * j] = b4.x, acc[4 * j + 1] = b4.y, acc[4 * j + 2] = b4.z, acc[4 * j + 3] = b4.w;
+        for (int j = 0; j < 4; ++j) {  // registers 4j .. 4j+3 are columns 32cb + 8j + 4g + 0..3
+          const float4 b4 = *reinterpret_cast<const float4*>(&tab[bias_at + 32 * cb + 8 * j + 4 * g]);
+          acc[4 * j] = b4.x, acc[4 * j + 1] = b4.y, acc[4 * j + 2] = b4.z, acc[4 * j + 3] = b4.w;
+        }
       }
+      // every fragment of the chunk is asked for before the first product (one wave per SIMD: nobody else covers the
+      // LDS latency, and left alone the compiler reads two fragments ahead and waits for them)
+      bf16x8 af[CF];
 #pragma unroll
-      for (int kk = 0; kk < KF; ++kk) acc = mfma32(buf[kk * 64 + lane], in[kk], acc);
-      if (!kTwo) __syncthreads();  // one buffer: everyone is done with it before the next block is written
+      for (int kk = 0; kk < CF; ++kk) af[kk] = buf[kk * 64 + lane];
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[i] = fmaxf(acc[i], 0.f);
-      if (keep != nullptr) {
-        keep[cb] = acc;
-      } else {
-        out[2 * cb] = pack_half(acc, 0);
-        out[2 * cb + 1] = pack_half(acc, 1);
+      for (int kk = 0; kk < CF; ++kk) acc = mfma32(af[kk], in[part * CF + kk], acc);
+      __builtin_amdgcn_sched_barrier(0);
+      if (part == CH - 1) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = fmaxf(acc[i], 0.f);
+        if (keep != nullptr) {
+          keep[cb] = acc;
+        } else {
+          out[2 * cb] = pack_half(acc, 0);
+          out[2 * cb + 1] = pack_half(acc, 1);
+        }
       }
     }
   };

@@ -68,11 +68,13 @@ def test_interaction_mlp(dtype, rows, d, widths):
     assert_close(scores.double().cpu().numpy(), orc.interaction_mlp(O, Ws, [np.zeros_like(b) for b in bs]), dtype, "scores without biases")
 
 
-def _request(idx, B, N, C, d, h, m, dc, dhid, widths, dtype, len_range):
+def _request(idx, B, N, C, d, h, m, dc, dhid, widths, dtype, len_range, plain_norm=None):
     w = synth.make_workload(idx, B=B, N=N, C=C, d=d, h=h, m=m, dtype=dtype, gain=4.0, len_range=len_range,
                             pad_value=np.nan if len_range else None)
     p = synth.scoring_params(idx, B, m, d, dc, dhid, widths, dtype)
-    g = lambda x: dev(x, dtype)  # noqa: E731
+    if plain_norm is not None:  # this normalisation without scale and shift
+        p[plain_norm] = (None, None)
+    g = lambda x: None if x is None else dev(x, dtype)  # noqa: E731
     pair = lambda t: tuple(g(x) for x in t)  # noqa: E731
     keep = dict(L=g(w.L), ctx=pair(p["ctx"]), hist=pair(p["hist"]), cand=pair(p["cand"]),
                 mlp=([g(x) for x in p["mlp"][0]], [g(x) for x in p["mlp"][1]]),
@@ -114,6 +116,12 @@ def _request(idx, B, N, C, d, h, m, dc, dhid, widths, dtype, len_range):
 ])
 def test_lime_scores_small(B, N, C, d, h, m, dc, dhid, widths, dtype):
     _request(730 + d, B, N, C, d, h, m, dc, dhid, widths, dtype, (max(1, N // 3), N))
+
+
+def test_lime_scores_with_a_normalisation_without_parameters():
+    """Without scale and shift for one of the normalisations the request takes the separate normalisation passes (the
+    kernels that normalise on the way in fetch both unconditionally): same shape as the first case above."""
+    _request(731, 3, 333, 517, 128, 4, 64, 24, 96, [512, 128, 64, 1], "bf16", (111, 333), plain_norm="ln_cand_q")
 
 
 def test_lime_scores_config2_full_size():
