@@ -452,6 +452,7 @@ def curves(binding, synth, torch, dev, timed, pct):
     """The three curves the method is about (Section 4 "Inference Speed", Fig. 1, Appendix F), p50 of event-timed calls:
     latency against the number of candidates (one user, N = 2048: near-flat), the XORA history pass against the history
     length (8 users: linear), and LIME against full target attention on identical inputs (16 users, ragged)."""
+    import numpy as np
     res = {}
 
     def t(x):
@@ -463,12 +464,15 @@ def curves(binding, synth, torch, dev, timed, pct):
     E, L, Wq, Wk, Wv, T = t(w.E), t(w.L), t(w.Wq), t(w.Wk), t(w.Wv), t(w.T)
     s = w.softmax_scale
     LP = binding.lime_link_history(E, None, L, Wq, Wk, Wv, w.h, s)
+    wsc = torch.empty(binding.workspace_bytes(binding.OP_REQUEST, B=w.B, N=w.N, C=w.C, d=w.d, h=w.h, m=w.m), dtype=torch.uint8, device=dev)
     sweep = {}
     for C in [16 << i for i in range(12)]:
         Tc = T[:, :C].contiguous()
         O = torch.empty_like(Tc)
-        cand = pct(timed(lambda i: binding.lime_score_candidates(Tc, L, LP, Wq, Wk, Wv, w.h, s, O=O), 60), 0.5)
-        req = pct(timed(lambda i: binding.lime_request(E, None, L, Wq, Wk, Wv, Tc, L, Wq, Wk, Wv, w.h, s, s, LP=LP, O=O), 60), 0.5)
+        binding.lime_request(E, None, L, Wq, Wk, Wv, Tc, L, Wq, Wk, Wv, w.h, s, s, LP=LP, O=O, workspace=wsc)  # (untimed)
+        cand = pct(timed(lambda i: binding.lime_score_candidates(Tc, L, LP, Wq, Wk, Wv, w.h, s, O=O, workspace=wsc), 60), 0.5)
+        req = pct(timed(lambda i: binding.lime_request(E, None, L, Wq, Wk, Wv, Tc, L, Wq, Wk, Wv, w.h, s, s, LP=LP, O=O,
+                                                       workspace=wsc), 60), 0.5)
         sweep[C] = {"lime_score_candidates_p50_ms": cand, "lime_request_p50_ms": req}
     res["latency_vs_candidates"] = {"workload": "BASELINE.json configs[2]: B=1, N=2048, d=256, h=4, m=64, bf16 (warm buffers)",
                                     "points": sweep}
@@ -486,18 +490,51 @@ def curves(binding, synth, torch, dev, timed, pct):
     res["embeddings_to_scores_p50_ms"] = {"workload": "the headline request, C = 32768, as lime_scores; keyed by the hidden widths of the "
                                                       "interaction network", "points": sc}
     del E, T
-    # (b) history length: one XORA layer (link states only, and with O[S]), N = 2048 ... 16384
+    # (b) history length: one XORA layer (link states only, and with O[S]) and the softmax link attention of Eq. 3,
+    # N = 2048 ... 16384 as in the paper's sweep, and two longer histories that show the slope beside the floor of the
+    # three dependent launches
     c4 = dict(synth.CONFIGS[4])
     xs = {}
-    for N in (2048, 4096, 8192, 16384):
+    lib = binding.lib()
+    ptr = lambda x: ctypes.c_void_p(x.data_ptr())  # noqa: E731
+    cur = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def checked(fn, a):
+        if fn(*a):
+            raise RuntimeError(binding.last_error())
+
+    for N in (2048, 4096, 8192, 16384, 32768, 65536):
         c4["N"] = N
         w4 = synth.make_workload(4, **c4)
         E4, L4, q4, k4, v4 = t(w4.E), t(w4.L), t(w4.Wq), t(w4.Wk), t(w4.Wv)
-        lp = pct(timed(lambda i: binding.lime_xor_history(E4, None, L4, q4, k4, v4, w4.h, 1.0), 40), 0.5)
-        both = pct(timed(lambda i: binding.lime_xor_history(E4, None, L4, q4, k4, v4, w4.h, 1.0, want_os=True), 40), 0.5)
-        xs[N] = {"lime_xor_history_p50_ms": lp, "with_OS_p50_ms": both}
-        del E4
-    res["latency_vs_history_length"] = {"workload": "BASELINE.json configs[3]: B=8, d=128, h=4, m=64, bf16, XORA", "points": xs}
+        LP4, OS4 = torch.empty((w4.B, w4.m, w4.d), dtype=torch.bfloat16, device=dev), torch.empty_like(E4)
+        ws4 = torch.empty(max(binding.workspace_bytes(binding.OP_XOR_HISTORY, B=w4.B, N=N, d=w4.d, h=w4.h, m=w4.m, flags=1),
+                              binding.workspace_bytes(binding.OP_LINK_HISTORY, B=w4.B, N=N, d=w4.d, h=w4.h, m=w4.m)),
+                          dtype=torch.uint8, device=dev)
+        # arguments marshalled once, as in the serving loop: a wrapper's host time per call would otherwise set the
+        # short histories' figures
+        head = (ptr(E4), None, ptr(L4), 0, ptr(q4), ptr(k4), ptr(v4), ptr(LP4))
+        tail = (w4.B, N, w4.d, w4.h, w4.m)
+        end = (binding.LIME_BF16, ptr(ws4), ws4.numel(), cur)
+        xa = head + (None,) + tail + (1.0,) + end
+        xb = head + (ptr(OS4),) + tail + (1.0,) + end
+        la = head + tail + (w4.softmax_scale,) + end
+        for a3 in (xa, xb):
+            checked(lib.lime_xor_history, a3)
+        checked(lib.lime_link_history, la)
+        lp = pct(timed(lambda i: checked(lib.lime_xor_history, xa), 40), 0.5)
+        both = pct(timed(lambda i: checked(lib.lime_xor_history, xb), 40), 0.5)
+        soft = pct(timed(lambda i: checked(lib.lime_link_history, la), 40), 0.5)
+        xs[N] = {"lime_xor_history_p50_ms": lp, "with_OS_p50_ms": both, "lime_link_history_p50_ms": soft}
+        del E4, OS4, w4
+    ns = sorted(xs)
+    fits = {}
+    for key in ("lime_xor_history_p50_ms", "with_OS_p50_ms", "lime_link_history_p50_ms"):
+        slope, floor = np.polyfit(np.array(ns, dtype=np.float64) / 1024.0, np.array([xs[n][key] for n in ns]) * 1e3, 1)
+        fits[key] = {"us_per_1024_items": float(slope), "floor_us": float(floor)}
+    res["latency_vs_history_length"] = {"workload": "BASELINE.json configs[3]: B=8, d=128, h=4, m=64, bf16; XORA (Eq. 6-7) and "
+                                                    "softmax (Eq. 3); 32768 and 65536 are beyond the paper's sweep",
+                                        "points": xs, "least_squares_line": fits}
     # (c) LIME against full target attention on identical inputs
     c5 = dict(synth.CONFIGS[5])
     c5["pad_value"] = 0.0

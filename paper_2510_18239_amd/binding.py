@@ -193,9 +193,10 @@ def get_workspace(nbytes: int, device, stream=None) -> torch.Tensor:
     Calls on different streams may run at the same time, so they must not share scratch memory; calls on one
     stream are ordered and may.  A buffer that is outgrown is replaced by one at least twice its size and kept
     until the process ends (work already queued on the stream may still use it)."""
-    device = torch.device(device)
-    with torch.cuda.device(device):
-        key = (device, _stream(stream))
+    if not isinstance(device, torch.device):
+        device = torch.device(device)
+    # (this runs on every call of every wrapper: no device context, one stream query)
+    key = (device.index, stream.cuda_stream if stream is not None else torch.cuda.current_stream(device).cuda_stream)
     ws = _workspaces.get(key)
     if ws is None or ws.numel() < nbytes:
         if ws is not None:

@@ -405,13 +405,16 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
           qf[2 * mb] = pack_half(acc1[mb], 0);
           qf[2 * mb + 1] = pack_half(acc1[mb], 1);
         }
+        // (the link blocks' chains interleaved: products into one accumulator issue every 51 cycles, into two in
+        // turn every 37)
 #pragma unroll
-        for (int lb = 0; lb < LB; ++lb) {
+        for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) acc2[lb][i] = 0.f;
 #pragma unroll
-          for (int kk = 0; kk < K2; ++kk) acc2[lb] = mfma32(ka[kk][lb], qf[kk], acc2[lb]);
-        }
+        for (int kk = 0; kk < K2; ++kk)
+#pragma unroll
+          for (int lb = 0; lb < LB; ++lb) acc2[lb] = mfma32(ka[kk][lb], qf[kk], acc2[lb]);
       }
 
       float inv;
@@ -462,12 +465,13 @@ __global__ __launch_bounds__(64 * H) void queries_over_links_kernel(MainArgs a) 
       unsigned char* otile = os[head];
       f32x16 acc3[MB];
 #pragma unroll
-      for (int ob = 0; ob < MB; ++ob) {
+      for (int ob = 0; ob < MB; ++ob)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc3[ob][i] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < K3; ++kk) acc3[ob] = mfma32(va[kk][ob], pf[kk], acc3[ob]);
-      }
+      for (int kk = 0; kk < K3; ++kk)
+#pragma unroll
+        for (int ob = 0; ob < MB; ++ob) acc3[ob] = mfma32(va[kk][ob], pf[kk], acc3[ob]);
 #pragma unroll
       for (int ob = 0; ob < MB; ++ob) {
         bf16x8 lo, hi;
