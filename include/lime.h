@@ -275,7 +275,10 @@ int32_t lime_xor_backward(const void* QS, const void* KS, const void* VS, const 
  *   key and value side each with its own (gamma, beta) - and where keys and values are the same tensor (the history
  *   in Eq. 3) one normalisation serves both.  `model` is a HOST struct of device pointers and sizes; E[B][N][d], lens,
  *   EC[B][dc], T[B][C][d] as elsewhere.  Out: scores[B][C] fp32; LC, LP [B][m][d] and O [B][C][d] when not NULL.
- *   Workspace: lime_scores_workspace_bytes, 256-byte aligned (it holds the normalised copies of E and T).
+ *   Workspace: lime_scores_workspace_bytes, 256-byte aligned (sized for normalised copies of E and T).  For bf16 on the
+ *   shapes the matrix-core kernels take, with 16-byte aligned pointers and scale and shift given for every
+ *   normalisation, only E is normalised by a pass of its own: L^C, L, L^P and T are normalised inside the kernels that
+ *   read them, each rounded to bf16 where the separate pass would have stored it.
  */
 typedef struct lime_scoring_model {
   int32_t d, h, m, dc, dhid;  /* embedding width, heads, links, width of the context vector, hidden width of Eq. 2's MLP */
