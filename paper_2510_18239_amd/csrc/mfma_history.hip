@@ -59,6 +59,26 @@ __global__ __launch_bounds__(COOP ? 64 * H : 64) void links_over_history_kernel(
   if (i_begin >= len) return;  // uniform over the workgroup: nothing for this chunk
   const int i_end = min(len, i_begin + a.chunk_items);
 
+  const bf16_t* Eb = a.E + static_cast<int64_t>(b) * a.N * D;
+  // rows at or beyond the end of the chunk are replaced by zeros (their content is never used)
+  auto load_tile = [&](int i0, bf16x8 (&x)[K1]) {
+    const int item = i0 + n;
+    const bf16_t* xrow = Eb + static_cast<int64_t>(min(item, a.N - 1)) * D + 8 * g;
+#pragma unroll
+    for (int kk = 0; kk < K1; ++kk) {
+      bf16x8 v;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = static_cast<__bf16>(0.f);
+      if (item < i_end) v = *reinterpret_cast<const bf16x8*>(xrow + 16 * kk);
+      x[kk] = v;
+    }
+  };
+  // The first tile's rows come from HBM and are asked for ahead of the operands, which come from L2: behind them, as
+  // the loop's own order has it, their latency would begin only once the operands had arrived (the W_K^T slice is
+  // waited for on its way into LDS).
+  bf16x8 xnext[COOP ? 1 : K1];
+  if constexpr (!COOP) load_tile(i_begin, xnext);
+
   bf16x8* lds_wk = lds_wk_all + (COOP ? head * K1 * MB * 64 : 0);  // this wave's slice
   bf16x8 wk[WK_LDS ? 1 : K1][WK_LDS ? 1 : MB];
   if (WK_LDS) {
@@ -108,20 +128,6 @@ __global__ __launch_bounds__(COOP ? 64 * H : 64) void links_over_history_kernel(
       for (int i = 0; i < 16; ++i) acc[ob][lb][i] = 0.f;
   }
 
-  const bf16_t* Eb = a.E + static_cast<int64_t>(b) * a.N * D;
-  // rows at or beyond the end of the chunk are replaced by zeros (their content is never used)
-  auto load_tile = [&](int i0, bf16x8 (&x)[K1]) {
-    const int item = i0 + n;
-    const bf16_t* xrow = Eb + static_cast<int64_t>(min(item, a.N - 1)) * D + 8 * g;
-#pragma unroll
-    for (int kk = 0; kk < K1; ++kk) {
-      bf16x8 v;
-#pragma unroll
-      for (int t = 0; t < 8; ++t) v[t] = static_cast<__bf16>(0.f);
-      if (item < i_end) v = *reinterpret_cast<const bf16x8*>(xrow + 16 * kk);
-      x[kk] = v;
-    }
-  };
   // COOP: this wave's share of a tile (32 rows = 64 D contiguous bytes), 16 bytes per lane and load
   auto issue = [&](int i0, bf16x8 (&r)[LW]) {
 #pragma unroll
@@ -262,8 +268,6 @@ __global__ __launch_bounds__(COOP ? 64 * H : 64) void links_over_history_kernel(
       }
     }
   } else {
-    bf16x8 xnext[K1];
-    load_tile(i_begin, xnext);
     for (int i0 = i_begin; i0 < i_end; i0 += 32) {
       bf16x8 x[K1];
 #pragma unroll
