@@ -229,6 +229,30 @@ int32_t lime_request_static(const void* E, const int32_t* lens, const void* LC, 
 size_t lime_request_static_capacity(void);
 
 /*
+ * Several independent requests (Eq. 3-4 each, Section 3.3: requests of different users share nothing) handed over
+ * at once: request i is lime_request(requests[i]...) on streams[i % n_streams].  The requests of one stream are
+ * submitted in order by one host thread, those of different streams by different threads (the caller's own for
+ * stream 0, threads the library keeps for the others, created on first use and alive until the process ends): a
+ * request is four kernel launches, each a few microseconds of host time, and a burst handed over from one thread
+ * reaches the GPU that much later.  Every request needs a workspace and an LP of its own (requests in flight at the
+ * same time must not share them); the fields are lime_request's arguments with the same meaning, layouts and errors.
+ * Returns when everything is enqueued (it does not wait for the GPU); on an error the first failing request's status,
+ * with its message in lime_last_error of the calling thread; requests after it on its stream are not submitted, the
+ * others may be.  Calls from several threads at once are served one after the other.
+ */
+typedef struct lime_request_args {
+  const void* E; const int32_t* lens; const void* LC; int64_t lc_user_stride;
+  const void *Wq_hist, *Wk_hist, *Wv_hist;
+  const void *T, *L, *Wq_cand, *Wk_cand, *Wv_cand;
+  void *LP, *O;
+  int32_t B, N, C, d, h, m;
+  float scale_hist, scale_cand;
+  int32_t xor_attention, dtype;
+  void* workspace; size_t ws_bytes;
+} lime_request_args;
+int32_t lime_request_many(const lime_request_args* requests, int32_t n, void* const* streams, int32_t n_streams);
+
+/*
  * Backward pass of one XORA layer with respect to its projected inputs (Appendix H.2; forward: Appendix H.1, Eq. 7).
  * Per user b and head (d cut into h contiguous blocks), with S the history rows (lens[b] valid, lens NULL = all N),
  * T the m links and phi(x) = SiLU(scale x) / n:

@@ -52,6 +52,7 @@ SIGNATURES = {
     "lime_request_static": (_i32, [_vp, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32,
                                    _i32, _i32, _i32, _f32, _f32, _i32, _i32, _vp]),
     "lime_request_static_capacity": (_sz, []),
+    "lime_request_many": (_i32, [_vp, _i32, _vp, _i32]),
     "lime_xor_backward": (_i32, [_vp] * 15 + [_i32] * 5 + [_f32, _i32, _vp, _sz, _vp]),
     "lime_score_candidates_gathered": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _sz,
                                               _vp]),
@@ -474,6 +475,39 @@ def lime_request(E, lens, LC, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand,
                                 _stream(stream))
     _raise(st)
     return LP, O
+
+
+class RequestArgs(ctypes.Structure):
+    """lime_request_args of include/lime.h: the arguments of lime_request, one request of a batch."""
+    _fields_ = [("E", _vp), ("lens", _vp), ("LC", _vp), ("lc_user_stride", _i64), ("Wq_hist", _vp), ("Wk_hist", _vp),
+                ("Wv_hist", _vp), ("T", _vp), ("L", _vp), ("Wq_cand", _vp), ("Wk_cand", _vp), ("Wv_cand", _vp), ("LP", _vp),
+                ("O", _vp), ("B", _i32), ("N", _i32), ("C", _i32), ("d", _i32), ("h", _i32), ("m", _i32),
+                ("scale_hist", _f32), ("scale_cand", _f32), ("xor_attention", _i32), ("dtype", _i32), ("workspace", _vp),
+                ("ws_bytes", _sz)]
+
+
+def request_args(E, lens, LC, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand, Wv_cand, h, scale_hist, scale_cand, LP, O,
+                 workspace, xor_attention=False) -> RequestArgs:
+    """One entry of the array lime_request_many takes (shapes as lime_request; LP, O and workspace are required: requests
+    in flight at the same time must not share them).  The tensors must stay alive until the GPU has passed the request."""
+    first = _check(E, LC, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand, Wv_cand, LP, O)
+    B, N, d = E.shape
+    C = T.shape[1]
+    m, stride = (LC.shape[0], 0) if LC.dim() == 2 else (LC.shape[1], LC.shape[1] * LC.shape[2])
+    lens = _lens_arg(lens, B, E.device)
+    r = RequestArgs(_ptr(E), _ptr(lens), _ptr(LC), stride, _ptr(Wq_hist), _ptr(Wk_hist), _ptr(Wv_hist), _ptr(T), _ptr(L),
+                    _ptr(Wq_cand), _ptr(Wk_cand), _ptr(Wv_cand), _ptr(LP), _ptr(O), B, N, C, d, h, m, float(scale_hist),
+                    float(scale_cand), 1 if xor_attention else 0, _dtype_code(first), _ptr(workspace), workspace.numel())
+    r._keep = (lens,)
+    return r
+
+
+def lime_request_many(requests, streams) -> None:
+    """Submits the requests (a list of RequestArgs) over the streams (torch streams or raw handles), request i on
+    streams[i % len(streams)], from one host thread per stream; returns when everything is enqueued."""
+    arr = (RequestArgs * len(requests))(*requests)
+    handles = (_vp * len(streams))(*[s.cuda_stream if hasattr(s, "cuda_stream") else s for s in streams])
+    _raise(lib().lime_request_many(ctypes.cast(arr, _vp), len(requests), ctypes.cast(handles, _vp), len(streams)))
 
 
 def lime_request_static(E, lens, LC, Wq_hist, Wk_hist, Wv_hist, T, L, Wq_cand, Wk_cand, Wv_cand, h, scale_hist, scale_cand,

@@ -28,6 +28,14 @@ int32_t fail(int32_t status, const char* fmt, ...) {
   return status;
 }
 
+}  // namespace
+
+namespace lime {
+int32_t set_error(int32_t status, const char* text) { return fail(status, "%s", text); }
+}  // namespace lime
+
+namespace {
+
 #define LIME_HIP(expr)                                                                            \
   do {                                                                                            \
     hipError_t e_ = (expr);                                                                       \

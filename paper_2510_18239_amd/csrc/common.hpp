@@ -34,6 +34,8 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 // Compute units of the current device (256 when the query fails): what the launchers size their grids by.
 int compute_units();
+// Sets the calling thread's error text (what lime_last_error returns) and hands the status back.
+int32_t set_error(int32_t status, const char* text);
 
 // ----------------------------------------------------------------------------- per-kernel timing (profile.hip)
 enum ProfiledKernel { kKernelQueriesOverLinks = 0, kKernelLinksOverHistory = 1, kKernelTargetAttention = 2,
