@@ -7,7 +7,8 @@
  *   entry points never allocate, free, copy to the host or synchronise (the one
  *   exception is the benchmark's timing helper at the end of this file:
  *   lime_profile_enable makes launches create HIP events, lime_profile_collect
- *   waits for them).  `lens` is a device pointer too.  Outputs must not alias inputs.
+ *   waits for them; lime_request_many keeps a few host threads, no GPU resource).
+ *   `lens` is a device pointer too.  Outputs must not alias inputs.
  * Layout.  Row-major, innermost dimension contiguous, no padding between rows:
  *   E[B][N][d], T[B][C][d], L[m][d], LP[B][m][d], W[d_in][d_out] (so that the
  *   projection of Eq. 1 is X~ = X W).
