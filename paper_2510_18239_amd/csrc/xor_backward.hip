@@ -398,6 +398,407 @@ __global__ __launch_bounds__(256, (DH == 32 ? 2 : 1)) void xor_backward_side_mfm
   }
 }
 
+// Both sides in one pass (bf16 storage, d/h = 32, at most 32 MB links): the history rows, which are the bulk of the
+// operands, are read once, and phi, phi' - an exponential and a reciprocal per logit, the vector ALUs' share, which
+// sets the pace of the two-kernel form - are evaluated once per pair instead of once per side.
+// A workgroup of eight waves (two per SIMD: one wave's waits for LDS, memory and the matrix cores are the other's
+// time to issue) takes a chunk of the history of one (user, head); each wave walks its own 32-row tiles of it.  The
+// links' operands lie in LDS as fragment images, shared by the waves and read where they are used: in registers they
+// would leave no room for a second wave.  Per tile:
+//   1. its four tensors come straight from memory as operand fragments, asked for while the previous tile's last
+//      products run; Q[S], K[S], G[S] are also parked transposed in the wave's piece of LDS;
+//   2. per block of 32 links, one direction after the other: a logit tile and a <G, V> tile with the history rows as
+//      A operand and the links as B operand (lane = link t, registers = history rows s), phi and phi' register by
+//      register, rounded to bf16: p1, e1 (direction O[T]), then p2, e2 (direction O[S]);
+//   3. the links' gradients sum over the history rows, which those blocks hold in their registers: p2, e1, e2 are
+//      chained B operands as they stand (as in the kernel above), dV[T]^T += G[S]^T p2, dQ[T]^T += K[S]^T e1,
+//      dK[T]^T += Q[S]^T e2, accumulated over the wave's whole walk;
+//   4. the history rows' gradients sum over the links, the lane index of those blocks: p1, e1, e2 are parked in LDS
+//      ([history row][link], one bf16 at a time) and, after the last block of links, read back as B operands (lane =
+//      history row, eight links per lane) against the links' transposed operands: dV[S]^T += G[T]^T p1^T,
+//      dK[S]^T += Q[T]^T e1^T, dQ[S]^T += K[T]^T e2^T; stored through LDS as whole head slices of a few rows.
+// The constant factors (scale, 1/n_S, 1/m) are left out of the tiles and applied to the sums.  At the end the waves'
+// sums for the links meet in LDS pairwise in a fixed order; chunk sums as above.  The steps of a tile are fenced
+// against the instruction scheduler: moved into each other they need more registers than two waves per SIMD leave.
+typedef bf16x8 __attribute__((may_alias)) bf16x8_any;
+typedef unsigned short __attribute__((may_alias)) u16_any;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+struct FusedArgs {
+  const void *qs, *ks, *vs, *gs;  // [B][N][d]; gs nullable (no upstream gradient for O[S])
+  const void *qt, *kt, *vt, *gt;  // [B][m][d]
+  void *dqs, *dks, *dvs;          // [B][N][d]
+  void *dqt, *dkt, *dvt;          // [B][m][d]: written when chunks == 1
+  float* partial;                 // [B][chunks][3][m][d]: written when chunks > 1
+  const int32_t* lens;            // valid history rows per user, nullable = all
+  int N, m, d, chunks, chunk_rows;  // chunk_rows: history rows per chunk, a multiple of the workgroup's step
+  float scale;
+};
+constexpr int kFusedWaves = 8, kFusedStep = 32 * kFusedWaves;  // waves per workgroup; history rows per workgroup step
+template <int DH, int MB>
+constexpr size_t fused_lds_bytes() {
+  constexpr size_t wave = 2 * (3 * DH * 40 + 3 * 32 * 40), red = sizeof(float) * 3 * MB * (DH / 32) * 16 * 64;
+  constexpr size_t links = 7 * MB * (DH / 16) * 64 * 16;  // seven fragment images of the links' operands
+  return (kFusedWaves * wave > red ? kFusedWaves * wave : red) + links;
+}
+template <int DH, int MB>
+__global__ __launch_bounds__(64 * kFusedWaves, 1) void xor_backward_fused_kernel(FusedArgs a) {
+  constexpr int KS = DH / 16, TT = DH / 32;
+  constexpr int PITCH = 40;                 // transposed copy of a history tile: bf16 per row (8-byte reads)
+  constexpr int P2 = DH + 8, CPR = DH / 8;  // staged rows: bf16 per row; 16-byte pieces per row
+  constexpr int PP = 40;                    // parked p1, e1, e2: bf16 per history row (16-byte reads of 8 links)
+  constexpr int kCopy = 3 * DH * PITCH, kPark = 3 * 32 * PP;  // bf16 per wave
+  static_assert(kCopy >= kPark, "the last block's tiles are parked in the transposed copy's room");
+  static_assert(kCopy >= 32 * P2, "and a staged block of rows fits it");
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, wv = tid / 64, lane = tid % 64, n = lane % 32, g = lane / 32, d = a.d;
+  const int chunk = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
+  const int len = a.lens ? min(max(a.lens[b], 0), a.N) : a.N;
+  const float inv_ns = len > 0 ? 1.f / static_cast<float>(len) : 0.f, inv_m = 1.f / static_cast<float>(a.m);
+  const float minus_log2e_scale = -1.4426950408889634f * a.scale;
+  // the factors left out of p1 = SiLU(s1) / n_S, e1 (scale / n_S) and p2, e2 (1 / m, scale / m), by accumulator:
+  const float factor_s[3] = {a.scale * inv_ns, a.scale * inv_ns, a.scale * inv_m};  // dV[S] (p1), dK[S] (e1), dQ[S] (e2)
+  const float factor_t[3] = {a.scale * inv_m, a.scale * inv_ns, a.scale * inv_m};   // dV[T] (p2), dQ[T] (e1), dK[T] (e2)
+  bf16_any* yt = reinterpret_cast<bf16_any*>(smem) + wv * (kCopy + kPark);  // [3][DH][PITCH]: Q[S]^T, K[S]^T, G[S]^T
+  bf16_any* pk = yt + kCopy;                                                // [3][32][PP]: p1, e1, e2 of one block
+  bf16x8 zero;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) zero[t] = static_cast<__bf16>(0.f);
+  // A block of 32 links' rows (head slice), fetched row-contiguous (16 bytes per lane, DH/8 lanes per row) and staged
+  // in the wave's piece of LDS; rows at or past m are read from row m - 1 instead and staged as zeros: the loads
+  // themselves carry no condition.  (A uniform 64-bit base and a 32-bit offset per lane, here and below: addresses
+  // take few registers; the host checks that a user's slab stays below 4 GiB.)
+  auto stage_links = [&](const void* base, int lb) {
+    const char* slab = static_cast<const char*>(base) + (static_cast<int64_t>(b) * a.m * d + head * DH) * 2;
+    bf16x8 piece[KS];
+#pragma unroll
+    for (int i = 0; i < KS; ++i) {
+      const int idx = lane + 64 * i, row = min(32 * lb + idx / CPR, a.m - 1);
+      piece[i] = *reinterpret_cast<const bf16x8*>(slab + static_cast<uint32_t>(row * d + 8 * (idx % CPR)) * 2u);
+    }
+#pragma unroll
+    for (int i = 0; i < KS; ++i) {
+      const int idx = lane + 64 * i;
+      *reinterpret_cast<bf16x8_any*>(yt + (idx / CPR) * P2 + 8 * (idx % CPR)) = 32 * lb + idx / CPR >= a.m ? zero : piece[i];
+    }
+  };
+  // operand fragments of the staged block: lane (n, g) holds columns 16ks + 8g .. + 7 of row n
+  auto fragments = [&](bf16x8 (&fr)[KS]) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) fr[ks] = *reinterpret_cast<const bf16x8_any*>(yt + n * P2 + 16 * ks + 8 * g);
+  };
+  // and of its transpose: lane (n, g) holds rows 16kp + 8g .. + 7 of column 32tt + n
+  auto transposed = [&](bf16x8 (&fr)[2][TT]) {
+#pragma unroll
+    for (int kp = 0; kp < 2; ++kp)
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) fr[kp][tt][j] = yt[(16 * kp + 8 * g + j) * P2 + 32 * tt + n];
+  };
+  const int c_begin = chunk * a.chunk_rows, c_end = min(c_begin + a.chunk_rows, a.N);
+  // the wave's next tile of history rows: asked for one tile ahead
+  struct Rows { bf16x8 q[KS], k[KS], v[KS], g[KS]; };
+  Rows rows;
+  const int c_stop = min(c_end, len);  // tiles from here on hold padding only
+  // operand fragments straight from memory: lane (n, g) reads columns 16ks + 8g .. + 7 of row c0 + n (rows at or past
+  // len from row len - 1 instead; they count as zeros when used)
+  auto fetch_fragments = [&](const void* base, int c0, bf16x8 (&fr)[KS]) {
+    if (base == nullptr) return;
+    const char* slab = static_cast<const char*>(base) + (static_cast<int64_t>(b) * a.N * d + head * DH) * 2;
+    const int row = min(c0 + n, len - 1);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) fr[ks] = *reinterpret_cast<const bf16x8*>(slab + static_cast<uint32_t>(row * d + 16 * ks + 8 * g) * 2u);
+  };
+  auto ask = [&](int c0) {
+    if (c0 >= c_stop) return;
+    fetch_fragments(a.qs, c0, rows.q), fetch_fragments(a.ks, c0, rows.k), fetch_fragments(a.vs, c0, rows.v), fetch_fragments(a.gs, c0, rows.g);
+  };
+  // (the first tile's rows are on their way while the links' operands are prepared)
+  const int c_first = c_begin + 32 * wv;
+  ask(c_first);
+  // The links' operands, as fragment images in LDS shared by the waves (in registers they would not leave room
+  // for the sums): B operands of the dot products (kinds 0-3: q, k, v, g; index ks) and transposed A operands of the
+  // history rows' sums (kinds 4-6: q, k, g; index 2tt + kp).  Wave w prepares tensor w.
+  constexpr int KF = DH / 16;
+  bf16x8_any* links = reinterpret_cast<bf16x8_any*>(smem + fused_lds_bytes<DH, MB>() - 7 * MB * KF * 64 * 16);
+  auto link_fragment = [&](int kind, int lb, int k) -> bf16x8_any& { return links[((kind * MB + lb) * KF + k) * 64 + lane]; };
+  if (wv < 4) {
+    const void* src = wv == 0 ? a.qt : (wv == 1 ? a.kt : (wv == 2 ? a.vt : a.gt));
+#pragma unroll
+    for (int lb = 0; lb < MB; ++lb) {
+      bf16x8 fr[KS], tr[2][TT];
+      stage_links(src, lb), fragments(fr);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) link_fragment(wv, lb, ks) = fr[ks];
+      if (wv != 2) {
+        transposed(tr);
+#pragma unroll
+        for (int kp = 0; kp < 2; ++kp)
+#pragma unroll
+          for (int tt = 0; tt < TT; ++tt) link_fragment(wv == 3 ? 6 : 4 + wv, lb, 2 * tt + kp) = tr[kp][tt];
+      }
+    }
+  }
+  __syncthreads();
+  f32x16 acc_t[3][MB][TT];  // dV[T]^T, dQ[T]^T, dK[T]^T: lane = link 32lb + n, register 4j + rr = head column 32tt + 8j + 4g + rr
+#pragma unroll
+  for (int o = 0; o < 3; ++o)
+#pragma unroll
+    for (int lb = 0; lb < MB; ++lb)
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc_t[o][lb][tt][i] = 0.f;
+  // a tile's three gradients leave through the staged tile's room, so that a store instruction writes whole head
+  // slices of a few rows (16 bytes per lane)
+  bf16_t* outs[3] = {static_cast<bf16_t*>(a.dvs), static_cast<bf16_t*>(a.dks), static_cast<bf16_t*>(a.dqs)};
+  auto store_rows = [&](bf16_t* out, int c0) {
+#pragma unroll
+    for (int i = 0; i < 32 * CPR / 64; ++i) {
+      const int idx = lane + 64 * i, row = idx / CPR, piece = idx % CPR;
+      const bf16x8 v = *reinterpret_cast<const bf16x8_any*>(yt + row * P2 + 8 * piece);
+      char* slab = reinterpret_cast<char*>(out) + (static_cast<int64_t>(b) * a.N * d + head * DH) * 2;
+      if (c0 + row < a.N) *reinterpret_cast<bf16x8_any*>(slab + static_cast<uint32_t>((c0 + row) * d + 8 * piece) * 2u) = v;
+    }
+  };
+  for (int c0 = c_first; c0 < c_end; c0 += kFusedStep) {
+    if (c0 >= len) {
+      // padding only: zero gradients, nothing to read
+#pragma unroll
+      for (int i = 0; i < 32 * CPR / 64; ++i) *reinterpret_cast<bf16x8_any*>(yt + (lane + 64 * i) / CPR * P2 + 8 * ((lane + 64 * i) % CPR)) = zero;
+#pragma unroll
+      for (int o = 0; o < 3; ++o) store_rows(outs[o], c0);
+      continue;
+    }
+    bf16x8 yq[KS], yk[KS], yv[KS], yg[KS];
+    {
+      const bool valid = c0 + n < len;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        yq[ks] = valid ? rows.q[ks] : zero, yk[ks] = valid ? rows.k[ks] : zero, yv[ks] = valid ? rows.v[ks] : zero;
+        yg[ks] = (valid && a.gs != nullptr) ? rows.g[ks] : zero;
+      }
+    }
+    // the transposed copy: column 16ks + 8g + t of row c0 + n goes to [column][n]
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const int col = 16 * ks + 8 * g + t;
+        yt[(0 * DH + col) * PITCH + n] = yq[ks][t];
+        yt[(1 * DH + col) * PITCH + n] = yk[ks][t];
+        yt[(2 * DH + col) * PITCH + n] = yg[ks][t];
+      }
+    // Per block of links: the two directions, the links' sums, and p1, e1, e2 parked for the rows' sums, which come
+    // after the last block (their accumulators would not fit beside a block's tiles).  The last block's tiles are
+    // parked in the transposed copy's room, which its links' sums are the last to read; the one before in a room of
+    // its own.
+    u16_any* park_room[2] = {reinterpret_cast<u16_any*>(pk), reinterpret_cast<u16_any*>(yt)};
+#pragma unroll
+    for (int lb = 0; lb < MB; ++lb) {
+      // (the phases of a block are kept apart: moved into each other by the scheduler they need more registers than
+      // two waves per SIMD leave)
+      // Rounded to bf16 once, two registers to a word: a word's halves are what gets parked, four words are an
+      // operand of the links' sums.  (The words are opaque to the compiler, which would otherwise convert again for
+      // every 16-bit store.)
+      unsigned wp1[8], we1[8], wp2[8], we2[8];
+      auto round_pairs = [&](const f32x16& x, unsigned (&w)[8]) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          bf16x2 pair;
+          pair[0] = static_cast<__bf16>(x[2 * k]), pair[1] = static_cast<__bf16>(x[2 * k + 1]);
+          w[k] = __builtin_bit_cast(unsigned, pair);
+          asm volatile("" : "+v"(w[k]));
+        }
+      };
+      // One direction at a time: a logit tile z and a tile w of <G, V>, phi and phi' register by register up to the
+      // constant factors, which the sums take at their end: z becomes SiLU(s) / scale, w becomes w SiLU'(s).
+      auto direction = [&](const bf16x8 (&za)[KS], int zkind, const bf16x8 (&wa)[KS], int wkind, unsigned (&wp)[8], unsigned (&we)[8]) {
+        __builtin_amdgcn_sched_barrier(0);
+        f32x16 z, w;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) z[i] = w[i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          z = mfma32(za[ks], link_fragment(zkind, lb, ks), z);
+          w = mfma32(wa[ks], link_fragment(wkind, lb, ks), w);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float gg = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(z[i] * minus_log2e_scale));
+          z[i] *= gg;
+          w[i] *= fmaf(z[i] * (1.f - gg), a.scale, gg);  // SiLU'(s) = g + s g (1 - g)
+        }
+        round_pairs(z, wp), round_pairs(w, we);
+      };
+      direction(yk, 0, yv, 3, wp1, we1);  // <K[S]_s, Q[T]_t>, <V[S]_s, G[T]_t>: p1, e1
+      direction(yq, 1, yg, 2, wp2, we2);  // <Q[S]_s, K[T]_t>, <G[S]_s, V[T]_t>: p2, e2
+      __builtin_amdgcn_sched_barrier(0);
+      auto half_of = [&](const unsigned (&w)[8], int f) {
+        u32x4 v;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) v[t] = w[4 * f + t];
+        return __builtin_bit_cast(bf16x8, v);
+      };
+      // p1, e1, e2 parked as [history row][link]: registers 2k, 2k + 1 of lane (n, g) are rows 8 (k / 2) + 4g +
+      // 2 (k % 2) and the next, link n
+      auto park = [&](u16_any* room) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int row = 8 * (k / 2) + 4 * g + 2 * (k % 2);
+          room[(0 * 32 + row) * PP + n] = static_cast<unsigned short>(wp1[k]), room[(0 * 32 + row + 1) * PP + n] = static_cast<unsigned short>(wp1[k] >> 16);
+          room[(1 * 32 + row) * PP + n] = static_cast<unsigned short>(we1[k]), room[(1 * 32 + row + 1) * PP + n] = static_cast<unsigned short>(we1[k] >> 16);
+          room[(2 * 32 + row) * PP + n] = static_cast<unsigned short>(we2[k]), room[(2 * 32 + row + 1) * PP + n] = static_cast<unsigned short>(we2[k] >> 16);
+        }
+      };
+      if (lb < MB - 1) park(park_room[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      // the links' sums over this tile's rows
+#pragma unroll
+      for (int f = 0; f < 2; ++f) {
+        const bf16x8 bp2 = half_of(wp2, f), be1 = half_of(we1, f), be2 = half_of(we2, f);
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+          // slot t of lane (n, g): row c0 + 16f + chain_k(g, t) of the history, head column 32tt + n
+          auto chained = [&](int arr) {
+            const bf16_any* src = yt + (arr * DH + 32 * tt + n) * PITCH + 16 * f + 4 * g;
+            const bf16x4 lo = *reinterpret_cast<const bf16x4_any*>(src), hi = *reinterpret_cast<const bf16x4_any*>(src + 8);
+            bf16x8 v;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) v[t] = lo[t], v[4 + t] = hi[t];
+            return v;
+          };
+          acc_t[0][lb][tt] = mfma32(chained(2), bp2, acc_t[0][lb][tt]);  // dV[T]^T += G[S]^T p2
+          acc_t[1][lb][tt] = mfma32(chained(1), be1, acc_t[1][lb][tt]);  // dQ[T]^T += K[S]^T e1
+          acc_t[2][lb][tt] = mfma32(chained(0), be2, acc_t[2][lb][tt]);  // dK[T]^T += Q[S]^T e2
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (lb == MB - 1) park(park_room[1]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // (the next tile's rows are asked for here, every block's tiles and words used up: earlier there are no
+    // registers for them, and the workgroup's other waves have work while this one waits for them)
+    ask(c0 + kFusedStep);
+    __builtin_amdgcn_sched_barrier(0);
+    // the rows' sums over all links
+    f32x16 acc_s[3][TT];  // dV[S]^T, dK[S]^T, dQ[S]^T: lane = row c0 + n, register 4j + rr = head column 32tt + 8j + 4g + rr
+#pragma unroll
+    for (int o = 0; o < 3; ++o)
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc_s[o][tt][i] = 0.f;
+#pragma unroll
+    for (int lb = 0; lb < MB; ++lb)
+#pragma unroll
+      for (int kp = 0; kp < 2; ++kp) {
+        const bf16_any* room = reinterpret_cast<const bf16_any*>(park_room[lb == MB - 1 ? 1 : 0]);
+        const bf16x8 bp1 = *reinterpret_cast<const bf16x8_any*>(room + (0 * 32 + n) * PP + 16 * kp + 8 * g);
+        const bf16x8 bf1 = *reinterpret_cast<const bf16x8_any*>(room + (1 * 32 + n) * PP + 16 * kp + 8 * g);
+        const bf16x8 bf2 = *reinterpret_cast<const bf16x8_any*>(room + (2 * 32 + n) * PP + 16 * kp + 8 * g);
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+          acc_s[0][tt] = mfma32(link_fragment(6, lb, 2 * tt + kp), bp1, acc_s[0][tt]);  // dV[S]^T += G[T]^T p1^T
+          acc_s[1][tt] = mfma32(link_fragment(4, lb, 2 * tt + kp), bf1, acc_s[1][tt]);  // dK[S]^T += Q[T]^T e1^T
+          acc_s[2][tt] = mfma32(link_fragment(5, lb, 2 * tt + kp), bf2, acc_s[2][tt]);  // dQ[S]^T += K[T]^T e2^T
+        }
+        __builtin_amdgcn_sched_barrier(0);  // (a half's operands at a time)
+      }
+#pragma unroll
+    for (int o = 0; o < 3; ++o) {
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          bf16x4 v;
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) v[rr] = static_cast<__bf16>(acc_s[o][tt][4 * j + rr] * factor_s[o]);
+          *reinterpret_cast<bf16x4_any*>(yt + n * P2 + 32 * tt + 8 * j + 4 * g) = v;
+        }
+      store_rows(outs[o], c0);
+    }
+  }
+  // The waves' sums for the links meet in LDS, pairwise in a fixed order - (w, w + 4), then (w, w + 2), then (0, 1):
+  // the upper half of the waves still in play writes, the lower half adds.  Four registers (four adjacent head
+  // columns) to an LDS access.
+  constexpr int kRed = 3 * MB * TT * 16 * 64;  // floats: one wave's accumulators
+  static_assert(kFusedWaves / 2 * sizeof(float) * kRed <= kFusedWaves * 2 * (kCopy + kPark), "the slots fit the waves' own pieces");
+  typedef float4 __attribute__((may_alias)) float4_any;
+  float* red = reinterpret_cast<float*>(smem);
+  auto slot_of = [&](int slot, int o, int lb, int tt, int j) {
+    return reinterpret_cast<float4_any*>(red + slot * kRed) + (((o * MB + lb) * TT + tt) * 4 + j) * 64 + lane;
+  };
+  for (int half = kFusedWaves / 2; half >= 1; half /= 2) {
+    __syncthreads();  // (the first one also ends every wave's use of its own piece; later ones the reads of a round)
+    if (wv >= half && wv < 2 * half) {
+#pragma unroll
+      for (int o = 0; o < 3; ++o)
+#pragma unroll
+        for (int lb = 0; lb < MB; ++lb)
+#pragma unroll
+          for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const f32x16& x = acc_t[o][lb][tt];
+              *slot_of(wv - half, o, lb, tt, j) = make_float4(x[4 * j], x[4 * j + 1], x[4 * j + 2], x[4 * j + 3]);
+            }
+    }
+    __syncthreads();
+    if (wv < half) {
+#pragma unroll
+      for (int o = 0; o < 3; ++o)
+#pragma unroll
+        for (int lb = 0; lb < MB; ++lb)
+#pragma unroll
+          for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const float4 y = *slot_of(wv, o, lb, tt, j);
+              f32x16& x = acc_t[o][lb][tt];
+              x[4 * j] += y.x, x[4 * j + 1] += y.y, x[4 * j + 2] += y.z, x[4 * j + 3] += y.w;
+            }
+    }
+  }
+  // Wave 0 holds the sums: laid out row-major in LDS ([output][link][head column], rows padded by four floats), so
+  // that the workgroup stores whole head slices of a link's row, 16 bytes per lane.
+  constexpr int RP = DH + 4;  // floats per row
+  static_assert(3 * MB * 32 * RP <= kFusedWaves / 2 * kRed, "the row-major copy fits the slots");
+  __syncthreads();
+  if (wv == 0) {
+#pragma unroll
+    for (int o = 0; o < 3; ++o)
+#pragma unroll
+      for (int lb = 0; lb < MB; ++lb)
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const f32x16& x = acc_t[o][lb][tt];
+            // lane (n, g): link 32lb + n, head columns 32tt + 8j + 4g .. + 3
+            *reinterpret_cast<float4_any*>(red + ((o * MB + lb) * 32 + n) * RP + 32 * tt + 8 * j + 4 * g) =
+                make_float4(x[4 * j] * factor_t[o], x[4 * j + 1] * factor_t[o], x[4 * j + 2] * factor_t[o], x[4 * j + 3] * factor_t[o]);
+          }
+  }
+  __syncthreads();
+  const int64_t plane = static_cast<int64_t>(a.m) * d;
+  constexpr int kQuads = 3 * MB * 32 * (DH / 4);  // 16-byte pieces of the three outputs
+  for (int e = tid; e < kQuads; e += 64 * kFusedWaves) {
+    const int quad = e % (DH / 4), row = (e / (DH / 4)) % (32 * MB), o = e / (DH / 4 * 32 * MB);
+    if (row >= a.m) continue;
+    const float4 v = *reinterpret_cast<const float4_any*>(red + (o * MB * 32 + row) * RP + 4 * quad);
+    const int which = o == 0 ? 2 : (o == 1 ? 0 : 1);  // accumulators are (dV, dQ, dK); outputs are ordered (dQ, dK, dV)
+    const int64_t at = (static_cast<int64_t>(b) * a.m + row) * d + head * DH + 4 * quad;
+    if (a.chunks == 1) {
+      bf16_t* out = static_cast<bf16_t*>(which == 0 ? a.dqt : (which == 1 ? a.dkt : a.dvt)) + at;
+      store_as(out, v.x), store_as(out + 1, v.y), store_as(out + 2, v.z), store_as(out + 3, v.w);
+    } else {
+      *reinterpret_cast<float4*>(a.partial + ((static_cast<int64_t>(b) * a.chunks + chunk) * 3 + which) * plane +
+                                 static_cast<int64_t>(row) * d + head * DH + 4 * quad) = v;
+    }
+  }
+}
+
 // out[b][which][row][col] = sum over the chunks, in ascending order
 template <typename T>
 __global__ __launch_bounds__(256) void xor_backward_reduce_kernel(const float* partial, T* dq, T* dk, T* dv, int chunks,
@@ -442,6 +843,51 @@ hipError_t launch_side(const SideArgs& a, dim3 grid, bool on_mfma, bool own_per_
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// The one-pass form: d/h = 32 and at most 64 links (the links' operands and sums must fit a wave's registers).
+constexpr int kFusedLinks = 64;
+bool fused_shape(int N, int m, int d, int dh) {
+  return dh == 32 && m <= kFusedLinks && static_cast<int64_t>(N) * d * 2 < (int64_t{1} << 32);  // (32-bit offsets within a user)
+}
+int chunks_for_fused(int B, int N, int h) {
+  // one workgroup per compute unit (a wave per SIMD), but no chunk shorter than one step
+  const int64_t per_chunk = static_cast<int64_t>(h) * B;
+  const int64_t steps = (N + kFusedStep - 1) / kFusedStep;
+  int64_t chunks = std::min<int64_t>(steps, (compute_units() + per_chunk - 1) / per_chunk);
+  if (chunks < 1) chunks = 1;
+  const int64_t steps_per_chunk = (steps + chunks - 1) / chunks;
+  return static_cast<int>((steps + steps_per_chunk - 1) / steps_per_chunk);  // no empty chunk
+}
+
+template <int DH, int MB>
+hipError_t launch_fused(const FusedArgs& a, dim3 grid, hipStream_t s) {
+  auto kernel = xor_backward_fused_kernel<DH, MB>;
+  constexpr size_t lds = fused_lds_bytes<DH, MB>();
+  static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+  if (attr != hipSuccess) return attr;
+  hipLaunchKernelGGL(kernel, grid, dim3(64 * kFusedWaves), lds, s, a);
+  return hipGetLastError();
+}
+
+hipError_t xor_backward_fused(const XorBackward& g, void* workspace, hipStream_t s) {
+  FusedArgs a{};
+  a.qs = g.QS, a.ks = g.KS, a.vs = g.VS, a.gs = g.dOS, a.qt = g.QT, a.kt = g.KT, a.vt = g.VT, a.gt = g.dOT;
+  a.dqs = g.dQS, a.dks = g.dKS, a.dvs = g.dVS, a.dqt = g.dQT, a.dkt = g.dKT, a.dvt = g.dVT;
+  a.partial = static_cast<float*>(workspace), a.lens = g.lens;
+  a.N = g.N, a.m = g.m, a.d = g.d, a.scale = g.scale;
+  a.chunks = chunks_for_fused(g.B, g.N, g.h);
+  const int steps = (g.N + kFusedStep - 1) / kFusedStep;
+  a.chunk_rows = (steps + a.chunks - 1) / a.chunks * kFusedStep;
+  const dim3 grid(a.chunks, g.h, g.B);
+  hipError_t e = g.m <= 32 ? launch_fused<32, 1>(a, grid, s) : launch_fused<32, 2>(a, grid, s);
+  if (e != hipSuccess || a.chunks == 1) return e;
+  const int64_t plane = static_cast<int64_t>(g.m) * g.d;
+  hipLaunchKernelGGL(xor_backward_reduce_kernel<bf16_t>, dim3(static_cast<unsigned>((plane + 255) / 256), 3, g.B), dim3(256), 0, s,
+                     static_cast<const float*>(workspace), static_cast<bf16_t*>(g.dQT), static_cast<bf16_t*>(g.dKT),
+                     static_cast<bf16_t*>(g.dVT), a.chunks, plane);
+  return hipGetLastError();
+}
+
 template <typename T>
 hipError_t xor_backward_typed(const XorBackward& g, void* workspace, hipStream_t s) {
   SideArgs a{};
@@ -450,6 +896,7 @@ hipError_t xor_backward_typed(const XorBackward& g, void* workspace, hipStream_t
   bool on_mfma = g.dtype == 1 && (a.dh == 32 || a.dh == 64);
   for (const void* p : {g.QS, g.KS, g.VS, g.QT, g.KT, g.VT, g.dOT, g.dOS}) on_mfma = on_mfma && aligned16(p);
   for (const void* p : {g.dQS, g.dKS, g.dVS}) on_mfma = on_mfma && aligned16(p);  // (stored 16 bytes at a time)
+  if (on_mfma && fused_shape(g.N, g.m, g.d, a.dh)) return xor_backward_fused(g, workspace, s);
   const int step = step_rows(a.dh, on_mfma);
   // history side: every block of 32 history rows against all links
   a.qx = g.QS, a.kx = g.KS, a.vx = g.VS, a.gx = g.dOS;
@@ -485,8 +932,9 @@ bool xor_backward_supported(int d, int h) { return h > 0 && d % h == 0 && d / h 
 
 size_t xor_backward_workspace(int B, int N, int m, int d, int h) {
   // large enough for either kernel (a bf16 call whose pointers are not 16-byte aligned runs on the vector ALUs)
-  const int chunks = std::max(chunks_for_links(B, N, m, h, step_rows(d / h, false)),
-                              chunks_for_links(B, N, m, h, step_rows(d / h, true)));
+  int chunks = std::max(chunks_for_links(B, N, m, h, step_rows(d / h, false)),
+                        chunks_for_links(B, N, m, h, step_rows(d / h, true)));
+  if (fused_shape(N, m, d, d / h)) chunks = std::max(chunks, chunks_for_fused(B, N, h));
   return chunks == 1 ? 256 : align_up(static_cast<size_t>(B) * chunks * 3 * m * d * sizeof(float));
 }
 

@@ -32,6 +32,9 @@ def _run(t, h, scale, dtype, with_dos=True):
     (3, 700, 64, 128, 4, "bf16", 1.0),      # many chunks
     (2, 333, 128, 256, 4, "bf16", 0.7),     # d/h = 64, the widest head
     (2, 50, 40, 128, 4, "bf16", 1.0),       # matrix-core form with m and N that fill no tile
+    (2, 300, 32, 128, 4, "bf16", 1.0),      # one block of links
+    (3, 1000, 17, 64, 2, "bf16", 0.8),      # one ragged block of links, chunks of several tiles per wave
+    (2, 600, 96, 128, 4, "bf16", 1.0),      # more links than the one-pass form holds: the two-kernel form
     (2, 200, 64, 64, 4, "bf16", 1.0),       # bf16 with d/h = 16: the fp32-arithmetic kernel on bf16 storage
     (1, 65, 5, 24, 1, "fp32", 1.0),         # m and d/h far from any tile size
     (2, 47, 37, 40, 5, "fp32", -0.5),       # d/h = 8, negative scale
