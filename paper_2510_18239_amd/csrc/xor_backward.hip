@@ -436,17 +436,17 @@ struct FusedArgs {
 constexpr int kFusedWaves = 8, kFusedStep = 32 * kFusedWaves;  // waves per workgroup; history rows per workgroup step
 template <int DH, int MB>
 constexpr size_t fused_lds_bytes() {
-  constexpr size_t wave = 2 * (3 * DH * 40 + 3 * 32 * 40), red = sizeof(float) * 3 * MB * (DH / 32) * 16 * 64;
+  constexpr size_t copy = 3 * DH * 36 > 3 * 32 * 40 ? 3 * DH * 36 : 3 * 32 * 40, wave = 2 * (copy + 3 * 32 * 40), red = sizeof(float) * 3 * MB * (DH / 32) * 16 * 64;
   constexpr size_t links = 7 * MB * (DH / 16) * 64 * 16;  // seven fragment images of the links' operands
   return (kFusedWaves * wave > red ? kFusedWaves * wave : red) + links;
 }
 template <int DH, int MB>
 __global__ __launch_bounds__(64 * kFusedWaves, 1) void xor_backward_fused_kernel(FusedArgs a) {
   constexpr int KS = DH / 16, TT = DH / 32;
-  constexpr int PITCH = 40;                 // transposed copy of a history tile: bf16 per row (8-byte reads)
+  constexpr int PITCH = 36;                 // transposed copy of a history tile: bf16 per row (8-byte reads, no bank conflicts)
   constexpr int P2 = DH + 8, CPR = DH / 8;  // staged rows: bf16 per row; 16-byte pieces per row
   constexpr int PP = 40;                    // parked p1, e1, e2: bf16 per history row (16-byte reads of 8 links)
-  constexpr int kCopy = 3 * DH * PITCH, kPark = 3 * 32 * PP;  // bf16 per wave
+  constexpr int kPark = 3 * 32 * PP, kCopy = 3 * DH * PITCH > kPark ? 3 * DH * PITCH : kPark;  // bf16 per wave: two rooms
   static_assert(kCopy >= kPark, "the last block's tiles are parked in the transposed copy's room");
   static_assert(kCopy >= 32 * P2, "and a staged block of rows fits it");
   extern __shared__ __align__(16) unsigned char smem[];
