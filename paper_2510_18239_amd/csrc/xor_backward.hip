@@ -398,13 +398,14 @@ __global__ __launch_bounds__(256, (DH == 32 ? 2 : 1)) void xor_backward_side_mfm
   }
 }
 
-// Both sides in one pass (bf16 storage, d/h = 32, at most 32 MB links): the history rows, which are the bulk of the
+// Both sides in one pass (bf16 storage, d/h = 32 or 64, at most 32 MB links): the history rows, which are the bulk of the
 // operands, are read once, and phi, phi' - an exponential and a reciprocal per logit, the vector ALUs' share, which
 // sets the pace of the two-kernel form - are evaluated once per pair instead of once per side.
-// A workgroup of eight waves (two per SIMD: one wave's waits for LDS, memory and the matrix cores are the other's
-// time to issue) takes a chunk of the history of one (user, head); each wave walks its own 32-row tiles of it.  The
-// links' operands lie in LDS as fragment images, shared by the waves and read where they are used: in registers they
-// would leave no room for a second wave.  Per tile:
+// A workgroup of eight waves at d/h = 32 (two per SIMD: one wave's waits for LDS, memory and the matrix cores are the
+// other's time to issue; at d/h = 64 the sums alone are 192 registers and a workgroup is four waves) takes a chunk
+// of the history of one (user, head); each wave walks its own 32-row tiles of it.  The links' operands lie in LDS as
+// fragment images, shared by the waves and read where they are used: in registers they would leave no room for a
+// second wave.  Per tile:
 //   1. its four tensors come straight from memory as operand fragments, asked for while the previous tile's last
 //      products run; Q[S], K[S], G[S] are also parked transposed in the wave's piece of LDS;
 //   2. per block of 32 links, one direction after the other: a logit tile and a <G, V> tile with the history rows as
@@ -433,16 +434,18 @@ struct FusedArgs {
   int N, m, d, chunks, chunk_rows;  // chunk_rows: history rows per chunk, a multiple of the workgroup's step
   float scale;
 };
-constexpr int kFusedWaves = 8, kFusedStep = 32 * kFusedWaves;  // waves per workgroup; history rows per workgroup step
+// waves per workgroup: two per SIMD where a wave fits 256 registers (d/h = 32), one where it does not (d/h = 64)
+constexpr int fused_waves(int dh) { return dh == 32 ? 8 : 4; }
 template <int DH, int MB>
 constexpr size_t fused_lds_bytes() {
   constexpr size_t copy = 3 * DH * 36 > 3 * 32 * 40 ? 3 * DH * 36 : 3 * 32 * 40, wave = 2 * (copy + 3 * 32 * 40), red = sizeof(float) * 3 * MB * (DH / 32) * 16 * 64;
   constexpr size_t links = 7 * MB * (DH / 16) * 64 * 16;  // seven fragment images of the links' operands
-  return (kFusedWaves * wave > red ? kFusedWaves * wave : red) + links;
+  return (fused_waves(DH) * wave > red ? fused_waves(DH) * wave : red) + links;
 }
 template <int DH, int MB>
-__global__ __launch_bounds__(64 * kFusedWaves, 1) void xor_backward_fused_kernel(FusedArgs a) {
+__global__ __launch_bounds__(64 * fused_waves(DH), 1) void xor_backward_fused_kernel(FusedArgs a) {
   constexpr int KS = DH / 16, TT = DH / 32;
+  constexpr int kFusedWaves = fused_waves(DH), kFusedStep = 32 * kFusedWaves;  // history rows per workgroup step
   constexpr int PITCH = 36;                 // transposed copy of a history tile: bf16 per row (8-byte reads, no bank conflicts)
   constexpr int P2 = DH + 8, CPR = DH / 8;  // staged rows: bf16 per row; 16-byte pieces per row
   constexpr int PP = 40;                    // parked p1, e1, e2: bf16 per history row (16-byte reads of 8 links)
@@ -723,14 +726,14 @@ __global__ __launch_bounds__(64 * kFusedWaves, 1) void xor_backward_fused_kernel
   // the upper half of the waves still in play writes, the lower half adds.  Four registers (four adjacent head
   // columns) to an LDS access.
   constexpr int kRed = 3 * MB * TT * 16 * 64;  // floats: one wave's accumulators
-  static_assert(kFusedWaves / 2 * sizeof(float) * kRed <= kFusedWaves * 2 * (kCopy + kPark), "the slots fit the waves' own pieces");
+  static_assert(kFusedWaves / 2 * sizeof(float) * kRed <= fused_lds_bytes<DH, MB>(), "the slots fit the workgroup's LDS (all of it is free by now)");
   typedef float4 __attribute__((may_alias)) float4_any;
   float* red = reinterpret_cast<float*>(smem);
   auto slot_of = [&](int slot, int o, int lb, int tt, int j) {
     return reinterpret_cast<float4_any*>(red + slot * kRed) + (((o * MB + lb) * TT + tt) * 4 + j) * 64 + lane;
   };
   for (int half = kFusedWaves / 2; half >= 1; half /= 2) {
-    __syncthreads();  // (the first one also ends every wave's use of its own piece; later ones the reads of a round)
+    __syncthreads();  // (the first one also ends every wave's use of its own piece and of the links' images; later ones the reads of a round)
     if (wv >= half && wv < 2 * half) {
 #pragma unroll
       for (int o = 0; o < 3; ++o)
@@ -843,12 +846,13 @@ hipError_t launch_side(const SideArgs& a, dim3 grid, bool on_mfma, bool own_per_
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// The one-pass form: d/h = 32 and at most 64 links (the links' operands and sums must fit a wave's registers).
+// The one-pass form: d/h = 32 or 64 and at most 64 links (the links' sums must fit a wave's registers).
 constexpr int kFusedLinks = 64;
 bool fused_shape(int N, int m, int d, int dh) {
-  return dh == 32 && m <= kFusedLinks && static_cast<int64_t>(N) * d * 2 < (int64_t{1} << 32);  // (32-bit offsets within a user)
+  return (dh == 32 || dh == 64) && m <= kFusedLinks && static_cast<int64_t>(N) * d * 2 < (int64_t{1} << 32);  // (32-bit offsets within a user)
 }
-int chunks_for_fused(int B, int N, int h) {
+int chunks_for_fused(int B, int N, int h, int dh) {
+  const int kFusedStep = 32 * fused_waves(dh);
   // one workgroup per compute unit (a wave per SIMD), but no chunk shorter than one step
   const int64_t per_chunk = static_cast<int64_t>(h) * B;
   const int64_t steps = (N + kFusedStep - 1) / kFusedStep;
@@ -865,7 +869,7 @@ hipError_t launch_fused(const FusedArgs& a, dim3 grid, hipStream_t s) {
   static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
   if (attr != hipSuccess) return attr;
-  hipLaunchKernelGGL(kernel, grid, dim3(64 * kFusedWaves), lds, s, a);
+  hipLaunchKernelGGL(kernel, grid, dim3(64 * fused_waves(DH)), lds, s, a);
   return hipGetLastError();
 }
 
@@ -875,11 +879,13 @@ hipError_t xor_backward_fused(const XorBackward& g, void* workspace, hipStream_t
   a.dqs = g.dQS, a.dks = g.dKS, a.dvs = g.dVS, a.dqt = g.dQT, a.dkt = g.dKT, a.dvt = g.dVT;
   a.partial = static_cast<float*>(workspace), a.lens = g.lens;
   a.N = g.N, a.m = g.m, a.d = g.d, a.scale = g.scale;
-  a.chunks = chunks_for_fused(g.B, g.N, g.h);
+  const int dh = g.d / g.h, kFusedStep = 32 * fused_waves(dh);
+  a.chunks = chunks_for_fused(g.B, g.N, g.h, dh);
   const int steps = (g.N + kFusedStep - 1) / kFusedStep;
   a.chunk_rows = (steps + a.chunks - 1) / a.chunks * kFusedStep;
   const dim3 grid(a.chunks, g.h, g.B);
-  hipError_t e = g.m <= 32 ? launch_fused<32, 1>(a, grid, s) : launch_fused<32, 2>(a, grid, s);
+  hipError_t e = dh == 32 ? (g.m <= 32 ? launch_fused<32, 1>(a, grid, s) : launch_fused<32, 2>(a, grid, s))
+                          : (g.m <= 32 ? launch_fused<64, 1>(a, grid, s) : launch_fused<64, 2>(a, grid, s));
   if (e != hipSuccess || a.chunks == 1) return e;
   const int64_t plane = static_cast<int64_t>(g.m) * g.d;
   hipLaunchKernelGGL(xor_backward_reduce_kernel<bf16_t>, dim3(static_cast<unsigned>((plane + 255) / 256), 3, g.B), dim3(256), 0, s,
@@ -934,7 +940,7 @@ size_t xor_backward_workspace(int B, int N, int m, int d, int h) {
   // large enough for either kernel (a bf16 call whose pointers are not 16-byte aligned runs on the vector ALUs)
   int chunks = std::max(chunks_for_links(B, N, m, h, step_rows(d / h, false)),
                         chunks_for_links(B, N, m, h, step_rows(d / h, true)));
-  if (fused_shape(N, m, d, d / h)) chunks = std::max(chunks, chunks_for_fused(B, N, h));
+  if (fused_shape(N, m, d, d / h)) chunks = std::max(chunks, chunks_for_fused(B, N, h, d / h));
   return chunks == 1 ? 256 : align_up(static_cast<size_t>(B) * chunks * 3 * m * d * sizeof(float));
 }
 

@@ -30,7 +30,9 @@ def _run(t, h, scale, dtype, with_dos=True):
 @pytest.mark.parametrize("B,N,m,d,h,dtype,scale", [
     (2, 100, 64, 128, 4, "bf16", 1.0),      # matrix-core form (bf16, d/h = 32), ragged tail in N
     (3, 700, 64, 128, 4, "bf16", 1.0),      # many chunks
-    (2, 333, 128, 256, 4, "bf16", 0.7),     # d/h = 64, the widest head
+    (2, 333, 128, 256, 4, "bf16", 0.7),     # d/h = 64, the widest head; 128 links: the two-kernel form
+    (2, 333, 64, 256, 4, "bf16", 0.7),      # d/h = 64 in one pass, two blocks of links
+    (3, 700, 24, 128, 2, "bf16", 1.0),      # d/h = 64 in one pass, one ragged block of links
     (2, 50, 40, 128, 4, "bf16", 1.0),       # matrix-core form with m and N that fill no tile
     (2, 300, 32, 128, 4, "bf16", 1.0),      # one block of links
     (3, 1000, 17, 64, 2, "bf16", 0.8),      # one ragged block of links, chunks of several tiles per wave
