@@ -86,3 +86,29 @@ def test_xor_backward_at_benchmark_size_is_deterministic():
     again, _ = _run(t, 4, 1.0, "bf16")
     for x, y in zip(got, again):
         np.testing.assert_array_equal(x, y)
+
+
+def test_xor_backward_random_shapes():
+    """Thirty seeded random shapes of the bf16 forms (d/h = 32 or 64, 1 .. 129 links, histories of up to 2600 rows, full
+    or ragged with NaN padding, now and then an empty user, with and without dOS, four scales): every gradient against
+    the oracle, padded rows exactly zero.  Both the one-pass form (up to 64 links) and the two-kernel form are drawn."""
+    rng = np.random.default_rng(12345)
+    for case in range(30):
+        dh, h = int(rng.choice([32, 64])), int(rng.choice([1, 2, 4]))
+        m, N, B = int(rng.integers(1, 130)), int(rng.integers(1, 2600)), int(rng.integers(1, 5))
+        scale, with_dos, ragged = float(rng.choice([1.0, 0.7, -0.5, 1.3])), bool(rng.integers(0, 4) > 0), bool(rng.integers(0, 3) > 0)
+        kw = dict(len_range=(1, N), pad_value=np.nan) if ragged else {}
+        t = synth.backward_inputs(1000 + case, B, N, m, dh * h, h, "bf16", **kw, **SIZED)
+        if ragged and B >= 2 and case % 5 == 0:
+            t["lens"][B - 1] = 0
+            for k in ("QS", "KS", "VS", "dOS"):
+                t[k][B - 1] = np.nan
+        print(f"case {case}: B={B} N={N} m={m} d={dh * h} h={h} scale={scale} dOS={with_dos} "
+              f"lens={None if t['lens'] is None else t['lens'].tolist()}", flush=True)
+        got, ref = _run(t, h, scale, "bf16", with_dos=with_dos)
+        for name, x, r in zip(NAMES, got, ref):
+            assert_close(x, r, "bf16", f"case {case} {name}")
+        if t["lens"] is not None:
+            for name, x in zip(NAMES[:3], got[:3]):
+                for b in range(B):
+                    assert not x[b, t["lens"][b]:].any(), f"case {case} {name}: padded rows of user {b} must get zero gradients"
