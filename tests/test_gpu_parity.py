@@ -603,3 +603,25 @@ def test_xor_layers(B, N, d, h, m, n_layers, per_user):
         Lb = LC if LC.ndim == 3 else np.broadcast_to(LC, (B,) + LC.shape)
         want = np.stack([orc.gated_mlp(host(OT)[b], Lb[b], Wu[0], Wo[0]) for b in range(B)])
         assert_close(host(LP), want, "bf16", "one layer on the GPU's own O[T]")
+
+
+def test_random_shapes_all_paths():
+    """Thirty seeded random shapes through every forward entry point (both storage types; d/h = 32 / 64 on the matrix
+    cores and 8 .. 48 on the general kernels; 1 .. 129 links; histories and candidate lists of up to 1500 rows; full or
+    ragged with NaN padding), half of them from the benchmark distribution, half with sharp logits."""
+    rng = np.random.default_rng(777)
+    for case in range(30):
+        dtype = "bf16" if rng.integers(0, 4) > 0 else "fp32"
+        dh = int(rng.choice([32, 64])) if dtype == "bf16" and rng.integers(0, 5) > 0 else int(rng.choice([8, 16, 24, 48]))
+        h = int(rng.choice([1, 2, 4]))
+        m = int(rng.choice([32, 64, 96, 128])) if rng.integers(0, 3) > 0 else int(rng.integers(1, 130))
+        N, C, B = int(rng.integers(8, 1500)), int(rng.integers(1, 1500)), int(rng.integers(1, 4))
+        kw = dict(len_range=(8, N), pad_value=np.nan) if rng.integers(0, 3) > 0 else {}
+        if case % 2:
+            w = _sharp(workload=5000 + case, B=B, N=N, C=C, d=dh * h, h=h, m=m, dtype=dtype, **kw)
+        else:
+            w = synth.make_workload(5000 + case, B=B, N=N, C=C, d=dh * h, h=h, m=m, dtype=dtype, value_gain=0.25, **kw)
+        print(f"case {case}: {dtype} B={B} N={N} C={C} d={dh * h} h={h} m={m} gain={w.meta['gain']:.2f} "
+              f"lens={None if w.lens is None else w.lens.tolist()}", flush=True)
+        for name, (got, ref) in run_all_paths(w, xor_scale=w.softmax_scale if case % 2 else 1.0).items():
+            assert_close(got, ref, dtype, f"case {case} {name}")
