@@ -751,7 +751,7 @@ def extras(binding, synth, torch, dev, timed, pct):
     res["lime_xor_layers_n3_vs_N"] = layers
     # The backward pass of one XORA layer (Appendix H.2) at the same shapes: ten products of N x m x d/h per head and
     # user (two logit matrices and two G V^T matrices recomputed, six gradients), 20 N m d flops per user.  bf16
-    # storage, d/h = 32 or 64, at most 64 links: one pass over the history on the matrix cores (four history-side tensors read once,
+    # storage, d/h = 32 (at most 128 links) or 64 (at most 64): one pass over the history on the matrix cores (four history-side tensors read once,
     # three gradients written); the form with one kernel per side, which other shapes still take, read them twice.
     back = {}
     for N in (2048, 16384):

@@ -398,7 +398,7 @@ __global__ __launch_bounds__(256, (DH == 32 ? 2 : 1)) void xor_backward_side_mfm
   }
 }
 
-// Both sides in one pass (bf16 storage, d/h = 32 or 64, at most 32 MB links): the history rows, which are the bulk of the
+// Both sides in one pass (bf16 storage, d/h = 32 or 64, MB blocks of 32 links): the history rows, which are the bulk of the
 // operands, are read once, and phi, phi' - an exponential and a reciprocal per logit, the vector ALUs' share, which
 // sets the pace of the two-kernel form - are evaluated once per pair instead of once per side.
 // A workgroup of eight waves at d/h = 32 (two per SIMD: one wave's waits for LDS, memory and the matrix cores are the
@@ -434,18 +434,23 @@ struct FusedArgs {
   int N, m, d, chunks, chunk_rows;  // chunk_rows: history rows per chunk, a multiple of the workgroup's step
   float scale;
 };
-// waves per workgroup: two per SIMD where a wave fits 256 registers (d/h = 32), one where it does not (d/h = 64)
-constexpr int fused_waves(int dh) { return dh == 32 ? 8 : 4; }
+// waves per workgroup: two per SIMD where a wave fits 256 registers (d/h = 32, up to 64 links), one where it does not
+constexpr int fused_waves(int dh, int link_blocks) { return dh == 32 && link_blocks <= 2 ? 8 : 4; }
 template <int DH, int MB>
 constexpr size_t fused_lds_bytes() {
   constexpr size_t copy = 3 * DH * 36 > 3 * 32 * 40 ? 3 * DH * 36 : 3 * 32 * 40, wave = 2 * (copy + 3 * 32 * 40), red = sizeof(float) * 3 * MB * (DH / 32) * 16 * 64;
   constexpr size_t links = 7 * MB * (DH / 16) * 64 * 16;  // seven fragment images of the links' operands
-  return (fused_waves(DH) * wave > red ? fused_waves(DH) * wave : red) + links;
+  return (fused_waves(DH, MB) * wave > red ? fused_waves(DH, MB) * wave : red) + links;
 }
 template <int DH, int MB>
-__global__ __launch_bounds__(64 * fused_waves(DH), 1) void xor_backward_fused_kernel(FusedArgs a) {
+__global__ __launch_bounds__(64 * fused_waves(DH, MB), 1) void xor_backward_fused_kernel(FusedArgs a) {
   constexpr int KS = DH / 16, TT = DH / 32;
-  constexpr int kFusedWaves = fused_waves(DH), kFusedStep = 32 * kFusedWaves;  // history rows per workgroup step
+  constexpr int kFusedWaves = fused_waves(DH, MB), kFusedStep = 32 * kFusedWaves;  // history rows per workgroup step
+  // With up to two blocks of links the rows' sums wait until the last block is through (their accumulators do not fit
+  // beside a block's tiles where two waves share a SIMD, nor beside the sums of 64 links at d/h = 64), each block's
+  // tiles parked in a room of its own; with three or four blocks (d/h = 32, one wave per SIMD) each block's tiles go
+  // into them right away, through one room.
+  constexpr bool kDeferred = MB <= 2;
   constexpr int PITCH = 36;                 // transposed copy of a history tile: bf16 per row (8-byte reads, no bank conflicts)
   constexpr int P2 = DH + 8, CPR = DH / 8;  // staged rows: bf16 per row; 16-byte pieces per row
   constexpr int PP = 40;                    // parked p1, e1, e2: bf16 per history row (16-byte reads of 8 links)
@@ -597,6 +602,30 @@ __global__ __launch_bounds__(64 * fused_waves(DH), 1) void xor_backward_fused_ke
     // parked in the transposed copy's room, which its links' sums are the last to read; the one before in a room of
     // its own.
     u16_any* park_room[2] = {reinterpret_cast<u16_any*>(pk), reinterpret_cast<u16_any*>(yt)};
+    f32x16 acc_s[3][TT];  // dV[S]^T, dK[S]^T, dQ[S]^T: lane = row c0 + n, register 4j + rr = head column 32tt + 8j + 4g + rr
+#pragma unroll
+    for (int o = 0; o < 3; ++o)
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc_s[o][tt][i] = 0.f;
+    // the rows' sums over one block's links, from its parked tiles
+    auto rows_sums = [&](int lb, const u16_any* parked) {
+      const bf16_any* room = reinterpret_cast<const bf16_any*>(parked);
+#pragma unroll
+      for (int kp = 0; kp < 2; ++kp) {
+        const bf16x8 bp1 = *reinterpret_cast<const bf16x8_any*>(room + (0 * 32 + n) * PP + 16 * kp + 8 * g);
+        const bf16x8 bf1 = *reinterpret_cast<const bf16x8_any*>(room + (1 * 32 + n) * PP + 16 * kp + 8 * g);
+        const bf16x8 bf2 = *reinterpret_cast<const bf16x8_any*>(room + (2 * 32 + n) * PP + 16 * kp + 8 * g);
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+          acc_s[0][tt] = mfma32(link_fragment(6, lb, 2 * tt + kp), bp1, acc_s[0][tt]);  // dV[S]^T += G[T]^T p1^T
+          acc_s[1][tt] = mfma32(link_fragment(4, lb, 2 * tt + kp), bf1, acc_s[1][tt]);  // dK[S]^T += Q[T]^T e1^T
+          acc_s[2][tt] = mfma32(link_fragment(5, lb, 2 * tt + kp), bf2, acc_s[2][tt]);  // dQ[S]^T += K[T]^T e2^T
+        }
+        __builtin_amdgcn_sched_barrier(0);  // (a half's operands at a time)
+      }
+    };
 #pragma unroll
     for (int lb = 0; lb < MB; ++lb) {
       // (the phases of a block are kept apart: moved into each other by the scheduler they need more registers than
@@ -654,7 +683,7 @@ __global__ __launch_bounds__(64 * fused_waves(DH), 1) void xor_backward_fused_ke
           room[(2 * 32 + row) * PP + n] = static_cast<unsigned short>(we2[k]), room[(2 * 32 + row + 1) * PP + n] = static_cast<unsigned short>(we2[k] >> 16);
         }
       };
-      if (lb < MB - 1) park(park_room[0]);
+      if (kDeferred && lb < MB - 1) park(park_room[0]);
       __builtin_amdgcn_sched_barrier(0);
       // the links' sums over this tile's rows
 #pragma unroll
@@ -677,37 +706,24 @@ __global__ __launch_bounds__(64 * fused_waves(DH), 1) void xor_backward_fused_ke
         }
       }
       __builtin_amdgcn_sched_barrier(0);
-      if (lb == MB - 1) park(park_room[1]);
+      if constexpr (kDeferred) {
+        if (lb == MB - 1) park(park_room[1]);
+      } else {
+        park(park_room[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        rows_sums(lb, park_room[0]);
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
     // (the next tile's rows are asked for here, every block's tiles and words used up: earlier there are no
     // registers for them, and the workgroup's other waves have work while this one waits for them)
     ask(c0 + kFusedStep);
     __builtin_amdgcn_sched_barrier(0);
-    // the rows' sums over all links
-    f32x16 acc_s[3][TT];  // dV[S]^T, dK[S]^T, dQ[S]^T: lane = row c0 + n, register 4j + rr = head column 32tt + 8j + 4g + rr
+    if constexpr (kDeferred) {
+      // the rows' sums over all links
 #pragma unroll
-    for (int o = 0; o < 3; ++o)
-#pragma unroll
-      for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc_s[o][tt][i] = 0.f;
-#pragma unroll
-    for (int lb = 0; lb < MB; ++lb)
-#pragma unroll
-      for (int kp = 0; kp < 2; ++kp) {
-        const bf16_any* room = reinterpret_cast<const bf16_any*>(park_room[lb == MB - 1 ? 1 : 0]);
-        const bf16x8 bp1 = *reinterpret_cast<const bf16x8_any*>(room + (0 * 32 + n) * PP + 16 * kp + 8 * g);
-        const bf16x8 bf1 = *reinterpret_cast<const bf16x8_any*>(room + (1 * 32 + n) * PP + 16 * kp + 8 * g);
-        const bf16x8 bf2 = *reinterpret_cast<const bf16x8_any*>(room + (2 * 32 + n) * PP + 16 * kp + 8 * g);
-#pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-          acc_s[0][tt] = mfma32(link_fragment(6, lb, 2 * tt + kp), bp1, acc_s[0][tt]);  // dV[S]^T += G[T]^T p1^T
-          acc_s[1][tt] = mfma32(link_fragment(4, lb, 2 * tt + kp), bf1, acc_s[1][tt]);  // dK[S]^T += Q[T]^T e1^T
-          acc_s[2][tt] = mfma32(link_fragment(5, lb, 2 * tt + kp), bf2, acc_s[2][tt]);  // dQ[S]^T += K[T]^T e2^T
-        }
-        __builtin_amdgcn_sched_barrier(0);  // (a half's operands at a time)
-      }
+      for (int lb = 0; lb < MB; ++lb) rows_sums(lb, park_room[lb == MB - 1 ? 1 : 0]);
+    }
 #pragma unroll
     for (int o = 0; o < 3; ++o) {
 #pragma unroll
@@ -846,13 +862,14 @@ hipError_t launch_side(const SideArgs& a, dim3 grid, bool on_mfma, bool own_per_
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// The one-pass form: d/h = 32 or 64 and at most 64 links (the links' sums must fit a wave's registers).
-constexpr int kFusedLinks = 64;
+// The one-pass form: at most 128 links at d/h = 32, 64 at d/h = 64 (the links' sums must fit a wave's registers).
+constexpr int kFusedLinks32 = 128, kFusedLinks64 = 64;  // by head width
 bool fused_shape(int N, int m, int d, int dh) {
-  return (dh == 32 || dh == 64) && m <= kFusedLinks && static_cast<int64_t>(N) * d * 2 < (int64_t{1} << 32);  // (32-bit offsets within a user)
+  return ((dh == 32 && m <= kFusedLinks32) || (dh == 64 && m <= kFusedLinks64)) &&
+         static_cast<int64_t>(N) * d * 2 < (int64_t{1} << 32);  // (32-bit offsets within a user)
 }
-int chunks_for_fused(int B, int N, int h, int dh) {
-  const int kFusedStep = 32 * fused_waves(dh);
+int chunks_for_fused(int B, int N, int h, int dh, int m) {
+  const int kFusedStep = 32 * fused_waves(dh, (m + 31) / 32);
   // one workgroup per compute unit (a wave per SIMD), but no chunk shorter than one step
   const int64_t per_chunk = static_cast<int64_t>(h) * B;
   const int64_t steps = (N + kFusedStep - 1) / kFusedStep;
@@ -869,7 +886,7 @@ hipError_t launch_fused(const FusedArgs& a, dim3 grid, hipStream_t s) {
   static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
   if (attr != hipSuccess) return attr;
-  hipLaunchKernelGGL(kernel, grid, dim3(64 * fused_waves(DH)), lds, s, a);
+  hipLaunchKernelGGL(kernel, grid, dim3(64 * fused_waves(DH, MB)), lds, s, a);
   return hipGetLastError();
 }
 
@@ -879,13 +896,18 @@ hipError_t xor_backward_fused(const XorBackward& g, void* workspace, hipStream_t
   a.dqs = g.dQS, a.dks = g.dKS, a.dvs = g.dVS, a.dqt = g.dQT, a.dkt = g.dKT, a.dvt = g.dVT;
   a.partial = static_cast<float*>(workspace), a.lens = g.lens;
   a.N = g.N, a.m = g.m, a.d = g.d, a.scale = g.scale;
-  const int dh = g.d / g.h, kFusedStep = 32 * fused_waves(dh);
-  a.chunks = chunks_for_fused(g.B, g.N, g.h, dh);
+  const int dh = g.d / g.h, blocks = (g.m + 31) / 32, kFusedStep = 32 * fused_waves(dh, blocks);
+  a.chunks = chunks_for_fused(g.B, g.N, g.h, dh, g.m);
   const int steps = (g.N + kFusedStep - 1) / kFusedStep;
   a.chunk_rows = (steps + a.chunks - 1) / a.chunks * kFusedStep;
   const dim3 grid(a.chunks, g.h, g.B);
-  hipError_t e = dh == 32 ? (g.m <= 32 ? launch_fused<32, 1>(a, grid, s) : launch_fused<32, 2>(a, grid, s))
-                          : (g.m <= 32 ? launch_fused<64, 1>(a, grid, s) : launch_fused<64, 2>(a, grid, s));
+  hipError_t e = hipErrorInvalidValue;
+  if (dh == 32) {
+    e = blocks == 1 ? launch_fused<32, 1>(a, grid, s) : blocks == 2 ? launch_fused<32, 2>(a, grid, s)
+      : blocks == 3 ? launch_fused<32, 3>(a, grid, s) : launch_fused<32, 4>(a, grid, s);
+  } else {
+    e = blocks == 1 ? launch_fused<64, 1>(a, grid, s) : launch_fused<64, 2>(a, grid, s);
+  }
   if (e != hipSuccess || a.chunks == 1) return e;
   const int64_t plane = static_cast<int64_t>(g.m) * g.d;
   hipLaunchKernelGGL(xor_backward_reduce_kernel<bf16_t>, dim3(static_cast<unsigned>((plane + 255) / 256), 3, g.B), dim3(256), 0, s,
@@ -940,7 +962,7 @@ size_t xor_backward_workspace(int B, int N, int m, int d, int h) {
   // large enough for either kernel (a bf16 call whose pointers are not 16-byte aligned runs on the vector ALUs)
   int chunks = std::max(chunks_for_links(B, N, m, h, step_rows(d / h, false)),
                         chunks_for_links(B, N, m, h, step_rows(d / h, true)));
-  if (fused_shape(N, m, d, d / h)) chunks = std::max(chunks, chunks_for_fused(B, N, h, d / h));
+  if (fused_shape(N, m, d, d / h)) chunks = std::max(chunks, chunks_for_fused(B, N, h, d / h, m));
   return chunks == 1 ? 256 : align_up(static_cast<size_t>(B) * chunks * 3 * m * d * sizeof(float));
 }
 
