@@ -229,6 +229,16 @@ def main():
     lat_hist = timed(lambda i: binding.lime_link_history(E, None, L, Wq, Wk, Wv, h, scale, LP=LP, workspace=ws), reps)
     lat_cand = timed(lambda i: binding.lime_score_candidates(Ts[i % n_pairs], L, LP, Wq, Wk, Wv, h, scale,
                                                              O=Os[i % n_pairs], workspace=ws), reps)
+    # the same request on operands prepared once per model (weights and shared links packed by lime_prepare: what a
+    # server with fixed weights calls per request; three kernels instead of four)
+    lat_prep = None
+    if one_call:
+        prepared = binding.lime_prepare(L, L, Wq, Wk, Wv, Wq, Wk, h, scale, scale)
+        ws_prep = torch.empty(binding.workspace_bytes(binding.OP_REQUEST_PREPARED, B=B, N=N, C=C, d=d, h=h, m=m),
+                              dtype=torch.uint8, device=dev)
+        LP_prep = torch.empty_like(LP)
+        lat_prep = timed(lambda i: binding.lime_request_prepared(E, None, Ts[i % n_pairs], Wv, prepared, h, m, scale, scale,
+                                                                  LP=LP_prep, O=Os[i % n_pairs], workspace=ws_prep), reps)
     # The dominant kernel's own duration: requests one at a time, exactly as the step issues them, every launch of
     # the candidate-side kernel with a start and a stop event of its own (the dispatch's time stamps: no event-pair
     # cost to take off, and the figure a kernel trace of this command reports for the same launches).
@@ -279,7 +289,8 @@ def main():
                    "rotating_buffer_pairs": n_pairs, "rotating_mib": n_pairs * pair_bytes / 2 ** 20},
         "latency_ms": {"request_p50": pct(lat_step, 0.5), "request_p10": pct(lat_step, 0.1),
                        "request_p90": pct(lat_step, 0.9), "lime_link_history_p50": pct(lat_hist, 0.5),
-                       "lime_score_candidates_p50": pct(lat_cand, 0.5)},
+                       "lime_score_candidates_p50": pct(lat_cand, 0.5),
+                       "request_on_prepared_operands_p50": pct(lat_prep, 0.5) if lat_prep else None},
         "host_launch_ms_per_step": host_ms_per_step,
         "one_request_in_flight": {"ms_per_step": ms_per_step_single, "candidates_per_s": B * C / (ms_per_step_single * 1e-3)},
         "candidates_per_s_candidate_call_only": B * C / (pct(lat_cand, 0.5) * 1e-3),
