@@ -401,9 +401,9 @@ __global__ __launch_bounds__(256, (DH == 32 ? 2 : 1)) void xor_backward_side_mfm
 // Both sides in one pass (bf16 storage, d/h = 32 or 64, MB blocks of 32 links): the history rows, which are the bulk of the
 // operands, are read once, and phi, phi' - an exponential and a reciprocal per logit, the vector ALUs' share, which
 // sets the pace of the two-kernel form - are evaluated once per pair instead of once per side.
-// A workgroup of eight waves at d/h = 32 (two per SIMD: one wave's waits for LDS, memory and the matrix cores are the
-// other's time to issue; at d/h = 64 the sums alone are 192 registers and a workgroup is four waves) takes a chunk
-// of the history of one (user, head); each wave walks its own 32-row tiles of it.  The links' operands lie in LDS as
+// A workgroup of eight waves at d/h = 32 with up to 64 links (two per SIMD: one wave's waits for LDS, memory and the
+// matrix cores are the other's time to issue; at d/h = 64, and with 96 or 128 links, the links' sums alone are 144 to
+// 192 registers and a workgroup is four waves) takes a chunk of the history of one (user, head); each wave walks its own 32-row tiles of it.  The links' operands lie in LDS as
 // fragment images, shared by the waves and read where they are used: in registers they would leave no room for a
 // second wave.  Per tile:
 //   1. its four tensors come straight from memory as operand fragments, asked for while the previous tile's last
@@ -415,8 +415,9 @@ __global__ __launch_bounds__(256, (DH == 32 ? 2 : 1)) void xor_backward_side_mfm
 //      chained B operands as they stand (as in the kernel above), dV[T]^T += G[S]^T p2, dQ[T]^T += K[S]^T e1,
 //      dK[T]^T += Q[S]^T e2, accumulated over the wave's whole walk;
 //   4. the history rows' gradients sum over the links, the lane index of those blocks: p1, e1, e2 are parked in LDS
-//      ([history row][link], one bf16 at a time) and, after the last block of links, read back as B operands (lane =
-//      history row, eight links per lane) against the links' transposed operands: dV[S]^T += G[T]^T p1^T,
+//      ([history row][link], one bf16 at a time) and - after the last block of links, or with three and four
+//      blocks right away - read back as B operands (lane = history row, eight links per lane) against the links'
+//      transposed operands: dV[S]^T += G[T]^T p1^T,
 //      dK[S]^T += Q[T]^T e1^T, dQ[S]^T += K[T]^T e2^T; stored through LDS as whole head slices of a few rows.
 // The constant factors (scale, 1/n_S, 1/m) are left out of the tiles and applied to the sums.  At the end the waves'
 // sums for the links meet in LDS pairwise in a fixed order; chunk sums as above.  The steps of a tile are fenced
